@@ -1,0 +1,198 @@
+/*
+ * libskipkv — the periodic sentence-level KV-cache compression step of SkipKV
+ * (Sec. 4.1 "Skipping KV Storage with Sentence-level Scoring", Alg. 1 eviction line)
+ * and the steering-vector injection (Sec. 4.2), for AMD MI355X (gfx950).
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - Plain C ABI.  Every call returns an int status: SKIPKV_OK (0) or a negative code;
+ *    skipkv_strerror() names it.  No exceptions, no global state.
+ *  - Pointers marked "device" must be GPU-accessible memory owned by the caller and must
+ *    stay valid until the work enqueued by the call has finished.  The library never
+ *    allocates or frees device memory; scratch space comes from the caller's workspace
+ *    (size from skipkv_workspace_bytes).
+ *  - All GPU work is enqueued on the caller's stream (`stream` is a hipStream_t passed as
+ *    void*; NULL is the default stream).  No call synchronises the device: outputs are
+ *    valid after the caller synchronises the stream.  Argument structs are read before
+ *    the call returns.
+ *  - Arguments are validated on the host before anything is enqueued; on a validation
+ *    error nothing has been launched.  Problems only visible on the device (non-monotone
+ *    sentence offsets, more sentences per chunk of work than the kernels support) are
+ *    reported by OR-ing SKIPKV_DEV_* bits into *params->dev_status when it is non-NULL.
+ *  - Re-entrant for calls that use distinct buffers, workspaces and streams.
+ *
+ * Data layout
+ * -----------
+ *  A "head" is one (layer l, KV head h, sequence b) triple.  Sequences are stored
+ *  unpadded, one after another along the token axis (CSR offsets seq_off), the same
+ *  packing for every layer and head.  Element (l, h, t, d) of K (or V), t being the
+ *  packed token index, lives at  base + l*stride_layer + h*stride_head + t*stride_tok + d
+ *  (strides in elements, d contiguous, head_dim = 128).
+ *  Sentence spans are per sequence and shared by all layers and heads: sequence b has
+ *  S_b = sent_ptr[b+1]-sent_ptr[b]-1 sentences; sentence s is the half-open token span
+ *  [o[s], o[s+1]) with o = sent_off + sent_ptr[b], relative to the start of the sequence,
+ *  o[0] = 0, o[S_b] = N_b (the cache length of b), strictly ascending.
+ *  Per-sentence arrays are laid out [n_layers, n_kv_heads, total_sentences]; sentence s of
+ *  sequence b is at column sent_ptr[b] - b + s.  Per-token arrays are
+ *  [n_layers, n_kv_heads, total_tokens] with column seq_off[b] + t.
+ */
+#ifndef SKIPKV_H
+#define SKIPKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SKIPKV_VERSION 100 /* major*10000 + minor*100 + patch */
+
+enum {
+  SKIPKV_OK = 0,
+  SKIPKV_EINVAL = -1,     /* null pointer, bad shape, stride, alignment or dtype          */
+  SKIPKV_EBUDGET = -2,    /* budget < protect_window, or obs_window > protect_window      */
+  SKIPKV_ECAPACITY = -3,  /* shape outside what the kernels are built for (see limits)    */
+  SKIPKV_EWORKSPACE = -4, /* workspace NULL, misaligned or smaller than required          */
+  SKIPKV_EHIP = -5        /* a HIP runtime call failed (launch error)                     */
+};
+
+/* bits OR-ed into *dev_status by kernels */
+enum {
+  SKIPKV_DEV_BAD_OFFSETS = 1,  /* sentence offsets not strictly ascending from 0 to N_b   */
+  SKIPKV_DEV_TOO_MANY_SENT = 2 /* a sequence has more than SKIPKV_MAX_SENTENCES sentences */
+};
+
+typedef enum { SKIPKV_F32 = 0, SKIPKV_BF16 = 1 } skipkv_dtype;
+
+/* Limits of this build. */
+#define SKIPKV_HEAD_DIM 128
+#define SKIPKV_MAX_GROUP 8        /* n = n_q_heads / n_kv_heads                           */
+#define SKIPKV_MAX_OBS_WINDOW 32  /* alpha                                                */
+#define SKIPKV_MAX_SENTENCES 4096 /* per sequence                                         */
+
+/* The KV cache and its ragged structure (Sec. 4.1: K, V in R^{bs x H_k x N' x d}). */
+typedef struct skipkv_cache {
+  void *k;               /* device, rewritten in place by skipkv_compact / skipkv_step    */
+  void *v;               /* device, same layout as k                                      */
+  int64_t stride_layer;  /* elements; multiples of 8 so that every row is 16-byte aligned */
+  int64_t stride_head;
+  int64_t stride_tok;    /* >= head_dim                                                   */
+  int32_t dtype;         /* skipkv_dtype of k, v and the observation queries              */
+  int32_t n_layers;
+  int32_t n_kv_heads;    /* H_k                                                           */
+  int32_t n_q_heads;     /* H_q, a multiple of H_k; query head i uses KV head i / n       */
+  int32_t head_dim;      /* must be 128                                                   */
+  int32_t batch;         /* number of sequences                                           */
+  int32_t total_tokens;  /* host copy of seq_off[batch]                                   */
+  int32_t total_sentences; /* host copy of sum_b S_b                                      */
+  const int32_t *seq_off;  /* device [batch+1], seq_off[0] = 0                            */
+  const int32_t *sent_ptr; /* device [batch+1], sent_ptr[0] = 0                           */
+  const int32_t *sent_off; /* device [total_sentences + batch]                            */
+} skipkv_cache;
+
+/* Scalars of the method (Appendix "Hyper-parameters": sigma = 0.1, tau in [0.95, 0.99]). */
+typedef struct skipkv_params {
+  int32_t obs_window;     /* alpha: number of recent query positions that score the cache */
+  int32_t protect_window; /* w >= alpha: the last min(w, N_b) tokens are never evicted     */
+  float sigma;            /* weight of the importance term in the cumulative score (Eq. 6) */
+  float tau;              /* similarity threshold of the redundant set (Eq. 3), strict >   */
+  const int32_t *budget;  /* device [batch] per-sequence token budget, or NULL ...         */
+  int32_t budget_scalar;  /* ... then this budget applies to every sequence                */
+  int32_t max_budget;     /* host upper bound on any budget (sizes kept_idx rows)          */
+  int32_t *dev_status;    /* device, nullable: SKIPKV_DEV_* bits are OR-ed into it         */
+  void *profile;          /* nullable: handle from skipkv_profile_create                   */
+} skipkv_params;
+
+/* Bytes of device scratch that skipkv_score / skipkv_step need for this problem.         */
+int skipkv_workspace_bytes(const skipkv_cache *cache, const skipkv_params *params, size_t *out_bytes);
+
+/*
+ * Scores (Sec. 4.1, Eq. 1-4 and Eq. 6).  Per head:
+ *   token importance I[t]: softmax over the cached keys of q.k/sqrt(d) for each of the n
+ *     query heads of the GQA group and each of the alpha window queries (window query a
+ *     sits at cache position N-alpha+a and sees keys t <= N-alpha+a), max over the n heads,
+ *     mean over the alpha queries;
+ *   sentence embedding: mean of the head's keys over the sentence; lambda_s = largest
+ *     cosine between sentence s and any LATER sentence (-inf for the last one);
+ *   sent_score[s] = sigma * mean_t I[t] - (1-sigma) * mean_t R[t] - (lambda_s if lambda_s > tau),
+ *     means over the part of s that lies before the protected window; +inf for sentences
+ *     that start inside the protected window.
+ * q_obs           device [n_layers, batch, n_q_heads, obs_window, 128], cache dtype.
+ * tok_redundancy  device [n_layers, n_kv_heads, total_tokens] fp32 or NULL (R = 0).
+ * sent_score, sent_lambda   device out [n_layers, n_kv_heads, total_sentences] fp32.
+ * tok_importance  device out [n_layers, n_kv_heads, total_tokens] fp32, or NULL.
+ * ws              device workspace, 256-byte aligned, >= skipkv_workspace_bytes().
+ */
+int skipkv_score(const skipkv_cache *cache, const skipkv_params *params, const void *q_obs,
+                 const float *tok_redundancy, float *sent_score, float *sent_lambda,
+                 float *tok_importance, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Budgeted whole-sentence selection (Sec. 4.1 after Eq. 6: evict in increasing order of
+ * the score until the budget is met; surviving index set P of the range-remap paragraph).
+ * Per head: if N_b <= budget everything is kept.  Otherwise candidates (sentences that
+ * start before the protected window, counted with their unprotected length) are ranked by
+ * (score descending, sentence index descending) and the longest prefix of that ranking
+ * whose lengths sum to <= budget - min(w, N_b) is kept, plus the protected window.
+ * sent_keep     device out [n_layers, n_kv_heads, total_sentences] u8, nullable: 1 if the
+ *               unprotected part of the sentence survives (1 for non-candidates).
+ * kept_idx      device out [n_layers, n_kv_heads, batch, kept_stride] int32: ascending
+ *               sequence-relative indices of the surviving tokens, new_len entries valid.
+ * new_len       device out [n_layers, n_kv_heads, batch] int32.
+ * new_sent_off  device out [n_layers, n_kv_heads, total_sentences + batch] int32, nullable:
+ *               offsets of the surviving sentences in the compacted cache (Eq. 11), stored
+ *               at column sent_ptr[b]; new_sent_cnt [n_layers, n_kv_heads, batch] holds
+ *               their number (both NULL or both non-NULL).
+ * kept_stride   row pitch of kept_idx, >= min(max_budget, longest sequence).
+ */
+int skipkv_select(const skipkv_cache *cache, const skipkv_params *params, const float *sent_score,
+                  uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len, int32_t *new_sent_off,
+                  int32_t *new_sent_cnt, int32_t kept_stride, void *stream);
+
+/*
+ * In-place compaction (Alg. 1 eviction line): for every head and k < new_len,
+ * K[k] <- K[kept_idx[k]] and V[k] <- V[kept_idx[k]], bit for bit.  kept_idx rows must be
+ * strictly ascending (so kept_idx[k] >= k).  Rows at and beyond new_len are unspecified
+ * afterwards.  Only cache->k, v, strides, dtype, shape and seq_off are used.
+ */
+int skipkv_compact(const skipkv_cache *cache, const int32_t *kept_idx, const int32_t *new_len,
+                   int32_t kept_stride, void *stream);
+
+/* score + select + compact enqueued back to back with no host round trip in between.     */
+int skipkv_step(const skipkv_cache *cache, const skipkv_params *params, const void *q_obs,
+                const float *tok_redundancy, float *sent_score, float *sent_lambda,
+                float *tok_importance, uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len,
+                int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride, void *ws,
+                size_t ws_bytes, void *stream);
+
+/*
+ * Steering injection (Sec. 4.2): hidden[b, :] <- hidden[b, :] + coef_b * vec for every row b
+ * with row_mask[b] != 0 (all rows when row_mask is NULL).  coef_b = coef[b] when coef is
+ * non-NULL, else coef_scalar.  The sum is formed in fp64 and rounded once (nearest even)
+ * to the storage dtype.
+ * hidden   device in/out [rows, d_model], dtype; vec device [d_model], dtype;
+ * coef     device [rows] fp32 or NULL; row_mask device [rows] u8 or NULL.
+ */
+int skipkv_steer_add(void *hidden, const void *vec, const float *coef, float coef_scalar,
+                     const uint8_t *row_mask, int32_t rows, int32_t d_model, int32_t dtype,
+                     void *stream);
+
+/*
+ * Optional per-kernel timing.  A profile owns HIP events; when params->profile is set the
+ * library records one before and after each kernel it launches.  skipkv_profile_read
+ * synchronises those events and returns, for slot i < *n, the kernel's name and the
+ * milliseconds between its two events for the most recent call that used the profile.
+ */
+#define SKIPKV_PROFILE_SLOTS 16
+int skipkv_profile_create(void **out_profile);
+int skipkv_profile_read(void *profile, int32_t *n, const char **names, float *ms);
+int skipkv_profile_destroy(void *profile);
+
+const char *skipkv_strerror(int status);
+int skipkv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SKIPKV_H */

@@ -1,0 +1,219 @@
+"""Thin ctypes binding of libskipkv.so: argument marshalling only.
+
+Every function has the name and argument order of the C entry point in include/skipkv.h.
+Tensors are torch tensors used purely as device-memory handles (data_ptr()); all work
+runs in the library's HIP kernels on the current torch stream unless `stream` is given.
+There is no fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+F32, BF16 = 0, 1
+OK, EINVAL, EBUDGET, ECAPACITY, EWORKSPACE, EHIP = 0, -1, -2, -3, -4, -5
+DEV_BAD_OFFSETS, DEV_TOO_MANY_SENT = 1, 2
+PROFILE_SLOTS = 16
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libskipkv.so")
+_lib = None
+
+
+class CCache(C.Structure):
+    _fields_ = [
+        ("k", C.c_void_p), ("v", C.c_void_p),
+        ("stride_layer", C.c_int64), ("stride_head", C.c_int64), ("stride_tok", C.c_int64),
+        ("dtype", C.c_int32), ("n_layers", C.c_int32), ("n_kv_heads", C.c_int32),
+        ("n_q_heads", C.c_int32), ("head_dim", C.c_int32), ("batch", C.c_int32),
+        ("total_tokens", C.c_int32), ("total_sentences", C.c_int32),
+        ("seq_off", C.c_void_p), ("sent_ptr", C.c_void_p), ("sent_off", C.c_void_p),
+    ]
+
+
+class CParams(C.Structure):
+    _fields_ = [
+        ("obs_window", C.c_int32), ("protect_window", C.c_int32),
+        ("sigma", C.c_float), ("tau", C.c_float),
+        ("budget", C.c_void_p), ("budget_scalar", C.c_int32), ("max_budget", C.c_int32),
+        ("dev_status", C.c_void_p), ("profile", C.c_void_p),
+    ]
+
+
+def lib() -> C.CDLL:
+    """Load libskipkv.so (built by paper_2512_07993_amd.build); raise if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(
+                "libskipkv.so is not built: run `python -m paper_2512_07993_amd.build` "
+                "(there is no CPU fallback)")
+        L = C.CDLL(_LIB_PATH)
+        vp, i32, sz, fl = C.c_void_p, C.c_int32, C.c_size_t, C.c_float
+        cp, pp = C.POINTER(CCache), C.POINTER(CParams)
+        L.skipkv_workspace_bytes.argtypes = [cp, pp, C.POINTER(sz)]
+        L.skipkv_score.argtypes = [cp, pp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.skipkv_select.argtypes = [cp, pp, vp, vp, vp, vp, vp, vp, i32, vp]
+        L.skipkv_compact.argtypes = [cp, vp, vp, i32, vp]
+        L.skipkv_step.argtypes = [cp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+        L.skipkv_steer_add.argtypes = [vp, vp, vp, fl, vp, i32, i32, i32, vp]
+        L.skipkv_profile_create.argtypes = [C.POINTER(vp)]
+        L.skipkv_profile_read.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_char_p), C.POINTER(fl)]
+        L.skipkv_profile_destroy.argtypes = [vp]
+        L.skipkv_strerror.argtypes = [C.c_int]
+        L.skipkv_strerror.restype = C.c_char_p
+        L.skipkv_version.argtypes = []
+        for name in ("skipkv_workspace_bytes", "skipkv_score", "skipkv_select", "skipkv_compact", "skipkv_step",
+                     "skipkv_steer_add", "skipkv_profile_create", "skipkv_profile_read", "skipkv_profile_destroy",
+                     "skipkv_version"):
+            getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+class SkipKVError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__("libskipkv: %s (%d)" % (lib().skipkv_strerror(status).decode(), status))
+
+
+def _check(status: int) -> None:
+    if status != OK:
+        raise SkipKVError(status)
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else None
+    return stream if isinstance(stream, int) else stream.cuda_stream
+
+
+def dtype_code(t: torch.dtype) -> int:
+    if t == torch.float32:
+        return F32
+    if t == torch.bfloat16:
+        return BF16
+    raise ValueError("unsupported dtype %s" % t)
+
+
+@dataclass
+class Cache:
+    """Python mirror of skipkv_cache.  k, v: [L, Hk, T, D] tensors (any strides with D contiguous)."""
+    k: torch.Tensor
+    v: torch.Tensor
+    n_q_heads: int
+    seq_off: torch.Tensor      # int32 device [B+1]
+    sent_ptr: torch.Tensor     # int32 device [B+1]
+    sent_off: torch.Tensor     # int32 device [S_total + B]
+    total_tokens: int
+    total_sentences: int
+
+    @property
+    def batch(self) -> int:
+        return int(self.seq_off.numel()) - 1
+
+    def c(self) -> CCache:
+        k = self.k
+        assert k.dim() == 4 and k.stride(3) == 1 and self.v.stride() == k.stride() and self.v.shape == k.shape
+        return CCache(k.data_ptr(), self.v.data_ptr(), k.stride(0), k.stride(1), k.stride(2), dtype_code(k.dtype),
+                      k.shape[0], k.shape[1], self.n_q_heads, k.shape[3], self.batch,
+                      self.total_tokens, self.total_sentences,
+                      _ptr(self.seq_off), _ptr(self.sent_ptr), _ptr(self.sent_off))
+
+
+@dataclass
+class Params:
+    """Python mirror of skipkv_params."""
+    obs_window: int
+    protect_window: int
+    budget: "int | torch.Tensor"
+    max_budget: int = -1
+    sigma: float = 0.1
+    tau: float = 0.95
+    dev_status: Optional[torch.Tensor] = None
+    profile: Optional[int] = None
+
+    def c(self) -> CParams:
+        if isinstance(self.budget, int):
+            bptr, bs = None, self.budget
+            mb = self.budget if self.max_budget < 0 else self.max_budget
+        else:
+            bptr, bs, mb = self.budget.data_ptr(), 0, self.max_budget
+        return CParams(self.obs_window, self.protect_window, self.sigma, self.tau, bptr, bs, mb,
+                       _ptr(self.dev_status), self.profile)
+
+
+def skipkv_version() -> int:
+    return lib().skipkv_version()
+
+
+def skipkv_strerror(status: int) -> str:
+    return lib().skipkv_strerror(status).decode()
+
+
+def skipkv_workspace_bytes(cache: Cache, params: Params) -> int:
+    out = C.c_size_t(0)
+    _check(lib().skipkv_workspace_bytes(C.byref(cache.c()), C.byref(params.c()), C.byref(out)))
+    return int(out.value)
+
+
+def skipkv_score(cache: Cache, params: Params, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance,
+                 ws, stream=None) -> None:
+    _check(lib().skipkv_score(C.byref(cache.c()), C.byref(params.c()), _ptr(q_obs), _ptr(tok_redundancy),
+                              _ptr(sent_score), _ptr(sent_lambda), _ptr(tok_importance), _ptr(ws),
+                              ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
+
+
+def skipkv_select(cache: Cache, params: Params, sent_score, sent_keep, kept_idx, new_len, new_sent_off,
+                  new_sent_cnt, kept_stride: int, stream=None) -> None:
+    _check(lib().skipkv_select(C.byref(cache.c()), C.byref(params.c()), _ptr(sent_score), _ptr(sent_keep),
+                               _ptr(kept_idx), _ptr(new_len), _ptr(new_sent_off), _ptr(new_sent_cnt),
+                               kept_stride, _stream(stream)))
+
+
+def skipkv_compact(cache: Cache, kept_idx, new_len, kept_stride: int, stream=None) -> None:
+    _check(lib().skipkv_compact(C.byref(cache.c()), _ptr(kept_idx), _ptr(new_len), kept_stride, _stream(stream)))
+
+
+def skipkv_step(cache: Cache, params: Params, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance,
+                sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride: int, ws, stream=None) -> None:
+    _check(lib().skipkv_step(C.byref(cache.c()), C.byref(params.c()), _ptr(q_obs), _ptr(tok_redundancy),
+                             _ptr(sent_score), _ptr(sent_lambda), _ptr(tok_importance), _ptr(sent_keep),
+                             _ptr(kept_idx), _ptr(new_len), _ptr(new_sent_off), _ptr(new_sent_cnt), kept_stride,
+                             _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
+
+
+def skipkv_steer_add(hidden, vec, coef, coef_scalar: float, row_mask, stream=None) -> None:
+    rows, d_model = hidden.shape
+    assert hidden.is_contiguous() and vec.is_contiguous() and vec.dtype == hidden.dtype
+    _check(lib().skipkv_steer_add(_ptr(hidden), _ptr(vec), _ptr(coef), float(coef_scalar), _ptr(row_mask),
+                                  rows, d_model, dtype_code(hidden.dtype), _stream(stream)))
+
+
+def skipkv_profile_create() -> int:
+    out = C.c_void_p(0)
+    _check(lib().skipkv_profile_create(C.byref(out)))
+    return int(out.value)
+
+
+def skipkv_profile_read(profile: int) -> "list[tuple[str, float]]":
+    n = C.c_int32(0)
+    names = (C.c_char_p * PROFILE_SLOTS)()
+    ms = (C.c_float * PROFILE_SLOTS)()
+    _check(lib().skipkv_profile_read(profile, C.byref(n), names, ms))
+    return [(names[i].decode(), float(ms[i])) for i in range(n.value)]
+
+
+def skipkv_profile_destroy(profile: int) -> None:
+    _check(lib().skipkv_profile_destroy(profile))

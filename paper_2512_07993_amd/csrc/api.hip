@@ -1,0 +1,365 @@
+// Host side of libskipkv: argument validation, workspace carving, kernel sequencing, timing.
+// No device work happens here and nothing is allocated on the device.
+#include <new>
+
+#include "common.h"
+
+namespace skipkv {
+
+struct Profile {
+  hipEvent_t ev[2 * SKIPKV_PROFILE_SLOTS];
+  const char *name[SKIPKV_PROFILE_SLOTS];
+  int32_t n;
+};
+
+namespace {
+
+inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_cache(const skipkv_cache *c, bool need_sentences) {
+  if (!c) return SKIPKV_EINVAL;
+  if (c->dtype != SKIPKV_F32 && c->dtype != SKIPKV_BF16) return SKIPKV_EINVAL;
+  if (c->head_dim != SKIPKV_HEAD_DIM) return SKIPKV_ECAPACITY;
+  if (c->n_layers < 0 || c->n_kv_heads < 0 || c->batch < 0 || c->total_tokens < 0) return SKIPKV_EINVAL;
+  const bool empty = c->n_layers == 0 || c->n_kv_heads == 0 || c->batch == 0;
+  if (empty) return SKIPKV_OK;
+  if (!c->seq_off) return SKIPKV_EINVAL;
+  if (c->total_tokens > 0) {
+    if (!c->k || !c->v || !aligned16(c->k) || !aligned16(c->v)) return SKIPKV_EINVAL;
+    if (c->stride_tok < c->head_dim || (c->stride_tok % 8) || (c->stride_head % 8) || (c->stride_layer % 8)) return SKIPKV_EINVAL;
+    if (c->stride_head < 0 || c->stride_layer < 0) return SKIPKV_EINVAL;
+  }
+  if (need_sentences) {
+    if (!c->sent_ptr || !c->sent_off || c->total_sentences < 0) return SKIPKV_EINVAL;
+    if (c->n_q_heads <= 0 || c->n_q_heads % c->n_kv_heads) return SKIPKV_EINVAL;
+  }
+  return SKIPKV_OK;
+}
+
+int check_params(const skipkv_cache *c, const skipkv_params *p, RowLayout *rl) {
+  if (!p) return SKIPKV_EINVAL;
+  if (p->obs_window < 1 || p->protect_window < 0) return SKIPKV_EINVAL;
+  if (!(p->sigma >= 0.f && p->sigma <= 1.f) || !(p->tau == p->tau)) return SKIPKV_EINVAL;
+  if (p->obs_window > p->protect_window) return SKIPKV_EBUDGET;
+  if (p->max_budget < 0) return SKIPKV_EINVAL;
+  if (!p->budget && (p->budget_scalar < p->protect_window || p->budget_scalar > p->max_budget)) return SKIPKV_EBUDGET;
+  if (p->budget && p->max_budget < p->protect_window) return SKIPKV_EBUDGET;
+  const int n = c->n_kv_heads > 0 ? c->n_q_heads / c->n_kv_heads : 1;
+  if (!make_row_layout(n, p->obs_window, rl)) return SKIPKV_ECAPACITY;
+  if (c->dtype == SKIPKV_F32 && rl->rows > 160) return SKIPKV_ECAPACITY;  // fp32 query tile would not fit in LDS
+  return SKIPKV_OK;
+}
+
+// Carve the workspace.  `base` may be NULL to only compute the size.
+Workspace carve(const skipkv_cache *c, const RowLayout &rl, void *base) {
+  Workspace w{};
+  const size_t B = (size_t)c->batch, LH = (size_t)c->n_layers * c->n_kv_heads;
+  const size_t T = (size_t)c->total_tokens, S = (size_t)c->total_sentences;
+  w.nc_max = (int32_t)((T + kChunkWindow - 1) / kChunkWindow + B + (S + kChunkMaxSent - 1) / kChunkMaxSent);
+  w.nrb_max = (int32_t)((S + kRowBlock - 1) / kRowBlock + B);
+  w.rows = rl.rows;
+  size_t off = 0;
+  char *p = static_cast<char *>(base);
+  auto take = [&](size_t bytes) {
+    void *r = p ? p + off : nullptr;
+    off += align_up(bytes);
+    return r;
+  };
+  w.hdr = static_cast<PlanHeader *>(take(sizeof(PlanHeader)));
+  w.chunk_base = static_cast<int32_t *>(take(B * 4));
+  w.chunk_cnt = static_cast<int32_t *>(take(B * 4));
+  w.rb_base = static_cast<int32_t *>(take(B * 4));
+  w.rb_cnt = static_cast<int32_t *>(take(B * 4));
+  w.chunks = static_cast<Chunk *>(take((size_t)w.nc_max * sizeof(Chunk)));
+  w.rowblocks = static_cast<RowBlock *>(take((size_t)w.nrb_max * sizeof(RowBlock)));
+  w.stat_part = static_cast<float2 *>(take(LH * w.nc_max * rl.rows * sizeof(float2)));
+  w.row_norm = static_cast<float *>(take(LH * B * rl.rows * sizeof(float)));
+  w.vhat_hi = static_cast<uint16_t *>(take(LH * S * kD * 2));
+  w.vhat_lo = static_cast<uint16_t *>(take(LH * S * kD * 2));
+  w.sent_imp = static_cast<float *>(take(LH * S * 4));
+  w.sent_red = static_cast<float *>(take(LH * S * 4));
+  w.bytes = off;
+  return w;
+}
+
+struct Timer {
+  Profile *p;
+  hipStream_t st;
+  Timer(void *prof, hipStream_t s) : p(static_cast<Profile *>(prof)), st(s) {
+    if (p) p->n = 0;
+  }
+  template <class F>
+  hipError_t run(const char *name, F &&f) {
+    int slot = -1;
+    if (p && p->n < SKIPKV_PROFILE_SLOTS) {
+      slot = p->n++;
+      p->name[slot] = name;
+      (void)hipEventRecord(p->ev[2 * slot], st);
+    }
+    const hipError_t e = f();
+    if (slot >= 0) (void)hipEventRecord(p->ev[2 * slot + 1], st);
+    return e;
+  }
+};
+
+int do_score(Timer &tm, const skipkv_cache *c, const skipkv_params *p, const RowLayout &rl, const void *q_obs,
+             const float *tok_red, float *sent_score, float *sent_lambda, float *tok_imp, void *ws, hipStream_t st) {
+  const Workspace w = carve(c, rl, ws);
+  PlanArgs pa{c->seq_off, c->sent_ptr, c->sent_off, c->batch, w, p->dev_status};
+  if (tm.run("plan", [&] { return launch_plan(pa, st); }) != hipSuccess) return SKIPKV_EHIP;
+  ScanArgs sa{};
+  sa.k = c->k;
+  sa.q = q_obs;
+  sa.stride_layer = c->stride_layer;
+  sa.stride_head = c->stride_head;
+  sa.stride_tok = c->stride_tok;
+  sa.dtype = c->dtype;
+  sa.n_layers = c->n_layers;
+  sa.n_kv_heads = c->n_kv_heads;
+  sa.n_q_heads = c->n_q_heads;
+  sa.batch = c->batch;
+  sa.total_tokens = c->total_tokens;
+  sa.total_sentences = c->total_sentences;
+  sa.alpha = p->obs_window;
+  sa.protect = p->protect_window;
+  sa.seq_off = c->seq_off;
+  sa.sent_ptr = c->sent_ptr;
+  sa.sent_off = c->sent_off;
+  sa.tok_red = tok_red;
+  sa.tok_imp = tok_imp;
+  sa.ws = w;
+  sa.rl = rl;
+  if (tm.run("scan_stats", [&] { return launch_scan_stats(sa, st); }) != hipSuccess) return SKIPKV_EHIP;
+  if (tm.run("row_norm", [&] { return launch_row_norm(sa, st); }) != hipSuccess) return SKIPKV_EHIP;
+  if (tm.run("scan_scores", [&] { return launch_scan_scores(sa, st); }) != hipSuccess) return SKIPKV_EHIP;
+  CosineArgs ca{};
+  ca.n_lh = c->n_layers * c->n_kv_heads;
+  ca.batch = c->batch;
+  ca.total_sentences = c->total_sentences;
+  ca.protect = p->protect_window;
+  ca.sigma = p->sigma;
+  ca.tau = p->tau;
+  ca.has_red = tok_red != nullptr;
+  ca.seq_off = c->seq_off;
+  ca.sent_ptr = c->sent_ptr;
+  ca.sent_off = c->sent_off;
+  ca.ws = w;
+  ca.sent_score = sent_score;
+  ca.sent_lambda = sent_lambda;
+  if (tm.run("redundancy", [&] { return launch_cosine(ca, st); }) != hipSuccess) return SKIPKV_EHIP;
+  return SKIPKV_OK;
+}
+
+int do_select(Timer &tm, const skipkv_cache *c, const skipkv_params *p, const float *sent_score, uint8_t *sent_keep,
+              int32_t *kept_idx, int32_t *new_len, int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride,
+              hipStream_t st) {
+  SelectArgs a{};
+  a.n_lh = c->n_layers * c->n_kv_heads;
+  a.batch = c->batch;
+  a.total_sentences = c->total_sentences;
+  a.protect = p->protect_window;
+  a.budget_scalar = p->budget_scalar;
+  a.kept_stride = kept_stride;
+  a.budget = p->budget;
+  a.seq_off = c->seq_off;
+  a.sent_ptr = c->sent_ptr;
+  a.sent_off = c->sent_off;
+  a.sent_score = sent_score;
+  a.sent_keep = sent_keep;
+  a.kept_idx = kept_idx;
+  a.new_len = new_len;
+  a.new_sent_off = new_sent_off;
+  a.new_sent_cnt = new_sent_cnt;
+  a.dev_status = p->dev_status;
+  if (tm.run("select", [&] { return launch_select(a, st); }) != hipSuccess) return SKIPKV_EHIP;
+  return SKIPKV_OK;
+}
+
+int do_compact(Timer &tm, const skipkv_cache *c, const int32_t *kept_idx, const int32_t *new_len, int32_t kept_stride,
+               hipStream_t st) {
+  CompactArgs a{};
+  a.k = c->k;
+  a.v = c->v;
+  a.stride_layer = c->stride_layer;
+  a.stride_head = c->stride_head;
+  a.stride_tok = c->stride_tok;
+  a.dtype = c->dtype;
+  a.n_layers = c->n_layers;
+  a.n_kv_heads = c->n_kv_heads;
+  a.batch = c->batch;
+  a.kept_stride = kept_stride;
+  a.seq_off = c->seq_off;
+  a.kept_idx = kept_idx;
+  a.new_len = new_len;
+  if (tm.run("compact", [&] { return launch_compact(a, st); }) != hipSuccess) return SKIPKV_EHIP;
+  return SKIPKV_OK;
+}
+
+bool is_empty(const skipkv_cache *c) { return c->n_layers == 0 || c->n_kv_heads == 0 || c->batch == 0; }
+
+int check_score_args(const skipkv_cache *c, const skipkv_params *p, RowLayout *rl, const void *q_obs, float *sent_score,
+                     float *sent_lambda, void *ws, size_t ws_bytes) {
+  int rc = check_cache(c, true);
+  if (rc) return rc;
+  rc = check_params(c, p, rl);
+  if (rc) return rc;
+  if (is_empty(c)) return SKIPKV_OK;
+  if (!q_obs || !aligned16(q_obs)) return SKIPKV_EINVAL;
+  if (c->total_sentences > 0 && (!sent_score || !sent_lambda)) return SKIPKV_EINVAL;
+  const Workspace w = carve(c, *rl, nullptr);
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < w.bytes) return SKIPKV_EWORKSPACE;
+  return SKIPKV_OK;
+}
+
+int check_select_args(const skipkv_cache *c, const skipkv_params *p, RowLayout *rl, const float *sent_score,
+                      int32_t *kept_idx, int32_t *new_len, int32_t *new_sent_off, int32_t *new_sent_cnt,
+                      int32_t kept_stride) {
+  int rc = check_cache(c, true);
+  if (rc) return rc;
+  rc = check_params(c, p, rl);
+  if (rc) return rc;
+  if (is_empty(c)) return SKIPKV_OK;
+  if (!new_len || (c->total_sentences > 0 && !sent_score)) return SKIPKV_EINVAL;
+  if ((new_sent_off == nullptr) != (new_sent_cnt == nullptr)) return SKIPKV_EINVAL;
+  const int32_t need = p->max_budget < c->total_tokens ? p->max_budget : c->total_tokens;
+  if (kept_stride < need || (need > 0 && !kept_idx)) return SKIPKV_EINVAL;
+  return SKIPKV_OK;
+}
+
+}  // namespace
+}  // namespace skipkv
+
+using namespace skipkv;
+
+extern "C" {
+
+int skipkv_workspace_bytes(const skipkv_cache *cache, const skipkv_params *params, size_t *out_bytes) {
+  if (!out_bytes) return SKIPKV_EINVAL;
+  int rc = check_cache(cache, true);
+  if (rc) return rc;
+  RowLayout rl;
+  rc = check_params(cache, params, &rl);
+  if (rc) return rc;
+  *out_bytes = carve(cache, rl, nullptr).bytes;
+  return SKIPKV_OK;
+}
+
+int skipkv_score(const skipkv_cache *cache, const skipkv_params *params, const void *q_obs,
+                 const float *tok_redundancy, float *sent_score, float *sent_lambda, float *tok_importance,
+                 void *ws, size_t ws_bytes, void *stream) {
+  RowLayout rl;
+  const int rc = check_score_args(cache, params, &rl, q_obs, sent_score, sent_lambda, ws, ws_bytes);
+  if (rc) return rc;
+  if (is_empty(cache)) return SKIPKV_OK;
+  Timer tm(params->profile, static_cast<hipStream_t>(stream));
+  return do_score(tm, cache, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, ws,
+                  static_cast<hipStream_t>(stream));
+}
+
+int skipkv_select(const skipkv_cache *cache, const skipkv_params *params, const float *sent_score,
+                  uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len, int32_t *new_sent_off,
+                  int32_t *new_sent_cnt, int32_t kept_stride, void *stream) {
+  RowLayout rl;
+  const int rc = check_select_args(cache, params, &rl, sent_score, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride);
+  if (rc) return rc;
+  if (is_empty(cache)) return SKIPKV_OK;
+  Timer tm(params->profile, static_cast<hipStream_t>(stream));
+  return do_select(tm, cache, params, sent_score, sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride,
+                   static_cast<hipStream_t>(stream));
+}
+
+int skipkv_compact(const skipkv_cache *cache, const int32_t *kept_idx, const int32_t *new_len, int32_t kept_stride,
+                   void *stream) {
+  const int rc = check_cache(cache, false);
+  if (rc) return rc;
+  if (is_empty(cache)) return SKIPKV_OK;
+  if (!new_len || kept_stride < 0 || (!kept_idx && cache->total_tokens > 0)) return SKIPKV_EINVAL;
+  Timer tm(nullptr, static_cast<hipStream_t>(stream));
+  return do_compact(tm, cache, kept_idx, new_len, kept_stride, static_cast<hipStream_t>(stream));
+}
+
+int skipkv_step(const skipkv_cache *cache, const skipkv_params *params, const void *q_obs,
+                const float *tok_redundancy, float *sent_score, float *sent_lambda, float *tok_importance,
+                uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len, int32_t *new_sent_off,
+                int32_t *new_sent_cnt, int32_t kept_stride, void *ws, size_t ws_bytes, void *stream) {
+  RowLayout rl;
+  int rc = check_score_args(cache, params, &rl, q_obs, sent_score, sent_lambda, ws, ws_bytes);
+  if (rc) return rc;
+  rc = check_select_args(cache, params, &rl, sent_score, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride);
+  if (rc) return rc;
+  if (is_empty(cache)) return SKIPKV_OK;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Timer tm(params->profile, st);
+  rc = do_score(tm, cache, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, ws, st);
+  if (rc) return rc;
+  rc = do_select(tm, cache, params, sent_score, sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride, st);
+  if (rc) return rc;
+  return do_compact(tm, cache, kept_idx, new_len, kept_stride, st);
+}
+
+int skipkv_steer_add(void *hidden, const void *vec, const float *coef, float coef_scalar, const uint8_t *row_mask,
+                     int32_t rows, int32_t d_model, int32_t dtype, void *stream) {
+  if (rows < 0 || d_model < 0) return SKIPKV_EINVAL;
+  if (dtype != SKIPKV_F32 && dtype != SKIPKV_BF16) return SKIPKV_EINVAL;
+  if (rows == 0 || d_model == 0) return SKIPKV_OK;
+  if (!hidden || !vec) return SKIPKV_EINVAL;
+  if (rows > 65535) return SKIPKV_ECAPACITY;
+  SteerArgs a{hidden, vec, coef, coef_scalar, row_mask, rows, d_model, dtype};
+  return launch_steer(a, static_cast<hipStream_t>(stream)) == hipSuccess ? SKIPKV_OK : SKIPKV_EHIP;
+}
+
+int skipkv_profile_create(void **out_profile) {
+  if (!out_profile) return SKIPKV_EINVAL;
+  Profile *p = new (std::nothrow) Profile();
+  if (!p) return SKIPKV_EINVAL;
+  p->n = 0;
+  for (int i = 0; i < 2 * SKIPKV_PROFILE_SLOTS; ++i) {
+    if (hipEventCreate(&p->ev[i]) != hipSuccess) {
+      for (int j = 0; j < i; ++j) (void)hipEventDestroy(p->ev[j]);
+      delete p;
+      return SKIPKV_EHIP;
+    }
+  }
+  *out_profile = p;
+  return SKIPKV_OK;
+}
+
+int skipkv_profile_read(void *profile, int32_t *n, const char **names, float *ms) {
+  if (!profile || !n) return SKIPKV_EINVAL;
+  Profile *p = static_cast<Profile *>(profile);
+  *n = p->n;
+  for (int i = 0; i < p->n; ++i) {
+    if (hipEventSynchronize(p->ev[2 * i + 1]) != hipSuccess) return SKIPKV_EHIP;
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, p->ev[2 * i], p->ev[2 * i + 1]) != hipSuccess) return SKIPKV_EHIP;
+    if (names) names[i] = p->name[i];
+    if (ms) ms[i] = t;
+  }
+  return SKIPKV_OK;
+}
+
+int skipkv_profile_destroy(void *profile) {
+  if (!profile) return SKIPKV_EINVAL;
+  Profile *p = static_cast<Profile *>(profile);
+  for (int i = 0; i < 2 * SKIPKV_PROFILE_SLOTS; ++i) (void)hipEventDestroy(p->ev[i]);
+  delete p;
+  return SKIPKV_OK;
+}
+
+const char *skipkv_strerror(int status) {
+  switch (status) {
+    case SKIPKV_OK: return "ok";
+    case SKIPKV_EINVAL: return "invalid argument (null pointer, shape, stride, alignment or dtype)";
+    case SKIPKV_EBUDGET: return "budget smaller than the protected window, or observation window larger than the protected window";
+    case SKIPKV_ECAPACITY: return "shape outside the limits this build supports";
+    case SKIPKV_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case SKIPKV_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int skipkv_version(void) { return SKIPKV_VERSION; }
+
+}  // extern "C"

@@ -1,0 +1,191 @@
+// Shared definitions of the libskipkv kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "skipkv.h"
+
+namespace skipkv {
+
+constexpr int kD = SKIPKV_HEAD_DIM;  // head dimension
+constexpr int kChunkWindow = 256;    // a chunk of scan work = the sentences that START in one window of this many tokens
+constexpr int kChunkMaxSent = 32;    // ... split further so that no chunk has more sentences than this
+constexpr int kRowBlock = 64;        // sentences per row block of the redundancy kernel
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+// One unit of scan work: sentences [s0, s1) of sequence b (s0 == s1: empty).
+struct Chunk {
+  int32_t b, s0, s1, pad;
+};
+// One unit of redundancy work: rows [r0, r0 + kRowBlock) of sequence b.
+struct RowBlock {
+  int32_t b, r0;
+};
+
+// Device scalars at the head of the workspace.
+struct PlanHeader {
+  int32_t n_chunks;
+  int32_t n_rowblocks;
+  int32_t pad[62];
+};
+
+// Carved-up view of the caller's workspace.  All sections 256-byte aligned.
+struct Workspace {
+  PlanHeader *hdr;
+  int32_t *chunk_base;   // [B] first chunk of each sequence (ranges are handed out by an atomic counter)
+  int32_t *chunk_cnt;    // [B] number of chunks of each sequence
+  int32_t *rb_base;      // [B] first row block of each sequence
+  int32_t *rb_cnt;       // [B]
+  Chunk *chunks;         // [nc_max]
+  RowBlock *rowblocks;   // [nrb_max]
+  float2 *stat_part;     // [LH, nc_max, R]  per-chunk (max, sum) of every query row, log2 domain
+  float *row_norm;       // [LH, B, R]       log2 of the softmax normaliser of every query row
+  uint16_t *vhat_hi;     // [LH, S_total, 128] bf16 high part of the unit sentence embedding
+  uint16_t *vhat_lo;     // [LH, S_total, 128] bf16 low part (residual)
+  float *sent_imp;       // [LH, S_total]    mean token importance over the candidate span
+  float *sent_red;       // [LH, S_total]    mean token redundancy over the candidate span
+  int32_t nc_max, nrb_max, rows;  // rows = R, padded query rows per head
+  size_t bytes;
+};
+
+// How the n*alpha query rows of a head are laid over MFMA row tiles.
+// Lane group g = lane/16 of a 16x16 tile owns output rows 4g..4g+3 of every row tile; we give
+// it the window queries a = g, g+4, g+8, ... and, for each, the NP (>= n) heads of the group,
+// so that the max over the group's heads is a max over registers of one lane.
+struct RowLayout {
+  int np;    // padded group size
+  int al;    // window queries per lane group = ceil(alpha / 4)
+  int nt;    // row tiles of 16 rows
+  int rows;  // nt * 16
+};
+
+inline bool make_row_layout(int n, int alpha, RowLayout *out) {
+  // the scan kernels are instantiated for NP in {4, 8} x AL in {2, 4, 8}, plus the exact
+  // shapes (NP, AL) = (5, 8) and (7, 2) of the two Qwen-distill configurations
+  int al = alpha <= 8 ? 2 : (alpha <= 16 ? 4 : 8);
+  int np = n <= 4 ? 4 : ((n == 5 && al == 8) ? 5 : ((n == 7 && al == 2) ? 7 : 8));
+  if (n < 1 || n > SKIPKV_MAX_GROUP || alpha < 1 || alpha > SKIPKV_MAX_OBS_WINDOW) return false;
+  out->np = np;
+  out->al = al;
+  out->nt = (np * al + 3) / 4;
+  out->rows = out->nt * 16;
+  return true;
+}
+
+struct Profile;  // api.hip
+
+// ---- kernel launchers (one per .hip file) -------------------------------------------------
+struct PlanArgs {
+  const int32_t *seq_off, *sent_ptr, *sent_off;
+  int32_t batch;
+  Workspace ws;
+  int32_t *dev_status;
+};
+hipError_t launch_plan(const PlanArgs &a, hipStream_t st);
+
+struct ScanArgs {
+  const void *k;
+  const void *q;
+  int64_t stride_layer, stride_head, stride_tok;
+  int32_t dtype, n_layers, n_kv_heads, n_q_heads, batch, total_tokens, total_sentences;
+  int32_t alpha, protect;
+  const int32_t *seq_off, *sent_ptr, *sent_off;
+  const float *tok_red;  // nullable
+  float *tok_imp;        // nullable
+  Workspace ws;
+  RowLayout rl;
+};
+hipError_t launch_scan_stats(const ScanArgs &a, hipStream_t st);    // pass A: row statistics + sentence embeddings
+hipError_t launch_row_norm(const ScanArgs &a, hipStream_t st);      // combine the per-chunk statistics
+hipError_t launch_scan_scores(const ScanArgs &a, hipStream_t st);   // pass B: token importance, sentence means
+
+struct CosineArgs {
+  int32_t n_lh, batch, total_sentences, protect;
+  float sigma, tau;
+  bool has_red;
+  const int32_t *seq_off, *sent_ptr, *sent_off;
+  Workspace ws;
+  float *sent_score, *sent_lambda;
+};
+hipError_t launch_cosine(const CosineArgs &a, hipStream_t st);
+
+struct SelectArgs {
+  int32_t n_lh, batch, total_sentences, protect, budget_scalar, kept_stride;
+  const int32_t *budget;
+  const int32_t *seq_off, *sent_ptr, *sent_off;
+  const float *sent_score;
+  uint8_t *sent_keep;
+  int32_t *kept_idx, *new_len, *new_sent_off, *new_sent_cnt;
+  int32_t *dev_status;
+};
+hipError_t launch_select(const SelectArgs &a, hipStream_t st);
+
+struct CompactArgs {
+  void *k, *v;
+  int64_t stride_layer, stride_head, stride_tok;
+  int32_t dtype, n_layers, n_kv_heads, batch, kept_stride;
+  const int32_t *seq_off, *kept_idx, *new_len;
+};
+hipError_t launch_compact(const CompactArgs &a, hipStream_t st);
+
+struct SteerArgs {
+  void *hidden;
+  const void *vec;
+  const float *coef;
+  float coef_scalar;
+  const uint8_t *row_mask;
+  int32_t rows, d_model, dtype;
+};
+hipError_t launch_steer(const SteerArgs &a, hipStream_t st);
+
+// ---- device helpers -----------------------------------------------------------------------
+#if defined(__HIPCC__)
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+// Rotate within each row of 16 lanes by N lanes (DPP row_ror).
+template <int N>
+__device__ __forceinline__ float row_ror(float v) {
+  return __builtin_amdgcn_update_dpp(0.f, v, 0x120 + N, 0xf, 0xf, false);
+}
+// All 16 lanes of a row end up with the sum / max over the row.
+__device__ __forceinline__ float row16_sum(float v) {
+  v += row_ror<8>(v);
+  v += row_ror<4>(v);
+  v += row_ror<2>(v);
+  v += row_ror<1>(v);
+  return v;
+}
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, row_ror<8>(v));
+  v = fmaxf(v, row_ror<4>(v));
+  v = fmaxf(v, row_ror<2>(v));
+  v = fmaxf(v, row_ror<1>(v));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+  v = row16_sum(v);
+  v += __shfl_xor(v, 16);
+  v += __shfl_xor(v, 32);
+  return v;
+}
+
+// Blocks are dealt round-robin to the 8 XCDs, each with its own L2.  Remap the block index so
+// that every XCD works on one contiguous range of work items (neighbouring items share the
+// head's queries and sentence offsets).
+__device__ __forceinline__ uint32_t xcd_contiguous_item(uint32_t block, uint32_t n_blocks) {
+  const uint32_t per = (n_blocks + 7u) / 8u;
+  return (block % 8u) * per + block / 8u;
+}
+#endif
+
+}  // namespace skipkv

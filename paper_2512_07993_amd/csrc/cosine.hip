@@ -1,0 +1,118 @@
+// Sentence-by-sentence redundancy (Sec. 4.1 "Sentence Similarity Score", Eq. 1 and Eq. 3) and
+// the fused per-sentence score (Eq. 6).
+//
+// Per head the unit sentence embeddings form an S x 128 matrix; lambda_s is the row maximum of
+// the strictly upper triangle of its Gram matrix.  The Gram tiles run on the bf16 matrix cores;
+// to keep fp32-grade cosines (the ranking among near-duplicates depends on differences of
+// ~1e-3) each embedding is carried as bf16 hi + bf16 lo and a tile is hi*hi + hi*lo + lo*hi.
+// One workgroup owns 64 rows (16 per wave, A operands in registers) and walks the column
+// blocks at and to the right of the diagonal, staged through LDS and shared by the 4 waves.
+#include "common.h"
+
+namespace skipkv {
+
+namespace {
+
+constexpr int LSTR = 272;  // bytes per staged embedding row (256 + 16 so that 16-byte reads of 8 rows hit distinct banks)
+
+__global__ void __launch_bounds__(256) k_cosine(CosineArgs a) {
+  __shared__ __align__(16) char col_hi[kRowBlock * LSTR];
+  __shared__ __align__(16) char col_lo[kRowBlock * LSTR];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, c16 = lane & 15, g = lane >> 4;
+  const uint32_t item = xcd_contiguous_item(blockIdx.x, gridDim.x);
+  if (item >= (uint32_t)a.n_lh * (uint32_t)a.ws.nrb_max) return;
+  const int lh = item / a.ws.nrb_max, rb = item % a.ws.nrb_max;
+  if (rb >= a.ws.hdr->n_rowblocks) return;
+  const RowBlock blk = a.ws.rowblocks[rb];
+  const int b = blk.b, r0 = blk.r0;
+  const int sp = a.sent_ptr[b];
+  const int n_sent = a.sent_ptr[b + 1] - sp - 1;
+  const int64_t col0 = (int64_t)lh * a.total_sentences + (sp - b);
+  const char *hi = reinterpret_cast<const char *>(a.ws.vhat_hi) + col0 * 256;
+  const char *lo = reinterpret_cast<const char *>(a.ws.vhat_lo) + col0 * 256;
+
+  // A operands: this wave's 16 rows, lane (row c16, head-dim slice g)
+  const int rw0 = r0 + 16 * wave;
+  bf16x8 a_hi[4], a_lo[4];
+  {
+    const int row = rw0 + c16;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      uint4 vh = make_uint4(0, 0, 0, 0), vl = make_uint4(0, 0, 0, 0);
+      if (row < n_sent) {
+        vh = *reinterpret_cast<const uint4 *>(hi + (int64_t)row * 256 + g * 64 + kk * 16);
+        vl = *reinterpret_cast<const uint4 *>(lo + (int64_t)row * 256 + g * 64 + kk * 16);
+      }
+      a_hi[kk] = __builtin_bit_cast(bf16x8, vh);
+      a_lo[kk] = __builtin_bit_cast(bf16x8, vl);
+    }
+  }
+  float rmax[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+
+  for (int jb = r0; jb < n_sent; jb += kRowBlock) {
+    // stage columns [jb, jb+64) (hi and lo) in LDS
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int idx = it * 256 + tid, half = idx >> 10, rem = idx & 1023, row = rem >> 4, piece = rem & 15;
+      uint4 val = make_uint4(0, 0, 0, 0);
+      if (jb + row < n_sent) val = *reinterpret_cast<const uint4 *>((half ? lo : hi) + (int64_t)(jb + row) * 256 + piece * 16);
+      *reinterpret_cast<uint4 *>((half ? col_lo : col_hi) + row * LSTR + piece * 16) = val;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) {
+      const int cbase = jb + 16 * ct;
+      if (cbase + 15 <= rw0 || cbase >= n_sent || rw0 >= n_sent) continue;  // nothing right of the diagonal in this tile
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const bf16x8 b_hi = *reinterpret_cast<const bf16x8 *>(col_hi + (16 * ct + c16) * LSTR + g * 64 + kk * 16);
+        const bf16x8 b_lo = *reinterpret_cast<const bf16x8 *>(col_lo + (16 * ct + c16) * LSTR + g * 64 + kk * 16);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo[kk], b_hi, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi[kk], b_lo, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi[kk], b_hi, acc, 0, 0, 0);
+      }
+      const int col = cbase + c16;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int row = rw0 + 4 * g + j;
+        if (col > row && col < n_sent) rmax[j] = fmaxf(rmax[j], acc[j]);
+      }
+    }
+    __syncthreads();
+  }
+
+  // row maxima across the 16 column lanes, then the fused score of Eq. 6
+  const int tok0 = a.seq_off[b];
+  const int n_tok = a.seq_off[b + 1] - tok0;
+  const int p_start = n_tok - min(a.protect, n_tok);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float lam = row16_max(rmax[j]);
+    const int row = rw0 + 4 * g + j;
+    if (c16 == 0 && row < n_sent) {
+      const int64_t o = col0 + row;
+      float score = INFINITY;
+      if (a.sent_off[sp + row] < p_start) {
+        score = a.sigma * a.ws.sent_imp[o];
+        if (a.has_red) score -= (1.f - a.sigma) * a.ws.sent_red[o];
+        if (lam > a.tau) score -= lam;
+      }
+      a.sent_lambda[o] = lam;
+      a.sent_score[o] = score;
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_cosine(const CosineArgs &a, hipStream_t st) {
+  const int64_t items = (int64_t)a.n_lh * a.ws.nrb_max;
+  if (items == 0) return hipSuccess;
+  const int64_t grid = (items + 7) / 8 * 8;
+  hipLaunchKernelGGL(k_cosine, dim3((unsigned)grid), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace skipkv

@@ -1,0 +1,391 @@
+// The key scan of the compression step (Sec. 4.1 "Token Importance Score", Eq. 4, and the
+// sentence embedding of Eq. 2 taken over the head's keys).
+//
+// One workgroup (4 waves) handles one chunk of one head: a run of whole sentences, about
+// kChunkWindow tokens.  Keys stream HBM -> LDS in tiles of TT tokens with 16-byte-per-lane
+// coalesced loads; each wave multiplies its 16*NSUB tokens against all query rows of the GQA
+// group on the matrix cores (16x16 MFMA tiles, fp32 accumulate), so a lane ends up holding, for
+// ONE token, the logits of every (window query a, group head i) pair assigned to its lane group.
+//
+// The softmax of Eq. 4 runs over all N keys of the head, which span many chunks, so it takes
+// two passes over K:
+//   pass A (PASSB = false): per chunk, the running (max, sum of exp) of every query row, and the
+//       mean-pooled, L2-normalised key of every sentence of the chunk (split into bf16 hi + lo);
+//   k_row_norm: merges the per-chunk statistics into log2 of each row's normaliser;
+//   pass B (PASSB = true): recomputes the logits, forms I[t] = (1/alpha) sum_a max_i softmax and
+//       its mean over the unprotected part of every sentence.
+// exp() is evaluated in base 2: logits are scaled by log2(e)/sqrt(d).
+#include "common.h"
+
+namespace skipkv {
+
+namespace {
+
+constexpr float kScale2 = 0.08838834764831845f * 1.4426950408889634f;  // log2(e) / sqrt(128)
+constexpr float kRefInit = -3.0e38f;  // "no key seen yet" reference, finite so that -inf - ref stays -inf
+constexpr float kRescaleSlack = 16.f;  // a lane's reference is refreshed when a logit exceeds it by this much (log2 units)
+
+template <int DT>
+struct Tr;
+template <>
+struct Tr<SKIPKV_BF16> {
+  static constexpr int ESZ = 2, ROWB = 256, LSTR = 272;  // LDS row stride: +16 B so that 16-byte reads of 8 consecutive rows hit distinct banks
+};
+template <>
+struct Tr<SKIPKV_F32> {
+  static constexpr int ESZ = 4, ROWB = 512, LSTR = 528;
+};
+
+// acc[T] += Q[16T.., :] * K[token, :]^T for the lane's token.  Both operands use the same
+// (arbitrary but identical) assignment of head-dim slices to MFMA k-steps: lane group g covers
+// bytes [64g, 64g+64) of a bf16 row over the 4 k-steps, so every lane reads contiguous 16-byte
+// pieces.
+template <int DT, int NT>
+__device__ __forceinline__ void tile_logits(const char *qt, const char *krow, int c16, int g, f32x4 (&acc)[NT]) {
+  constexpr int LSTR = Tr<DT>::LSTR;
+  if constexpr (DT == SKIPKV_BF16) {
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(krow + g * 64 + kk * 16);
+#pragma unroll
+      for (int T = 0; T < NT; ++T) {
+        const bf16x8 afrag = *reinterpret_cast<const bf16x8 *>(qt + (16 * T + c16) * LSTR + g * 64 + kk * 16);
+        acc[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag, acc[T], 0, 0, 0);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const float4 bfrag = *reinterpret_cast<const float4 *>(krow + c * 64 + g * 16);
+#pragma unroll
+      for (int T = 0; T < NT; ++T) {
+        const float4 afrag = *reinterpret_cast<const float4 *>(qt + (16 * T + c16) * LSTR + c * 64 + g * 16);
+        acc[T] = __builtin_amdgcn_mfma_f32_16x16x4f32(afrag.x, bfrag.x, acc[T], 0, 0, 0);
+        acc[T] = __builtin_amdgcn_mfma_f32_16x16x4f32(afrag.y, bfrag.y, acc[T], 0, 0, 0);
+        acc[T] = __builtin_amdgcn_mfma_f32_16x16x4f32(afrag.z, bfrag.z, acc[T], 0, 0, 0);
+        acc[T] = __builtin_amdgcn_mfma_f32_16x16x4f32(afrag.w, bfrag.w, acc[T], 0, 0, 0);
+      }
+    }
+  }
+}
+
+template <int DT, int NP, int AL, int NSUB, bool PASSB>
+__global__ void __launch_bounds__(256) k_scan(ScanArgs a) {
+  constexpr int SL = NP * AL;        // used (a, i) slots per lane group
+  constexpr int NT = (SL + 3) / 4;   // row tiles
+  constexpr int SLP = 4 * NT;        // slots incl. padding
+  constexpr int R = 16 * NT;         // padded query rows
+  constexpr int WT = 16 * NSUB;      // tokens per wave per tile
+  constexpr int TT = 4 * WT;         // tokens per tile
+  constexpr int LSTR = Tr<DT>::LSTR, ROWB = Tr<DT>::ROWB, ESZ = Tr<DT>::ESZ;
+  constexpr int PPR = ROWB / 16;     // 16-byte pieces per row
+  constexpr int LOADS = TT * PPR / 256;
+
+  __shared__ __align__(16) char kt[TT * LSTR];
+  __shared__ __align__(16) char qt[R * LSTR];
+  __shared__ int soff[kChunkMaxSent + 1];
+  // pass A: sentence key sums [kChunkMaxSent][128] then per-wave row statistics [4][R][2]
+  // pass B: token importance of the tile [TT], sentence sums of I and of R [2][kChunkMaxSent]
+  constexpr int SBUF = PASSB ? (TT + 2 * kChunkMaxSent) : (kChunkMaxSent * kD + 8 * R);
+  __shared__ float sbuf[SBUF];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, c16 = lane & 15, g = lane >> 4;
+  const int n_lh = a.n_layers * a.n_kv_heads;
+  const uint32_t item = xcd_contiguous_item(blockIdx.x, gridDim.x);
+  if (item >= (uint32_t)n_lh * (uint32_t)a.ws.nc_max) return;
+  const int lh = item / a.ws.nc_max, c = item % a.ws.nc_max;
+  if (c >= a.ws.hdr->n_chunks) return;
+  const Chunk ch = a.ws.chunks[c];
+  const int b = ch.b, ns = ch.s1 - ch.s0;
+  if (ns <= 0) return;
+  const int l = lh / a.n_kv_heads, h = lh % a.n_kv_heads;
+  const int n = a.n_q_heads / a.n_kv_heads;
+  const int tok0 = a.seq_off[b];
+  const int n_tok = a.seq_off[b + 1] - tok0;
+  const int sent_col0 = a.sent_ptr[b] - b + ch.s0;  // column of the chunk's first sentence in [.., S_total] arrays
+
+  if (tid <= ns) soff[tid] = a.sent_off[a.sent_ptr[b] + ch.s0 + tid];
+  for (int i = tid; i < SBUF; i += 256) sbuf[i] = 0.f;
+
+  // ---- queries of the group -> LDS, one padded row per (lane group, slot)
+  {
+    const char *qbase = static_cast<const char *>(a.q);
+    for (int r0 = 0; r0 < R; r0 += 256 / PPR) {
+      const int r = r0 + tid / PPR, piece = tid % PPR;
+      const int slot = 4 * (r >> 4) + (r & 3), gq = (r >> 2) & 3;
+      const int al = slot / NP, i = slot % NP, aq = gq + 4 * al;
+      uint4 val = make_uint4(0, 0, 0, 0);
+      if (slot < SL && i < n && aq < a.alpha) {
+        const int64_t row = (((int64_t)l * a.batch + b) * a.n_q_heads + (h * n + i)) * a.alpha + aq;
+        val = *reinterpret_cast<const uint4 *>(qbase + row * ROWB + piece * 16);
+      }
+      *reinterpret_cast<uint4 *>(qt + r * LSTR + piece * 16) = val;
+    }
+  }
+  __syncthreads();
+
+  const int t_begin = soff[0], t_end = soff[ns];
+  const char *kbase = static_cast<const char *>(a.k) +
+                      ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head + (int64_t)tok0 * a.stride_tok) * ESZ;
+  const int64_t tok_pitch = a.stride_tok * ESZ;
+  const int last_free = n_tok - a.alpha;  // keys t <= last_free are visible to every window query
+
+  // per-lane state
+  float ref[SLP], lsum[SLP];  // pass A: reference (uniform over the 16 lanes of a row) and sum of exp2(x - ref)
+  float cn[SLP];              // pass B: log2 normaliser of the slot's query row (+inf: unused slot)
+  if constexpr (!PASSB) {
+#pragma unroll
+    for (int q = 0; q < SLP; ++q) {
+      ref[q] = kRefInit;
+      lsum[q] = 0.f;
+    }
+  } else {
+    const float *rn = a.ws.row_norm + ((int64_t)lh * a.batch + b) * R;
+#pragma unroll
+    for (int q = 0; q < SLP; ++q) {
+      const int al = q / NP, i = q % NP;
+      const bool used = q < SL && i < n && (g + 4 * al) < a.alpha;
+      cn[q] = used ? rn[16 * (q >> 2) + 4 * g + (q & 3)] : INFINITY;
+    }
+  }
+  const int p_start = n_tok - min(a.protect, n_tok);  // first protected token
+
+  for (int tile_t = t_begin; tile_t < t_end; tile_t += TT) {
+    // ---- stream the tile into LDS
+    {
+      uint4 regs[LOADS];
+#pragma unroll
+      for (int it = 0; it < LOADS; ++it) {
+        const int idx = it * 256 + tid, row = idx / PPR, piece = idx % PPR, t = tile_t + row;
+        regs[it] = make_uint4(0, 0, 0, 0);
+        if (t < t_end) regs[it] = *reinterpret_cast<const uint4 *>(kbase + (int64_t)t * tok_pitch + piece * 16);
+      }
+#pragma unroll
+      for (int it = 0; it < LOADS; ++it) {
+        const int idx = it * 256 + tid, row = idx / PPR, piece = idx % PPR;
+        *reinterpret_cast<uint4 *>(kt + row * LSTR + piece * 16) = regs[it];
+      }
+    }
+    __syncthreads();
+
+    const int wt0 = tile_t + wave * WT;  // first token of this wave's share
+    f32x4 acc[NSUB][NT];
+#pragma unroll
+    for (int s = 0; s < NSUB; ++s) {
+#pragma unroll
+      for (int T = 0; T < NT; ++T) acc[s][T] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (wt0 + 16 * s < t_end)
+        tile_logits<DT, NT>(qt, kt + (wave * WT + 16 * s + c16) * LSTR, c16, g, acc[s]);
+    }
+
+    if constexpr (!PASSB) {
+      // ---- running softmax statistics of every query row over this wave's tokens
+      float tmax[SLP];
+#pragma unroll
+      for (int q = 0; q < SLP; ++q) tmax[q] = -INFINITY;
+#pragma unroll
+      for (int s = 0; s < NSUB; ++s) {
+        const int t = wt0 + 16 * s + c16;
+        const bool edge = (wt0 + 16 * s + 15 >= t_end) || (wt0 + 16 * s + 15 > last_free);
+#pragma unroll
+        for (int q = 0; q < SLP; ++q) {
+          float x = acc[s][q >> 2][q & 3] * kScale2;
+          if (edge) {
+            const int aq = g + 4 * (q / NP);
+            if (!(t < t_end && t <= last_free + aq)) x = -INFINITY;
+          }
+          acc[s][q >> 2][q & 3] = x;
+          tmax[q] = fmaxf(tmax[q], x);
+        }
+      }
+      bool need = false;
+#pragma unroll
+      for (int q = 0; q < SLP; ++q) need |= tmax[q] > ref[q] + kRescaleSlack;
+      if (__any(need)) {
+#pragma unroll
+        for (int q = 0; q < SLP; ++q) {
+          const float nr = fmaxf(ref[q], row16_max(tmax[q]));
+          lsum[q] *= __builtin_amdgcn_exp2f(ref[q] - nr);
+          ref[q] = nr;
+        }
+      }
+#pragma unroll
+      for (int s = 0; s < NSUB; ++s)
+#pragma unroll
+        for (int q = 0; q < SLP; ++q) lsum[q] += __builtin_amdgcn_exp2f(acc[s][q >> 2][q & 3] - ref[q]);
+
+      // ---- sentence key sums: the wave walks its tokens in order, lane = 2 head-dim columns
+      {
+        int t = wt0;
+        const int t_hi = min(wt0 + WT, t_end);
+        if (t < t_hi) {
+          const bool before = lane < ns && soff[lane + 1] <= t;
+          int si = __popcll(__ballot(before));
+          while (t < t_hi) {
+            const int run_end = min(soff[si + 1], t_hi);
+            float s0 = 0.f, s1 = 0.f;
+            for (; t < run_end; ++t) {
+              const char *rowp = kt + (t - tile_t) * LSTR;
+              if constexpr (DT == SKIPKV_BF16) {
+                const uint32_t w = *reinterpret_cast<const uint32_t *>(rowp + lane * 4);
+                s0 += __uint_as_float(w << 16);
+                s1 += __uint_as_float(w & 0xFFFF0000u);
+              } else {
+                const float2 w = *reinterpret_cast<const float2 *>(rowp + lane * 8);
+                s0 += w.x;
+                s1 += w.y;
+              }
+            }
+            atomicAdd(&sbuf[si * kD + 2 * lane], s0);
+            atomicAdd(&sbuf[si * kD + 2 * lane + 1], s1);
+            ++si;
+          }
+        }
+      }
+    } else {
+      // ---- token importance: max over the group's heads in registers, exp2, sum over window queries
+      float *imp = sbuf;
+#pragma unroll
+      for (int s = 0; s < NSUB; ++s) {
+        const int t = wt0 + 16 * s + c16;
+        const bool edge = (wt0 + 16 * s + 15 > last_free);
+        float sum = 0.f;
+#pragma unroll
+        for (int al = 0; al < AL; ++al) {
+          float gm = -INFINITY;
+#pragma unroll
+          for (int i = 0; i < NP; ++i) {
+            const int q = al * NP + i;
+            gm = fmaxf(gm, fmaf(acc[s][q >> 2][q & 3], kScale2, -cn[q]));
+          }
+          if (edge && t > last_free + g + 4 * al) gm = -INFINITY;
+          sum += __builtin_amdgcn_exp2f(gm);
+        }
+        sum += __shfl_xor(sum, 16);
+        sum += __shfl_xor(sum, 32);
+        if (g == 0) imp[wave * WT + 16 * s + c16] = (t < t_end) ? sum / (float)a.alpha : 0.f;
+      }
+      __syncthreads();
+      // sentence sums over the unprotected part, and the optional per-token outputs / inputs
+      const int64_t tok_col = (int64_t)lh * a.total_tokens + tok0;
+      if (tid < ns) {
+        const int lo = max(soff[tid], tile_t), hi = min(min(soff[tid + 1], p_start), tile_t + TT);
+        float si = 0.f, sr = 0.f;
+        for (int t = lo; t < hi; ++t) {
+          si += imp[t - tile_t];
+          if (a.tok_red) sr += a.tok_red[tok_col + t];
+        }
+        sbuf[TT + tid] += si;
+        sbuf[TT + kChunkMaxSent + tid] += sr;
+      }
+      if (a.tok_imp) {
+        for (int i = tid; i < TT && tile_t + i < t_end; i += 256) a.tok_imp[tok_col + tile_t + i] = imp[i];
+      }
+    }
+    __syncthreads();  // the next tile overwrites kt / imp
+  }
+
+  if constexpr (!PASSB) {
+    // ---- unit sentence embeddings, split into bf16 hi + lo, one wave per sentence
+    for (int si = wave; si < ns; si += 4) {
+      const float inv_len = 1.f / (float)(soff[si + 1] - soff[si]);
+      const float m0 = sbuf[si * kD + 2 * lane] * inv_len, m1 = sbuf[si * kD + 2 * lane + 1] * inv_len;
+      const float nrm = sqrtf(wave_sum(m0 * m0 + m1 * m1));
+      const float inv = 1.f / (nrm + 1e-12f);
+      const float u0 = m0 * inv, u1 = m1 * inv;
+      const uint32_t h0 = f32_to_bf16_bits(u0), h1 = f32_to_bf16_bits(u1);
+      const uint32_t l0 = f32_to_bf16_bits(u0 - bf16_bits_to_f32(h0)), l1 = f32_to_bf16_bits(u1 - bf16_bits_to_f32(h1));
+      const int64_t o = ((int64_t)lh * a.total_sentences + sent_col0 + si) * (kD / 2) + lane;
+      reinterpret_cast<uint32_t *>(a.ws.vhat_hi)[o] = h0 | (h1 << 16);
+      reinterpret_cast<uint32_t *>(a.ws.vhat_lo)[o] = l0 | (l1 << 16);
+    }
+    // ---- merge the row statistics of the 4 waves and publish the chunk's partial
+    float *wstat = sbuf + kChunkMaxSent * kD;
+#pragma unroll
+    for (int q = 0; q < SLP; ++q) {
+      const float tot = row16_sum(lsum[q]);
+      if (c16 == 0) {
+        const int r = 16 * (q >> 2) + 4 * g + (q & 3);
+        wstat[(wave * R + r) * 2] = ref[q];
+        wstat[(wave * R + r) * 2 + 1] = tot;
+      }
+    }
+    __syncthreads();
+    for (int r = tid; r < R; r += 256) {
+      float m = kRefInit;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) m = fmaxf(m, wstat[(w * R + r) * 2]);
+      float s = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) s += wstat[(w * R + r) * 2 + 1] * __builtin_amdgcn_exp2f(wstat[(w * R + r) * 2] - m);
+      a.ws.stat_part[((int64_t)lh * a.ws.nc_max + c) * R + r] = make_float2(m, s);
+    }
+  } else {
+    if (tid < ns) {
+      const int len = min(soff[tid + 1], p_start) - soff[tid];
+      const int64_t o = (int64_t)lh * a.total_sentences + sent_col0 + tid;
+      a.ws.sent_imp[o] = len > 0 ? sbuf[TT + tid] / (float)len : 0.f;
+      a.ws.sent_red[o] = len > 0 ? sbuf[TT + kChunkMaxSent + tid] / (float)len : 0.f;
+    }
+  }
+}
+
+// log2 of the softmax normaliser of every query row: merge the chunk partials of a head.
+__global__ void k_row_norm(ScanArgs a, int R) {
+  const int lhb = blockIdx.x, lh = lhb / a.batch, b = lhb % a.batch;
+  const int c0 = a.ws.chunk_base[b], nc = a.ws.chunk_cnt[b];
+  for (int r = threadIdx.x; r < R; r += blockDim.x) {
+    float m = kRefInit, s = 0.f;
+    for (int c = c0; c < c0 + nc; ++c) {
+      const float2 p = a.ws.stat_part[((int64_t)lh * a.ws.nc_max + c) * R + r];
+      const float nm = fmaxf(m, p.x);
+      s = s * __builtin_amdgcn_exp2f(m - nm) + p.y * __builtin_amdgcn_exp2f(p.x - nm);
+      m = nm;
+    }
+    a.ws.row_norm[(int64_t)lhb * R + r] = s > 0.f ? m + __builtin_amdgcn_logf(s) : INFINITY;
+  }
+}
+
+template <int DT, int NP, int AL, bool PASSB>
+hipError_t launch_one(const ScanArgs &a, hipStream_t st) {
+  constexpr int NT = (NP * AL + 3) / 4;
+  constexpr int NSUB = (DT == SKIPKV_F32) ? 1 : (NT <= 4 ? 2 : 1);
+  const int64_t items = (int64_t)a.n_layers * a.n_kv_heads * a.ws.nc_max;
+  if (items == 0) return hipSuccess;
+  const int64_t grid = (items + 7) / 8 * 8;
+  hipLaunchKernelGGL((k_scan<DT, NP, AL, NSUB, PASSB>), dim3((unsigned)grid), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+template <bool PASSB>
+hipError_t dispatch(const ScanArgs &a, hipStream_t st) {
+#define SKIPKV_CASE(NP_, AL_)                                                       \
+  if (a.rl.np == NP_ && a.rl.al == AL_)                                             \
+    return a.dtype == SKIPKV_BF16 ? launch_one<SKIPKV_BF16, NP_, AL_, PASSB>(a, st) \
+                                  : launch_one<SKIPKV_F32, NP_, AL_, PASSB>(a, st);
+  SKIPKV_CASE(4, 2)
+  SKIPKV_CASE(4, 4)
+  SKIPKV_CASE(4, 8)
+  SKIPKV_CASE(8, 2)
+  SKIPKV_CASE(8, 4)
+  if (a.rl.np == 8 && a.rl.al == 8)  // 256 fp32 query rows do not fit in LDS: bf16 only
+    return a.dtype == SKIPKV_BF16 ? launch_one<SKIPKV_BF16, 8, 8, PASSB>(a, st) : hipErrorInvalidValue;
+  SKIPKV_CASE(5, 8)
+  SKIPKV_CASE(7, 2)
+#undef SKIPKV_CASE
+  return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+hipError_t launch_scan_stats(const ScanArgs &a, hipStream_t st) { return dispatch<false>(a, st); }
+hipError_t launch_scan_scores(const ScanArgs &a, hipStream_t st) { return dispatch<true>(a, st); }
+
+hipError_t launch_row_norm(const ScanArgs &a, hipStream_t st) {
+  const int blocks = a.n_layers * a.n_kv_heads * a.batch;
+  if (blocks == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_row_norm, dim3(blocks), dim3(64), 0, st, a, a.rl.rows);
+  return hipGetLastError();
+}
+
+}  // namespace skipkv
