@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Benchmark of the SkipKV compression step on one MI355X.
+
+A "step" is one pass of the whole hot path (score -> select -> compact, one skipkv_step call)
+over one batch of synthetic input already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3]
+
+Compaction rewrites the cache in place, so every timed step gets its own pristine copy of
+K and V (copied outside the timed region); steps are timed in groups of as many copies as
+were allocated, each group bracketed by torch.cuda.synchronize().
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def _oracle_worker(args):
+    import oracle  # test infrastructure, used here only for the reported CPU baseline
+    from threadpoolctl import threadpool_limits
+    qq, kk, vv, off, budget, protect = args
+    with threadpool_limits(limits=1):
+        t = time.perf_counter()
+        oracle.compress_head(qq, kk, vv, off, budget, protect)
+        return time.perf_counter() - t
+
+
+def cpu_baseline(cfg, st, k0, v0, q, n_heads=320, seed=1):
+    """Times the oracle as it stands on a bounded sample of heads of the same workload."""
+    import multiprocessing as mp
+
+    import numpy as np
+
+    from paper_2512_07993_amd import workloads as W
+    rng = np.random.default_rng(seed)
+    cores = min(os.cpu_count() or 1, 16, n_heads)
+    # heads spanning the length distribution: stratify over sequences sorted by length
+    order = np.argsort(st.seq_len)
+    picks = [int(order[int(i)]) for i in np.linspace(0, len(order) - 1, min(n_heads, len(order)))]
+    while len(picks) < n_heads:
+        picks.append(int(rng.integers(0, cfg.batch)))
+    jobs, tok_heads = [], 0
+    for b in picks:
+        l, h = int(rng.integers(0, cfg.n_layers)), int(rng.integers(0, cfg.n_kv_heads))
+        qq, kk, vv, off = W.head_arrays(cfg, st, k0, v0, q, l, h, b)
+        jobs.append((qq, kk, vv, off, cfg.budget, cfg.protect_window))
+        tok_heads += kk.shape[0]
+    t = time.perf_counter()
+    with mp.get_context("spawn").Pool(cores) as pool:
+        pool.map(_oracle_worker, jobs)
+    wall = time.perf_counter() - t
+    lh = cfg.n_layers * cfg.n_kv_heads
+    return {
+        "value": tok_heads / wall / lh,
+        "unit": "tokens/s",
+        "cores": cores,
+        "kind": "oracle",
+        "sample": "%d heads of the same workload stratified over sequence length (%d token-heads, %.1f s wall), "
+                  "scaled by token-heads to all %d heads" % (n_heads, tok_heads, wall, lh * cfg.batch),
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=3, help="workload: index into BASELINE.json configs (1-based)")
+    ap.add_argument("--copies", type=int, default=5, help="pristine-copy working buffers (HBM: 2 x cache each)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (heads are independent: more GPUs would only shard them); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+
+    import torch
+
+    from paper_2512_07993_amd import binding as B
+    from paper_2512_07993_amd import workloads as W
+
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    cfg = W.CONFIGS[args.config]
+    st = W.make_structure(cfg)
+    k0, v0, q = W.fill_cache(cfg, st, device=dev)
+    L, H, Bn, S, T = cfg.n_layers, cfg.n_kv_heads, cfg.batch, st.total_sentences, st.total_tokens
+    esz = k0.element_size()
+
+    so = torch.from_numpy(st.seq_off).to(dev)
+    sp = torch.from_numpy(st.sent_ptr).to(dev)
+    sf = torch.from_numpy(st.sent_off).to(dev)
+    n_copies = max(1, min(args.copies, max(args.steps, args.warmup)))
+    bufs = [(torch.empty_like(k0), torch.empty_like(v0)) for _ in range(n_copies)]
+    caches = [B.Cache(k, v, cfg.n_q_heads, so, sp, sf, T, S) for (k, v) in bufs]
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    prof = B.skipkv_profile_create()
+    params = B.Params(cfg.obs_window, cfg.protect_window, cfg.budget, dev_status=status, profile=prof)
+    ws = torch.empty(B.skipkv_workspace_bytes(caches[0], params), dtype=torch.uint8, device=dev)
+    kept_stride = min(cfg.budget, T)
+    sent_score = torch.empty((L, H, S), dtype=torch.float32, device=dev)
+    sent_lambda = torch.empty_like(sent_score)
+    sent_keep = torch.empty((L, H, S), dtype=torch.uint8, device=dev)
+    kept_idx = torch.empty((L, H, Bn, kept_stride), dtype=torch.int32, device=dev)
+    new_len = torch.empty((L, H, Bn), dtype=torch.int32, device=dev)
+
+    def restore(n):
+        for i in range(n):
+            bufs[i][0].copy_(k0)
+            bufs[i][1].copy_(v0)
+
+    def step(i):
+        B.skipkv_step(caches[i], params, q, None, sent_score, sent_lambda, None, sent_keep, kept_idx, new_len,
+                      None, None, kept_stride, ws)
+
+    def run_group(n, timed):
+        restore(n)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        per_kernel = {}
+        total = 0.0
+        for i in range(n):
+            e0.record()
+            step(i)
+            e1.record()
+            torch.cuda.synchronize()
+            if timed:
+                total += e0.elapsed_time(e1)
+                for name, ms in B.skipkv_profile_read(prof):
+                    per_kernel.setdefault(name, []).append(ms)
+        return total, per_kernel
+
+    done = 0
+    while done < args.warmup:
+        n = min(n_copies, args.warmup - done)
+        run_group(n, False)
+        done += n
+    total_ms, kernels = 0.0, {}
+    done = 0
+    while done < args.steps:
+        n = min(n_copies, args.steps - done)
+        t, pk = run_group(n, True)
+        total_ms += t
+        for name, v in pk.items():
+            kernels.setdefault(name, []).extend(v)
+        done += n
+    assert int(status.item()) == 0, "device status %d" % int(status.item())
+    ms_per_step = total_ms / args.steps
+
+    # ---- algorithmic bytes of one step (what the method must move, not what the kernels do)
+    ar = torch.arange(kept_stride, device=dev, dtype=torch.int32)
+    valid = ar[None, None, None, :] < new_len[..., None]
+    moved_rows = int(((kept_idx != ar) & valid).sum().item())
+    k_scan_bytes = L * H * T * 128 * esz
+    q_bytes = q.numel() * esz
+    off_bytes = L * H * (S + Bn) * 4
+    move_bytes = 4 * moved_rows * 128 * esz   # K and V rows that change place: read + write
+    step_bytes = k_scan_bytes + move_bytes + q_bytes + off_bytes
+    kernel_bytes = {
+        "scan_stats": k_scan_bytes + q_bytes + off_bytes,
+        "scan_scores": k_scan_bytes + q_bytes + off_bytes,
+        "compact": move_bytes,
+    }
+    avg = {name: sum(v) / len(v) for name, v in kernels.items()}
+    dominant = max((n for n in avg if n in kernel_bytes), key=lambda n: avg[n])
+    achieved = kernel_bytes[dominant] / (avg[dominant] * 1e-3) / 1e9
+    result = {
+        "metric": "compressed KV tokens/sec per compression step; achieved HBM GB/s vs peak",
+        "value": T / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {
+            "workload": "config %d: %s" % (cfg.config_id, cfg.name),
+            "batch": Bn, "layers": L, "kv_heads": H, "q_heads": cfg.n_q_heads, "head_dim": 128,
+            "tokens": T, "sentences": S, "budget": cfg.budget, "obs_window": cfg.obs_window,
+            "protect_window": cfg.protect_window, "heads": L * H * Bn,
+            "token_heads_per_s": T * L * H / (ms_per_step * 1e-3),
+            "kept_tokens_mean": float(new_len.float().mean().item()),
+            "moved_rows": moved_rows,
+        },
+        "step_algorithmic_bytes": step_bytes,
+        "step_algorithmic_gbps": step_bytes / (ms_per_step * 1e-3) / 1e9,
+        "step_frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "kernel_ms": {n: round(t, 4) for n, t in avg.items()},
+        "roofline": {
+            "kernel": dominant, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+            "algorithmic_bytes_per_launch": kernel_bytes[dominant],
+        },
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, st, k0, v0, q)
+    B.skipkv_profile_destroy(prof)
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
