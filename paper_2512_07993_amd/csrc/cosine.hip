@@ -4,7 +4,8 @@
 // Per head the unit sentence embeddings form an S x 128 matrix; lambda_s is the row maximum of
 // the strictly upper triangle of its Gram matrix.  The Gram tiles run on the bf16 matrix cores;
 // to keep fp32-grade cosines (the ranking among near-duplicates depends on differences of
-// ~1e-3) each embedding is carried as bf16 hi + bf16 lo and a tile is hi*hi + hi*lo + lo*hi.
+// ~1e-3) each embedding is carried as bf16 hi + bf16 lo and a tile is the full product
+// (hi + lo)(hi + lo)^T: four bf16 MFMAs, small terms accumulated first.
 // One workgroup owns 64 rows (16 per wave, A operands in registers) and walks the column
 // blocks at and to the right of the diagonal, staged through LDS and shared by the 4 waves.
 #include "common.h"
@@ -69,6 +70,7 @@ __global__ void __launch_bounds__(256) k_cosine(CosineArgs a) {
       for (int kk = 0; kk < 4; ++kk) {
         const bf16x8 b_hi = *reinterpret_cast<const bf16x8 *>(col_hi + (16 * ct + c16) * LSTR + g * 64 + kk * 16);
         const bf16x8 b_lo = *reinterpret_cast<const bf16x8 *>(col_lo + (16 * ct + c16) * LSTR + g * 64 + kk * 16);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo[kk], b_lo, acc, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo[kk], b_hi, acc, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi[kk], b_lo, acc, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi[kk], b_hi, acc, 0, 0, 0);

@@ -1,0 +1,127 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared symbol, and
+rejects bad arguments on the host before anything touches a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2512_07993_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _built():
+    if not os.path.exists(B._LIB_PATH):
+        from paper_2512_07993_amd.build import build_library
+        build_library()
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "skipkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(skipkv_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared()
+    assert {"skipkv_score", "skipkv_select", "skipkv_compact", "skipkv_steer_add", "skipkv_step",
+            "skipkv_workspace_bytes", "skipkv_strerror", "skipkv_version"} <= set(names)
+    lib = B.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+    assert B.skipkv_version() == 100
+    for code in (0, -1, -2, -3, -4, -5, -99):
+        assert len(B.skipkv_strerror(code)) > 0
+
+
+def _cache(**kw):
+    d = dict(k=0x1000, v=0x2000, stride_layer=8 * 4096 * 128, stride_head=4096 * 128, stride_tok=128, dtype=B.BF16,
+             n_layers=2, n_kv_heads=8, n_q_heads=32, head_dim=128, batch=1, total_tokens=4096, total_sentences=200,
+             seq_off=0x3000, sent_ptr=0x4000, sent_off=0x5000)
+    d.update(kw)
+    return B.CCache(*[d[f[0]] for f in B.CCache._fields_])
+
+
+def _params(**kw):
+    d = dict(obs_window=16, protect_window=64, sigma=0.1, tau=0.95, budget=None, budget_scalar=2048, max_budget=2048,
+             dev_status=None, profile=None)
+    d.update(kw)
+    return B.CParams(*[d[f[0]] for f in B.CParams._fields_])
+
+
+def _ws_bytes(cache, params):
+    out = C.c_size_t(0)
+    return B.lib().skipkv_workspace_bytes(C.byref(cache), C.byref(params), C.byref(out)), out.value
+
+
+def test_workspace_size_is_computed_on_the_host():
+    rc, n = _ws_bytes(_cache(), _params())
+    assert rc == B.OK and n > 2 * 16 * 200 * 128 * 2 and n % 256 == 0
+    rc2, n2 = _ws_bytes(_cache(total_tokens=8192), _params())
+    assert rc2 == B.OK and n2 > n
+
+
+@pytest.mark.parametrize("ckw,pkw,expect", [
+    (dict(head_dim=64), {}, B.ECAPACITY),
+    (dict(dtype=7), {}, B.EINVAL),
+    (dict(k=None), {}, B.EINVAL),
+    (dict(k=0x1004), {}, B.EINVAL),                       # not 16-byte aligned
+    (dict(stride_tok=64), {}, B.EINVAL),
+    (dict(stride_tok=132), {}, B.EINVAL),                 # rows would lose 16-byte alignment
+    (dict(n_q_heads=30), {}, B.EINVAL),                   # not a multiple of the KV heads
+    (dict(n_q_heads=8 * 9), {}, B.ECAPACITY),             # group larger than supported
+    (dict(seq_off=None), {}, B.EINVAL),
+    (dict(sent_off=None), {}, B.EINVAL),
+    ({}, dict(obs_window=0), B.EINVAL),
+    ({}, dict(obs_window=64, protect_window=32), B.EBUDGET),
+    ({}, dict(budget_scalar=32), B.EBUDGET),              # budget < protected window
+    ({}, dict(obs_window=33, protect_window=64), B.ECAPACITY),
+    ({}, dict(sigma=1.5), B.EINVAL),
+])
+def test_validation_errors(ckw, pkw, expect):
+    rc, _ = _ws_bytes(_cache(**ckw), _params(**pkw))
+    assert rc == expect
+
+
+def test_score_rejects_missing_or_small_workspace_and_null_outputs():
+    lib, cache, params = B.lib(), _cache(), _params()
+    rc, need = _ws_bytes(cache, params)
+    assert rc == B.OK
+    args = lambda ws, n, score=0x7000: (C.byref(cache), C.byref(params), 0x6000, None, score, 0x8000, None, ws, n, None)
+    assert lib.skipkv_score(*args(None, need)) == B.EWORKSPACE
+    assert lib.skipkv_score(*args(0x10000, need - 1)) == B.EWORKSPACE
+    assert lib.skipkv_score(*args(0x10010, need)) == B.EWORKSPACE     # not 256-byte aligned
+    assert lib.skipkv_score(*args(0x10000, need, score=None)) == B.EINVAL
+    assert lib.skipkv_score(C.byref(cache), C.byref(params), None, None, 0x7000, 0x8000, None, 0x10000, need, None) == B.EINVAL
+
+
+def test_select_and_compact_reject_bad_arguments():
+    lib, cache, params = B.lib(), _cache(), _params()
+    sel = lambda **kw: lib.skipkv_select(C.byref(cache), C.byref(params), kw.get("score", 0x7000), None,
+                                         kw.get("kept", 0x9000), kw.get("new_len", 0xA000), kw.get("noff"),
+                                         kw.get("ncnt"), kw.get("stride", 2048), None)
+    assert sel(stride=100) == B.EINVAL                    # kept_idx rows shorter than the budget
+    assert sel(new_len=None) == B.EINVAL
+    assert sel(noff=0xB000) == B.EINVAL                   # offsets without counts
+    assert lib.skipkv_compact(C.byref(cache), None, 0xA000, 2048, None) == B.EINVAL
+    assert lib.skipkv_compact(C.byref(cache), 0x9000, None, 2048, None) == B.EINVAL
+    assert lib.skipkv_compact(None, 0x9000, 0xA000, 2048, None) == B.EINVAL
+
+
+def test_empty_problems_are_accepted_without_launching():
+    lib = B.lib()
+    cache, params = _cache(batch=0, total_tokens=0, total_sentences=0, k=None, v=None), _params()
+    assert lib.skipkv_score(C.byref(cache), C.byref(params), None, None, None, None, None, None, 0, None) == B.OK
+    assert lib.skipkv_compact(C.byref(cache), None, None, 0, None) == B.OK
+    assert lib.skipkv_steer_add(None, None, None, 1.0, None, 0, 128, B.BF16, None) == B.OK
+    assert lib.skipkv_steer_add(None, None, None, 1.0, None, 4, 128, B.BF16, None) == B.EINVAL
+    assert lib.skipkv_steer_add(0x1000, 0x2000, None, 1.0, None, 4, 128, 9, None) == B.EINVAL
+
+
+def test_binding_refuses_to_run_without_the_library(monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "_LIB_PATH", "/nonexistent/libskipkv.so")
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        B.lib()

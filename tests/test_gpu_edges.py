@@ -1,0 +1,186 @@
+"""GPU parity on the degenerate and ragged cases of the method, and on the optional inputs
+and outputs of the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2512_07993_amd import binding as B
+from paper_2512_07993_amd import workloads as W
+
+from helpers import compare_head, make_cache, oracle_head, run_step
+
+pytestmark = pytest.mark.gpu
+
+
+def _structure(offsets):
+    """Structure from explicit per-sequence sentence offsets."""
+    seq_len = np.asarray([o[-1] for o in offsets], dtype=np.int32)
+    seq_off = np.concatenate([[0], np.cumsum(seq_len)]).astype(np.int32)
+    sent_ptr = np.concatenate([[0], np.cumsum([len(o) for o in offsets])]).astype(np.int32)
+    sent_off = np.concatenate([np.asarray(o, dtype=np.int32) for o in offsets])
+    return W.Structure(seq_len, seq_off, sent_ptr, sent_off, [np.full(len(o) - 1, -1) for o in offsets])
+
+
+def _random_kvq(cfg, st, seed, stride_tok=128):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    dt = W.torch_dtype(cfg)
+    shape = (cfg.n_layers, cfg.n_kv_heads, st.total_tokens, stride_tok)
+    k = torch.randn(shape, generator=g, device="cuda").to(dt)[..., :128]
+    v = torch.randn(shape, generator=g, device="cuda").to(dt)[..., :128]
+    q = torch.randn((cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.obs_window, 128), generator=g, device="cuda").to(dt)
+    return k, v, q
+
+
+def _clone(t):
+    """Clone that preserves strides (a strided cache stays strided)."""
+    out = torch.empty_strided(t.shape, t.stride(), dtype=t.dtype, device=t.device)
+    out.copy_(t)
+    return out
+
+
+def _compare_all(cfg, st, out, k, v, k0, v0, q, budgets=None, red=None, skip_empty=True):
+    stats = {}
+    for l in range(cfg.n_layers):
+        for h in range(cfg.n_kv_heads):
+            for b in range(cfg.batch):
+                if st.seq_len[b] == 0:
+                    assert int(out.new_len[l, h, b]) == 0 and int(out.new_sent_cnt[l, h, b]) == 0
+                    continue
+                bud = None if budgets is None else int(budgets[b])
+                ora = oracle_head(cfg, st, k0, v0, q, l, h, b, budget=bud, red=red)
+                compare_head(cfg, st, out, k, v, k0, v0, ora, l, h, b, stats, budget=bud)
+    return stats
+
+
+def _edge_cfg(dtype="bf16", batch=5):
+    return W.Config("edges", 9, batch, 1, 2, 8, dtype, 0, 0, 64, 8, 16, 16.0, 0.0)
+
+
+def _edge_offsets():
+    rng = np.random.default_rng(5)
+    long_seq = [0, 3, 4, 5, 705]                       # a 700-token sentence spanning several chunks and tiles
+    while long_seq[-1] < 1500:
+        long_seq.append(min(1500, long_seq[-1] + int(rng.integers(1, 40))))
+    return [
+        [0],                                           # empty sequence
+        [0, 2, 5],                                     # shorter than the observation window
+        [0, 7, 19, 40],                                # fits the budget: nothing evicted
+        long_seq,
+        list(range(0, 301)),                           # 300 one-token sentences (more than a chunk may hold)
+    ]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_ragged_degenerate_batch(dtype):
+    cfg = _edge_cfg(dtype)
+    st = _structure(_edge_offsets())
+    k0, v0, q = _random_kvq(cfg, st, 11)
+    k, v = k0.clone(), v0.clone()
+    out = run_step(cfg, st, k, v, q)
+    assert int(out.dev_status.item()) == 0
+    stats = _compare_all(cfg, st, out, k, v, k0, v0, q)
+    assert stats["heads"] == 8
+    # sequences that fit are untouched, bit for bit
+    for b in (1, 2):
+        t0, t1 = int(st.seq_off[b]), int(st.seq_off[b + 1])
+        assert torch.equal(k[:, :, t0:t1], k0[:, :, t0:t1]) and torch.equal(v[:, :, t0:t1], v0[:, :, t0:t1])
+        assert int(out.new_len[0, 0, b]) == t1 - t0
+
+
+def test_per_sequence_budgets_and_token_redundancy_input():
+    cfg = W.CONFIGS[3].scaled(n_layers=1, batch=4, len_lo=600, len_hi=2500, budget=512)
+    st = W.make_structure(cfg)
+    k0, v0, q = W.fill_cache(cfg, st, device="cuda")
+    k, v = k0.clone(), v0.clone()
+    budgets = torch.tensor([256, 512, 300, 4000], dtype=torch.int32, device="cuda")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(3)
+    red = torch.rand((cfg.n_layers, cfg.n_kv_heads, st.total_tokens), generator=g, device="cuda") * 1e-3
+    out = run_step(cfg, st, k, v, q, budget=budgets, red=red)
+    stats = _compare_all(cfg, st, out, k, v, k0, v0, q, budgets=budgets.cpu().numpy(), red=red)
+    assert stats["heads"] == 32
+    assert (out.new_len[0, 0].cpu().numpy() <= budgets.cpu().numpy()).all()
+
+
+def test_strided_cache_rows():
+    cfg = W.CONFIGS[2].scaled(n_layers=1, len_lo=900, len_hi=900, budget=512)
+    st = W.make_structure(cfg)
+    k0, v0, q = _random_kvq(cfg, st, 21, stride_tok=192)
+    assert k0.stride(2) == 192
+    k, v = _clone(k0), _clone(v0)
+    assert k.stride() == k0.stride()
+    out = run_step(cfg, st, k, v, q)
+    _compare_all(cfg, st, out, k, v, k0, v0, q)
+
+
+def test_exact_duplicates_score_maximal_redundancy():
+    cfg = W.CONFIGS[1]
+    st = W.make_structure(cfg)
+    k0, v0, q = W.fill_cache(cfg, st, device="cuda", dup_noise=0.0)
+    k, v = k0.clone(), v0.clone()
+    out = run_step(cfg, st, k, v, q)
+    lam = out.sent_lambda[0].cpu().numpy()
+    srcs = sorted(set(int(j) for j in st.dup_src[0] if j >= 0))
+    np.testing.assert_allclose(lam[:, srcs], 1.0, atol=2e-6)
+    _compare_all(cfg, st, out, k, v, k0, v0, q)
+
+
+def test_bad_offsets_are_reported_not_executed():
+    cfg = _edge_cfg(batch=2)
+    st = _structure([[0, 10, 10, 30], [0, 5, 40]])         # first sequence: an empty sentence
+    k0, v0, q = _random_kvq(cfg, st, 31)
+    k, v = k0.clone(), v0.clone()
+    out = run_step(cfg, st, k, v, q)
+    assert int(out.dev_status.item()) & B.DEV_BAD_OFFSETS
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_compact_generic_gather(dtype):
+    # token-level kept sets (not whole sentences): shift-by-one, every other row, random subset
+    L, H, n_tok = 2, 3, 777
+    st = _structure([[0, n_tok], [0, n_tok], [0, n_tok]])
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    k0 = torch.randn((L, H, st.total_tokens, 128), generator=g, device="cuda").to(dtype)
+    v0 = torch.randn((L, H, st.total_tokens, 128), generator=g, device="cuda").to(dtype)
+    k, v = k0.clone(), v0.clone()
+    rng = np.random.default_rng(6)
+    rows = [np.arange(1, n_tok), np.arange(0, n_tok, 2), np.sort(rng.choice(n_tok, 300, replace=False))]
+    stride = n_tok
+    kept = torch.full((L, H, 3, stride), -1, dtype=torch.int32, device="cuda")
+    new_len = torch.zeros((L, H, 3), dtype=torch.int32, device="cuda")
+    for b, r in enumerate(rows):
+        kept[:, :, b, :len(r)] = torch.from_numpy(r.astype(np.int32)).cuda()
+        new_len[:, :, b] = len(r)
+    cfg = W.Config("gather", 9, 3, L, H, H, "bf16" if dtype == torch.bfloat16 else "f32", 0, 0, 0, 1, 1, 1.0, 0.0)
+    B.skipkv_compact(make_cache(cfg, st, k, v), kept, new_len, stride)
+    torch.cuda.synchronize()
+    for b, r in enumerate(rows):
+        t0 = int(st.seq_off[b])
+        idx = torch.from_numpy(r).cuda() + t0
+        assert torch.equal(k[:, :, t0:t0 + len(r)], k0[:, :, idx]) and torch.equal(v[:, :, t0:t0 + len(r)], v0[:, :, idx])
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_steer_add_matches_oracle_bit_for_bit(dtype):
+    cfg = W.CONFIGS[4]
+    dt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    h0, vec, coef = W.fill_steer(cfg, device="cuda")
+    h0, vec = h0.to(dt), vec.to(dt)
+    assert h0.shape == (64, 3584)
+    # scalar coefficient on every row (the config's recipe)
+    h = h0.clone()
+    B.skipkv_steer_add(h, vec, None, coef, None)
+    ref = oracle.steer_add(h0.double().cpu().numpy(), vec.double().cpu().numpy(), coef, dtype=dtype)
+    np.testing.assert_array_equal(h.double().cpu().numpy(), ref)
+    # adaptive per-sample strength alpha_0 + gamma * N_o and a delimiter-row mask
+    n_o = torch.arange(64, device="cuda", dtype=torch.float32)
+    coefs = (1.0 + 0.02 * n_o).contiguous()
+    mask = (torch.arange(64, device="cuda") % 3 != 1).to(torch.uint8)
+    h = h0.clone()
+    B.skipkv_steer_add(h, vec, coefs, 0.0, mask)
+    ref = oracle.steer_add(h0.double().cpu().numpy(), vec.double().cpu().numpy(), coefs.cpu().numpy(),
+                           mask.cpu().numpy(), dtype=dtype)
+    np.testing.assert_array_equal(h.double().cpu().numpy(), ref)
