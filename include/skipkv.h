@@ -60,7 +60,8 @@ enum {
 /* bits OR-ed into *dev_status by kernels */
 enum {
   SKIPKV_DEV_BAD_OFFSETS = 1,  /* sentence offsets not strictly ascending from 0 to N_b   */
-  SKIPKV_DEV_TOO_MANY_SENT = 2 /* a sequence has more than SKIPKV_MAX_SENTENCES sentences */
+  SKIPKV_DEV_TOO_MANY_SENT = 2, /* a sequence has more than SKIPKV_MAX_SENTENCES sentences */
+  SKIPKV_DEV_TIMEOUT = 4        /* a bounded cross-workgroup wait ran out: scores are invalid  */
 };
 
 typedef enum { SKIPKV_F32 = 0, SKIPKV_BF16 = 1 } skipkv_dtype;

@@ -1,5 +1,6 @@
 // Host side of libskipkv: argument validation, workspace carving, kernel sequencing, timing.
 // No device work happens here and nothing is allocated on the device.
+#include <cstdlib>
 #include <new>
 
 #include "common.h"
@@ -57,7 +58,7 @@ Workspace carve(const skipkv_cache *c, const RowLayout &rl, void *base) {
   Workspace w{};
   const size_t B = (size_t)c->batch, LH = (size_t)c->n_layers * c->n_kv_heads;
   const size_t T = (size_t)c->total_tokens, S = (size_t)c->total_sentences;
-  w.nc_max = (int32_t)((T + kChunkWindow - 1) / kChunkWindow + B + (S + kChunkMaxSent - 1) / kChunkMaxSent);
+  w.nc_max = (int32_t)(2 * ((T + kChunkCap - 1) / kChunkCap) + B + (S + kChunkMaxSent - 1) / kChunkMaxSent);
   w.nrb_max = (int32_t)((S + kRowBlock - 1) / kRowBlock + B);
   w.rows = rl.rows;
   size_t off = 0;
@@ -72,6 +73,9 @@ Workspace carve(const skipkv_cache *c, const RowLayout &rl, void *base) {
   w.chunk_cnt = static_cast<int32_t *>(take(B * 4));
   w.rb_base = static_cast<int32_t *>(take(B * 4));
   w.rb_cnt = static_cast<int32_t *>(take(B * 4));
+  w.seq_fused = static_cast<int32_t *>(take(B * 4));
+  w.arrive = static_cast<int32_t *>(take(2 * LH * B * 4));
+  w.ready = w.arrive ? w.arrive + LH * B : nullptr;
   w.chunks = static_cast<Chunk *>(take((size_t)w.nc_max * sizeof(Chunk)));
   w.rowblocks = static_cast<RowBlock *>(take((size_t)w.nrb_max * sizeof(RowBlock)));
   w.stat_part = static_cast<float2 *>(take(LH * w.nc_max * rl.rows * sizeof(float2)));
@@ -107,7 +111,7 @@ struct Timer {
 int do_score(Timer &tm, const skipkv_cache *c, const skipkv_params *p, const RowLayout &rl, const void *q_obs,
              const float *tok_red, float *sent_score, float *sent_lambda, float *tok_imp, void *ws, hipStream_t st) {
   const Workspace w = carve(c, rl, ws);
-  PlanArgs pa{c->seq_off, c->sent_ptr, c->sent_off, c->batch, w, p->dev_status};
+  PlanArgs pa{c->seq_off, c->sent_ptr, c->sent_off, c->batch, c->n_layers * c->n_kv_heads, w, p->dev_status};
   if (tm.run("plan", [&] { return launch_plan(pa, st); }) != hipSuccess) return SKIPKV_EHIP;
   ScanArgs sa{};
   sa.k = c->k;
@@ -131,6 +135,14 @@ int do_score(Timer &tm, const skipkv_cache *c, const skipkv_params *p, const Row
   sa.tok_imp = tok_imp;
   sa.ws = w;
   sa.rl = rl;
+  // Debugging aids (environment): SKIPKV_FORCE_TWO_PASS=1 sends every sequence through the
+  // two-pass scan; SKIPKV_SPIN_LIMIT bounds the polls of the single-pass scan's wait.
+  const char *env_two = std::getenv("SKIPKV_FORCE_TWO_PASS");
+  const char *env_spin = std::getenv("SKIPKV_SPIN_LIMIT");
+  sa.force_two_pass = (env_two && env_two[0] == '1') || !scan_fused_supported(rl);
+  sa.spin_limit = env_spin ? std::atoi(env_spin) : 4000000;
+  sa.dev_status = p->dev_status;
+  if (tm.run("scan_fused", [&] { return launch_scan_fused(sa, st); }) != hipSuccess) return SKIPKV_EHIP;
   if (tm.run("scan_stats", [&] { return launch_scan_stats(sa, st); }) != hipSuccess) return SKIPKV_EHIP;
   if (tm.run("row_norm", [&] { return launch_row_norm(sa, st); }) != hipSuccess) return SKIPKV_EHIP;
   if (tm.run("scan_scores", [&] { return launch_scan_scores(sa, st); }) != hipSuccess) return SKIPKV_EHIP;

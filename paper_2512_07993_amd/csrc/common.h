@@ -9,16 +9,21 @@
 namespace skipkv {
 
 constexpr int kD = SKIPKV_HEAD_DIM;  // head dimension
-constexpr int kChunkWindow = 256;    // a chunk of scan work = the sentences that START in one window of this many tokens
-constexpr int kChunkMaxSent = 32;    // ... split further so that no chunk has more sentences than this
+constexpr int kChunkCap = 256;       // a chunk of scan work = a maximal run of whole sentences of at most this many tokens
+constexpr int kChunkMaxSent = 32;    // ... and at most this many sentences (a single longer sentence is a chunk of its own)
+constexpr int kFuseMaxChunks = 256;  // sequences with more chunks than this take the two-pass scan (see scan_fused.hip)
 constexpr int kRowBlock = 64;        // sentences per row block of the redundancy kernel
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
-// One unit of scan work: sentences [s0, s1) of sequence b (s0 == s1: empty).
+// One unit of scan work: sentences [s0, s0 + ns) of sequence b, tokens [t_begin, t_begin + len)
+// relative to the sequence.  Carries what a kernel needs to start without further lookups.
 struct Chunk {
-  int32_t b, s0, s1, pad;
+  int32_t b, s0, ns, t_begin, len;
+  int32_t soff_idx;  // index into sent_off of the chunk's first offset
+  int32_t tok0;      // packed index of the sequence's first token
+  int32_t n_tok;     // length of the sequence
 };
 // One unit of redundancy work: rows [r0, r0 + kRowBlock) of sequence b.
 struct RowBlock {
@@ -29,7 +34,8 @@ struct RowBlock {
 struct PlanHeader {
   int32_t n_chunks;
   int32_t n_rowblocks;
-  int32_t pad[62];
+  int32_t n_unfused;  // number of sequences that take the two-pass scan
+  int32_t pad[61];
 };
 
 // Carved-up view of the caller's workspace.  All sections 256-byte aligned.
@@ -39,6 +45,9 @@ struct Workspace {
   int32_t *chunk_cnt;    // [B] number of chunks of each sequence
   int32_t *rb_base;      // [B] first row block of each sequence
   int32_t *rb_cnt;       // [B]
+  int32_t *seq_fused;    // [B] 1: the sequence goes through the single-pass scan
+  int32_t *arrive;       // [LH, B] chunks of the head that have published their row statistics
+  int32_t *ready;        // [LH, B] 1 once the head's row normalisers are final
   Chunk *chunks;         // [nc_max]
   RowBlock *rowblocks;   // [nrb_max]
   float2 *stat_part;     // [LH, nc_max, R]  per-chunk (max, sum) of every query row, log2 domain
@@ -80,7 +89,7 @@ struct Profile;  // api.hip
 // ---- kernel launchers (one per .hip file) -------------------------------------------------
 struct PlanArgs {
   const int32_t *seq_off, *sent_ptr, *sent_off;
-  int32_t batch;
+  int32_t batch, n_lh;
   Workspace ws;
   int32_t *dev_status;
 };
@@ -97,7 +106,12 @@ struct ScanArgs {
   float *tok_imp;        // nullable
   Workspace ws;
   RowLayout rl;
+  int32_t force_two_pass;  // debugging aid: send every sequence through the two-pass scan
+  int32_t spin_limit;      // bound on the polls of a cross-workgroup wait in the single-pass scan
+  int32_t *dev_status;
 };
+bool scan_fused_supported(const RowLayout &rl);
+hipError_t launch_scan_fused(const ScanArgs &a, hipStream_t st);    // single pass over K (sequences the plan marked fused)
 hipError_t launch_scan_stats(const ScanArgs &a, hipStream_t st);    // pass A: row statistics + sentence embeddings
 hipError_t launch_row_norm(const ScanArgs &a, hipStream_t st);      // combine the per-chunk statistics
 hipError_t launch_scan_scores(const ScanArgs &a, hipStream_t st);   // pass B: token importance, sentence means

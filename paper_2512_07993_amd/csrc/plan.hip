@@ -1,98 +1,106 @@
 // Work decomposition for one compression step: cuts every sequence's sentence list into
-// chunks (units of the key scan) and row blocks (units of the redundancy kernel), and checks
-// the sentence offsets.  Shared by all layers and heads of the batch, so it is tiny.
+// chunks (units of the key scan) and row blocks (units of the redundancy kernel), checks the
+// sentence offsets, and decides per sequence which scan variant handles it.  Shared by all
+// layers and heads of the batch, so it is tiny.
 #include "common.h"
 
 namespace skipkv {
 
-__global__ void k_plan_reset(PlanHeader *hdr) {
-  if (threadIdx.x == 0) {
+__global__ void k_plan_reset(PlanHeader *hdr, int32_t *flags, int n_flags) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i == 0) {
     hdr->n_chunks = 0;
     hdr->n_rowblocks = 0;
+    hdr->n_unfused = 0;
   }
+  for (int j = i; j < n_flags; j += gridDim.x * blockDim.x) flags[j] = 0;
 }
 
-// One block per sequence.  A sentence s begins a new chunk when it starts in a different
-// window of kChunkWindow tokens than sentence s-1, or when it is the (k*kChunkMaxSent)-th
-// sentence starting in its window.  Chunks therefore hold whole sentences, at most
-// kChunkMaxSent of them, and about kChunkWindow tokens.
+// End (exclusive sentence index) of the chunk that starts at sentence `start`: the largest e in
+// (start, start + kChunkMaxSent] with off[e] - off[start] <= kChunkCap, at least start + 1.
+__device__ __forceinline__ int chunk_end(const int *off, int start, int n_sent) {
+  int lo = start + 1, hi = min(n_sent, start + kChunkMaxSent);
+  const int limit = off[start] + kChunkCap;
+  while (lo < hi) {  // invariant: the answer lies in [lo, hi]
+    const int mid = (lo + hi + 1) >> 1;
+    if (off[mid] <= limit) lo = mid; else hi = mid - 1;
+  }
+  return lo;
+}
+
+// One block per sequence.  Chunks are packed greedily: a chunk is the longest run of whole
+// sentences with at most kChunkCap tokens and kChunkMaxSent sentences (a sentence longer than
+// kChunkCap is a chunk of its own, and sends its sequence to the two-pass scan).
 __global__ void __launch_bounds__(256) k_plan(PlanArgs a) {
   const int b = blockIdx.x;
   const int tid = threadIdx.x;
-  const int n_tok = a.seq_off[b + 1] - a.seq_off[b];
+  const int tok0 = a.seq_off[b];
+  const int n_tok = a.seq_off[b + 1] - tok0;
   const int sp = a.sent_ptr[b];
   const int n_sent = a.sent_ptr[b + 1] - sp - 1;
   const int32_t *off = a.sent_off + sp;
 
-  __shared__ int s_cnt[256];
-  __shared__ int s_base;
+  __shared__ int s_off[SKIPKV_MAX_SENTENCES + 1];
   __shared__ int s_bad;
   if (tid == 0) s_bad = 0;
   __syncthreads();
 
-  if (n_sent > SKIPKV_MAX_SENTENCES || n_sent < 0) {
-    if (tid == 0) {
-      if (a.dev_status) atomicOr(a.dev_status, SKIPKV_DEV_TOO_MANY_SENT);
-      a.ws.chunk_base[b] = 0;
-      a.ws.chunk_cnt[b] = 0;
-      a.ws.rb_base[b] = 0;
-      a.ws.rb_cnt[b] = 0;
+  bool reject = n_sent > SKIPKV_MAX_SENTENCES || n_sent < 0;
+  if (!reject) {
+    // validation: o[0] = 0, o[S] = N, strictly ascending
+    int bad = 0;
+    for (int s = tid; s <= n_sent; s += 256) {
+      const int o = off[s];
+      s_off[s] = o;
+      if (s < n_sent) bad |= (off[s + 1] <= o);
     }
+    if (tid == 0) bad |= (off[0] != 0) | (off[n_sent] != n_tok) | (n_sent == 0 && n_tok != 0);
+    if (bad) s_bad = 1;
+  }
+  __syncthreads();
+  if (tid != 0) return;
+
+  if (reject || s_bad) {
+    if (a.dev_status) atomicOr(a.dev_status, reject ? SKIPKV_DEV_TOO_MANY_SENT : SKIPKV_DEV_BAD_OFFSETS);
+    a.ws.chunk_base[b] = 0;
+    a.ws.chunk_cnt[b] = 0;
+    a.ws.rb_base[b] = 0;
+    a.ws.rb_cnt[b] = 0;
+    a.ws.seq_fused[b] = 1;  // nothing to scan either way
     return;
   }
 
-  // validation: o[0] = 0, o[S] = N, strictly ascending
-  int bad = 0;
-  for (int s = tid; s < n_sent; s += 256) bad |= (off[s + 1] <= off[s]);
-  if (tid == 0) bad |= (off[0] != 0) | (off[n_sent] != n_tok) | (n_sent == 0 && n_tok != 0);
-  if (bad) s_bad = 1;
-
-  // each thread owns up to 16 consecutive sentences
-  const int per = (n_sent + 255) / 256;
-  const int lo = tid * per, hi = min(lo + per, n_sent);
-  auto begins = [&](int s) -> bool {
-    const int w = off[s] / kChunkWindow;
-    if (s == 0 || off[s - 1] / kChunkWindow != w) return true;
-    int first = s - 1;
-    while (first > 0 && off[first - 1] / kChunkWindow == w) --first;
-    return ((s - first) % kChunkMaxSent) == 0;
-  };
-  int cnt = 0;
-  for (int s = lo; s < hi; ++s) cnt += begins(s);
-  s_cnt[tid] = cnt;
-  __syncthreads();
-  if (tid == 0) {
-    int run = 0;
-    for (int i = 0; i < 256; ++i) {
-      const int c = s_cnt[i];
-      s_cnt[i] = run;
-      run += c;
-    }
-    const int nrb = (n_sent + kRowBlock - 1) / kRowBlock;
-    const bool ok = !s_bad;
-    const int nchunks = ok ? run : 0;
-    s_base = atomicAdd(&a.ws.hdr->n_chunks, nchunks);
-    a.ws.chunk_base[b] = s_base;
-    a.ws.chunk_cnt[b] = nchunks;
-    const int rb0 = atomicAdd(&a.ws.hdr->n_rowblocks, ok ? nrb : 0);
-    a.ws.rb_base[b] = rb0;
-    a.ws.rb_cnt[b] = ok ? nrb : 0;
-    for (int i = 0; ok && i < nrb; ++i) a.ws.rowblocks[rb0 + i] = RowBlock{b, i * kRowBlock};
-    if (!ok && a.dev_status) atomicOr(a.dev_status, SKIPKV_DEV_BAD_OFFSETS);
+  // pass 1: count chunks
+  int n_chunks = 0, longest = 0;
+  for (int start = 0; start < n_sent;) {
+    const int e = chunk_end(s_off, start, n_sent);
+    longest = max(longest, s_off[e] - s_off[start]);
+    ++n_chunks;
+    start = e;
   }
-  __syncthreads();
-  if (s_bad) return;
-  int idx = s_base + s_cnt[tid];
-  for (int s = lo; s < hi; ++s) {
-    if (!begins(s)) continue;
-    int e = s + 1;
-    while (e < n_sent && !begins(e)) ++e;
-    a.ws.chunks[idx++] = Chunk{b, s, e, 0};
+  const int base = atomicAdd(&a.ws.hdr->n_chunks, n_chunks);
+  a.ws.chunk_base[b] = base;
+  a.ws.chunk_cnt[b] = n_chunks;
+  const bool fused = longest <= kChunkCap && n_chunks <= kFuseMaxChunks;
+  a.ws.seq_fused[b] = fused;
+  if (!fused && n_chunks > 0) atomicAdd(&a.ws.hdr->n_unfused, 1);
+  // pass 2: emit
+  int idx = base;
+  for (int start = 0; start < n_sent;) {
+    const int e = chunk_end(s_off, start, n_sent);
+    a.ws.chunks[idx++] = Chunk{b, start, e - start, s_off[start], s_off[e] - s_off[start], sp + start, tok0, n_tok};
+    start = e;
   }
+  const int nrb = (n_sent + kRowBlock - 1) / kRowBlock;
+  const int rb0 = atomicAdd(&a.ws.hdr->n_rowblocks, nrb);
+  a.ws.rb_base[b] = rb0;
+  a.ws.rb_cnt[b] = nrb;
+  for (int i = 0; i < nrb; ++i) a.ws.rowblocks[rb0 + i] = RowBlock{b, i * kRowBlock};
 }
 
 hipError_t launch_plan(const PlanArgs &a, hipStream_t st) {
-  hipLaunchKernelGGL(k_plan_reset, dim3(1), dim3(64), 0, st, a.ws.hdr);
+  const int n_flags = 2 * a.n_lh * a.batch;  // arrive and ready are one allocation
+  hipLaunchKernelGGL(k_plan_reset, dim3(64), dim3(256), 0, st, a.ws.hdr, a.ws.arrive, n_flags);
   if (a.batch > 0) hipLaunchKernelGGL(k_plan, dim3(a.batch), dim3(256), 0, st, a);
   return hipGetLastError();
 }

@@ -1,8 +1,8 @@
 // The key scan of the compression step (Sec. 4.1 "Token Importance Score", Eq. 4, and the
 // sentence embedding of Eq. 2 taken over the head's keys).
 //
-// One workgroup (4 waves) handles one chunk of one head: a run of whole sentences, about
-// kChunkWindow tokens.  Keys stream HBM -> LDS in tiles of TT tokens with 16-byte-per-lane
+// One workgroup (4 waves) handles one chunk of one head: a run of whole sentences of up to
+// kChunkCap tokens (longer only when a single sentence is).  Keys stream HBM -> LDS in tiles of TT tokens with 16-byte-per-lane
 // coalesced loads; each wave multiplies its 16*NSUB tokens against all query rows of the GQA
 // group on the matrix cores (16x16 MFMA tiles, fp32 accumulate), so a lane ends up holding, for
 // ONE token, the logits of every (window query a, group head i) pair assigned to its lane group.
@@ -15,59 +15,11 @@
 //   pass B (PASSB = true): recomputes the logits, forms I[t] = (1/alpha) sum_a max_i softmax and
 //       its mean over the unprotected part of every sentence.
 // exp() is evaluated in base 2: logits are scaled by log2(e)/sqrt(d).
-#include "common.h"
+#include "scan_common.h"
 
 namespace skipkv {
 
 namespace {
-
-constexpr float kScale2 = 0.08838834764831845f * 1.4426950408889634f;  // log2(e) / sqrt(128)
-constexpr float kRefInit = -3.0e38f;  // "no key seen yet" reference, finite so that -inf - ref stays -inf
-constexpr float kRescaleSlack = 16.f;  // a lane's reference is refreshed when a logit exceeds it by this much (log2 units)
-
-template <int DT>
-struct Tr;
-template <>
-struct Tr<SKIPKV_BF16> {
-  static constexpr int ESZ = 2, ROWB = 256, LSTR = 272;  // LDS row stride: +16 B so that 16-byte reads of 8 consecutive rows hit distinct banks
-};
-template <>
-struct Tr<SKIPKV_F32> {
-  static constexpr int ESZ = 4, ROWB = 512, LSTR = 528;
-};
-
-// acc[T] += Q[16T.., :] * K[token, :]^T for the lane's token.  Both operands use the same
-// (arbitrary but identical) assignment of head-dim slices to MFMA k-steps: lane group g covers
-// bytes [64g, 64g+64) of a bf16 row over the 4 k-steps, so every lane reads contiguous 16-byte
-// pieces.
-template <int DT, int NT>
-__device__ __forceinline__ void tile_logits(const char *qt, const char *krow, int c16, int g, f32x4 (&acc)[NT]) {
-  constexpr int LSTR = Tr<DT>::LSTR;
-  if constexpr (DT == SKIPKV_BF16) {
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(krow + g * 64 + kk * 16);
-#pragma unroll
-      for (int T = 0; T < NT; ++T) {
-        const bf16x8 afrag = *reinterpret_cast<const bf16x8 *>(qt + (16 * T + c16) * LSTR + g * 64 + kk * 16);
-        acc[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag, acc[T], 0, 0, 0);
-      }
-    }
-  } else {
-#pragma unroll
-    for (int c = 0; c < 8; ++c) {
-      const float4 bfrag = *reinterpret_cast<const float4 *>(krow + c * 64 + g * 16);
-#pragma unroll
-      for (int T = 0; T < NT; ++T) {
-        const float4 afrag = *reinterpret_cast<const float4 *>(qt + (16 * T + c16) * LSTR + c * 64 + g * 16);
-        acc[T] = __builtin_amdgcn_mfma_f32_16x16x4f32(afrag.x, bfrag.x, acc[T], 0, 0, 0);
-        acc[T] = __builtin_amdgcn_mfma_f32_16x16x4f32(afrag.y, bfrag.y, acc[T], 0, 0, 0);
-        acc[T] = __builtin_amdgcn_mfma_f32_16x16x4f32(afrag.z, bfrag.z, acc[T], 0, 0, 0);
-        acc[T] = __builtin_amdgcn_mfma_f32_16x16x4f32(afrag.w, bfrag.w, acc[T], 0, 0, 0);
-      }
-    }
-  }
-}
 
 template <int DT, int NP, int AL, int NSUB, bool PASSB>
 __global__ void __launch_bounds__(256) k_scan(ScanArgs a) {
@@ -90,21 +42,25 @@ __global__ void __launch_bounds__(256) k_scan(ScanArgs a) {
   __shared__ float sbuf[SBUF];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, c16 = lane & 15, g = lane >> 4;
+  // Fallback path: only sequences that the single-pass scan cannot take (a sentence longer than
+  // a chunk, or too many chunks), unless the caller forces this path for everything.
+  if (!a.force_two_pass && a.ws.hdr->n_unfused == 0) return;
   const int n_lh = a.n_layers * a.n_kv_heads;
-  const uint32_t item = xcd_contiguous_item(blockIdx.x, gridDim.x);
-  if (item >= (uint32_t)n_lh * (uint32_t)a.ws.nc_max) return;
-  const int lh = item / a.ws.nc_max, c = item % a.ws.nc_max;
-  if (c >= a.ws.hdr->n_chunks) return;
-  const Chunk ch = a.ws.chunks[c];
-  const int b = ch.b, ns = ch.s1 - ch.s0;
-  if (ns <= 0) return;
-  const int l = lh / a.n_kv_heads, h = lh % a.n_kv_heads;
+  const int n_chunks = a.ws.hdr->n_chunks;
+  const uint32_t n_items = (uint32_t)n_lh * (uint32_t)n_chunks;
   const int n = a.n_q_heads / a.n_kv_heads;
-  const int tok0 = a.seq_off[b];
-  const int n_tok = a.seq_off[b + 1] - tok0;
-  const int sent_col0 = a.sent_ptr[b] - b + ch.s0;  // column of the chunk's first sentence in [.., S_total] arrays
+  for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+  const int lh = item / n_chunks, c = item % n_chunks;
+  const Chunk ch = a.ws.chunks[c];
+  const int b = ch.b, ns = ch.ns;
+  if (!a.force_two_pass && a.ws.seq_fused[b]) continue;
+  const int l = lh / a.n_kv_heads, h = lh % a.n_kv_heads;
+  const int tok0 = ch.tok0;
+  const int n_tok = ch.n_tok;
+  const int sent_col0 = ch.soff_idx - b;  // column of the chunk's first sentence in [.., S_total] arrays
+  __syncthreads();  // the previous item's readers of LDS are done
 
-  if (tid <= ns) soff[tid] = a.sent_off[a.sent_ptr[b] + ch.s0 + tid];
+  if (tid <= ns) soff[tid] = a.sent_off[ch.soff_idx + tid];
   for (int i = tid; i < SBUF; i += 256) sbuf[i] = 0.f;
 
   // ---- queries of the group -> LDS, one padded row per (lane group, slot)
@@ -328,11 +284,13 @@ __global__ void __launch_bounds__(256) k_scan(ScanArgs a) {
       a.ws.sent_red[o] = len > 0 ? sbuf[TT + kChunkMaxSent + tid] / (float)len : 0.f;
     }
   }
+  }  // item loop
 }
 
 // log2 of the softmax normaliser of every query row: merge the chunk partials of a head.
 __global__ void k_row_norm(ScanArgs a, int R) {
   const int lhb = blockIdx.x, lh = lhb / a.batch, b = lhb % a.batch;
+  if (!a.force_two_pass && a.ws.seq_fused[b]) return;  // the single-pass scan computed these itself
   const int c0 = a.ws.chunk_base[b], nc = a.ws.chunk_cnt[b];
   for (int r = threadIdx.x; r < R; r += blockDim.x) {
     float m = kRefInit, s = 0.f;
@@ -352,7 +310,7 @@ hipError_t launch_one(const ScanArgs &a, hipStream_t st) {
   constexpr int NSUB = (DT == SKIPKV_F32) ? 1 : (NT <= 4 ? 2 : 1);
   const int64_t items = (int64_t)a.n_layers * a.n_kv_heads * a.ws.nc_max;
   if (items == 0) return hipSuccess;
-  const int64_t grid = (items + 7) / 8 * 8;
+  const int64_t grid = items < 4096 ? items : 4096;  // grid-stride over the items
   hipLaunchKernelGGL((k_scan<DT, NP, AL, NSUB, PASSB>), dim3((unsigned)grid), dim3(256), 0, st, a);
   return hipGetLastError();
 }
