@@ -17,19 +17,30 @@
 // The wait is bounded anyway (spin_limit polls): on expiry SKIPKV_DEV_TIMEOUT is raised and the
 // kernel runs to completion with invalid scores rather than hanging.
 //
-// Inside a workgroup the 4 waves are independent streams: wave w owns tokens [64w, 64w+64) of the
-// chunk, stages its own rows HBM -> registers -> its private LDS region (no workgroup barrier per
-// tile), multiplies them against the query tile on the matrix cores, updates the running row
-// statistics and pools keys per sentence.  A sentence that lies inside one wave's range is
-// normalised and written straight from registers; the (at most 3) sentences that cross wave
-// boundaries are pieced together through LDS in a fixed order, so results are reproducible.
+// Data movement.  Inside a workgroup the 4 waves are independent streams: wave w owns tokens
+// [64w, 64w+64) of the chunk, in stages of 16 rows.  Rows go HBM -> LDS directly
+// (global_load_lds, 16 bytes per lane, no staging registers) into a ring of NBUF stage buffers
+// private to the wave, and the wave always keeps NBUF-1 stages in flight ahead of the one it is
+// computing on - also across the end of an item, so the synchronisation at the end of a chunk
+// overlaps with the first loads of the next one.  A direct load writes LDS at base + lane*16, so
+// rows are stored unpadded; bank conflicts are avoided by an XOR swizzle instead: the 16-byte
+// piece p of row r is kept at piece position p ^ (r & 15), which each lane arranges by choosing
+// which global piece it fetches.
+//
+// Pooling.  A sentence that lies inside one wave's range is normalised and written straight from
+// registers; the (at most 3) sentences that cross wave boundaries are pieced together through
+// LDS in a fixed order, so results are reproducible.
 #include "scan_common.h"
 
 namespace skipkv {
 
 namespace {
 
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+
 constexpr int kCapW = kChunkCap / 4;  // tokens per wave
+constexpr int kStageRows = 16;        // rows per pipeline stage = one MFMA sub-tile of tokens
+constexpr int kStagesPerWave = kCapW / kStageRows;
 
 // Cross-workgroup communication (the workgroups may sit on different XCDs, whose L2 caches are not
 // coherent with each other).  Everything that is communicated - chunk statistics, row normalisers,
@@ -53,72 +64,171 @@ __device__ __forceinline__ float2 coherent_load2(const float2 *p) {
       __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   return make_float2(__uint_as_float((uint32_t)u), __uint_as_float((uint32_t)(u >> 32)));
 }
-__device__ __forceinline__ void stores_done() { __builtin_amdgcn_s_waitcnt(0); }  // vmcnt(0): every earlier store is acknowledged
+
+// s_waitcnt immediates (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14)
+template <int N>
+__device__ __forceinline__ void wait_vm() {  // at most N vector-memory operations still outstanding
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | (0x7 << 4) | (0xF << 8) | ((N >> 4) << 14));
+}
+__device__ __forceinline__ void wait_all() { __builtin_amdgcn_s_waitcnt(0); }
+// Workgroup barrier for data exchanged through LDS: waits for this wave's LDS operations only, so
+// that key loads already in flight for later stages are not drained (a __syncthreads() would).
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+  __builtin_amdgcn_s_barrier();
+}
+
+// Direct HBM -> LDS load: every lane fetches 16 bytes from its own global address; the wave's 64
+// pieces land at wave_lds_base + lane * 16 (the base travels in M0).  Issued through inline
+// assembly on purpose: the compiler orders LDS reads against direct loads it knows about by
+// waiting for ALL of them, which would drain the ring of stages on every read; here the stages
+// are ordered by hand with wait_vm<>() (loads complete in issue order).  Nothing else in this
+// kernel uses M0.
+__device__ __forceinline__ void load_to_lds_16(const void *gsrc, void *wave_lds_base) {
+  const uint32_t l = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)wave_lds_base;
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(l), "v"(gsrc) : "memory");
+}
 
 template <int DT, int NP, int AL>
-__global__ void __launch_bounds__(256) k_scan_fused(ScanArgs a) {
+__global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused(ScanArgs a) {
   constexpr int SL = NP * AL;
   constexpr int NT = (SL + 3) / 4;
   constexpr int SLP = 4 * NT;
   constexpr int R = 16 * NT;
-  constexpr int SUBS = kCapW / 16;                       // 16-token sub-tiles per wave
-  constexpr int NSUB = (DT == SKIPKV_BF16) ? 2 : 1;      // sub-tiles staged and multiplied per step
-  constexpr int STEPS = SUBS / NSUB;
-  constexpr int WT = 16 * NSUB;                          // tokens per step
+  constexpr int SUBS = kStagesPerWave;
   constexpr int LSTR = Tr<DT>::LSTR, ROWB = Tr<DT>::ROWB, ESZ = Tr<DT>::ESZ;
-  constexpr int PPR = ROWB / 16;
-  constexpr int LOADS = WT * PPR / 64;                   // 16-byte loads per lane per step
+  constexpr int PPR = ROWB / 16;                      // 16-byte pieces per row
+  constexpr int GL = kStageRows * PPR / 64;           // direct loads per stage
+  constexpr int RPL = 64 / PPR;                       // rows covered by one direct load
+  constexpr int NBUF = (DT == SKIPKV_BF16) ? 3 : 2;   // stage buffers per wave
+  constexpr int STAGEB = kStageRows * ROWB;
 
-  __shared__ __align__(16) char kt[4][WT * LSTR];
+  __shared__ __align__(16) char kt[4][NBUF][STAGEB];
   __shared__ __align__(16) char qt[R * LSTR];
-  __shared__ int soff[kChunkMaxSent + 2];
+  __shared__ int soff_buf[2][kChunkMaxSent + 2];
   __shared__ float part_first[4][kD];  // key sum, over this wave's range, of the sentence already running at its start
   __shared__ float part_last[4][kD];   // key sum of the sentence that starts in this wave's range and runs past its end
   __shared__ float wstat[4][R][2];
   __shared__ float imp[kChunkCap];
   __shared__ int s_flag;
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, c16 = lane & 15, g = lane >> 4;
+  const int tid = threadIdx.x, lane = tid & 63, c16 = lane & 15, g = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: everything derived from it is uniform control flow
   const int n_lh = a.n_layers * a.n_kv_heads;
   const int n_chunks = a.ws.hdr->n_chunks;
   const uint32_t n_items = (uint32_t)n_lh * (uint32_t)n_chunks;
   const int n = a.n_q_heads / a.n_kv_heads;
   const int64_t tok_pitch = a.stride_tok * ESZ;
   const float inv_alpha = 1.f / (float)a.alpha;
+  if (a.force_two_pass) return;
+  // The plan is constant while this kernel runs: reading it through the constant address space
+  // lets the compiler use scalar loads, which do not queue behind the key loads in flight.
+  typedef const __attribute__((address_space(4))) int32_t *ConstIntPtr;
+  static_assert(sizeof(Chunk) == 8 * sizeof(int32_t), "chunk records are read as 8 ints");
+  const ConstIntPtr chunks_c = (ConstIntPtr)a.ws.chunks;
+  const ConstIntPtr seq_fused_c = (ConstIntPtr)a.ws.seq_fused;
+  const ConstIntPtr chunk_cnt_c = (ConstIntPtr)a.ws.chunk_cnt;
+  const ConstIntPtr chunk_base_c = (ConstIntPtr)a.ws.chunk_base;
 
-  for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
-    const int lh = item / n_chunks, c = item % n_chunks;
-    const Chunk ch = a.ws.chunks[c];
-    const int b = ch.b, ns = ch.ns;
-    if (a.force_two_pass || !a.ws.seq_fused[b]) continue;
-    const int l = lh / a.n_kv_heads, h = lh % a.n_kv_heads;
-    const int n_tok = ch.n_tok;
-    const int t_begin = ch.t_begin, t_end = ch.t_begin + ch.len;
-    const int sent_col0 = ch.soff_idx - b;
-    const int lhb = lh * a.batch + b;
-    __syncthreads();  // the previous item's readers of LDS are done
-
-    if (tid <= ns) soff[tid] = a.sent_off[ch.soff_idx + tid];
-    {  // queries of the group -> LDS, one padded row per (lane group, slot)
-      const char *qbase = static_cast<const char *>(a.q);
-      for (int r0 = 0; r0 < R; r0 += 256 / PPR) {
-        const int r = r0 + tid / PPR, piece = tid % PPR;
-        const int slot = 4 * (r >> 4) + (r & 3), gq = (r >> 2) & 3;
-        const int al = slot / NP, i = slot % NP, aq = gq + 4 * al;
-        uint4 val = make_uint4(0, 0, 0, 0);
-        if (slot < SL && i < n && aq < a.alpha) {
-          const int64_t row = (((int64_t)l * a.batch + b) * a.n_q_heads + (h * n + i)) * a.alpha + aq;
-          val = *reinterpret_cast<const uint4 *>(qbase + row * ROWB + piece * 16);
-        }
-        *reinterpret_cast<uint4 *>(qt + r * LSTR + piece * 16) = val;
-      }
+  // ---- item descriptors ------------------------------------------------------------------
+  struct Item {
+    uint32_t item;     // >= n_items: none
+    int lh, c, b, ns, t_begin, t_end, n_tok, tok0, soff_idx;
+    int w0, w1, nst;   // this wave's token range and number of stages
+    const char *kbase;
+  };
+  auto load_item = [&](uint32_t item) -> Item {  // first fused item at or after `item` in this workgroup's sequence
+    Item it{};
+    for (; item < n_items; item += gridDim.x) {
+      const int c = item % n_chunks;
+      Chunk ch;
+      ch.b = chunks_c[8 * c + 0];
+      ch.s0 = chunks_c[8 * c + 1];
+      ch.ns = chunks_c[8 * c + 2];
+      ch.t_begin = chunks_c[8 * c + 3];
+      ch.len = chunks_c[8 * c + 4];
+      ch.soff_idx = chunks_c[8 * c + 5];
+      ch.tok0 = chunks_c[8 * c + 6];
+      ch.n_tok = chunks_c[8 * c + 7];
+      if (!seq_fused_c[ch.b]) continue;
+      it.lh = item / n_chunks;
+      it.c = c;
+      it.b = ch.b;
+      it.ns = ch.ns;
+      it.t_begin = ch.t_begin;
+      it.t_end = ch.t_begin + ch.len;
+      it.n_tok = ch.n_tok;
+      it.tok0 = ch.tok0;
+      it.soff_idx = ch.soff_idx;
+      it.w0 = ch.t_begin + wave * kCapW;
+      it.w1 = min(it.w0 + kCapW, it.t_end);
+      it.nst = it.w1 > it.w0 ? (it.w1 - it.w0 + kStageRows - 1) / kStageRows : 0;
+      const int l = it.lh / a.n_kv_heads, h = it.lh % a.n_kv_heads;
+      it.kbase = static_cast<const char *>(a.k) +
+                 ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head + (int64_t)ch.tok0 * a.stride_tok) * ESZ;
+      break;
     }
-    __syncthreads();
+    it.item = item;
+    return it;
+  };
+  auto load_q_soff = [&](const Item &it, int sbuf) {  // queries of the group -> LDS (padded rows), sentence offsets
+    if (tid <= it.ns) soff_buf[sbuf][tid] = a.sent_off[it.soff_idx + tid];
+    const char *qbase = static_cast<const char *>(a.q);
+    const int l = it.lh / a.n_kv_heads, h = it.lh % a.n_kv_heads;
+    for (int r0 = 0; r0 < R; r0 += 256 / PPR) {
+      const int r = r0 + tid / PPR, piece = tid % PPR;
+      const int slot = 4 * (r >> 4) + (r & 3), gq = (r >> 2) & 3;
+      const int al = slot / NP, i = slot % NP, aq = gq + 4 * al;
+      uint4 val = make_uint4(0, 0, 0, 0);
+      if (slot < SL && i < n && aq < a.alpha) {
+        const int64_t row = (((int64_t)l * a.batch + it.b) * a.n_q_heads + (h * n + i)) * a.alpha + aq;
+        val = *reinterpret_cast<const uint4 *>(qbase + row * ROWB + piece * 16);
+      }
+      *reinterpret_cast<uint4 *>(qt + r * LSTR + piece * 16) = val;
+    }
+  };
 
-    const char *kbase = static_cast<const char *>(a.k) +
-                        ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head + (int64_t)ch.tok0 * a.stride_tok) * ESZ;
+  // ---- the wave's load stream: stages of consecutive items, NBUF-1 ahead of the compute ------
+  Item iss = load_item(blockIdx.x);  // item whose stages are being issued
+  int iss_st = 0;                    // next stage of `iss` to issue
+  uint32_t iss_cnt = 0;              // stages issued so far (ring position)
+  auto issue_next = [&]() -> bool {
+    while (iss.item < n_items && iss_st >= iss.nst) {
+      iss = load_item(iss.item + gridDim.x);
+      iss_st = 0;
+    }
+    if (iss.item >= n_items) return false;
+    char *dst = kt[wave][iss_cnt % NBUF];
+    const int ts = iss.w0 + iss_st * kStageRows;
+#pragma unroll
+    for (int j = 0; j < GL; ++j) {
+      const int row = j * RPL + lane / PPR;                       // row of the stage this lane's 16 bytes belong to
+      const int piece = (lane % PPR) ^ (row & 15);                // swizzle: LDS position (lane % PPR) holds this global piece
+      const int t = min(ts + row, iss.w1 - 1);                    // rows past the range re-read its last row (masked later)
+      load_to_lds_16(iss.kbase + (int64_t)t * tok_pitch + piece * 16, dst + j * 1024);
+    }
+    ++iss_st;
+    ++iss_cnt;
+    return true;
+  };
+
+  Item cur = load_item(blockIdx.x);
+  if (cur.item >= n_items) return;
+#pragma unroll
+  for (int i = 0; i < NBUF - 1; ++i) issue_next();
+  uint32_t cmp_cnt = 0;  // stages computed so far (ring position)
+  int sb = 0;            // which soff buffer holds the current item's offsets
+  load_q_soff(cur, sb);
+  lds_barrier();
+
+  while (cur.item < n_items) {
+    const int *soff = soff_buf[sb];
+    const int lh = cur.lh, c = cur.c, b = cur.b, ns = cur.ns;
+    const int t_begin = cur.t_begin, t_end = cur.t_end, n_tok = cur.n_tok;
+    const int w0 = cur.w0, w1 = cur.w1;
+    const int sent_col0 = cur.soff_idx - b;
+    const int lhb = lh * a.batch + b;
     const int last_free = n_tok - a.alpha;  // keys t <= last_free are visible to every window query
-    const int w0 = t_begin + wave * kCapW, w1 = min(w0 + kCapW, t_end);  // this wave's tokens
 
     f32x4 acc[SUBS][NT];
     float ref[SLP], lsum[SLP];
@@ -131,6 +241,17 @@ __global__ void __launch_bounds__(256) k_scan_fused(ScanArgs a) {
     for (int s = 0; s < SUBS; ++s)
 #pragma unroll
       for (int T = 0; T < NT; ++T) acc[s][T] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // bf16: the query operand of the matrix products lives in registers for the whole item
+    // (read from LDS once per item instead of once per stage)
+    bf16x8 qa[NT][4];
+    if constexpr (DT == SKIPKV_BF16) {
+#pragma unroll
+      for (int T = 0; T < NT; ++T)
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+          qa[T][kk] = *reinterpret_cast<const bf16x8 *>(qt + (16 * T + c16) * LSTR + g * 64 + kk * 16);
+    }
 
     // sentence pooling state: current sentence, its running key sum (lane = 2 head-dim columns)
     int si = 0;
@@ -150,104 +271,99 @@ __global__ void __launch_bounds__(256) k_scan_fused(ScanArgs a) {
     };
 
 #pragma unroll
-    for (int step = 0; step < STEPS; ++step) {
-      const int ts = w0 + step * WT;
-      if (ts < w1) {
-        const int te = min(ts + WT, w1);
-        char *ktw = kt[wave];
-        {  // stage this wave's rows: HBM -> registers -> private LDS region
-          uint4 regs[LOADS];
-#pragma unroll
-          for (int it = 0; it < LOADS; ++it) {
-            const int idx = it * 64 + lane, row = idx / PPR, piece = idx % PPR, t = ts + row;
-            regs[it] = make_uint4(0, 0, 0, 0);
-            if (t < te) regs[it] = *reinterpret_cast<const uint4 *>(kbase + (int64_t)t * tok_pitch + piece * 16);
-          }
-#pragma unroll
-          for (int it = 0; it < LOADS; ++it) {
-            const int idx = it * 64 + lane, row = idx / PPR, piece = idx % PPR;
-            *reinterpret_cast<uint4 *>(ktw + row * LSTR + piece * 16) = regs[it];
-          }
-        }
-        __builtin_amdgcn_wave_barrier();  // LDS operations of one wave execute in order: later reads see these writes
+    for (int st = 0; st < SUBS; ++st) {
+      if (st < cur.nst) {
+        const int ts = w0 + st * kStageRows, te = min(ts + kStageRows, w1);
+        // keep the load stream NBUF-1 stages ahead, then wait for this stage's rows to land
+        if (issue_next())
+          wait_vm<GL *(NBUF - 1)>();
+        else
+          wait_all();
+        const char *stage = kt[wave][cmp_cnt % NBUF];
+        ++cmp_cnt;
 
+        // ---- logits of this stage's 16 tokens against all query rows
+        if constexpr (DT == SKIPKV_BF16) {
 #pragma unroll
-        for (int s = 0; s < NSUB; ++s)
-          if (ts + 16 * s < te) tile_logits<DT, NT>(qt, ktw + (16 * s + c16) * LSTR, c16, g, acc[step * NSUB + s]);
-
-        // ---- running softmax statistics of every query row over these tokens
-        float tmax[SLP];
+          for (int kk = 0; kk < 4; ++kk) {
+            const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(stage + c16 * ROWB + (((4 * g + kk) ^ c16) * 16));
 #pragma unroll
-        for (int q = 0; q < SLP; ++q) tmax[q] = -INFINITY;
+            for (int T = 0; T < NT; ++T)
+              acc[st][T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[T][kk], bfrag, acc[st][T], 0, 0, 0);
+          }
+        } else {
 #pragma unroll
-        for (int s = 0; s < NSUB; ++s) {
-          const int t = ts + 16 * s + c16;
-          const bool edge = (ts + 16 * s + 15 >= te) || (ts + 16 * s + 15 > last_free);
+          for (int cc = 0; cc < 8; ++cc) {
+            const float4 bfrag = *reinterpret_cast<const float4 *>(stage + c16 * ROWB + (((4 * cc + g) ^ c16) * 16));
 #pragma unroll
-          for (int q = 0; q < SLP; ++q) {
-            float x = acc[step * NSUB + s][q >> 2][q & 3] * kScale2;
-            if (edge) {
-              const int aq = g + 4 * (q / NP);
-              if (!(t < te && t <= last_free + aq)) x = -INFINITY;
+            for (int T = 0; T < NT; ++T) {
+              const float4 afrag = *reinterpret_cast<const float4 *>(qt + (16 * T + c16) * LSTR + cc * 64 + g * 16);
+              acc[st][T] = __builtin_amdgcn_mfma_f32_16x16x4f32(afrag.x, bfrag.x, acc[st][T], 0, 0, 0);
+              acc[st][T] = __builtin_amdgcn_mfma_f32_16x16x4f32(afrag.y, bfrag.y, acc[st][T], 0, 0, 0);
+              acc[st][T] = __builtin_amdgcn_mfma_f32_16x16x4f32(afrag.z, bfrag.z, acc[st][T], 0, 0, 0);
+              acc[st][T] = __builtin_amdgcn_mfma_f32_16x16x4f32(afrag.w, bfrag.w, acc[st][T], 0, 0, 0);
             }
-            acc[step * NSUB + s][q >> 2][q & 3] = x;
-            tmax[q] = fmaxf(tmax[q], x);
           }
         }
-        bool need = false;
+
+        // ---- running softmax statistics of every query row (accumulators stay unscaled)
+        {
+          const int t = ts + c16;
+          const bool edge = (ts + 15 >= te) || (ts + 15 > last_free);
+          if (edge) {
 #pragma unroll
-        for (int q = 0; q < SLP; ++q) need |= tmax[q] > ref[q] + kRescaleSlack;
-        if (__any(need)) {
-#pragma unroll
-          for (int q = 0; q < SLP; ++q) {
-            const float nr = fmaxf(ref[q], row16_max(tmax[q]));
-            lsum[q] *= __builtin_amdgcn_exp2f(ref[q] - nr);
-            ref[q] = nr;
+            for (int q = 0; q < SLP; ++q) {
+              const int aq = g + 4 * (q / NP);
+              if (!(t < te && t <= last_free + aq)) acc[st][q >> 2][q & 3] = -INFINITY;
+            }
           }
+          bool need = false;
+#pragma unroll
+          for (int q = 0; q < SLP; ++q) need |= acc[st][q >> 2][q & 3] * kScale2 > ref[q] + kRescaleSlack;
+          if (__any(need)) {
+#pragma unroll
+            for (int q = 0; q < SLP; ++q) {
+              const float nr = fmaxf(ref[q], row16_max(acc[st][q >> 2][q & 3]) * kScale2);
+              lsum[q] *= __builtin_amdgcn_exp2f(ref[q] - nr);
+              ref[q] = nr;
+            }
+          }
+#pragma unroll
+          for (int q = 0; q < SLP; ++q) lsum[q] += __builtin_amdgcn_exp2f(fmaf(acc[st][q >> 2][q & 3], kScale2, -ref[q]));
         }
-#pragma unroll
-        for (int s = 0; s < NSUB; ++s)
-#pragma unroll
-          for (int q = 0; q < SLP; ++q) lsum[q] += __builtin_amdgcn_exp2f(acc[step * NSUB + s][q >> 2][q & 3] - ref[q]);
 
         // ---- sentence key sums over tokens [ts, te), walked in order
         int t = ts;
         while (t < te) {
           const int run_end = min(soff[si + 1], te);
-          const char *rowp = ktw + (t - ts) * LSTR;
-          float q0 = 0.f, q1 = 0.f, r0 = 0.f, r1 = 0.f;  // two independent chains
+          if (run_end <= t) break;  // cannot happen with validated offsets; never spin on bad ones
+          float q0 = 0.f, q1 = 0.f;
+          int r = t - ts;            // row within the stage
           int cnt = run_end - t;
           if constexpr (DT == SKIPKV_BF16) {
-            for (; cnt >= 2; cnt -= 2, rowp += 2 * LSTR) {
-              const uint32_t wa = *reinterpret_cast<const uint32_t *>(rowp + lane * 4);
-              const uint32_t wb = *reinterpret_cast<const uint32_t *>(rowp + LSTR + lane * 4);
-              q0 += __uint_as_float(wa << 16);
-              q1 += __uint_as_float(wa & 0xFFFF0000u);
-              r0 += __uint_as_float(wb << 16);
-              r1 += __uint_as_float(wb & 0xFFFF0000u);
+            // lane = dword `lane` of the row = piece lane/4 (swizzled by the row), bytes (lane%4)*4
+            const bf16x2_t ones = __builtin_bit_cast(bf16x2_t, 0x3F803F80u);
+            for (; cnt >= 2; cnt -= 2, r += 2) {
+              const uint32_t wa = *reinterpret_cast<const uint32_t *>(stage + r * ROWB + (((lane >> 2) ^ (r & 15)) * 16) + (lane & 3) * 4);
+              const uint32_t wb = *reinterpret_cast<const uint32_t *>(stage + (r + 1) * ROWB + (((lane >> 2) ^ ((r + 1) & 15)) * 16) + (lane & 3) * 4);
+              // (lo_a, lo_b) and (hi_a, hi_b) pairs, each summed into fp32 by one dot instruction
+              q0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, __builtin_amdgcn_perm(wb, wa, 0x05040100u)), ones, q0, false);
+              q1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, __builtin_amdgcn_perm(wb, wa, 0x07060302u)), ones, q1, false);
             }
             if (cnt) {
-              const uint32_t wa = *reinterpret_cast<const uint32_t *>(rowp + lane * 4);
+              const uint32_t wa = *reinterpret_cast<const uint32_t *>(stage + r * ROWB + (((lane >> 2) ^ (r & 15)) * 16) + (lane & 3) * 4);
               q0 += __uint_as_float(wa << 16);
               q1 += __uint_as_float(wa & 0xFFFF0000u);
             }
           } else {
-            for (; cnt >= 2; cnt -= 2, rowp += 2 * LSTR) {
-              const float2 wa = *reinterpret_cast<const float2 *>(rowp + lane * 8);
-              const float2 wb = *reinterpret_cast<const float2 *>(rowp + LSTR + lane * 8);
-              q0 += wa.x;
-              q1 += wa.y;
-              r0 += wb.x;
-              r1 += wb.y;
-            }
-            if (cnt) {
-              const float2 wa = *reinterpret_cast<const float2 *>(rowp + lane * 8);
+            for (; cnt > 0; --cnt, ++r) {
+              const float2 wa = *reinterpret_cast<const float2 *>(stage + r * ROWB + (((lane >> 1) ^ (r & 15)) * 16) + (lane & 1) * 8);
               q0 += wa.x;
               q1 += wa.y;
             }
           }
-          ps0 += q0 + r0;
-          ps1 += q1 + r1;
+          ps0 += q0;
+          ps1 += q1;
           t = run_end;
           if (t == soff[si + 1]) {  // the sentence ends here
             if (soff[si] >= w0) {
@@ -276,7 +392,7 @@ __global__ void __launch_bounds__(256) k_scan_fused(ScanArgs a) {
         wstat[wave][r][1] = tot;
       }
     }
-    __syncthreads();
+    lds_barrier();  // every wave is done with the query tile and has left its partials
 
     // ---- sentences that cross wave boundaries: the wave in whose range one starts pieces it together
     if (w0 < w1) {
@@ -300,21 +416,22 @@ __global__ void __launch_bounds__(256) k_scan_fused(ScanArgs a) {
       for (int w = 0; w < 4; ++w) s += wstat[w][r][1] * __builtin_amdgcn_exp2f(wstat[w][r][0] - m);
       coherent_store2(&a.ws.stat_part[((int64_t)lh * a.ws.nc_max + c) * R + r], make_float2(m, s));
     }
-    stores_done();
-    __syncthreads();
+    // the next item's queries and offsets can come in now: their latency hides behind the wait below
+    const Item nxt = load_item(cur.item + gridDim.x);
+    if (nxt.item < n_items) load_q_soff(nxt, sb ^ 1);
+    wait_all();  // the statistics are acknowledged (and so are the loads already in flight)
+    __builtin_amdgcn_s_barrier();
     if (tid == 0) {
       const int old = __hip_atomic_fetch_add(&a.ws.arrive[lhb], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      s_flag = (old == a.ws.chunk_cnt[b] - 1);
+      s_flag = (old == chunk_cnt_c[b] - 1);
     }
-    __syncthreads();
+    lds_barrier();
     float *rn = a.ws.row_norm + (int64_t)lhb * R;
     if (s_flag) {  // last chunk of the head to arrive: merge the partials into the normalisers
       // lane = query row, wave w takes chunks c0+w, c0+w+4, ...; 8 independent loads in flight per lane
-      const int c0 = a.ws.chunk_base[b], nc = a.ws.chunk_cnt[b];
-      float m = kRefInit, s = 0.f;
+      const int c0 = chunk_base_c[b], nc = chunk_cnt_c[b];
       for (int r = lane; r < R; r += 64) {
-        m = kRefInit;
-        s = 0.f;
+        float m = kRefInit, s = 0.f;
         for (int cc = wave; cc < nc; cc += 32) {
           float2 pv[8];
 #pragma unroll
@@ -332,7 +449,7 @@ __global__ void __launch_bounds__(256) k_scan_fused(ScanArgs a) {
         wstat[wave][r][0] = m;
         wstat[wave][r][1] = s;
       }
-      __syncthreads();
+      lds_barrier();
       for (int r = tid; r < R; r += 256) {
         float mm = kRefInit;
 #pragma unroll
@@ -342,21 +459,21 @@ __global__ void __launch_bounds__(256) k_scan_fused(ScanArgs a) {
         for (int w = 0; w < 4; ++w) ss += wstat[w][r][1] * __builtin_amdgcn_exp2f(wstat[w][r][0] - mm);
         coherent_store(&rn[r], ss > 0.f ? mm + __builtin_amdgcn_logf(ss) : INFINITY);
       }
-      stores_done();
-      __syncthreads();
+      wait_all();
+      __builtin_amdgcn_s_barrier();
       if (tid == 0) __hip_atomic_store(&a.ws.ready[lhb], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     } else {
       if (tid == 0) {
         int polls = 0;
         while (__hip_atomic_load(&a.ws.ready[lhb], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) {
-          __builtin_amdgcn_s_sleep(4);
+          __builtin_amdgcn_s_sleep(2);
           if (++polls > a.spin_limit) {
             if (a.dev_status) atomicOr(a.dev_status, SKIPKV_DEV_TIMEOUT);
             break;
           }
         }
       }
-      __syncthreads();
+      __builtin_amdgcn_s_barrier();
     }
 
     // ---- token importance from the logits still in registers
@@ -377,7 +494,7 @@ __global__ void __launch_bounds__(256) k_scan_fused(ScanArgs a) {
 #pragma unroll
         for (int i = 0; i < NP; ++i) {
           const int q = al * NP + i;
-          gm = fmaxf(gm, acc[s][q >> 2][q & 3] - cn[q]);  // logits were scaled and masked in the first phase
+          gm = fmaxf(gm, fmaf(acc[s][q >> 2][q & 3], kScale2, -cn[q]));  // masked logits are -inf already
         }
         sum += __builtin_amdgcn_exp2f(gm);
       }
@@ -385,9 +502,9 @@ __global__ void __launch_bounds__(256) k_scan_fused(ScanArgs a) {
       sum += __shfl_xor(sum, 32);
       if (g == 0) imp[wave * kCapW + 16 * s + c16] = (t < w1) ? sum * inv_alpha : 0.f;
     }
-    __syncthreads();
+    lds_barrier();
     const int p_start = n_tok - min(a.protect, n_tok);
-    const int64_t tok_col = (int64_t)lh * a.total_tokens + ch.tok0;
+    const int64_t tok_col = (int64_t)lh * a.total_tokens + cur.tok0;
     if (tid < ns) {
       const int lo = soff[tid], hi = min(soff[tid + 1], p_start);
       float sum_i = 0.f, sum_r = 0.f;
@@ -401,6 +518,9 @@ __global__ void __launch_bounds__(256) k_scan_fused(ScanArgs a) {
     }
     if (a.tok_imp)
       for (int i = tid; i < t_end - t_begin; i += 256) a.tok_imp[tok_col + t_begin + i] = imp[i];
+    lds_barrier();  // imp, the offsets and the partial buffers are free again; the next item's query tile is in place
+    cur = nxt;
+    sb ^= 1;
   }
 }
 
