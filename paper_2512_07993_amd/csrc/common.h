@@ -11,7 +11,7 @@ namespace skipkv {
 constexpr int kD = SKIPKV_HEAD_DIM;  // head dimension
 constexpr int kChunkCap = 256;       // a chunk of scan work = a maximal run of whole sentences of at most this many tokens
 constexpr int kChunkMaxSent = 32;    // ... and at most this many sentences (a single longer sentence is a chunk of its own)
-constexpr int kFuseMaxChunks = 256;  // sequences with more chunks than this take the two-pass scan (see scan_fused.hip)
+constexpr int kFuseMaxChunks = 512;  // sequences with more chunks than this take the two-pass scan (see scan_fused.hip)
 constexpr int kRowBlock = 64;        // sentences per row block of the redundancy kernel
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
@@ -35,7 +35,8 @@ struct PlanHeader {
   int32_t n_chunks;
   int32_t n_rowblocks;
   int32_t n_unfused;  // number of sequences that take the two-pass scan
-  int32_t pad[61];
+  int32_t n_pairs;    // number of chunk pairs (units of the single-pass scan)
+  int32_t pad[60];
 };
 
 // Carved-up view of the caller's workspace.  All sections 256-byte aligned.
@@ -46,6 +47,8 @@ struct Workspace {
   int32_t *rb_base;      // [B] first row block of each sequence
   int32_t *rb_cnt;       // [B]
   int32_t *seq_fused;    // [B] 1: the sequence goes through the single-pass scan
+  int32_t *pair_first;   // [nc_max] first chunk of every pair of consecutive chunks of one sequence
+  int32_t *pair_cnt;     // [B] number of pairs of each sequence
   int32_t *arrive;       // [LH, B] chunks of the head that have published their row statistics
   int32_t *ready;        // [LH, B] 1 once the head's row normalisers are final
   Chunk *chunks;         // [nc_max]

@@ -12,6 +12,7 @@ __global__ void k_plan_reset(PlanHeader *hdr, int32_t *flags, int n_flags) {
     hdr->n_chunks = 0;
     hdr->n_rowblocks = 0;
     hdr->n_unfused = 0;
+    hdr->n_pairs = 0;
   }
   for (int j = i; j < n_flags; j += gridDim.x * blockDim.x) flags[j] = 0;
 }
@@ -67,6 +68,7 @@ __global__ void __launch_bounds__(256) k_plan(PlanArgs a) {
     a.ws.rb_base[b] = 0;
     a.ws.rb_cnt[b] = 0;
     a.ws.seq_fused[b] = 1;  // nothing to scan either way
+    a.ws.pair_cnt[b] = 0;
     return;
   }
 
@@ -91,6 +93,11 @@ __global__ void __launch_bounds__(256) k_plan(PlanArgs a) {
     a.ws.chunks[idx++] = Chunk{b, start, e - start, s_off[start], s_off[e] - s_off[start], sp + start, tok0, n_tok};
     start = e;
   }
+  // the single-pass scan works on pairs of consecutive chunks of a sequence
+  const int n_pairs = (n_chunks + 1) / 2;
+  const int pbase = atomicAdd(&a.ws.hdr->n_pairs, n_pairs);
+  a.ws.pair_cnt[b] = n_pairs;
+  for (int j = 0; j < n_pairs; ++j) a.ws.pair_first[pbase + j] = base + 2 * j;
   const int nrb = (n_sent + kRowBlock - 1) / kRowBlock;
   const int rb0 = atomicAdd(&a.ws.hdr->n_rowblocks, nrb);
   a.ws.rb_base[b] = rb0;

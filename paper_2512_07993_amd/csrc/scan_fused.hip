@@ -3,33 +3,35 @@
 //
 // The softmax normaliser of a query row needs all N keys of the head, which are spread over many
 // chunks, i.e. many workgroups.  Instead of a second pass over K, every workgroup keeps the
-// logits of its chunk in registers (they are MFMA accumulators anyway: 64 tokens per wave x all
-// query rows of the GQA group), publishes its chunk's (max, sum exp) per row, and waits until the
-// head's normalisers are final; the last chunk of a head to arrive merges the partials and
-// raises the head's ready flag.  Then each workgroup finishes I[t] from its registers.
+// logits of its share in registers (they are MFMA accumulators anyway: per wave 64 tokens x all
+// query rows of the GQA group, for each of two consecutive chunks), publishes the (max, sum exp)
+// of every row over its share, and waits until the head's normalisers are final; the last
+// share of a head to arrive merges the partials and raises the head's ready flag.  Then each
+// workgroup finishes I[t] from its registers.  A unit of work ("item") is a PAIR of consecutive
+// chunks of one head, so that the cross-workgroup round trips are paid once per 512 tokens.
 //
 // Forward progress.  The grid is persistent and no larger than what is co-resident on the chip
 // (occupancy query on the host).  Workgroup w takes items w, w+G, w+2G, ... in increasing order,
-// items being (head, chunk) pairs with a head's chunks consecutive.  A workgroup only ever waits
-// for the head of the item it has just published.  Since a head has at most kFuseMaxChunks <= G
-// chunks, its chunks belong to distinct workgroups, each of which reaches its chunk of that head
-// without waiting on that head first; by induction over heads in item order every wait ends.
-// The wait is bounded anyway (spin_limit polls): on expiry SKIPKV_DEV_TIMEOUT is raised and the
-// kernel runs to completion with invalid scores rather than hanging.
+// a head's items being consecutive.  A workgroup only ever waits for the head of the item it has
+// just published.  Since a head has at most kFuseMaxChunks/2 <= G items, they belong to distinct
+// workgroups, each of which reaches its item of that head without waiting on that head first;
+// by induction over heads in item order every wait ends.  The wait is bounded anyway
+// (spin_limit polls): on expiry SKIPKV_DEV_TIMEOUT is raised and the kernel runs to completion
+// with invalid scores rather than hanging.
 //
 // Data movement.  Inside a workgroup the 4 waves are independent streams: wave w owns tokens
-// [64w, 64w+64) of the chunk, in stages of 16 rows.  Rows go HBM -> LDS directly
+// [64w, 64w+64) of each chunk, in stages of 16 rows.  Rows go HBM -> LDS directly
 // (global_load_lds, 16 bytes per lane, no staging registers) into a ring of NBUF stage buffers
 // private to the wave, and the wave always keeps NBUF-1 stages in flight ahead of the one it is
-// computing on - also across the end of an item, so the synchronisation at the end of a chunk
+// computing on - also across the end of an item, so the synchronisation at the end of an item
 // overlaps with the first loads of the next one.  A direct load writes LDS at base + lane*16, so
 // rows are stored unpadded; bank conflicts are avoided by an XOR swizzle instead: the 16-byte
 // piece p of row r is kept at piece position p ^ (r & 15), which each lane arranges by choosing
 // which global piece it fetches.
 //
 // Pooling.  A sentence that lies inside one wave's range is normalised and written straight from
-// registers; the (at most 3) sentences that cross wave boundaries are pieced together through
-// LDS in a fixed order, so results are reproducible.
+// registers; the (at most 3 per chunk) sentences that cross wave boundaries are pieced together
+// through LDS in a fixed order, so results are reproducible.
 #include "scan_common.h"
 
 namespace skipkv {
@@ -38,12 +40,12 @@ namespace {
 
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
 
-constexpr int kCapW = kChunkCap / 4;  // tokens per wave
+constexpr int kCapW = kChunkCap / 4;  // tokens per wave per chunk
 constexpr int kStageRows = 16;        // rows per pipeline stage = one MFMA sub-tile of tokens
 constexpr int kStagesPerWave = kCapW / kStageRows;
 
 // Cross-workgroup communication (the workgroups may sit on different XCDs, whose L2 caches are not
-// coherent with each other).  Everything that is communicated - chunk statistics, row normalisers,
+// coherent with each other).  Everything that is communicated - share statistics, row normalisers,
 // the arrive counter and the ready flag - is accessed ONLY with device-scope relaxed atomics, which
 // are coherent by themselves; ordering comes from waiting until the data stores have been
 // acknowledged before the counter or flag is touched, and from program order plus a workgroup
@@ -89,6 +91,37 @@ __device__ __forceinline__ void load_to_lds_16(const void *gsrc, void *wave_lds_
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(l), "v"(gsrc) : "memory");
 }
 
+// Row (16-lane) reductions with the DPP modifier on the arithmetic instruction itself: one
+// instruction per step.  The s_nop covers the two wait states a DPP read needs after a VALU write.
+#define SKIPKV_DPP_STEP(OP, N)                                                                          \
+  asm volatile("s_nop 1\n\t" OP " %0, %1, %1 row_ror:" #N " row_mask:0xf bank_mask:0xf" : "=v"(v) : "v"(v))
+__device__ __forceinline__ float row16_max_fast(float v) {
+  SKIPKV_DPP_STEP("v_max_f32_dpp", 8);
+  SKIPKV_DPP_STEP("v_max_f32_dpp", 4);
+  SKIPKV_DPP_STEP("v_max_f32_dpp", 2);
+  SKIPKV_DPP_STEP("v_max_f32_dpp", 1);
+  return v;
+}
+__device__ __forceinline__ float row16_sum_fast(float v) {
+  SKIPKV_DPP_STEP("v_add_f32_dpp", 8);
+  SKIPKV_DPP_STEP("v_add_f32_dpp", 4);
+  SKIPKV_DPP_STEP("v_add_f32_dpp", 2);
+  SKIPKV_DPP_STEP("v_add_f32_dpp", 1);
+  return v;
+}
+#undef SKIPKV_DPP_STEP
+
+struct ChunkD {  // one chunk as seen by one wave
+  int ns, t_begin, t_end, soff_idx;
+  int w0, w1, nst;  // the wave's token range and its number of stages
+};
+struct Pair {  // one item
+  uint32_t item;  // >= n_items: none
+  int lh, b, c0, nch, n_tok, tok0;
+  const char *kbase;
+  ChunkD ch[2];
+};
+
 template <int DT, int NP, int AL>
 __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused(ScanArgs a) {
   constexpr int SL = NP * AL;
@@ -105,18 +138,18 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
 
   __shared__ __align__(16) char kt[4][NBUF][STAGEB];
   __shared__ __align__(16) char qt[R * LSTR];
-  __shared__ int soff_buf[2][kChunkMaxSent + 2];
-  __shared__ float part_first[4][kD];  // key sum, over this wave's range, of the sentence already running at its start
-  __shared__ float part_last[4][kD];   // key sum of the sentence that starts in this wave's range and runs past its end
+  __shared__ int soff_buf[2][2][kChunkMaxSent + 2];  // [item parity][chunk of the pair]
+  __shared__ float part_first[2][4][kD];  // key sum, over a wave's range, of the sentence already running at its start
+  __shared__ float part_last[2][4][kD];   // key sum of the sentence that starts in a wave's range and runs past its end
   __shared__ float wstat[4][R][2];
-  __shared__ float imp[kChunkCap];
+  __shared__ float imp[2][kChunkCap];
   __shared__ int s_flag;
 
   const int tid = threadIdx.x, lane = tid & 63, c16 = lane & 15, g = lane >> 4;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: everything derived from it is uniform control flow
   const int n_lh = a.n_layers * a.n_kv_heads;
-  const int n_chunks = a.ws.hdr->n_chunks;
-  const uint32_t n_items = (uint32_t)n_lh * (uint32_t)n_chunks;
+  const int n_pairs = a.ws.hdr->n_pairs;
+  const uint32_t n_items = (uint32_t)n_lh * (uint32_t)n_pairs;
   const int n = a.n_q_heads / a.n_kv_heads;
   const int64_t tok_pitch = a.stride_tok * ESZ;
   const float inv_alpha = 1.f / (float)a.alpha;
@@ -129,50 +162,46 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
   const ConstIntPtr seq_fused_c = (ConstIntPtr)a.ws.seq_fused;
   const ConstIntPtr chunk_cnt_c = (ConstIntPtr)a.ws.chunk_cnt;
   const ConstIntPtr chunk_base_c = (ConstIntPtr)a.ws.chunk_base;
+  const ConstIntPtr pair_first_c = (ConstIntPtr)a.ws.pair_first;
+  const ConstIntPtr pair_cnt_c = (ConstIntPtr)a.ws.pair_cnt;
 
   // ---- item descriptors ------------------------------------------------------------------
-  struct Item {
-    uint32_t item;     // >= n_items: none
-    int lh, c, b, ns, t_begin, t_end, n_tok, tok0, soff_idx;
-    int w0, w1, nst;   // this wave's token range and number of stages
-    const char *kbase;
+  auto load_chunk = [&](int c) -> ChunkD {
+    ChunkD d;
+    d.ns = chunks_c[8 * c + 2];
+    d.t_begin = chunks_c[8 * c + 3];
+    d.t_end = d.t_begin + chunks_c[8 * c + 4];
+    d.soff_idx = chunks_c[8 * c + 5];
+    d.w0 = d.t_begin + wave * kCapW;
+    d.w1 = min(d.w0 + kCapW, d.t_end);
+    d.nst = d.w1 > d.w0 ? (d.w1 - d.w0 + kStageRows - 1) / kStageRows : 0;
+    return d;
   };
-  auto load_item = [&](uint32_t item) -> Item {  // first fused item at or after `item` in this workgroup's sequence
-    Item it{};
+  auto load_pair = [&](uint32_t item) -> Pair {  // first fused item at or after `item` in this workgroup's sequence
+    Pair it{};
     for (; item < n_items; item += gridDim.x) {
-      const int c = item % n_chunks;
-      Chunk ch;
-      ch.b = chunks_c[8 * c + 0];
-      ch.s0 = chunks_c[8 * c + 1];
-      ch.ns = chunks_c[8 * c + 2];
-      ch.t_begin = chunks_c[8 * c + 3];
-      ch.len = chunks_c[8 * c + 4];
-      ch.soff_idx = chunks_c[8 * c + 5];
-      ch.tok0 = chunks_c[8 * c + 6];
-      ch.n_tok = chunks_c[8 * c + 7];
-      if (!seq_fused_c[ch.b]) continue;
-      it.lh = item / n_chunks;
-      it.c = c;
-      it.b = ch.b;
-      it.ns = ch.ns;
-      it.t_begin = ch.t_begin;
-      it.t_end = ch.t_begin + ch.len;
-      it.n_tok = ch.n_tok;
-      it.tok0 = ch.tok0;
-      it.soff_idx = ch.soff_idx;
-      it.w0 = ch.t_begin + wave * kCapW;
-      it.w1 = min(it.w0 + kCapW, it.t_end);
-      it.nst = it.w1 > it.w0 ? (it.w1 - it.w0 + kStageRows - 1) / kStageRows : 0;
+      const int c0 = pair_first_c[item % n_pairs];
+      const int b = chunks_c[8 * c0 + 0];
+      if (!seq_fused_c[b]) continue;
+      it.lh = item / n_pairs;
+      it.b = b;
+      it.c0 = c0;
+      it.nch = (c0 + 1 - chunk_base_c[b] < chunk_cnt_c[b]) ? 2 : 1;
+      it.tok0 = chunks_c[8 * c0 + 6];
+      it.n_tok = chunks_c[8 * c0 + 7];
+      it.ch[0] = load_chunk(c0);
+      it.ch[1] = it.nch == 2 ? load_chunk(c0 + 1) : ChunkD{};
       const int l = it.lh / a.n_kv_heads, h = it.lh % a.n_kv_heads;
       it.kbase = static_cast<const char *>(a.k) +
-                 ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head + (int64_t)ch.tok0 * a.stride_tok) * ESZ;
+                 ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head + (int64_t)it.tok0 * a.stride_tok) * ESZ;
       break;
     }
     it.item = item;
     return it;
   };
-  auto load_q_soff = [&](const Item &it, int sbuf) {  // queries of the group -> LDS (padded rows), sentence offsets
-    if (tid <= it.ns) soff_buf[sbuf][tid] = a.sent_off[it.soff_idx + tid];
+  auto load_q_soff = [&](const Pair &it, int par) {  // queries of the group -> LDS (padded rows), sentence offsets
+    if (tid <= it.ch[0].ns) soff_buf[par][0][tid] = a.sent_off[it.ch[0].soff_idx + tid];
+    if (it.nch == 2 && tid >= 64 && tid - 64 <= it.ch[1].ns) soff_buf[par][1][tid - 64] = a.sent_off[it.ch[1].soff_idx + tid - 64];
     const char *qbase = static_cast<const char *>(a.q);
     const int l = it.lh / a.n_kv_heads, h = it.lh % a.n_kv_heads;
     for (int r0 = 0; r0 < R; r0 += 256 / PPR) {
@@ -188,23 +217,30 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     }
   };
 
-  // ---- the wave's load stream: stages of consecutive items, NBUF-1 ahead of the compute ------
-  Item iss = load_item(blockIdx.x);  // item whose stages are being issued
-  int iss_st = 0;                    // next stage of `iss` to issue
+  // ---- the wave's load stream: stages of consecutive chunks, NBUF-1 ahead of the compute ------
+  Pair iss = load_pair(blockIdx.x);  // item whose stages are being issued
+  int iss_k = 0;                     // ... chunk of that item
+  int iss_st = 0;                    // ... next stage of that chunk
   uint32_t iss_cnt = 0;              // stages issued so far (ring position)
   auto issue_next = [&]() -> bool {
-    while (iss.item < n_items && iss_st >= iss.nst) {
-      iss = load_item(iss.item + gridDim.x);
+    while (iss.item < n_items && iss_st >= (iss_k ? iss.ch[1].nst : iss.ch[0].nst)) {
+      if (iss_k + 1 < iss.nch) {
+        ++iss_k;
+      } else {
+        iss = load_pair(iss.item + gridDim.x);
+        iss_k = 0;
+      }
       iss_st = 0;
     }
     if (iss.item >= n_items) return false;
     char *dst = kt[wave][iss_cnt % NBUF];
-    const int ts = iss.w0 + iss_st * kStageRows;
+    const int ts = (iss_k ? iss.ch[1].w0 : iss.ch[0].w0) + iss_st * kStageRows;
+    const int w1 = iss_k ? iss.ch[1].w1 : iss.ch[0].w1;
 #pragma unroll
     for (int j = 0; j < GL; ++j) {
-      const int row = j * RPL + lane / PPR;                       // row of the stage this lane's 16 bytes belong to
-      const int piece = (lane % PPR) ^ (row & 15);                // swizzle: LDS position (lane % PPR) holds this global piece
-      const int t = min(ts + row, iss.w1 - 1);                    // rows past the range re-read its last row (masked later)
+      const int row = j * RPL + lane / PPR;         // row of the stage this lane's 16 bytes belong to
+      const int piece = (lane % PPR) ^ (row & 15);  // swizzle: LDS position (lane % PPR) holds this global piece
+      const int t = min(ts + row, w1 - 1);          // rows past the range re-read its last row (masked later)
       load_to_lds_16(iss.kbase + (int64_t)t * tok_pitch + piece * 16, dst + j * 1024);
     }
     ++iss_st;
@@ -212,53 +248,30 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     return true;
   };
 
-  Item cur = load_item(blockIdx.x);
+  Pair cur = load_pair(blockIdx.x);
   if (cur.item >= n_items) return;
 #pragma unroll
   for (int i = 0; i < NBUF - 1; ++i) issue_next();
   uint32_t cmp_cnt = 0;  // stages computed so far (ring position)
-  int sb = 0;            // which soff buffer holds the current item's offsets
-  load_q_soff(cur, sb);
+  int par = 0;           // which soff buffers hold the current item's offsets
+  load_q_soff(cur, par);
   lds_barrier();
 
   while (cur.item < n_items) {
-    const int *soff = soff_buf[sb];
-    const int lh = cur.lh, c = cur.c, b = cur.b, ns = cur.ns;
-    const int t_begin = cur.t_begin, t_end = cur.t_end, n_tok = cur.n_tok;
-    const int w0 = cur.w0, w1 = cur.w1;
-    const int sent_col0 = cur.soff_idx - b;
+    const int lh = cur.lh, b = cur.b;
+    const int n_tok = cur.n_tok;
     const int lhb = lh * a.batch + b;
     const int last_free = n_tok - a.alpha;  // keys t <= last_free are visible to every window query
 
-    f32x4 acc[SUBS][NT];
+    f32x4 acc[2][SUBS][NT];
     float ref[SLP], lsum[SLP];
 #pragma unroll
     for (int q = 0; q < SLP; ++q) {
       ref[q] = kRefInit;
       lsum[q] = 0.f;
     }
-#pragma unroll
-    for (int s = 0; s < SUBS; ++s)
-#pragma unroll
-      for (int T = 0; T < NT; ++T) acc[s][T] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // bf16: the query operand of the matrix products lives in registers for the whole item
-    // (read from LDS once per item instead of once per stage)
-    bf16x8 qa[NT][4];
-    if constexpr (DT == SKIPKV_BF16) {
-#pragma unroll
-      for (int T = 0; T < NT; ++T)
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk)
-          qa[T][kk] = *reinterpret_cast<const bf16x8 *>(qt + (16 * T + c16) * LSTR + g * 64 + kk * 16);
-    }
-
-    // sentence pooling state: current sentence, its running key sum (lane = 2 head-dim columns)
-    int si = 0;
-    float ps0 = 0.f, ps1 = 0.f;
-    if (w0 < w1) si = __popcll(__ballot(lane < ns && soff[lane + 1] <= w0));
-
-    auto emit_sentence = [&](int s_idx, float k0, float k1) {  // unit embedding, bf16 hi + lo
+    auto emit_sentence = [&](const int *soff, int sent_col0, int s_idx, float k0, float k1) {  // unit embedding, bf16 hi + lo
       const float inv_len = 1.f / (float)(soff[s_idx + 1] - soff[s_idx]);
       const float m0 = k0 * inv_len, m1 = k1 * inv_len;
       const float inv = 1.f / (sqrtf(wave_sum(m0 * m0 + m1 * m1)) + 1e-12f);
@@ -270,122 +283,150 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
       reinterpret_cast<uint32_t *>(a.ws.vhat_lo)[o] = l0 | (l1 << 16);
     };
 
+    // =============== first phase: logits, row statistics and sentence key sums =================
 #pragma unroll
-    for (int st = 0; st < SUBS; ++st) {
-      if (st < cur.nst) {
-        const int ts = w0 + st * kStageRows, te = min(ts + kStageRows, w1);
-        // keep the load stream NBUF-1 stages ahead, then wait for this stage's rows to land
-        if (issue_next())
-          wait_vm<GL *(NBUF - 1)>();
-        else
-          wait_all();
-        const char *stage = kt[wave][cmp_cnt % NBUF];
-        ++cmp_cnt;
+    for (int k = 0; k < 2; ++k) {
+#pragma unroll
+      for (int s = 0; s < SUBS; ++s)
+#pragma unroll
+        for (int T = 0; T < NT; ++T) acc[k][s][T] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (k < cur.nch) {
+        const ChunkD &cd = cur.ch[k];
+        const int *soff = soff_buf[par][k];
+        const int ns = cd.ns, w0 = cd.w0, w1 = cd.w1;
+        const int sent_col0 = cd.soff_idx - b;
+        // sentence pooling state: current sentence, its running key sum (lane = 2 head-dim columns)
+        int si = 0;
+        float ps0 = 0.f, ps1 = 0.f;
+        if (w0 < w1) si = __popcll(__ballot(lane < ns && soff[lane + 1] <= w0));
 
-        // ---- logits of this stage's 16 tokens against all query rows
-        if constexpr (DT == SKIPKV_BF16) {
 #pragma unroll
-          for (int kk = 0; kk < 4; ++kk) {
-            const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(stage + c16 * ROWB + (((4 * g + kk) ^ c16) * 16));
-#pragma unroll
-            for (int T = 0; T < NT; ++T)
-              acc[st][T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[T][kk], bfrag, acc[st][T], 0, 0, 0);
-          }
-        } else {
-#pragma unroll
-          for (int cc = 0; cc < 8; ++cc) {
-            const float4 bfrag = *reinterpret_cast<const float4 *>(stage + c16 * ROWB + (((4 * cc + g) ^ c16) * 16));
-#pragma unroll
-            for (int T = 0; T < NT; ++T) {
-              const float4 afrag = *reinterpret_cast<const float4 *>(qt + (16 * T + c16) * LSTR + cc * 64 + g * 16);
-              acc[st][T] = __builtin_amdgcn_mfma_f32_16x16x4f32(afrag.x, bfrag.x, acc[st][T], 0, 0, 0);
-              acc[st][T] = __builtin_amdgcn_mfma_f32_16x16x4f32(afrag.y, bfrag.y, acc[st][T], 0, 0, 0);
-              acc[st][T] = __builtin_amdgcn_mfma_f32_16x16x4f32(afrag.z, bfrag.z, acc[st][T], 0, 0, 0);
-              acc[st][T] = __builtin_amdgcn_mfma_f32_16x16x4f32(afrag.w, bfrag.w, acc[st][T], 0, 0, 0);
-            }
-          }
-        }
+        for (int st = 0; st < SUBS; ++st) {
+          if (st < cd.nst) {
+            const int ts = w0 + st * kStageRows, te = min(ts + kStageRows, w1);
+            // keep the load stream NBUF-1 stages ahead, then wait for this stage's rows to land
+            if (issue_next())
+              wait_vm<GL *(NBUF - 1)>();
+            else
+              wait_all();
+            const char *stage = kt[wave][cmp_cnt % NBUF];
+            ++cmp_cnt;
 
-        // ---- running softmax statistics of every query row (accumulators stay unscaled)
-        {
-          const int t = ts + c16;
-          const bool edge = (ts + 15 >= te) || (ts + 15 > last_free);
-          if (edge) {
+            // ---- logits of this stage's 16 tokens against all query rows
+            if constexpr (DT == SKIPKV_BF16) {
 #pragma unroll
-            for (int q = 0; q < SLP; ++q) {
-              const int aq = g + 4 * (q / NP);
-              if (!(t < te && t <= last_free + aq)) acc[st][q >> 2][q & 3] = -INFINITY;
-            }
-          }
-          bool need = false;
+              for (int kk = 0; kk < 4; ++kk) {
+                const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(stage + c16 * ROWB + (((4 * g + kk) ^ c16) * 16));
 #pragma unroll
-          for (int q = 0; q < SLP; ++q) need |= acc[st][q >> 2][q & 3] * kScale2 > ref[q] + kRescaleSlack;
-          if (__any(need)) {
-#pragma unroll
-            for (int q = 0; q < SLP; ++q) {
-              const float nr = fmaxf(ref[q], row16_max(acc[st][q >> 2][q & 3]) * kScale2);
-              lsum[q] *= __builtin_amdgcn_exp2f(ref[q] - nr);
-              ref[q] = nr;
-            }
-          }
-#pragma unroll
-          for (int q = 0; q < SLP; ++q) lsum[q] += __builtin_amdgcn_exp2f(fmaf(acc[st][q >> 2][q & 3], kScale2, -ref[q]));
-        }
-
-        // ---- sentence key sums over tokens [ts, te), walked in order
-        int t = ts;
-        while (t < te) {
-          const int run_end = min(soff[si + 1], te);
-          if (run_end <= t) break;  // cannot happen with validated offsets; never spin on bad ones
-          float q0 = 0.f, q1 = 0.f;
-          int r = t - ts;            // row within the stage
-          int cnt = run_end - t;
-          if constexpr (DT == SKIPKV_BF16) {
-            // lane = dword `lane` of the row = piece lane/4 (swizzled by the row), bytes (lane%4)*4
-            const bf16x2_t ones = __builtin_bit_cast(bf16x2_t, 0x3F803F80u);
-            for (; cnt >= 2; cnt -= 2, r += 2) {
-              const uint32_t wa = *reinterpret_cast<const uint32_t *>(stage + r * ROWB + (((lane >> 2) ^ (r & 15)) * 16) + (lane & 3) * 4);
-              const uint32_t wb = *reinterpret_cast<const uint32_t *>(stage + (r + 1) * ROWB + (((lane >> 2) ^ ((r + 1) & 15)) * 16) + (lane & 3) * 4);
-              // (lo_a, lo_b) and (hi_a, hi_b) pairs, each summed into fp32 by one dot instruction
-              q0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, __builtin_amdgcn_perm(wb, wa, 0x05040100u)), ones, q0, false);
-              q1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, __builtin_amdgcn_perm(wb, wa, 0x07060302u)), ones, q1, false);
-            }
-            if (cnt) {
-              const uint32_t wa = *reinterpret_cast<const uint32_t *>(stage + r * ROWB + (((lane >> 2) ^ (r & 15)) * 16) + (lane & 3) * 4);
-              q0 += __uint_as_float(wa << 16);
-              q1 += __uint_as_float(wa & 0xFFFF0000u);
-            }
-          } else {
-            for (; cnt > 0; --cnt, ++r) {
-              const float2 wa = *reinterpret_cast<const float2 *>(stage + r * ROWB + (((lane >> 1) ^ (r & 15)) * 16) + (lane & 1) * 8);
-              q0 += wa.x;
-              q1 += wa.y;
-            }
-          }
-          ps0 += q0;
-          ps1 += q1;
-          t = run_end;
-          if (t == soff[si + 1]) {  // the sentence ends here
-            if (soff[si] >= w0) {
-              emit_sentence(si, ps0, ps1);
+                for (int T = 0; T < NT; ++T) {
+                  const bf16x8 afrag = *reinterpret_cast<const bf16x8 *>(qt + (16 * T + c16) * LSTR + g * 64 + kk * 16);
+                  acc[k][st][T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag, acc[k][st][T], 0, 0, 0);
+                }
+              }
             } else {
-              part_first[wave][2 * lane] = ps0;
-              part_first[wave][2 * lane + 1] = ps1;
+#pragma unroll
+              for (int cc = 0; cc < 8; ++cc) {
+                const float4 bfrag = *reinterpret_cast<const float4 *>(stage + c16 * ROWB + (((4 * cc + g) ^ c16) * 16));
+#pragma unroll
+                for (int T = 0; T < NT; ++T) {
+                  const float4 afrag = *reinterpret_cast<const float4 *>(qt + (16 * T + c16) * LSTR + cc * 64 + g * 16);
+                  acc[k][st][T] = __builtin_amdgcn_mfma_f32_16x16x4f32(afrag.x, bfrag.x, acc[k][st][T], 0, 0, 0);
+                  acc[k][st][T] = __builtin_amdgcn_mfma_f32_16x16x4f32(afrag.y, bfrag.y, acc[k][st][T], 0, 0, 0);
+                  acc[k][st][T] = __builtin_amdgcn_mfma_f32_16x16x4f32(afrag.z, bfrag.z, acc[k][st][T], 0, 0, 0);
+                  acc[k][st][T] = __builtin_amdgcn_mfma_f32_16x16x4f32(afrag.w, bfrag.w, acc[k][st][T], 0, 0, 0);
+                }
+              }
             }
-            ps0 = ps1 = 0.f;
-            ++si;
+
+            // ---- running softmax statistics of every query row (accumulators stay unscaled)
+            {
+              const int t = ts + c16;
+              const bool edge = (ts + 15 >= te) || (ts + 15 > last_free);
+              if (edge) {
+#pragma unroll
+                for (int q = 0; q < SLP; ++q) {
+                  const int aq = g + 4 * (q / NP);
+                  if (!(t < te && t <= last_free + aq)) acc[k][st][q >> 2][q & 3] = -INFINITY;
+                }
+              }
+              // exponent arguments relative to the running references; one test tells whether any of
+              // them has outgrown its reference (then the references are refreshed, rarely)
+              float e[SLP];
+              float emax = -INFINITY;
+#pragma unroll
+              for (int q = 0; q < SLP; ++q) {
+                e[q] = fmaf(acc[k][st][q >> 2][q & 3], kScale2, -ref[q]);
+                emax = fmaxf(emax, e[q]);
+              }
+              if (__any(emax > kRescaleSlack)) {
+#pragma unroll
+                for (int q = 0; q < SLP; ++q) {
+                  const float nr = fmaxf(ref[q], row16_max_fast(acc[k][st][q >> 2][q & 3]) * kScale2);
+                  lsum[q] *= __builtin_amdgcn_exp2f(ref[q] - nr);
+                  ref[q] = nr;
+                  e[q] = fmaf(acc[k][st][q >> 2][q & 3], kScale2, -nr);
+                }
+              }
+#pragma unroll
+              for (int q = 0; q < SLP; ++q) lsum[q] += __builtin_amdgcn_exp2f(e[q]);
+            }
+
+            // ---- sentence key sums over tokens [ts, te), walked in order
+            int t = ts;
+            while (t < te) {
+              const int run_end = min(soff[si + 1], te);
+              if (run_end <= t) break;  // cannot happen with validated offsets; never spin on bad ones
+              float q0 = 0.f, q1 = 0.f;
+              int r = t - ts;  // row within the stage
+              int cnt = run_end - t;
+              if constexpr (DT == SKIPKV_BF16) {
+                // lane = dword `lane` of the row = piece lane/4 (swizzled by the row), bytes (lane%4)*4
+                const bf16x2_t ones = __builtin_bit_cast(bf16x2_t, 0x3F803F80u);
+                for (; cnt >= 2; cnt -= 2, r += 2) {
+                  const uint32_t wa = *reinterpret_cast<const uint32_t *>(stage + r * ROWB + (((lane >> 2) ^ (r & 15)) * 16) + (lane & 3) * 4);
+                  const uint32_t wb = *reinterpret_cast<const uint32_t *>(stage + (r + 1) * ROWB + (((lane >> 2) ^ ((r + 1) & 15)) * 16) + (lane & 3) * 4);
+                  // (lo_a, lo_b) and (hi_a, hi_b) pairs, each summed into fp32 by one dot instruction
+                  q0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, __builtin_amdgcn_perm(wb, wa, 0x05040100u)), ones, q0, false);
+                  q1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, __builtin_amdgcn_perm(wb, wa, 0x07060302u)), ones, q1, false);
+                }
+                if (cnt) {
+                  const uint32_t wa = *reinterpret_cast<const uint32_t *>(stage + r * ROWB + (((lane >> 2) ^ (r & 15)) * 16) + (lane & 3) * 4);
+                  q0 += __uint_as_float(wa << 16);
+                  q1 += __uint_as_float(wa & 0xFFFF0000u);
+                }
+              } else {
+                for (; cnt > 0; --cnt, ++r) {
+                  const float2 wa = *reinterpret_cast<const float2 *>(stage + r * ROWB + (((lane >> 1) ^ (r & 15)) * 16) + (lane & 1) * 8);
+                  q0 += wa.x;
+                  q1 += wa.y;
+                }
+              }
+              ps0 += q0;
+              ps1 += q1;
+              t = run_end;
+              if (t == soff[si + 1]) {  // the sentence ends here
+                if (soff[si] >= w0) {
+                  emit_sentence(soff, sent_col0, si, ps0, ps1);
+                } else {
+                  part_first[k][wave][2 * lane] = ps0;
+                  part_first[k][wave][2 * lane + 1] = ps1;
+                }
+                ps0 = ps1 = 0.f;
+                ++si;
+              }
+            }
           }
+        }
+        if (w0 < w1 && si < ns && soff[si] < w1 && w1 < soff[si + 1]) {  // a sentence is still running at the end of this wave's range
+          float *dst = (soff[si] >= w0) ? part_last[k][wave] : part_first[k][wave];
+          dst[2 * lane] = ps0;
+          dst[2 * lane + 1] = ps1;
         }
       }
     }
-    if (w0 < w1 && si < ns && soff[si] < w1 && w1 < soff[si + 1]) {  // a sentence is still running at the end of this wave's range
-      float *dst = (soff[si] >= w0) ? part_last[wave] : part_first[wave];
-      dst[2 * lane] = ps0;
-      dst[2 * lane + 1] = ps1;
-    }
 #pragma unroll
     for (int q = 0; q < SLP; ++q) {
-      const float tot = row16_sum(lsum[q]);
+      const float tot = row16_sum_fast(lsum[q]);
       if (c16 == 0) {
         const int r = 16 * (q >> 2) + 4 * g + (q & 3);
         wstat[wave][r][0] = ref[q];
@@ -395,18 +436,25 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     lds_barrier();  // every wave is done with the query tile and has left its partials
 
     // ---- sentences that cross wave boundaries: the wave in whose range one starts pieces it together
-    if (w0 < w1) {
-      const int sl = __popcll(__ballot(lane < ns && soff[lane + 1] <= w1 - 1));  // sentence holding the wave's last token
-      if (soff[sl] >= w0 && soff[sl + 1] > w1) {
-        float k0 = part_last[wave][2 * lane], k1 = part_last[wave][2 * lane + 1];
-        for (int w = wave + 1; w < 4 && t_begin + w * kCapW < soff[sl + 1]; ++w) {
-          k0 += part_first[w][2 * lane];
-          k1 += part_first[w][2 * lane + 1];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      if (k < cur.nch) {
+        const ChunkD &cd = cur.ch[k];
+        const int *soff = soff_buf[par][k];
+        if (cd.w0 < cd.w1) {
+          const int sl = __popcll(__ballot(lane < cd.ns && soff[lane + 1] <= cd.w1 - 1));  // sentence holding the wave's last token
+          if (soff[sl] >= cd.w0 && soff[sl + 1] > cd.w1) {
+            float k0 = part_last[k][wave][2 * lane], k1 = part_last[k][wave][2 * lane + 1];
+            for (int w = wave + 1; w < 4 && cd.t_begin + w * kCapW < soff[sl + 1]; ++w) {
+              k0 += part_first[k][w][2 * lane];
+              k1 += part_first[k][w][2 * lane + 1];
+            }
+            emit_sentence(soff, cd.soff_idx - b, sl, k0, k1);
+          }
         }
-        emit_sentence(sl, k0, k1);
       }
     }
-    // ---- publish the chunk's row statistics
+    // ---- publish the share's row statistics (one record per item, filed under its first chunk)
     for (int r = tid; r < R; r += 256) {
       float m = kRefInit;
 #pragma unroll
@@ -414,30 +462,31 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
       float s = 0.f;
 #pragma unroll
       for (int w = 0; w < 4; ++w) s += wstat[w][r][1] * __builtin_amdgcn_exp2f(wstat[w][r][0] - m);
-      coherent_store2(&a.ws.stat_part[((int64_t)lh * a.ws.nc_max + c) * R + r], make_float2(m, s));
+      coherent_store2(&a.ws.stat_part[((int64_t)lh * a.ws.nc_max + cur.c0) * R + r], make_float2(m, s));
     }
     // the next item's queries and offsets can come in now: their latency hides behind the wait below
-    const Item nxt = load_item(cur.item + gridDim.x);
-    if (nxt.item < n_items) load_q_soff(nxt, sb ^ 1);
+    const Pair nxt = load_pair(cur.item + gridDim.x);
+    if (nxt.item < n_items) load_q_soff(nxt, par ^ 1);
     wait_all();  // the statistics are acknowledged (and so are the loads already in flight)
     __builtin_amdgcn_s_barrier();
     if (tid == 0) {
       const int old = __hip_atomic_fetch_add(&a.ws.arrive[lhb], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      s_flag = (old == chunk_cnt_c[b] - 1);
+      s_flag = (old == pair_cnt_c[b] - 1);
     }
     lds_barrier();
     float *rn = a.ws.row_norm + (int64_t)lhb * R;
-    if (s_flag) {  // last chunk of the head to arrive: merge the partials into the normalisers
-      // lane = query row, wave w takes chunks c0+w, c0+w+4, ...; 8 independent loads in flight per lane
-      const int c0 = chunk_base_c[b], nc = chunk_cnt_c[b];
+    if (s_flag) {  // last share of the head to arrive: merge the partials into the normalisers
+      // lane = query row, wave w takes items w, w+4, ...; 8 independent loads in flight per lane
+      const int c_first = chunk_base_c[b], np = pair_cnt_c[b];
       for (int r = lane; r < R; r += 64) {
         float m = kRefInit, s = 0.f;
-        for (int cc = wave; cc < nc; cc += 32) {
+        for (int pp = wave; pp < np; pp += 32) {
           float2 pv[8];
 #pragma unroll
           for (int u = 0; u < 8; ++u) {
             pv[u] = make_float2(kRefInit, 0.f);
-            if (cc + 4 * u < nc) pv[u] = coherent_load2(&a.ws.stat_part[((int64_t)lh * a.ws.nc_max + c0 + cc + 4 * u) * R + r]);
+            if (pp + 4 * u < np)
+              pv[u] = coherent_load2(&a.ws.stat_part[((int64_t)lh * a.ws.nc_max + c_first + 2 * (pp + 4 * u)) * R + r]);
           }
 #pragma unroll
           for (int u = 0; u < 8; ++u) {
@@ -476,7 +525,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
       __builtin_amdgcn_s_barrier();
     }
 
-    // ---- token importance from the logits still in registers
+    // =============== second phase: token importance from the logits still in registers =========
     float cn[SLP];
 #pragma unroll
     for (int q = 0; q < SLP; ++q) {
@@ -485,42 +534,58 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
       cn[q] = used ? coherent_load(&rn[16 * (q >> 2) + 4 * g + (q & 3)]) : INFINITY;
     }
 #pragma unroll
-    for (int s = 0; s < SUBS; ++s) {
-      const int t = w0 + 16 * s + c16;
-      float sum = 0.f;
+    for (int k = 0; k < 2; ++k) {
+      if (k < cur.nch) {
 #pragma unroll
-      for (int al = 0; al < AL; ++al) {
-        float gm = -INFINITY;
+        for (int s = 0; s < SUBS; ++s) {
+          const int t = cur.ch[k].w0 + 16 * s + c16;
+          float sum = 0.f;
 #pragma unroll
-        for (int i = 0; i < NP; ++i) {
-          const int q = al * NP + i;
-          gm = fmaxf(gm, fmaf(acc[s][q >> 2][q & 3], kScale2, -cn[q]));  // masked logits are -inf already
+          for (int al = 0; al < AL; ++al) {
+            float gm = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+              const int q = al * NP + i;
+              gm = fmaxf(gm, fmaf(acc[k][s][q >> 2][q & 3], kScale2, -cn[q]));  // masked logits are -inf already
+            }
+            sum += __builtin_amdgcn_exp2f(gm);
+          }
+          sum += __shfl_xor(sum, 16);
+          sum += __shfl_xor(sum, 32);
+          if (g == 0) imp[k][wave * kCapW + 16 * s + c16] = (t < cur.ch[k].w1) ? sum * inv_alpha : 0.f;
         }
-        sum += __builtin_amdgcn_exp2f(gm);
       }
-      sum += __shfl_xor(sum, 16);
-      sum += __shfl_xor(sum, 32);
-      if (g == 0) imp[wave * kCapW + 16 * s + c16] = (t < w1) ? sum * inv_alpha : 0.f;
     }
     lds_barrier();
     const int p_start = n_tok - min(a.protect, n_tok);
     const int64_t tok_col = (int64_t)lh * a.total_tokens + cur.tok0;
-    if (tid < ns) {
-      const int lo = soff[tid], hi = min(soff[tid + 1], p_start);
-      float sum_i = 0.f, sum_r = 0.f;
-      for (int t = lo; t < hi; ++t) {
-        sum_i += imp[t - t_begin];
-        if (a.tok_red) sum_r += a.tok_red[tok_col + t];
+    {  // sentence means: threads 0..63 take the first chunk's sentences, 64..127 the second's
+      const int k = tid >> 6, s_idx = tid & 63;
+      if (k < cur.nch && s_idx < (k ? cur.ch[1].ns : cur.ch[0].ns)) {
+        const int *soff = soff_buf[par][k];
+        const int t_begin = k ? cur.ch[1].t_begin : cur.ch[0].t_begin;
+        const int sent_col0 = (k ? cur.ch[1].soff_idx : cur.ch[0].soff_idx) - b;
+        const int lo = soff[s_idx], hi = min(soff[s_idx + 1], p_start);
+        float sum_i = 0.f, sum_r = 0.f;
+        for (int t = lo; t < hi; ++t) {
+          sum_i += imp[k][t - t_begin];
+          if (a.tok_red) sum_r += a.tok_red[tok_col + t];
+        }
+        const int64_t o = (int64_t)lh * a.total_sentences + sent_col0 + s_idx;
+        a.ws.sent_imp[o] = hi > lo ? sum_i / (float)(hi - lo) : 0.f;
+        a.ws.sent_red[o] = hi > lo ? sum_r / (float)(hi - lo) : 0.f;
       }
-      const int64_t o = (int64_t)lh * a.total_sentences + sent_col0 + tid;
-      a.ws.sent_imp[o] = hi > lo ? sum_i / (float)(hi - lo) : 0.f;
-      a.ws.sent_red[o] = hi > lo ? sum_r / (float)(hi - lo) : 0.f;
     }
-    if (a.tok_imp)
-      for (int i = tid; i < t_end - t_begin; i += 256) a.tok_imp[tok_col + t_begin + i] = imp[i];
+    if (a.tok_imp) {
+#pragma unroll
+      for (int k = 0; k < 2; ++k)
+        if (k < cur.nch)
+          for (int i = tid; i < cur.ch[k].t_end - cur.ch[k].t_begin; i += 256)
+            a.tok_imp[tok_col + cur.ch[k].t_begin + i] = imp[k][i];
+    }
     lds_barrier();  // imp, the offsets and the partial buffers are free again; the next item's query tile is in place
     cur = nxt;
-    sb ^= 1;
+    par ^= 1;
   }
 }
 
@@ -534,7 +599,7 @@ hipError_t launch_one(const ScanArgs &a, hipStream_t st) {
   e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_scan_fused<DT, NP, AL>, 256, 0);
   if (e != hipSuccess) return e;
   const int grid = cus * per_cu;  // persistent: every workgroup is resident at once
-  if (grid < kFuseMaxChunks) return hipErrorInvalidConfiguration;
+  if (grid < kFuseMaxChunks / 2) return hipErrorInvalidConfiguration;
   hipLaunchKernelGGL((k_scan_fused<DT, NP, AL>), dim3(grid), dim3(256), 0, st, a);
   return hipGetLastError();
 }
