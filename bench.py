@@ -167,6 +167,7 @@ def main() -> int:
     move_bytes = 4 * moved_rows * 128 * esz   # K and V rows that change place: read + write
     step_bytes = k_scan_bytes + move_bytes + q_bytes + off_bytes
     kernel_bytes = {
+        "scan_fused": k_scan_bytes + q_bytes + off_bytes,
         "scan_stats": k_scan_bytes + q_bytes + off_bytes,
         "scan_scores": k_scan_bytes + q_bytes + off_bytes,
         "compact": move_bytes,
