@@ -42,21 +42,69 @@ __global__ void __launch_bounds__(256) k_compact(CompactArgs a) {
     }
   }
 
+  // Software pipeline, two tiles deep.  Tile i's loads may be issued before tile i-1's stores
+  // (a tile only reads rows at or behind its own first row, a tile's stores only write rows of
+  // that tile), so the wave always has one tile of loads and one tile of stores in flight; the
+  // only ordering kept is that a tile's own loads have landed before its stores.  Vector memory
+  // operations complete in issue order, which lets a counted wait express exactly that.  The
+  // tile's source indices come in with one coalesced load, a tile ahead of their use.
   const int sub = lane / PPR, piece = lane % PPR;
-  for (int k0 = first; k0 < nl; k0 += U * RPI) {
-    uint4 regs[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int k = k0 + u * RPI + sub;
-      if (k < nl) regs[u] = *reinterpret_cast<const uint4 *>(base + (int64_t)kept[k] * pitch + piece * 16);
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // every load of the tile has landed before any store is issued
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int k = k0 + u * RPI + sub;
-      if (k < nl) *reinterpret_cast<uint4 *>(base + (int64_t)k * pitch + piece * 16) = regs[u];
-    }
+  constexpr int TR = U * RPI;  // rows per tile
+  static_assert(TR <= 64, "one lane per row index of a tile");
+  auto load_idx = [&](int k0) -> int {  // unconditional (clamped), so that it always counts as one outstanding load
+    return kept[min(k0 + lane, nl - 1)];
+  };
+  if (first >= nl) return;
+  // The two tiles are written out as named registers (A0..A7, B0..B7): arrays carried around the
+  // loop end up in scratch memory with this compiler.
+  static_assert(U == 8, "the tiles below are spelled out for 8 instructions");
+#define SKIPKV_EACH(X, T) X(T, 0) X(T, 1) X(T, 2) X(T, 3) X(T, 4) X(T, 5) X(T, 6) X(T, 7)
+#define SKIPKV_DECL(T, u) uint4 T##u;
+  // always U loads per tile: rows past the end re-read the last kept row (index loads are clamped)
+#define SKIPKV_LOAD(T, u) \
+  T##u = *reinterpret_cast<const uint4 *>(base + (int64_t)__shfl(idx_##T, u * RPI + sub) * pitch + piece * 16);
+#define SKIPKV_STORE(T, u) *reinterpret_cast<uint4 *>(base + (int64_t)(ks + u * RPI + sub) * pitch + piece * 16) = T##u;
+#define SKIPKV_STORE_TAIL(T, u) \
+  if (ks + u * RPI + sub < nl) *reinterpret_cast<uint4 *>(base + (int64_t)(ks + u * RPI + sub) * pitch + piece * 16) = T##u;
+#define SKIPKV_STORE_TILE(T, K0)        \
+  {                                     \
+    const int ks = (K0);                \
+    if (ks + TR <= nl) {                \
+      SKIPKV_EACH(SKIPKV_STORE, T)      \
+    } else {                            \
+      SKIPKV_EACH(SKIPKV_STORE_TAIL, T) \
+    }                                   \
   }
+  // Wait until the loads of the tile about to be stored have landed.  Behind them in the queue
+  // are the previous tile's U stores (none for the first tile), one index load and the next
+  // tile's U loads.  The next tile is always loaded, also past the end (clamped, one tile of
+  // wasted reads per stream): unconditional loads keep the counts exact and the registers in place.
+  SKIPKV_EACH(SKIPKV_DECL, A)
+  SKIPKV_EACH(SKIPKV_DECL, B)
+  int idx_A = load_idx(first);
+  int idx_B = load_idx(first + TR);
+  SKIPKV_EACH(SKIPKV_LOAD, A)
+  for (int k0 = first;; k0 += 2 * TR) {
+    idx_A = load_idx(k0 + 2 * TR);
+    SKIPKV_EACH(SKIPKV_LOAD, B)
+    if (k0 != first)
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * U + 1) : "memory");
+    else
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(U + 1) : "memory");
+    SKIPKV_STORE_TILE(A, k0)
+    if (k0 + TR >= nl) break;
+    idx_B = load_idx(k0 + 3 * TR);
+    SKIPKV_EACH(SKIPKV_LOAD, A)
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * U + 1) : "memory");
+    SKIPKV_STORE_TILE(B, k0 + TR)
+    if (k0 + 2 * TR >= nl) break;
+  }
+#undef SKIPKV_EACH
+#undef SKIPKV_DECL
+#undef SKIPKV_LOAD
+#undef SKIPKV_STORE
+#undef SKIPKV_STORE_TAIL
+#undef SKIPKV_STORE_TILE
 }
 
 }  // namespace
