@@ -2,40 +2,101 @@
 // increasing order of the score until the budget is met; here the unit of eviction is a
 // sentence) and the surviving index set P with the remapped sentence ranges (Eq. 11).
 //
-// One workgroup per head.  Candidates are ranked by (score descending, index descending) with
-// a bitonic sort of 64-bit keys in LDS; since every candidate has length >= 1 the prefix sums
-// of the ranked lengths are strictly increasing, so "longest prefix that fits" is simply
-// "inclusive prefix <= room" for each rank independently.
+// Candidates are ranked by the key (score descending, sentence index descending).  Keys are
+// distinct and every candidate has length >= 1, so the kept set - the longest ranked prefix whose
+// lengths fit the room - is {key > K0}, where K0 is the largest key value for which the total
+// length of {key >= K0} exceeds the room.  K0 is found bit by bit (32 score bits, then 12 index
+// bits); every step is one masked sum over the candidates.  Nothing is sorted.
+//
+// A head with at most 1024 sentences is handled by ONE wave, 16 sentences per lane in registers,
+// without any workgroup barrier; four such heads share a workgroup.  A head with more sentences
+// (up to 4096) is handled afterwards by the four waves together, with the same code.
 #include "common.h"
 
 namespace skipkv {
 
 namespace {
 
-constexpr int kMaxS = SKIPKV_MAX_SENTENCES;
+constexpr int kEPL = 16;                  // sentences per lane
+constexpr int kWaveSent = 64 * kEPL;      // sentences one wave can rank
+static_assert(4 * kWaveSent >= SKIPKV_MAX_SENTENCES, "a workgroup ranks any admissible head");
+static_assert(SKIPKV_MAX_SENTENCES <= (1 << 12), "the index part of the key is searched over 12 bits");
 
-// Inclusive scan of one int per thread over the 256 threads of the block.
-__device__ __forceinline__ int block_scan_incl(int v, int *tmp /*[256]*/, int tid) {
-  tmp[tid] = v;
-  __syncthreads();
-  for (int d = 1; d < 256; d <<= 1) {
-    const int add = tid >= d ? tmp[tid - d] : 0;
-    __syncthreads();
-    tmp[tid] += add;
-    __syncthreads();
-  }
-  return tmp[tid];
+// Sum over the wave in a scalar register: one DPP add per step (rotations inside the rows of 16
+// lanes, then row 0 -> 1 and 2 -> 3, then the lower half -> the upper half; lane 63 has the total).
+__device__ __forceinline__ int wave_sum_i(int v) {
+#define SKIPKV_ROR(N) \
+  asm volatile("s_nop 1\n\tv_add_u32_dpp %0, %1, %1 row_ror:" #N " row_mask:0xf bank_mask:0xf" : "=v"(v) : "v"(v))
+  SKIPKV_ROR(8);
+  SKIPKV_ROR(4);
+  SKIPKV_ROR(2);
+  SKIPKV_ROR(1);
+#undef SKIPKV_ROR
+  // rows that are masked off keep their value, so the operand is read-write (same register)
+  asm volatile("s_nop 1\n\tv_add_u32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf" : "+v"(v));
+  asm volatile("s_nop 1\n\tv_add_u32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf" : "+v"(v));
+  return __builtin_amdgcn_readlane(v, 63);
 }
 
-__global__ void __launch_bounds__(256) k_select(SelectArgs a) {
-  __shared__ unsigned long long keys[kMaxS];
-  __shared__ int dst[kMaxS + 1];       // first: ranked candidate lengths, then destination offsets by sentence
-  __shared__ uint8_t keep[kMaxS];
-  __shared__ int tmp[256];
-  __shared__ int s_total, s_nsurv;
+__device__ __forceinline__ int wave_scan_incl(int v, int lane) {
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int up = __shfl_up(v, d);
+    if (lane >= d) v += up;
+  }
+  return v;
+}
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int lhb = blockIdx.x, lh = lhb / a.batch, b = lhb % a.batch;
+// Cross-wave exchange slots of a workgroup (used only when four waves share a head).  Calls
+// alternate between two sets of slots, so one barrier per call is enough.
+struct Exchange {
+  int *slots;  // [2][4]
+  int call;
+};
+
+template <int NW>
+__device__ __forceinline__ int group_sum(int v, int gw, Exchange &x) {
+  const int s = wave_sum_i(v);
+  if constexpr (NW == 1) {
+    return s;
+  } else {
+    int *slot = x.slots + 4 * (x.call & 1);
+    ++x.call;
+    if ((threadIdx.x & 63) == 0) slot[gw] = s;
+    __syncthreads();
+    return slot[0] + slot[1] + slot[2] + slot[3];
+  }
+}
+
+// Exclusive prefix of v over the group's threads in thread order; `total` gets the group's sum.
+template <int NW>
+__device__ __forceinline__ int group_scan_excl(int v, int gw, int lane, Exchange &x, int &total) {
+  const int incl = wave_scan_incl(v, lane);
+  const int wtot = __builtin_amdgcn_readlane(incl, 63);
+  if constexpr (NW == 1) {
+    total = wtot;
+    return incl - v;
+  } else {
+    int *slot = x.slots + 4 * (x.call & 1);
+    ++x.call;
+    if (lane == 0) slot[gw] = wtot;
+    __syncthreads();
+    int before = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+      if (w < gw) before += slot[w];
+    total = slot[0] + slot[1] + slot[2] + slot[3];
+    return before + incl - v;
+  }
+}
+
+// One head, handled by NW waves; gt = thread index inside the group, gw = wave inside the group.
+// keep_l: 1024 * NW bytes of LDS, 16-byte aligned.
+template <int NW>
+__device__ __forceinline__ void select_head(const SelectArgs &a, int lhb, int gt, int gw, uint8_t *keep_l, Exchange &x) {
+  constexpr int G = 64 * NW;
+  const int lane = gt & 63;
+  const int lh = lhb / a.batch, b = lhb % a.batch;
   const int n_tok = a.seq_off[b + 1] - a.seq_off[b];
   const int sp = a.sent_ptr[b];
   const int n_sent = a.sent_ptr[b + 1] - sp - 1;
@@ -45,22 +106,13 @@ __global__ void __launch_bounds__(256) k_select(SelectArgs a) {
   int32_t *noff = a.new_sent_off ? a.new_sent_off + (int64_t)lh * (a.total_sentences + a.batch) + sp : nullptr;
   const int budget = a.budget ? a.budget[b] : a.budget_scalar;
 
-  if (n_sent > kMaxS || n_sent < 0) {
-    if (tid == 0) {
-      if (a.dev_status) atomicOr(a.dev_status, SKIPKV_DEV_TOO_MANY_SENT);
-      a.new_len[lhb] = 0;
-      if (a.new_sent_cnt) a.new_sent_cnt[lhb] = 0;
-    }
-    return;
-  }
-
   if (n_tok <= budget) {  // the cache already fits: nothing is evicted
-    for (int t = tid; t < n_tok; t += 256) kept[t] = t;
-    for (int s = tid; s < n_sent; s += 256)
-      if (a.sent_keep) a.sent_keep[col0 + s] = 1;
+    for (int t = gt; t < n_tok; t += G) kept[t] = t;
+    if (a.sent_keep)
+      for (int s = gt; s < n_sent; s += G) a.sent_keep[col0 + s] = 1;
     if (noff)
-      for (int s = tid; s <= n_sent; s += 256) noff[s] = off[s];
-    if (tid == 0) {
+      for (int s = gt; s <= n_sent; s += G) noff[s] = off[s];
+    if (gt == 0) {
       a.new_len[lhb] = n_tok;
       if (a.new_sent_cnt) a.new_sent_cnt[lhb] = n_sent;
     }
@@ -69,111 +121,163 @@ __global__ void __launch_bounds__(256) k_select(SelectArgs a) {
 
   const int p_start = n_tok - min(a.protect, n_tok);
   const int room = budget - (n_tok - p_start);
-  int p2 = 256;
-  while (p2 < n_sent) p2 <<= 1;
 
-  // ---- keys: order-preserving image of the score in the high word, sentence index in the low
-  for (int s = tid; s < p2; s += 256) {
-    unsigned long long key = 0;  // padding and non-candidates rank last
-    if (s < n_sent && off[s] < p_start) {
-      const uint32_t u = __float_as_uint(a.sent_score[col0 + s] + 0.f);  // +0: -0.0 ties with 0.0
-      const uint32_t ord = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-      key = ((unsigned long long)ord << 32) | (uint32_t)s;
-    }
-    keys[s] = key;
-    if (s < n_sent) keep[s] = 1;
-  }
-  __syncthreads();
-
-  // ---- bitonic sort, descending
-  for (int k = 2; k <= p2; k <<= 1) {
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      for (int i = tid; i < p2; i += 256) {
-        const int ixj = i ^ j;
-        if (ixj > i) {
-          const unsigned long long x = keys[i], y = keys[ixj];
-          const bool desc = (i & k) == 0;
-          if (desc ? (x < y) : (x > y)) {
-            keys[i] = y;
-            keys[ixj] = x;
-          }
-        }
+  // ---- candidates, sentence s = r * G + gt: order-preserving image of the score, unprotected length
+  uint32_t hi[kEPL];
+  int len[kEPL];
+#pragma unroll
+  for (int r = 0; r < kEPL; ++r) {
+    const int s = r * G + gt;
+    hi[r] = 0;
+    len[r] = 0;  // not a candidate: protected, or past the end
+    if (s < n_sent) {
+      const int o0 = off[s];
+      if (o0 < p_start) {
+        uint32_t u = __float_as_uint(a.sent_score[col0 + s]);
+        if (u == 0x80000000u) u = 0;  // -0.0 ties with 0.0
+        hi[r] = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+        len[r] = min(off[s + 1], p_start) - o0;
       }
-      __syncthreads();
     }
   }
 
-  // ---- inclusive prefix of the ranked candidate lengths; keep while it fits
-  const int per = p2 / 256;
-  int local = 0;
-  for (int i = tid * per; i < (tid + 1) * per; ++i) {
-    const unsigned long long key = keys[i];
-    int len = 0;
-    if (key != 0) {
-      const int s = (int)(uint32_t)key;
-      len = min(off[s + 1], p_start) - off[s];
+  // ---- score part of K0: the largest H such that the candidates with hi >= H do not fit.
+  // (All candidates together are p_start > room tokens, so H = 0 qualifies.)
+  uint32_t H = 0;
+  for (int bit = 31; bit >= 0; --bit) {
+    const uint32_t th = H | (1u << bit);
+    int part = 0;
+#pragma unroll
+    for (int r = 0; r < kEPL; ++r) part += hi[r] >= th ? len[r] : 0;
+    if (group_sum<NW>(part, gw, x) > room) H = th;
+  }
+  // ---- index part: among the candidates with hi == H, the largest index bound L such that those
+  // with index >= L, together with everything above H (which fits), do not fit
+  int above = 0;
+  int se[kEPL];
+#pragma unroll
+  for (int r = 0; r < kEPL; ++r) {
+    above += hi[r] > H ? len[r] : 0;
+    se[r] = (hi[r] == H && len[r] > 0) ? r * G + gt : -1;
+  }
+  above = group_sum<NW>(above, gw, x);
+  int L = 0;
+  for (int bit = 11; bit >= 0; --bit) {
+    const int tl = L | (1 << bit);
+    int part = 0;
+#pragma unroll
+    for (int r = 0; r < kEPL; ++r) part += se[r] >= tl ? len[r] : 0;
+    if (above + group_sum<NW>(part, gw, x) > room) L = tl;
+  }
+  // ---- keep flags: key > (H, L); sentences that are not candidates keep their (protected) tokens
+#pragma unroll
+  for (int r = 0; r < kEPL; ++r) {
+    const int s = r * G + gt;
+    if (s < n_sent) {
+      const uint8_t k = len[r] == 0 || hi[r] > H || (hi[r] == H && s > L);
+      keep_l[s] = k;
+      if (a.sent_keep) a.sent_keep[col0 + s] = k;
     }
-    dst[i] = len;
-    local += len;
   }
-  int run = block_scan_incl(local, tmp, tid) - local;
-  for (int i = tid * per; i < (tid + 1) * per; ++i) {
-    run += dst[i];
-    const unsigned long long key = keys[i];
-    if (key != 0) keep[(int)(uint32_t)key] = run <= room;
-  }
-  __syncthreads();
+  if constexpr (NW > 1) __syncthreads();
 
-  // ---- surviving tokens of every sentence in index order -> destination offsets
-  const int per_s = (n_sent + 255) / 256;
-  const int s_lo = tid * per_s, s_hi = min(s_lo + per_s, n_sent);
-  int tok_cnt = 0, sent_cnt = 0;
-  for (int s = s_lo; s < s_hi; ++s) {
-    const int bgn = off[s], end = off[s + 1];
-    const int cand = keep[s] ? max(0, min(end, p_start) - bgn) : 0;
-    const int prot = max(0, end - max(bgn, p_start));
-    tok_cnt += cand + prot;
-    sent_cnt += (cand + prot) > 0;
+  // ---- sentences in index order, 16 consecutive ones per thread: every sentence keeps one
+  // contiguous run of tokens (its unprotected part if kept, followed by its protected part)
+  const int s0 = gt * kEPL;
+  const uint4 kb4 = *reinterpret_cast<const uint4 *>(keep_l + s0);
+  const uint32_t kb[4] = {kb4.x, kb4.y, kb4.z, kb4.w};
+  int run_bgn[kEPL], run_len[kEPL], run_dst[kEPL];
+  int o_prev = off[min(s0, n_sent)];
+  int tok = 0, sent = 0;
+#pragma unroll
+  for (int r = 0; r < kEPL; ++r) {
+    const int s = s0 + r;
+    const int end = off[min(s + 1, n_sent)];
+    const bool kp = (kb[r >> 2] >> (8 * (r & 3))) & 0xFF;
+    const int bgn = kp ? o_prev : max(o_prev, p_start);
+    const int n = s < n_sent ? max(0, end - bgn) : 0;
+    run_bgn[r] = bgn;
+    run_len[r] = n;
+    tok += n;
+    sent += n > 0;
+    o_prev = end;
   }
-  int tok_run = block_scan_incl(tok_cnt, tmp, tid) - tok_cnt;
-  if (tid == 255) s_total = tok_run + tok_cnt;
-  __syncthreads();
-  int sent_run = block_scan_incl(sent_cnt, tmp, tid) - sent_cnt;
-  if (tid == 255) s_nsurv = sent_run + sent_cnt;
-  for (int s = s_lo; s < s_hi; ++s) {
-    const int bgn = off[s], end = off[s + 1];
-    const int cand = keep[s] ? max(0, min(end, p_start) - bgn) : 0;
-    const int prot = max(0, end - max(bgn, p_start));
-    dst[s] = tok_run;
-    if (cand + prot > 0 && noff) noff[sent_run] = tok_run;
-    tok_run += cand + prot;
-    sent_run += (cand + prot) > 0;
-    if (a.sent_keep) a.sent_keep[col0 + s] = keep[s];
+  int total_tok, total_sent;
+  int tok_run = group_scan_excl<NW>(tok, gw, lane, x, total_tok);
+  int sent_run = group_scan_excl<NW>(sent, gw, lane, x, total_sent);
+#pragma unroll
+  for (int r = 0; r < kEPL; ++r) {
+    run_dst[r] = tok_run;
+    if (run_len[r] > 0) {
+      if (noff) noff[sent_run] = tok_run;
+      tok_run += run_len[r];
+      ++sent_run;
+    }
   }
-  __syncthreads();
-  if (tid == 0) {
-    a.new_len[lhb] = s_total;
-    if (a.new_sent_cnt) a.new_sent_cnt[lhb] = s_nsurv;
-    if (noff) noff[s_nsurv] = s_total;
+  if (gt == 0) {
+    a.new_len[lhb] = total_tok;
+    if (a.new_sent_cnt) a.new_sent_cnt[lhb] = total_sent;
+    if (noff) noff[total_sent] = total_tok;
   }
+  // ---- ascending surviving token indices: the wave writes the runs of its lanes one after the other
+#pragma unroll
+  for (int r = 0; r < kEPL; ++r) {
+    unsigned long long todo = __ballot(run_len[r] > 0);
+    while (todo) {
+      const int l = __builtin_ctzll(todo);
+      todo &= todo - 1;
+      const int bgn = __builtin_amdgcn_readlane(run_bgn[r], l);
+      const int n = __builtin_amdgcn_readlane(run_len[r], l);
+      const int d = __builtin_amdgcn_readlane(run_dst[r], l);
+      for (int i = lane; i < n; i += 64) kept[d + i] = bgn + i;
+    }
+  }
+}
 
-  // ---- ascending surviving token indices, one wave per sentence
-  for (int s = wave; s < n_sent; s += 4) {
-    const int bgn = off[s], end = off[s + 1];
-    const int c_end = keep[s] ? min(end, p_start) : bgn;  // kept candidate part [bgn, c_end)
-    const int p_bgn = max(bgn, p_start);                   // protected part [p_bgn, end)
-    const int n_c = max(0, c_end - bgn), n_p = max(0, end - p_bgn);
-    const int d0 = dst[s];
-    for (int i = lane; i < n_c + n_p; i += 64) kept[d0 + i] = i < n_c ? bgn + i : p_bgn + (i - n_c);
+__device__ __forceinline__ int head_sentences(const SelectArgs &a, int lhb) {
+  const int b = lhb % a.batch;
+  return a.sent_ptr[b + 1] - a.sent_ptr[b] - 1;
+}
+
+__global__ void __launch_bounds__(256) k_select(SelectArgs a) {
+  __shared__ __align__(16) uint8_t keep_l[4 * kWaveSent];
+  __shared__ int slots[8];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n_heads = a.n_lh * a.batch;
+  Exchange x{slots, 0};
+
+  {  // every wave takes one head of its own if the head is small enough
+    const int lhb = blockIdx.x * 4 + wave;
+    if (lhb < n_heads) {
+      const int n_sent = head_sentences(a, lhb);
+      if (n_sent >= 0 && n_sent <= kWaveSent) select_head<1>(a, lhb, lane, 0, keep_l + wave * kWaveSent, x);
+    }
+  }
+  for (int w = 0; w < 4; ++w) {  // the larger heads, one after the other, by the whole workgroup
+    const int lhb = blockIdx.x * 4 + w;
+    if (lhb >= n_heads) break;
+    const int n_sent = head_sentences(a, lhb);
+    if (n_sent >= 0 && n_sent <= kWaveSent) continue;
+    if (n_sent < 0 || n_sent > SKIPKV_MAX_SENTENCES) {
+      if (tid == 0) {
+        if (a.dev_status) atomicOr(a.dev_status, SKIPKV_DEV_TOO_MANY_SENT);
+        a.new_len[lhb] = 0;
+        if (a.new_sent_cnt) a.new_sent_cnt[lhb] = 0;
+      }
+      continue;
+    }
+    __syncthreads();  // the flag buffer is free: every wave is done with its own head (or the previous large one)
+    select_head<4>(a, lhb, tid, wave, keep_l, x);
   }
 }
 
 }  // namespace
 
 hipError_t launch_select(const SelectArgs &a, hipStream_t st) {
-  const int blocks = a.n_lh * a.batch;
-  if (blocks == 0) return hipSuccess;
-  hipLaunchKernelGGL(k_select, dim3(blocks), dim3(256), 0, st, a);
+  const int heads = a.n_lh * a.batch;
+  if (heads == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_select, dim3((heads + 3) / 4), dim3(256), 0, st, a);
   return hipGetLastError();
 }
 

@@ -136,6 +136,67 @@ def test_bad_offsets_are_reported_not_executed():
     assert int(out.dev_status.item()) & B.DEV_BAD_OFFSETS
 
 
+def test_select_ties_signs_and_all_group_sizes():
+    """skipkv_select on hand-made scores: heavy ties across the cut (index order decides), both
+    signed zeros, negative scores, denormals; sequences from 1 to 4096 sentences so that both the
+    one-wave and the four-wave ranking run, with budgets that cut at different depths.  Integer
+    work: everything must equal the oracle's selection exactly."""
+    rng = np.random.default_rng(11)
+    n_sents = [1, 2, 63, 64, 65, 500, 1023, 1024, 1025, 2500, 4096]
+    offsets = []
+    for ns in n_sents:
+        lens = rng.integers(1, 9, size=ns)
+        offsets.append(np.concatenate([[0], np.cumsum(lens)]).tolist())
+    st = _structure(offsets)
+    cfg = W.Config("select", 9, len(n_sents), 1, 2, 8, "bf16", 0, 0, 0, 8, 16, 4.0, 0.0)
+    k = torch.zeros((1, 2, st.total_tokens, 128), dtype=torch.bfloat16, device="cuda")
+    cache = make_cache(cfg, st, k, k.clone())
+    L, H, Bn, S, T = 1, 2, cfg.batch, st.total_sentences, st.total_tokens
+    palettes = [
+        np.array([0.0, -0.0, 1.0, -1.0, 0.5], dtype=np.float32),                       # few values: ties everywhere
+        np.array([1e-42, -1e-42, 3e38, -3e38, 0.25, 0.250001], dtype=np.float32),      # denormals and extremes
+    ]
+    score = np.empty((L, H, S), dtype=np.float32)
+    score[0, 0] = palettes[0][rng.integers(0, len(palettes[0]), size=S)]
+    score[0, 1] = np.where(rng.random(S) < 0.5, palettes[1][rng.integers(0, len(palettes[1]), size=S)],
+                           rng.standard_normal(S).astype(np.float32))
+    for frac in (0.05, 0.5, 0.97):
+        budgets = np.maximum(16, (st.seq_len * frac).astype(np.int32))
+        bud_t = torch.from_numpy(budgets).cuda()
+        max_budget = int(budgets.max())
+        status = torch.zeros(1, dtype=torch.int32, device="cuda")
+        params = B.Params(cfg.obs_window, cfg.protect_window, bud_t, max_budget=max_budget, dev_status=status)
+        kept_stride = min(max_budget, T)
+        sent_keep = torch.full((L, H, S), 77, dtype=torch.uint8, device="cuda")
+        kept_idx = torch.full((L, H, Bn, kept_stride), -1, dtype=torch.int32, device="cuda")
+        new_len = torch.full((L, H, Bn), -1, dtype=torch.int32, device="cuda")
+        new_off = torch.full((L, H, S + Bn), -1, dtype=torch.int32, device="cuda")
+        new_cnt = torch.full((L, H, Bn), -1, dtype=torch.int32, device="cuda")
+        B.skipkv_select(cache, params, torch.from_numpy(score).cuda(), sent_keep, kept_idx, new_len, new_off,
+                        new_cnt, kept_stride)
+        torch.cuda.synchronize()
+        assert int(status.item()) == 0
+        for h in range(H):
+            for b in range(Bn):
+                off = st.offsets(b).astype(np.int64)
+                sb, ns, n_tok = st.sent_base(b), int(st.n_sent[b]), int(off[-1])
+                p = n_tok - min(cfg.protect_window, n_tok)
+                candlen = np.clip(np.minimum(off[1:], p) - off[:-1], 0, None)
+                sc = score[0, h, sb:sb + ns].astype(np.float64)
+                ora = oracle.select_sentences(np.where(candlen > 0, sc, np.inf), candlen, off, int(budgets[b]),
+                                              cfg.protect_window)
+                tag = "frac %.2f head %d seq %d (S=%d)" % (frac, h, b, ns)
+                nl = int(new_len[0, h, b])
+                assert nl == ora["new_len"], tag
+                np.testing.assert_array_equal(kept_idx[0, h, b, :nl].cpu().numpy(), ora["kept_idx"], err_msg=tag)
+                np.testing.assert_array_equal(sent_keep[0, h, sb:sb + ns].cpu().numpy().astype(bool), ora["keep"],
+                                              err_msg=tag)
+                cnt = int(new_cnt[0, h, b])
+                assert cnt == len(ora["new_off"]) - 1, tag
+                np.testing.assert_array_equal(new_off[0, h, st.sent_ptr[b]:st.sent_ptr[b] + cnt + 1].cpu().numpy(),
+                                              ora["new_off"], err_msg=tag)
+
+
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
 def test_compact_generic_gather(dtype):
     # token-level kept sets (not whole sentences): shift-by-one, every other row, random subset
