@@ -16,7 +16,7 @@ import torch
 
 F32, BF16 = 0, 1
 OK, EINVAL, EBUDGET, ECAPACITY, EWORKSPACE, EHIP = 0, -1, -2, -3, -4, -5
-DEV_BAD_OFFSETS, DEV_TOO_MANY_SENT = 1, 2
+DEV_BAD_OFFSETS, DEV_TOO_MANY_SENT, DEV_TIMEOUT = 1, 2, 4
 PROFILE_SLOTS = 16
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libskipkv.so")

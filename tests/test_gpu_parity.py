@@ -50,3 +50,34 @@ def test_config4_qwen7b_gqa7_one_layer():
 
 def test_config5_longcot_one_layer():
     _run_and_compare(W.CONFIGS[5].scaled(n_layers=1, batch=1), 3)
+
+
+def test_two_pass_scan_matches_oracle(monkeypatch):
+    """The fallback scan (K read twice, no cross-workgroup wait), forced for every sequence."""
+    monkeypatch.setenv("SKIPKV_FORCE_TWO_PASS", "1")
+    _run_and_compare(W.CONFIGS[3].scaled(n_layers=1, batch=4), 8)
+    _run_and_compare(W.CONFIGS[1], 4)
+
+
+def test_bounded_wait_reports_timeout_and_returns(monkeypatch):
+    """With a poll limit of zero a workgroup that finds its head's normalisers not ready gives up
+    at once: the step must still run to completion, raise the time-out bit, and leave the
+    library usable (the next call, with the default limit, is correct again)."""
+    from paper_2512_07993_amd import binding as B
+    cfg = W.CONFIGS[3].scaled(n_layers=1, batch=4)
+    st = W.make_structure(cfg)
+    k0, v0, q = W.fill_cache(cfg, st, device="cuda")
+    monkeypatch.setenv("SKIPKV_SPIN_LIMIT", "0")
+    out = run_step(cfg, st, k0.clone(), v0.clone(), q)
+    assert int(out.dev_status.item()) & B.DEV_TIMEOUT
+    new_len = out.new_len.cpu().numpy()
+    assert (new_len >= 0).all() and (new_len <= cfg.budget).all()
+    monkeypatch.delenv("SKIPKV_SPIN_LIMIT")
+    _run_and_compare(cfg, 6)
+
+
+def test_config3_full_size_sampled_heads():
+    """The benchmark workload itself (all 32 layers, batch 16: the grid, plan and workspace sizes
+    that bench.py times), checked on heads sampled across layers, heads and sequences."""
+    stats = _run_and_compare(W.CONFIGS[3], 16, seed=3)
+    assert stats["heads"] == 16
