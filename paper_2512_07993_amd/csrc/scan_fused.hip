@@ -91,6 +91,16 @@ __device__ __forceinline__ void load_to_lds_16(const void *gsrc, void *wave_lds_
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(l), "v"(gsrc) : "memory");
 }
 
+__device__ __forceinline__ uint32_t lds_addr(const void *p) {
+  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char *)p;
+}
+__device__ __forceinline__ uint32_t lds_read_u32(uint32_t addr) {
+  return *(const __attribute__((address_space(3))) uint32_t *)(uintptr_t)addr;
+}
+__device__ __forceinline__ float lds_read_f32(uint32_t addr) {
+  return *(const __attribute__((address_space(3))) float *)(uintptr_t)addr;
+}
+
 // Row (16-lane) reductions with the DPP modifier on the arithmetic instruction itself: one
 // instruction per step.  The s_nop covers the two wait states a DPP read needs after a VALU write.
 #define SKIPKV_DPP_STEP(OP, N)                                                                          \
@@ -108,6 +118,16 @@ __device__ __forceinline__ float row16_sum_fast(float v) {
   SKIPKV_DPP_STEP("v_add_f32_dpp", 2);
   SKIPKV_DPP_STEP("v_add_f32_dpp", 1);
   return v;
+}
+// Sum over the whole wave, returned in a scalar register: rows first, then row 0 -> 1 and
+// 2 -> 3 (row_bcast:15), then the lower half -> the upper half (row_bcast:31); lane 63 ends up
+// with the total.
+__device__ __forceinline__ float wave_sum_fast(float v) {
+  v = row16_sum_fast(v);
+  // rows that are masked off keep their value, so the operand must be read-write (same register)
+  asm volatile("s_nop 1\n\tv_add_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf" : "+v"(v));
+  asm volatile("s_nop 1\n\tv_add_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf" : "+v"(v));
+  return __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v), 63));  // the builtin moves 32-bit integers
 }
 #undef SKIPKV_DPP_STEP
 
@@ -136,7 +156,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
   constexpr int NBUF = (DT == SKIPKV_BF16) ? 3 : 2;   // stage buffers per wave
   constexpr int STAGEB = kStageRows * ROWB;
 
-  __shared__ __align__(16) char kt[4][NBUF][STAGEB];
+  __shared__ __align__(256) char kt[4][NBUF][STAGEB];  // 256-byte aligned: the row swizzle is applied as an XOR on address bits
   __shared__ __align__(16) char qt[R * LSTR];
   __shared__ int soff_buf[2][2][kChunkMaxSent + 2];  // [item parity][chunk of the pair]
   __shared__ float part_first[2][4][kD];  // key sum, over a wave's range, of the sentence already running at its start
@@ -236,10 +256,12 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     char *dst = kt[wave][iss_cnt % NBUF];
     const int ts = (iss_k ? iss.ch[1].w0 : iss.ch[0].w0) + iss_st * kStageRows;
     const int w1 = iss_k ? iss.ch[1].w1 : iss.ch[0].w1;
+    int ln = lane;
+    asm volatile("" : "+v"(ln));  // opaque copy: the per-load address parts are recomputed here rather than kept live across the item
 #pragma unroll
     for (int j = 0; j < GL; ++j) {
-      const int row = j * RPL + lane / PPR;         // row of the stage this lane's 16 bytes belong to
-      const int piece = (lane % PPR) ^ (row & 15);  // swizzle: LDS position (lane % PPR) holds this global piece
+      const int row = j * RPL + ln / PPR;         // row of the stage this lane's 16 bytes belong to
+      const int piece = (ln % PPR) ^ (row & 15);    // swizzle: LDS position (lane % PPR) holds this global piece
       const int t = min(ts + row, w1 - 1);          // rows past the range re-read its last row (masked later)
       load_to_lds_16(iss.kbase + (int64_t)t * tok_pitch + piece * 16, dst + j * 1024);
     }
@@ -271,10 +293,10 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
       lsum[q] = 0.f;
     }
 
-    auto emit_sentence = [&](const int *soff, int sent_col0, int s_idx, float k0, float k1) {  // unit embedding, bf16 hi + lo
-      const float inv_len = 1.f / (float)(soff[s_idx + 1] - soff[s_idx]);
+    auto emit_sentence = [&](int len, int sent_col0, int s_idx, float k0, float k1) {  // unit embedding, bf16 hi + lo
+      const float inv_len = 1.f / (float)len;
       const float m0 = k0 * inv_len, m1 = k1 * inv_len;
-      const float inv = 1.f / (sqrtf(wave_sum(m0 * m0 + m1 * m1)) + 1e-12f);
+      const float inv = 1.f / (sqrtf(wave_sum_fast(m0 * m0 + m1 * m1)) + 1e-12f);
       const float u0 = m0 * inv, u1 = m1 * inv;
       const uint32_t h0 = f32_to_bf16_bits(u0), h1 = f32_to_bf16_bits(u1);
       const uint32_t l0 = f32_to_bf16_bits(u0 - bf16_bits_to_f32(h0)), l1 = f32_to_bf16_bits(u1 - bf16_bits_to_f32(h1));
@@ -295,10 +317,13 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
         const int *soff = soff_buf[par][k];
         const int ns = cd.ns, w0 = cd.w0, w1 = cd.w1;
         const int sent_col0 = cd.soff_idx - b;
-        // sentence pooling state: current sentence, its running key sum (lane = 2 head-dim columns)
+        // sentence pooling state: current sentence, its running key sum (lane = 2 head-dim columns);
+        // lane i keeps offset i of the chunk, so that boundaries are fetched with v_readlane
+        const int soff_v = soff[min(lane, ns)];
         int si = 0;
         float ps0 = 0.f, ps1 = 0.f;
-        if (w0 < w1) si = __popcll(__ballot(lane < ns && soff[lane + 1] <= w0));
+        if (w0 < w1) si = __popcll(__ballot(lane >= 1 && lane <= ns && soff_v <= w0));
+        int s_bgn = __builtin_amdgcn_readlane(soff_v, si), s_end = __builtin_amdgcn_readlane(soff_v, min(si + 1, ns));
 
 #pragma unroll
         for (int st = 0; st < SUBS; ++st) {
@@ -371,54 +396,69 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
               for (int q = 0; q < SLP; ++q) lsum[q] += __builtin_amdgcn_exp2f(e[q]);
             }
 
-            // ---- sentence key sums over tokens [ts, te), walked in order
-            int t = ts;
-            while (t < te) {
-              const int run_end = min(soff[si + 1], te);
-              if (run_end <= t) break;  // cannot happen with validated offsets; never spin on bad ones
-              float q0 = 0.f, q1 = 0.f;
-              int r = t - ts;  // row within the stage
-              int cnt = run_end - t;
+            // ---- sentence key sums over tokens [ts, te).  All rows of the stage come into registers
+            // with one LDS round trip (lane = 2 head-dim columns of every row); then every run of
+            // rows that belongs to one sentence is added with a 0/1 weight per row taken from a
+            // scalar bit mask, so there is no branch per row.
+            {
+              float x0[kStageRows], x1[kStageRows];
+              uint32_t xw[kStageRows];
+              // the stage buffers are 256-byte aligned, so the swizzle (piece ^ row) is an XOR on bits
+              // 4..7 of the address: one VALU op per row, the row's base goes into the offset field
               if constexpr (DT == SKIPKV_BF16) {
-                // lane = dword `lane` of the row = piece lane/4 (swizzled by the row), bytes (lane%4)*4
-                const bf16x2_t ones = __builtin_bit_cast(bf16x2_t, 0x3F803F80u);
-                for (; cnt >= 2; cnt -= 2, r += 2) {
-                  const uint32_t wa = *reinterpret_cast<const uint32_t *>(stage + r * ROWB + (((lane >> 2) ^ (r & 15)) * 16) + (lane & 3) * 4);
-                  const uint32_t wb = *reinterpret_cast<const uint32_t *>(stage + (r + 1) * ROWB + (((lane >> 2) ^ ((r + 1) & 15)) * 16) + (lane & 3) * 4);
-                  // (lo_a, lo_b) and (hi_a, hi_b) pairs, each summed into fp32 by one dot instruction
-                  q0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, __builtin_amdgcn_perm(wb, wa, 0x05040100u)), ones, q0, false);
-                  q1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, __builtin_amdgcn_perm(wb, wa, 0x07060302u)), ones, q1, false);
-                }
-                if (cnt) {
-                  const uint32_t wa = *reinterpret_cast<const uint32_t *>(stage + r * ROWB + (((lane >> 2) ^ (r & 15)) * 16) + (lane & 3) * 4);
-                  q0 += __uint_as_float(wa << 16);
-                  q1 += __uint_as_float(wa & 0xFFFF0000u);
-                }
+                const uint32_t la = lds_addr(stage) + ((lane >> 2) << 4) + (lane & 3) * 4;
+#pragma unroll
+                for (int i = 0; i < kStageRows; ++i) xw[i] = lds_read_u32((la ^ (i << 4)) + i * ROWB);
               } else {
-                for (; cnt > 0; --cnt, ++r) {
-                  const float2 wa = *reinterpret_cast<const float2 *>(stage + r * ROWB + (((lane >> 1) ^ (r & 15)) * 16) + (lane & 1) * 8);
-                  q0 += wa.x;
-                  q1 += wa.y;
+                const uint32_t la = lds_addr(stage) + ((lane >> 1) << 4) + (lane & 1) * 8;
+#pragma unroll
+                for (int i = 0; i < kStageRows; ++i) {
+                  x0[i] = lds_read_f32((la ^ (i << 4)) + i * ROWB);
+                  x1[i] = lds_read_f32((la ^ (i << 4)) + i * ROWB + 4);
                 }
               }
-              ps0 += q0;
-              ps1 += q1;
-              t = run_end;
-              if (t == soff[si + 1]) {  // the sentence ends here
-                if (soff[si] >= w0) {
-                  emit_sentence(soff, sent_col0, si, ps0, ps1);
+              int t = ts;
+              while (t < te) {
+                const int run_end = min(s_end, te);
+                if (run_end <= t) break;  // cannot happen with validated offsets; never spin on bad ones
+                const uint32_t rows = ((1u << (run_end - ts)) - 1u) & ~((1u << (t - ts)) - 1u);  // rows of this run
+                if constexpr (DT == SKIPKV_BF16) {
+                  // dot2 with (1, 0) adds the low half of the pair, with (0, 1) the high half
+#pragma unroll
+                  for (int i = 0; i < kStageRows; ++i) {
+                    const bool on = (rows >> i) & 1u;
+                    ps0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, xw[i]),
+                                                         __builtin_bit_cast(bf16x2_t, on ? 0x00003F80u : 0u), ps0, false);
+                    ps1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, xw[i]),
+                                                         __builtin_bit_cast(bf16x2_t, on ? 0x3F800000u : 0u), ps1, false);
+                  }
                 } else {
-                  part_first[k][wave][2 * lane] = ps0;
-                  part_first[k][wave][2 * lane + 1] = ps1;
+#pragma unroll
+                  for (int i = 0; i < kStageRows; ++i) {
+                    const float m = ((rows >> i) & 1u) ? 1.f : 0.f;
+                    ps0 = fmaf(x0[i], m, ps0);
+                    ps1 = fmaf(x1[i], m, ps1);
+                  }
                 }
-                ps0 = ps1 = 0.f;
-                ++si;
+                t = run_end;
+                if (t == s_end) {  // the sentence ends here
+                  if (s_bgn >= w0) {
+                    emit_sentence(s_end - s_bgn, sent_col0, si, ps0, ps1);
+                  } else {
+                    part_first[k][wave][2 * lane] = ps0;
+                    part_first[k][wave][2 * lane + 1] = ps1;
+                  }
+                  ps0 = ps1 = 0.f;
+                  ++si;
+                  s_bgn = s_end;
+                  s_end = __builtin_amdgcn_readlane(soff_v, min(si + 1, ns));
+                }
               }
             }
           }
         }
-        if (w0 < w1 && si < ns && soff[si] < w1 && w1 < soff[si + 1]) {  // a sentence is still running at the end of this wave's range
-          float *dst = (soff[si] >= w0) ? part_last[k][wave] : part_first[k][wave];
+        if (w0 < w1 && si < ns && s_bgn < w1 && w1 < s_end) {  // a sentence is still running at the end of this wave's range
+          float *dst = (s_bgn >= w0) ? part_last[k][wave] : part_first[k][wave];
           dst[2 * lane] = ps0;
           dst[2 * lane + 1] = ps1;
         }
@@ -449,7 +489,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
               k0 += part_first[k][w][2 * lane];
               k1 += part_first[k][w][2 * lane + 1];
             }
-            emit_sentence(soff, cd.soff_idx - b, sl, k0, k1);
+            emit_sentence(soff[sl + 1] - soff[sl], cd.soff_idx - b, sl, k0, k1);
           }
         }
       }
