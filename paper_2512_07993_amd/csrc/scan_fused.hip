@@ -91,6 +91,14 @@ __device__ __forceinline__ void load_to_lds_16(const void *gsrc, void *wave_lds_
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(l), "v"(gsrc) : "memory");
 }
 
+// (lo, hi) fp32 -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32).
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  bf16x2_t v;
+  v[0] = (__bf16)lo;
+  v[1] = (__bf16)hi;
+  return __builtin_bit_cast(uint32_t, v);
+}
+
 __device__ __forceinline__ uint32_t lds_addr(const void *p) {
   return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char *)p;
 }
@@ -294,15 +302,16 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     }
 
     auto emit_sentence = [&](int len, int sent_col0, int s_idx, float k0, float k1) {  // unit embedding, bf16 hi + lo
-      const float inv_len = 1.f / (float)len;
+      // 1-ulp reciprocal and square root: a common scale error of ~1e-7 on the unit vector
+      const float inv_len = __builtin_amdgcn_rcpf((float)len);
       const float m0 = k0 * inv_len, m1 = k1 * inv_len;
-      const float inv = 1.f / (sqrtf(wave_sum_fast(m0 * m0 + m1 * m1)) + 1e-12f);
+      const float inv = __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(wave_sum_fast(m0 * m0 + m1 * m1)) + 1e-12f);
       const float u0 = m0 * inv, u1 = m1 * inv;
-      const uint32_t h0 = f32_to_bf16_bits(u0), h1 = f32_to_bf16_bits(u1);
-      const uint32_t l0 = f32_to_bf16_bits(u0 - bf16_bits_to_f32(h0)), l1 = f32_to_bf16_bits(u1 - bf16_bits_to_f32(h1));
+      const uint32_t hi = pack_bf16x2(u0, u1);  // round to nearest even, both halves in one instruction
+      const uint32_t lo = pack_bf16x2(u0 - __uint_as_float(hi << 16), u1 - __uint_as_float(hi & 0xFFFF0000u));
       const int64_t o = ((int64_t)lh * a.total_sentences + sent_col0 + s_idx) * (kD / 2) + lane;
-      reinterpret_cast<uint32_t *>(a.ws.vhat_hi)[o] = h0 | (h1 << 16);
-      reinterpret_cast<uint32_t *>(a.ws.vhat_lo)[o] = l0 | (l1 << 16);
+      reinterpret_cast<uint32_t *>(a.ws.vhat_hi)[o] = hi;
+      reinterpret_cast<uint32_t *>(a.ws.vhat_lo)[o] = lo;
     };
 
     // =============== first phase: logits, row statistics and sentence key sums =================
