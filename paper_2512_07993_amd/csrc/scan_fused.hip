@@ -227,21 +227,40 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     it.item = item;
     return it;
   };
-  auto load_q_soff = [&](const Pair &it, int par) {  // queries of the group -> LDS (padded rows), sentence offsets
-    if (tid <= it.ch[0].ns) soff_buf[par][0][tid] = a.sent_off[it.ch[0].soff_idx + tid];
-    if (it.nch == 2 && tid >= 64 && tid - 64 <= it.ch[1].ns) soff_buf[par][1][tid - 64] = a.sent_off[it.ch[1].soff_idx + tid - 64];
+  // Queries of the group and the sentence offsets of an item, in two steps so that the global
+  // latency can hide behind other work: fetch into registers, later commit to LDS (padded rows).
+  constexpr int NQ = R * PPR / 256;  // 16-byte pieces of the query tile per thread
+  struct QFetch {
+    uint4 q[NQ];
+    int so;
+  };
+  auto q_fetch = [&](const Pair &it) -> QFetch {
+    QFetch f;
+    f.so = 0;
+    if (tid <= it.ch[0].ns) f.so = a.sent_off[it.ch[0].soff_idx + tid];
+    if (it.nch == 2 && tid >= 64 && tid - 64 <= it.ch[1].ns) f.so = a.sent_off[it.ch[1].soff_idx + tid - 64];
     const char *qbase = static_cast<const char *>(a.q);
     const int l = it.lh / a.n_kv_heads, h = it.lh % a.n_kv_heads;
-    for (int r0 = 0; r0 < R; r0 += 256 / PPR) {
-      const int r = r0 + tid / PPR, piece = tid % PPR;
+#pragma unroll
+    for (int u = 0; u < NQ; ++u) {
+      const int r = u * (256 / PPR) + tid / PPR, piece = tid % PPR;
       const int slot = 4 * (r >> 4) + (r & 3), gq = (r >> 2) & 3;
       const int al = slot / NP, i = slot % NP, aq = gq + 4 * al;
-      uint4 val = make_uint4(0, 0, 0, 0);
+      f.q[u] = make_uint4(0, 0, 0, 0);
       if (slot < SL && i < n && aq < a.alpha) {
         const int64_t row = (((int64_t)l * a.batch + it.b) * a.n_q_heads + (h * n + i)) * a.alpha + aq;
-        val = *reinterpret_cast<const uint4 *>(qbase + row * ROWB + piece * 16);
+        f.q[u] = *reinterpret_cast<const uint4 *>(qbase + row * ROWB + piece * 16);
       }
-      *reinterpret_cast<uint4 *>(qt + r * LSTR + piece * 16) = val;
+    }
+    return f;
+  };
+  auto q_commit = [&](const Pair &it, const QFetch &f, int par) {
+    if (tid <= it.ch[0].ns) soff_buf[par][0][tid] = f.so;
+    if (it.nch == 2 && tid >= 64 && tid - 64 <= it.ch[1].ns) soff_buf[par][1][tid - 64] = f.so;
+#pragma unroll
+    for (int u = 0; u < NQ; ++u) {
+      const int r = u * (256 / PPR) + tid / PPR, piece = tid % PPR;
+      *reinterpret_cast<uint4 *>(qt + r * LSTR + piece * 16) = f.q[u];
     }
   };
 
@@ -250,11 +269,13 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
   int iss_k = 0;                     // ... chunk of that item
   int iss_st = 0;                    // ... next stage of that chunk
   uint32_t iss_cnt = 0;              // stages issued so far (ring position)
+  uint32_t iss_from = 0xFFFFFFFFu;   // the item the stream was on before it moved to `iss`
   auto issue_next = [&]() -> bool {
     while (iss.item < n_items && iss_st >= (iss_k ? iss.ch[1].nst : iss.ch[0].nst)) {
       if (iss_k + 1 < iss.nch) {
         ++iss_k;
       } else {
+        iss_from = iss.item;
         iss = load_pair(iss.item + gridDim.x);
         iss_k = 0;
       }
@@ -284,7 +305,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
   for (int i = 0; i < NBUF - 1; ++i) issue_next();
   uint32_t cmp_cnt = 0;  // stages computed so far (ring position)
   int par = 0;           // which soff buffers hold the current item's offsets
-  load_q_soff(cur, par);
+  q_commit(cur, q_fetch(cur), par);
   lds_barrier();
 
   while (cur.item < n_items) {
@@ -473,6 +494,12 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
         }
       }
     }
+    // The next item is usually known already (the load stream has just moved on to it; after very
+    // short items it may be further ahead, then the descriptor is read again).  Its queries and
+    // offsets are fetched now and committed once every wave is done with the current query tile.
+    const Pair nxt = (iss_from == cur.item) ? iss : load_pair(cur.item + gridDim.x);
+    QFetch nq;
+    if (nxt.item < n_items) nq = q_fetch(nxt);
 #pragma unroll
     for (int q = 0; q < SLP; ++q) {
       const float tot = row16_sum_fast(lsum[q]);
@@ -513,9 +540,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
       for (int w = 0; w < 4; ++w) s += wstat[w][r][1] * __builtin_amdgcn_exp2f(wstat[w][r][0] - m);
       coherent_store2(&a.ws.stat_part[((int64_t)lh * a.ws.nc_max + cur.c0) * R + r], make_float2(m, s));
     }
-    // the next item's queries and offsets can come in now: their latency hides behind the wait below
-    const Pair nxt = load_pair(cur.item + gridDim.x);
-    if (nxt.item < n_items) load_q_soff(nxt, par ^ 1);
+    if (nxt.item < n_items) q_commit(nxt, nq, par ^ 1);
     wait_all();  // the statistics are acknowledged (and so are the loads already in flight)
     __builtin_amdgcn_s_barrier();
     if (tid == 0) {
@@ -608,21 +633,32 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     lds_barrier();
     const int p_start = n_tok - min(a.protect, n_tok);
     const int64_t tok_col = (int64_t)lh * a.total_tokens + cur.tok0;
-    {  // sentence means: threads 0..63 take the first chunk's sentences, 64..127 the second's
-      const int k = tid >> 6, s_idx = tid & 63;
-      if (k < cur.nch && s_idx < (k ? cur.ch[1].ns : cur.ch[0].ns)) {
+    {  // sentence means: 4 lanes per sentence; threads 0..127 take the first chunk, 128..255 the second
+      static_assert(kChunkMaxSent * 4 <= 128, "4 lanes per sentence of a chunk");
+      const int k = tid >> 7, s_idx = (tid & 127) >> 2, part = tid & 3;
+      const bool valid = k < cur.nch && s_idx < (k ? cur.ch[1].ns : cur.ch[0].ns);
+      float sum_i = 0.f, sum_r = 0.f;
+      int lo = 0, hi = 0;
+      if (valid) {
         const int *soff = soff_buf[par][k];
         const int t_begin = k ? cur.ch[1].t_begin : cur.ch[0].t_begin;
-        const int sent_col0 = (k ? cur.ch[1].soff_idx : cur.ch[0].soff_idx) - b;
-        const int lo = soff[s_idx], hi = min(soff[s_idx + 1], p_start);
-        float sum_i = 0.f, sum_r = 0.f;
-        for (int t = lo; t < hi; ++t) {
+        lo = soff[s_idx];
+        hi = min(soff[s_idx + 1], p_start);
+        for (int t = lo + part; t < hi; t += 4) {
           sum_i += imp[k][t - t_begin];
           if (a.tok_red) sum_r += a.tok_red[tok_col + t];
         }
+      }
+      sum_i += __shfl_xor(sum_i, 1);
+      sum_r += __shfl_xor(sum_r, 1);
+      sum_i += __shfl_xor(sum_i, 2);
+      sum_r += __shfl_xor(sum_r, 2);
+      if (valid && part == 0) {
+        const int sent_col0 = (k ? cur.ch[1].soff_idx : cur.ch[0].soff_idx) - b;
         const int64_t o = (int64_t)lh * a.total_sentences + sent_col0 + s_idx;
-        a.ws.sent_imp[o] = hi > lo ? sum_i / (float)(hi - lo) : 0.f;
-        a.ws.sent_red[o] = hi > lo ? sum_r / (float)(hi - lo) : 0.f;
+        const float inv = hi > lo ? 1.f / (float)(hi - lo) : 0.f;
+        a.ws.sent_imp[o] = sum_i * inv;
+        a.ws.sent_red[o] = sum_r * inv;
       }
     }
     if (a.tok_imp) {

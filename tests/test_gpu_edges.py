@@ -138,6 +138,31 @@ def test_bad_offsets_are_reported_not_executed():
     assert int(out.dev_status.item()) & B.DEV_BAD_OFFSETS
 
 
+def test_many_tiny_sequences_more_items_than_workgroups():
+    """Sequences of a few tokens: every work item of the single-pass scan has at most two stages
+    per wave, so its load stream runs two items ahead of the compute, and there are more items
+    than resident workgroups, so that every workgroup walks through several of them."""
+    rng = np.random.default_rng(23)
+    offsets = []
+    for _ in range(40):
+        n_sent = int(rng.integers(1, 7))
+        lens = rng.integers(1, 12, size=n_sent)
+        offsets.append(np.concatenate([[0], np.cumsum(lens)]).tolist())
+    st = _structure(offsets)
+    cfg = W.Config("tiny-seqs", 9, len(offsets), 4, 8, 32, "bf16", 0, 0, 12, 4, 4, 6.0, 0.0)
+    assert cfg.n_layers * cfg.n_kv_heads * cfg.batch > 1024
+    k0, v0, q = _random_kvq(cfg, st, 41)
+    k, v = k0.clone(), v0.clone()
+    out = run_step(cfg, st, k, v, q)
+    assert int(out.dev_status.item()) == 0
+    rs = np.random.default_rng(1)
+    stats = {}
+    for _ in range(60):
+        l, h, b = int(rs.integers(cfg.n_layers)), int(rs.integers(cfg.n_kv_heads)), int(rs.integers(cfg.batch))
+        ora = oracle_head(cfg, st, k0, v0, q, l, h, b)
+        compare_head(cfg, st, out, k, v, k0, v0, ora, l, h, b, stats)
+
+
 def test_select_ties_signs_and_all_group_sizes():
     """skipkv_select on hand-made scores: heavy ties across the cut (index order decides), both
     signed zeros, negative scores, denormals; sequences from 1 to 4096 sentences so that both the
