@@ -6,7 +6,6 @@
 namespace skipkv {
 
 constexpr float kScale2 = 0.08838834764831845f * 1.4426950408889634f;  // log2(e) / sqrt(128)
-constexpr float kRefInit = -3.0e38f;  // "no key seen yet" reference, finite so that -inf - ref stays -inf
 constexpr float kRescaleSlack = 16.f;  // a lane's reference is refreshed when a logit exceeds it by this much (log2 units)
 
 template <int DT>
