@@ -24,6 +24,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 
+# HBM bytes per launch measured with rocprofv3 counters (FETCH_SIZE and WRITE_SIZE, each scaled by what
+# the same counter reads for a copy of known size; profiles/scan_fused_config3_hbm_traffic.txt).
+# Only for the workload they were measured on.
+MEASURED_TRAFFIC = {(3, "scan_fused"): 12.47e9, (3, "compact"): 8.40e9}
+
 
 def _oracle_worker(args):
     import oracle  # test infrastructure, used here only for the reported CPU baseline
@@ -70,6 +75,32 @@ def cpu_baseline(cfg, st, k0, v0, q, n_heads=320, seed=1):
     }
 
 
+def calib_copy(reps: int = 3) -> int:
+    """Counter calibration: a plain shifted copy of known size through skipkv_compact (row k <- row
+    k+1 of every head: every byte of K and V is read once and written once), so that what
+    rocprofv3's FETCH_SIZE / WRITE_SIZE read for a known amount of HBM traffic can be compared."""
+    import torch
+
+    from paper_2512_07993_amd import binding as B
+    torch.cuda.set_device(0)
+    L, H, T = 8, 8, 65536
+    k = torch.randn((L, H, T, 128), device="cuda").to(torch.bfloat16)
+    v = torch.randn((L, H, T, 128), device="cuda").to(torch.bfloat16)
+    so = torch.tensor([0, T], dtype=torch.int32, device="cuda")
+    sp = torch.tensor([0, 2], dtype=torch.int32, device="cuda")
+    sf = torch.tensor([0, T], dtype=torch.int32, device="cuda")
+    cache = B.Cache(k, v, H, so, sp, sf, T, 1)
+    kept = (torch.arange(T - 1, dtype=torch.int32, device="cuda") + 1).repeat(L, H, 1, 1).contiguous()
+    new_len = torch.full((L, H, 1), T - 1, dtype=torch.int32, device="cuda")
+    for _ in range(reps):
+        B.skipkv_compact(cache, kept, new_len, T - 1)
+    torch.cuda.synchronize()
+    moved = 2 * L * H * (T - 1) * 256
+    print(json.dumps({"calibration": "shifted copy through k_compact", "launches": reps,
+                      "bytes_read_per_launch": moved, "bytes_written_per_launch": moved}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -78,7 +109,10 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=3, help="workload: index into BASELINE.json configs (1-based)")
     ap.add_argument("--copies", type=int, default=5, help="pristine-copy working buffers (HBM: 2 x cache each)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true", help="run only the counter-calibration copy (see profiles/)")
     args = ap.parse_args()
+    if args.calib_copy:
+        return calib_copy()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (heads are independent: more GPUs would only shard them); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -203,7 +237,7 @@ def main() -> int:
         "kernel_ms": {n: round(t, 4) for n, t in avg.items()},
         "roofline": {
             "kernel": dominant, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+            "frac": achieved / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC.get((args.config, dominant)),
             "algorithmic_bytes_per_launch": kernel_bytes[dominant],
         },
     }
