@@ -123,6 +123,12 @@ int skipkv_workspace_bytes(const skipkv_cache *cache, const skipkv_params *param
  * tok_redundancy  device [n_layers, n_kv_heads, total_tokens] fp32 or NULL (R = 0).
  * sent_score, sent_lambda   device out [n_layers, n_kv_heads, total_sentences] fp32.
  * tok_importance  device out [n_layers, n_kv_heads, total_tokens] fp32, or NULL.
+ * The key scan reads K once where it can (query rows n * obs_window <= 64 after padding, no
+ * sentence longer than 256 tokens, at most 131072 tokens per sequence) and twice otherwise.
+ * Its single-pass form waits across workgroups; the wait is bounded (environment variable
+ * SKIPKV_SPIN_LIMIT, polls, default 4000000): on expiry SKIPKV_DEV_TIMEOUT is OR-ed into
+ * dev_status, scores are invalid and the call still completes.  SKIPKV_FORCE_TWO_PASS=1
+ * selects the two-pass form for every sequence.
  * ws              device workspace, 256-byte aligned, >= skipkv_workspace_bytes().
  */
 int skipkv_score(const skipkv_cache *cache, const skipkv_params *params, const void *q_obs,
@@ -145,7 +151,7 @@ int skipkv_score(const skipkv_cache *cache, const skipkv_params *params, const v
  *               offsets of the surviving sentences in the compacted cache (Eq. 11), stored
  *               at column sent_ptr[b]; new_sent_cnt [n_layers, n_kv_heads, batch] holds
  *               their number (both NULL or both non-NULL).
- * kept_stride   row pitch of kept_idx, >= min(max_budget, longest sequence).
+ * kept_stride   row pitch of kept_idx, >= min(max_budget, total_tokens).
  */
 int skipkv_select(const skipkv_cache *cache, const skipkv_params *params, const float *sent_score,
                   uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len, int32_t *new_sent_off,
