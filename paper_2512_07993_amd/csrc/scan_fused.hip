@@ -75,6 +75,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
   __shared__ float wstat[4][R][2];
   __shared__ float imp[2][kChunkCap];
   __shared__ int s_flag;
+  __shared__ float row_norm_l[R];
 
   const int tid = threadIdx.x, lane = tid & 63, c16 = lane & 15, g = lane >> 4;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: everything derived from it is uniform control flow
@@ -503,12 +504,15 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     }
 
     // =============== second phase: token importance from the logits still in registers =========
+    // the head's normalisers come in once per workgroup (coherent loads are slow) and go round through LDS
+    if (tid < R) row_norm_l[tid] = coherent_load(&rn[tid]);
+    lds_barrier();
     float cn[SLP];
 #pragma unroll
     for (int q = 0; q < SLP; ++q) {
       const int al = q / NP, i = q % NP;
       const bool used = q < SL && i < n && (g + 4 * al) < a.alpha;
-      cn[q] = used ? coherent_load(&rn[16 * (q >> 2) + 4 * g + (q & 3)]) : INFINITY;
+      cn[q] = used ? row_norm_l[16 * (q >> 2) + 4 * g + (q & 3)] : INFINITY;
     }
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
