@@ -13,7 +13,7 @@ constexpr int kChunkCap = 256;       // a chunk of scan work = a maximal run of 
 constexpr int kChunkMaxSent = 32;    // ... and at most this many sentences (a single longer sentence is a chunk of its own)
 constexpr int kFuseMaxChunks = 512;  // sequences with more chunks than this take the two-pass scan (see scan_fused.hip)
 constexpr float kRefInit = -3.0e38f;  // "no key seen yet" softmax reference, finite so that -inf - ref stays -inf
-constexpr int kRowBlock = 64;        // sentences per row block of the redundancy kernel
+constexpr int kRowBlock = 128;       // sentences per row block of the redundancy kernel
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;

@@ -6,19 +6,23 @@
 // to keep fp32-grade cosines (the ranking among near-duplicates depends on differences of
 // ~1e-3) each embedding is carried as bf16 hi + bf16 lo and a tile is the full product
 // (hi + lo)(hi + lo)^T: four bf16 MFMAs, small terms accumulated first.
-// One workgroup owns 64 rows (16 per wave, A operands in registers) and walks the column
-// blocks at and to the right of the diagonal, staged through LDS and shared by the 4 waves.
+// One workgroup owns kRowBlock = 128 rows (32 per wave, A operands in registers) and walks the
+// 64-column blocks at and to the right of the diagonal, staged through LDS and shared by the 4
+// waves; the next column block is fetched into registers while the current one is multiplied.
 #include "common.h"
 
 namespace skipkv {
 
 namespace {
 
-constexpr int LSTR = 272;  // bytes per staged embedding row (256 + 16 so that 16-byte reads of 8 rows hit distinct banks)
+constexpr int LSTR = 272;    // bytes per staged embedding row (256 + 16 so that 16-byte reads of 8 rows hit distinct banks)
+constexpr int kColBlock = 64;
+constexpr int kRowTiles = kRowBlock / 64;  // 16-row tiles per wave
+static_assert(kRowBlock % 64 == 0, "four waves, whole tiles");
 
 __global__ void __launch_bounds__(256) k_cosine(CosineArgs a) {
-  __shared__ __align__(16) char col_hi[kRowBlock * LSTR];
-  __shared__ __align__(16) char col_lo[kRowBlock * LSTR];
+  __shared__ __align__(16) char col_hi[kColBlock * LSTR];
+  __shared__ __align__(16) char col_lo[kColBlock * LSTR];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, c16 = lane & 15, g = lane >> 4;
   const uint32_t item = xcd_contiguous_item(blockIdx.x, gridDim.x);
@@ -33,11 +37,12 @@ __global__ void __launch_bounds__(256) k_cosine(CosineArgs a) {
   const char *hi = reinterpret_cast<const char *>(a.ws.vhat_hi) + col0 * 256;
   const char *lo = reinterpret_cast<const char *>(a.ws.vhat_lo) + col0 * 256;
 
-  // A operands: this wave's 16 rows, lane (row c16, head-dim slice g)
-  const int rw0 = r0 + 16 * wave;
-  bf16x8 a_hi[4], a_lo[4];
-  {
-    const int row = rw0 + c16;
+  // A operands: this wave's rows, lane (row c16 of a tile, head-dim slice g)
+  const int rw0 = r0 + 16 * kRowTiles * wave;
+  bf16x8 a_hi[kRowTiles][4], a_lo[kRowTiles][4];
+#pragma unroll
+  for (int t = 0; t < kRowTiles; ++t) {
+    const int row = rw0 + 16 * t + c16;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       uint4 vh = make_uint4(0, 0, 0, 0), vl = make_uint4(0, 0, 0, 0);
@@ -45,41 +50,63 @@ __global__ void __launch_bounds__(256) k_cosine(CosineArgs a) {
         vh = *reinterpret_cast<const uint4 *>(hi + (int64_t)row * 256 + g * 64 + kk * 16);
         vl = *reinterpret_cast<const uint4 *>(lo + (int64_t)row * 256 + g * 64 + kk * 16);
       }
-      a_hi[kk] = __builtin_bit_cast(bf16x8, vh);
-      a_lo[kk] = __builtin_bit_cast(bf16x8, vl);
+      a_hi[t][kk] = __builtin_bit_cast(bf16x8, vh);
+      a_lo[t][kk] = __builtin_bit_cast(bf16x8, vl);
     }
   }
-  float rmax[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+  float rmax[kRowTiles][4];
+#pragma unroll
+  for (int t = 0; t < kRowTiles; ++t)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) rmax[t][j] = -INFINITY;
 
-  for (int jb = r0; jb < n_sent; jb += kRowBlock) {
-    // stage columns [jb, jb+64) (hi and lo) in LDS
+  // a column block is 2 x 64 rows x 16 pieces of 16 bytes: 8 pieces per thread
+  uint4 pre[8];
+  auto fetch = [&](int jb) {
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
       const int idx = it * 256 + tid, half = idx >> 10, rem = idx & 1023, row = rem >> 4, piece = rem & 15;
-      uint4 val = make_uint4(0, 0, 0, 0);
-      if (jb + row < n_sent) val = *reinterpret_cast<const uint4 *>((half ? lo : hi) + (int64_t)(jb + row) * 256 + piece * 16);
-      *reinterpret_cast<uint4 *>((half ? col_lo : col_hi) + row * LSTR + piece * 16) = val;
+      pre[it] = make_uint4(0, 0, 0, 0);
+      if (jb + row < n_sent) pre[it] = *reinterpret_cast<const uint4 *>((half ? lo : hi) + (int64_t)(jb + row) * 256 + piece * 16);
     }
+  };
+  auto commit = [&]() {
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int idx = it * 256 + tid, half = idx >> 10, rem = idx & 1023, row = rem >> 4, piece = rem & 15;
+      *reinterpret_cast<uint4 *>((half ? col_lo : col_hi) + row * LSTR + piece * 16) = pre[it];
+    }
+  };
+
+  if (r0 < n_sent) fetch(r0);
+  for (int jb = r0; jb < n_sent; jb += kColBlock) {
+    commit();
     __syncthreads();
+    if (jb + kColBlock < n_sent) fetch(jb + kColBlock);  // lands while this block is multiplied
 #pragma unroll
-    for (int ct = 0; ct < 4; ++ct) {
+    for (int ct = 0; ct < kColBlock / 16; ++ct) {
       const int cbase = jb + 16 * ct;
-      if (cbase + 15 <= rw0 || cbase >= n_sent || rw0 >= n_sent) continue;  // nothing right of the diagonal in this tile
-      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+      if (cbase >= n_sent) continue;
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const bf16x8 b_hi = *reinterpret_cast<const bf16x8 *>(col_hi + (16 * ct + c16) * LSTR + g * 64 + kk * 16);
-        const bf16x8 b_lo = *reinterpret_cast<const bf16x8 *>(col_lo + (16 * ct + c16) * LSTR + g * 64 + kk * 16);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo[kk], b_lo, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo[kk], b_hi, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi[kk], b_lo, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi[kk], b_hi, acc, 0, 0, 0);
-      }
-      const int col = cbase + c16;
+      for (int t = 0; t < kRowTiles; ++t) {
+        const int rt0 = rw0 + 16 * t;
+        if (cbase + 15 <= rt0 || rt0 >= n_sent) continue;  // nothing right of the diagonal in this tile
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int row = rw0 + 4 * g + j;
-        if (col > row && col < n_sent) rmax[j] = fmaxf(rmax[j], acc[j]);
+        for (int kk = 0; kk < 4; ++kk) {
+          const bf16x8 b_hi = *reinterpret_cast<const bf16x8 *>(col_hi + (16 * ct + c16) * LSTR + g * 64 + kk * 16);
+          const bf16x8 b_lo = *reinterpret_cast<const bf16x8 *>(col_lo + (16 * ct + c16) * LSTR + g * 64 + kk * 16);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo[t][kk], b_lo, acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo[t][kk], b_hi, acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi[t][kk], b_lo, acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi[t][kk], b_hi, acc, 0, 0, 0);
+        }
+        const int col = cbase + c16;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int row = rt0 + 4 * g + j;
+          if (col > row && col < n_sent) rmax[t][j] = fmaxf(rmax[t][j], acc[j]);
+        }
       }
     }
     __syncthreads();
@@ -90,19 +117,22 @@ __global__ void __launch_bounds__(256) k_cosine(CosineArgs a) {
   const int n_tok = a.seq_off[b + 1] - tok0;
   const int p_start = n_tok - min(a.protect, n_tok);
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const float lam = row16_max(rmax[j]);
-    const int row = rw0 + 4 * g + j;
-    if (c16 == 0 && row < n_sent) {
-      const int64_t o = col0 + row;
-      float score = INFINITY;
-      if (a.sent_off[sp + row] < p_start) {
-        score = a.sigma * a.ws.sent_imp[o];
-        if (a.has_red) score -= (1.f - a.sigma) * a.ws.sent_red[o];
-        if (lam > a.tau) score -= lam;
+  for (int t = 0; t < kRowTiles; ++t) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float lam = row16_max(rmax[t][j]);
+      const int row = rw0 + 16 * t + 4 * g + j;
+      if (c16 == 0 && row < n_sent) {
+        const int64_t o = col0 + row;
+        float score = INFINITY;
+        if (a.sent_off[sp + row] < p_start) {
+          score = a.sigma * a.ws.sent_imp[o];
+          if (a.has_red) score -= (1.f - a.sigma) * a.ws.sent_red[o];
+          if (lam > a.tau) score -= lam;
+        }
+        a.sent_lambda[o] = lam;
+        a.sent_score[o] = score;
       }
-      a.sent_lambda[o] = lam;
-      a.sent_score[o] = score;
     }
   }
 }
