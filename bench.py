@@ -40,7 +40,7 @@ def _oracle_worker(args):
         return time.perf_counter() - t
 
 
-def cpu_baseline(cfg, st, k0, v0, q, n_heads=320, seed=1):
+def cpu_baseline(cfg, st, k0, v0, q, n_heads=640, seed=1):
     """Times the oracle as it stands on a bounded sample of heads of the same workload."""
     import multiprocessing as mp
 
