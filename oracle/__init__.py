@@ -6,6 +6,7 @@ benchmark's ``cpu_baseline`` leg do.  It shares no code with the HIP kernels.
 """
 from .skipkv_oracle import (  # noqa: F401
     token_importance,
+    token_redundancy,
     sentence_embeddings,
     sentence_redundancy,
     sentence_scores,

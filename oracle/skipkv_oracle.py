@@ -23,6 +23,9 @@ notes of the repository):
     its penalty is the largest such cosine;
   * token scores are aggregated to a sentence by the arithmetic mean over its
     unprotected span; the token-redundancy term R is an optional input (0 if absent);
+  * token redundancy (Eq.5): softmax of the cosine matrix along each row, then the mean over
+    the rows: R[t] is the average share of softmax mass the head's keys give to key t;
+    the diagonal is kept, there is no causal mask and no padding (ragged layout), eps = 1e-12;
   * eviction is by whole sentences: rank by (score desc, index desc), keep the longest
     prefix that fits the budget left after the protected recent window.
 
@@ -41,6 +44,7 @@ __all__ = [
     "token_importance",
     "sentence_embeddings",
     "sentence_redundancy",
+    "token_redundancy",
     "sentence_scores",
     "select_sentences",
     "remap_ranges",
@@ -119,6 +123,28 @@ def sentence_redundancy(v: np.ndarray, eps: float = 1e-12) -> np.ndarray:
 # --------------------------------------------------------------------------------------
 # Sec. 4.1 "Sentence Redundancy Driven Cumulative Score" (Eq.6), lifted to sentences
 # --------------------------------------------------------------------------------------
+# --------------------------------------------------------------------------------------
+# Sec. 4.1 "Token Redundancy Score" (Eq.5)
+# --------------------------------------------------------------------------------------
+def token_redundancy(k: np.ndarray, eps: float = 1e-12) -> np.ndarray:
+    """R[t] for one KV head: mean over the rows of the row-wise softmax of Kbar Kbar^T.
+
+    k : [N, D] keys of the head.  Kbar = k / (||k||_2 + eps) row by row.  Returns R : [N]
+    (R sums to 1).  The cosine matrix is symmetric, so "softmax along rows, mean along columns"
+    would give the same vector; a mean along the softmax axis would be the constant 1/N and is
+    not what a per-token score can mean.
+    """
+    k = np.asarray(k, dtype=np.float64)
+    n_tok = k.shape[0]
+    if n_tok == 0:
+        return np.zeros(0)
+    kbar = k / (np.sqrt((k * k).sum(axis=1, keepdims=True)) + eps)
+    cos = kbar @ kbar.T
+    e = np.exp(cos - cos.max(axis=1, keepdims=True))
+    p = e / e.sum(axis=1, keepdims=True)
+    return p.mean(axis=0)
+
+
 def sentence_scores(imp, lam, off, protect, sigma=0.1, tau=0.95, red=None):
     """Per-sentence eviction score and the number of unprotected tokens of each sentence.
 
