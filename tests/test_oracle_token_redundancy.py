@@ -41,8 +41,8 @@ def test_two_orthogonal_clusters_closed_form():
     r_a = (m * math.e / za + (n - m) * 1.0 / zb) / n
     r_b = (m * 1.0 / za + (n - m) * math.e / zb) / n
     got = oracle.token_redundancy(k)
-    np.testing.assert_allclose(got[:m], r_a, rtol=1e-12)
-    np.testing.assert_allclose(got[m:], r_b, rtol=1e-12)
+    np.testing.assert_allclose(got[:m], r_a, rtol=1e-10)  # eps = 1e-12 in the norm moves the cosines by ~1e-12
+    np.testing.assert_allclose(got[m:], r_b, rtol=1e-10)
     assert r_b > r_a  # the larger cluster is the more redundant one
 
 
