@@ -174,6 +174,23 @@ int skipkv_step(const skipkv_cache *cache, const skipkv_params *params, const vo
                 size_t ws_bytes, void *stream);
 
 /*
+ * Token redundancy (Sec. 4.1 "Token Redundancy Score", Eq. 5).  Per head, with Kbar the rows of
+ * K scaled to unit length (1e-12 added to the norm):
+ *   R[t] = mean over rows i of softmax_j(Kbar Kbar^T)[i, t]
+ * (softmax along each row of the cosine matrix, mean over the rows; the diagonal is kept; no
+ * causal mask).  R sums to 1 over the tokens of a head.  Cost is quadratic in the cache length:
+ * 2 N^2 dot products of length 128 per head.  The dot products are taken in bf16 (fp32 caches
+ * are rounded to bf16 for this call), accumulated in fp32.  The result can be handed to
+ * skipkv_score / skipkv_step as tok_redundancy.
+ * tok_redundancy  device out [n_layers, n_kv_heads, total_tokens] fp32.
+ * ws, ws_bytes    device scratch of at least skipkv_redundancy_workspace_bytes, 256-byte aligned.
+ * Uses cache->k, strides, dtype, n_layers, n_kv_heads, batch, total_tokens, seq_off only.
+ */
+int skipkv_redundancy_workspace_bytes(const skipkv_cache *cache, size_t *out_bytes);
+int skipkv_token_redundancy(const skipkv_cache *cache, float *tok_redundancy, void *ws, size_t ws_bytes,
+                            void *stream);
+
+/*
  * Steering injection (Sec. 4.2): hidden[b, :] <- hidden[b, :] + coef_b * vec for every row b
  * with row_mask[b] != 0 (all rows when row_mask is NULL).  coef_b = coef[b] when coef is
  * non-NULL, else coef_scalar.  The sum is formed in fp64 and rounded once (nearest even)

@@ -59,6 +59,8 @@ def lib() -> C.CDLL:
         L.skipkv_select.argtypes = [cp, pp, vp, vp, vp, vp, vp, vp, i32, vp]
         L.skipkv_compact.argtypes = [cp, vp, vp, i32, vp]
         L.skipkv_step.argtypes = [cp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+        L.skipkv_redundancy_workspace_bytes.argtypes = [cp, C.POINTER(sz)]
+        L.skipkv_token_redundancy.argtypes = [cp, vp, vp, sz, vp]
         L.skipkv_steer_add.argtypes = [vp, vp, vp, fl, vp, i32, i32, i32, vp]
         L.skipkv_profile_create.argtypes = [C.POINTER(vp)]
         L.skipkv_profile_read.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_char_p), C.POINTER(fl)]
@@ -67,7 +69,8 @@ def lib() -> C.CDLL:
         L.skipkv_strerror.restype = C.c_char_p
         L.skipkv_version.argtypes = []
         for name in ("skipkv_workspace_bytes", "skipkv_score", "skipkv_select", "skipkv_compact", "skipkv_step",
-                     "skipkv_steer_add", "skipkv_profile_create", "skipkv_profile_read", "skipkv_profile_destroy",
+                     "skipkv_steer_add", "skipkv_redundancy_workspace_bytes", "skipkv_token_redundancy",
+                     "skipkv_profile_create", "skipkv_profile_read", "skipkv_profile_destroy",
                      "skipkv_version"):
             getattr(L, name).restype = C.c_int
         _lib = L
@@ -192,6 +195,17 @@ def skipkv_step(cache: Cache, params: Params, q_obs, tok_redundancy, sent_score,
                              _ptr(sent_score), _ptr(sent_lambda), _ptr(tok_importance), _ptr(sent_keep),
                              _ptr(kept_idx), _ptr(new_len), _ptr(new_sent_off), _ptr(new_sent_cnt), kept_stride,
                              _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
+
+
+def skipkv_redundancy_workspace_bytes(cache: Cache) -> int:
+    out = C.c_size_t(0)
+    _check(lib().skipkv_redundancy_workspace_bytes(C.byref(cache.c()), C.byref(out)))
+    return int(out.value)
+
+
+def skipkv_token_redundancy(cache: Cache, tok_redundancy, ws, stream=None) -> None:
+    _check(lib().skipkv_token_redundancy(C.byref(cache.c()), _ptr(tok_redundancy), _ptr(ws),
+                                         ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
 
 
 def skipkv_steer_add(hidden, vec, coef, coef_scalar: float, row_mask, stream=None) -> None:

@@ -313,6 +313,40 @@ int skipkv_step(const skipkv_cache *cache, const skipkv_params *params, const vo
   return do_compact(tm, cache, kept_idx, new_len, kept_stride, st);
 }
 
+int skipkv_redundancy_workspace_bytes(const skipkv_cache *cache, size_t *out_bytes) {
+  if (!out_bytes) return SKIPKV_EINVAL;
+  const int rc = check_cache(cache, false);
+  if (rc) return rc;
+  const size_t per = align_up((size_t)cache->n_layers * cache->n_kv_heads * (size_t)cache->total_tokens * sizeof(float));
+  *out_bytes = 2 * per;
+  return SKIPKV_OK;
+}
+
+int skipkv_token_redundancy(const skipkv_cache *cache, float *tok_redundancy, void *ws, size_t ws_bytes, void *stream) {
+  const int rc = check_cache(cache, false);
+  if (rc) return rc;
+  if (is_empty(cache) || cache->total_tokens == 0) return SKIPKV_OK;
+  if (!tok_redundancy) return SKIPKV_EINVAL;
+  const size_t per = align_up((size_t)cache->n_layers * cache->n_kv_heads * (size_t)cache->total_tokens * sizeof(float));
+  if (!ws || !aligned16(ws) || ws_bytes < 2 * per) return SKIPKV_EWORKSPACE;
+  TokRedArgs a{};
+  a.k = cache->k;
+  a.stride_layer = cache->stride_layer;
+  a.stride_head = cache->stride_head;
+  a.stride_tok = cache->stride_tok;
+  a.dtype = cache->dtype;
+  a.n_layers = cache->n_layers;
+  a.n_kv_heads = cache->n_kv_heads;
+  a.batch = cache->batch;
+  a.total_tokens = cache->total_tokens;
+  a.nrb_max = (cache->total_tokens + 255) / 256 + cache->batch;
+  a.seq_off = cache->seq_off;
+  a.scale = static_cast<float *>(ws);
+  a.neg_log_l = reinterpret_cast<float *>(static_cast<char *>(ws) + per);
+  a.out = tok_redundancy;
+  return launch_token_redundancy(a, static_cast<hipStream_t>(stream)) == hipSuccess ? SKIPKV_OK : SKIPKV_EHIP;
+}
+
 int skipkv_steer_add(void *hidden, const void *vec, const float *coef, float coef_scalar, const uint8_t *row_mask,
                      int32_t rows, int32_t d_model, int32_t dtype, void *stream) {
   if (rows < 0 || d_model < 0) return SKIPKV_EINVAL;

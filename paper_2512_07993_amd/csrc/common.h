@@ -149,6 +149,18 @@ struct CompactArgs {
 };
 hipError_t launch_compact(const CompactArgs &a, hipStream_t st);
 
+struct TokRedArgs {
+  const void *k;
+  int64_t stride_layer, stride_head, stride_tok;
+  int32_t dtype, n_layers, n_kv_heads, batch, total_tokens;
+  int32_t nrb_max;           // upper bound on the 256-row blocks of all sequences
+  const int32_t *seq_off;
+  float *scale;              // [LH, T] workspace: sqrt(log2 e) / (||k|| + eps)
+  float *neg_log_l;          // [LH, T] workspace: -log2 of the row sums
+  float *out;                // [LH, T] token redundancy
+};
+hipError_t launch_token_redundancy(const TokRedArgs &a, hipStream_t st);
+
 struct SteerArgs {
   void *hidden;
   const void *vec;

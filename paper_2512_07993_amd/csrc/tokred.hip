@@ -1,0 +1,225 @@
+// Token redundancy (Sec. 4.1 "Token Redundancy Score", Eq. 5): per head, with Kbar the rows of K
+// scaled to unit length, R[t] = mean over rows i of softmax_j(Kbar Kbar^T)[i, t].
+//
+// The cosine matrix is symmetric and its entries lie in [-1, 1], so no running maximum is
+// needed: with E = exp(Kbar Kbar^T), l = E 1 (row sums) and R = (1/N) E (1 / l).  Both are
+// "row block times all columns" sweeps over the same N x N matrix, which is never stored:
+//   sweep 1:  l_i = sum_j exp2(s_ij)                      -> kept as  -log2(l_i)
+//   sweep 2:  R_i = (1/N) sum_j exp2(s_ij - log2 l_j)
+// where s_ij = <k_i, k_j> * c_i * c_j and c = sqrt(log2 e) / (||k|| + eps) carries both the
+// normalisation and the change of base.  The dot products run on the bf16 matrix cores with the
+// RAW keys (exact products, fp32 accumulation; fp32 caches are rounded to bf16 first) and the
+// scale factors are applied to the accumulators.
+//
+// One workgroup owns 256 rows (64 per wave: the A operands stay in registers) and walks the
+// 64-column blocks of its sequence, staged through LDS and shared by the 4 waves; the next block
+// is fetched into registers while the current one is multiplied.
+#include <algorithm>
+
+#include "common.h"
+
+namespace skipkv {
+
+namespace {
+
+constexpr int kRows = 256;     // rows per workgroup
+constexpr int kCols = 64;      // columns per staged block
+constexpr int LSTR = 272;      // bytes per staged key row (256 + 16: 16-byte reads of 8 rows hit distinct banks)
+constexpr float kSqrtLog2e = 1.2011224087864498f;
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {  // two fp32 -> packed bf16, nearest even
+  typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+  bf16x2_t v;
+  v[0] = (__bf16)lo;
+  v[1] = (__bf16)hi;
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+// 16 bytes of a key row as bf16: piece p (8 elements) of the row at `row_ptr`.
+template <int DT>
+__device__ __forceinline__ uint4 load_piece_bf16(const char *row_ptr, int piece) {
+  if constexpr (DT == SKIPKV_BF16) {
+    return *reinterpret_cast<const uint4 *>(row_ptr + piece * 16);
+  } else {
+    const float4 x = *reinterpret_cast<const float4 *>(row_ptr + piece * 32);
+    const float4 y = *reinterpret_cast<const float4 *>(row_ptr + piece * 32 + 16);
+    return make_uint4(pack2(x.x, x.y), pack2(x.z, x.w), pack2(y.x, y.y), pack2(y.z, y.w));
+  }
+}
+
+// c[t] = sqrt(log2 e) / (||k_t|| + eps) for every key row; 16 lanes per row.
+template <int DT>
+__global__ void __launch_bounds__(256) k_key_scale(TokRedArgs a) {
+  constexpr int ESZ = DT == SKIPKV_BF16 ? 2 : 4;
+  const int lane16 = threadIdx.x & 15;
+  const int64_t n_rows = (int64_t)a.n_layers * a.n_kv_heads * a.total_tokens;
+  for (int64_t row = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 4; row < n_rows; row += ((int64_t)gridDim.x * 256) >> 4) {
+    const int64_t lh = row / a.total_tokens, t = row % a.total_tokens;
+    const int l = (int)(lh / a.n_kv_heads), h = (int)(lh % a.n_kv_heads);
+    const char *p = static_cast<const char *>(a.k) + ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head + t * a.stride_tok) * ESZ;
+    float ss = 0.f;
+    if constexpr (DT == SKIPKV_BF16) {
+      const uint4 v = *reinterpret_cast<const uint4 *>(p + lane16 * 16);
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float x = __uint_as_float(w[i] << 16), y = __uint_as_float(w[i] & 0xFFFF0000u);
+        ss += x * x + y * y;
+      }
+    } else {
+      // the dot products use the keys rounded to bf16: the norm is taken of the same values
+      const uint4 v = load_piece_bf16<DT>(p, lane16);
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float x = __uint_as_float(w[i] << 16), y = __uint_as_float(w[i] & 0xFFFF0000u);
+        ss += x * x + y * y;
+      }
+    }
+    ss = row16_sum(ss);
+    if (lane16 == 0) a.scale[row] = kSqrtLog2e / (sqrtf(ss) + 1e-12f);
+  }
+}
+
+// SWEEP 1: writes neg_log_l[row] = -log2(sum_j exp2(s_ij)).  SWEEP 2: writes R[row].
+template <int DT, int SWEEP>
+__global__ void __launch_bounds__(256) k_tokred_sweep(TokRedArgs a) {
+  constexpr int ESZ = DT == SKIPKV_BF16 ? 2 : 4;
+  __shared__ __align__(16) char cols[kCols * LSTR];
+  __shared__ float col_c[kCols];   // scale factor of each staged column
+  __shared__ float col_w[kCols];   // sweep 2: -log2 l of each staged column
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, c16 = lane & 15, g = lane >> 4;
+  // ---- which (head, sequence, row block) is this?
+  const uint32_t item = xcd_contiguous_item(blockIdx.x, gridDim.x);
+  if (item >= (uint32_t)a.n_layers * a.n_kv_heads * (uint32_t)a.nrb_max) return;
+  const int lh = item / a.nrb_max;
+  int j = item % a.nrb_max, b = 0, n_tok = 0, tok0 = 0;
+  for (; b < a.batch; ++b) {
+    tok0 = a.seq_off[b];
+    n_tok = a.seq_off[b + 1] - tok0;
+    const int cnt = (n_tok + kRows - 1) / kRows;
+    if (j < cnt) break;
+    j -= cnt;
+  }
+  if (b >= a.batch) return;
+  const int r0 = j * kRows;
+  const int l = lh / a.n_kv_heads, h = lh % a.n_kv_heads;
+  const char *kbase = static_cast<const char *>(a.k) + ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head + (int64_t)tok0 * a.stride_tok) * ESZ;
+  const int64_t pitch = a.stride_tok * ESZ;
+  const int64_t col0 = (int64_t)lh * a.total_tokens + tok0;  // index of the sequence's first token in the per-token arrays
+
+  // ---- A operands: this wave's 64 rows (4 tiles), lane (row c16 of a tile, head-dim slice g)
+  const int rw0 = r0 + 64 * wave;
+  bf16x8 af[4][4];
+  float row_c[4][4];  // scale factors of the lane's output rows (rows 4g+j of every tile)
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int row = min(rw0 + 16 * t + c16, n_tok - 1);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) af[t][kk] = __builtin_bit_cast(bf16x8, load_piece_bf16<DT>(kbase + (int64_t)row * pitch, 4 * g + kk));
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) row_c[t][jj] = a.scale[col0 + min(rw0 + 16 * t + 4 * g + jj, n_tok - 1)];
+  }
+  float rsum[4][4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) rsum[t][jj] = 0.f;
+
+  // a column block is 64 rows x 16 pieces of 16 bytes: 4 pieces per thread
+  uint4 pre[4];
+  float pre_c = 0.f, pre_w = 0.f;
+  auto fetch = [&](int jb) {
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int idx = it * 256 + tid, row = min(jb + (idx >> 4), n_tok - 1), piece = idx & 15;
+      pre[it] = load_piece_bf16<DT>(kbase + (int64_t)row * pitch, piece);
+    }
+    if (tid < kCols) {
+      const int col = min(jb + tid, n_tok - 1);
+      pre_c = a.scale[col0 + col];
+      if (SWEEP == 2) pre_w = a.neg_log_l[col0 + col];
+    }
+  };
+  auto commit = [&]() {
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int idx = it * 256 + tid, row = idx >> 4, piece = idx & 15;
+      *reinterpret_cast<uint4 *>(cols + row * LSTR + piece * 16) = pre[it];
+    }
+    if (tid < kCols) {
+      col_c[tid] = pre_c;
+      col_w[tid] = pre_w;
+    }
+  };
+
+  fetch(0);
+  for (int jb = 0; jb < n_tok; jb += kCols) {
+    commit();
+    __syncthreads();
+    if (jb + kCols < n_tok) fetch(jb + kCols);  // lands while this block is multiplied
+    if (rw0 < n_tok) {
+#pragma unroll
+      for (int ct = 0; ct < kCols / 16; ++ct) {
+        const int cbase = jb + 16 * ct;
+        if (cbase >= n_tok) continue;
+        bf16x8 bfr[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) bfr[kk] = *reinterpret_cast<const bf16x8 *>(cols + (16 * ct + c16) * LSTR + (4 * g + kk) * 16);
+        const bool live = cbase + c16 < n_tok;                  // this lane's column exists
+        const float cc = col_c[16 * ct + c16];
+        const float cw = live ? col_w[16 * ct + c16] : -INFINITY;  // exp2(-inf) = 0 drops columns past the end
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[t][kk], bfr[kk], acc, 0, 0, 0);
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) rsum[t][jj] += __builtin_amdgcn_exp2f(fmaf(acc[jj], row_c[t][jj] * cc, cw));
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  // ---- sums across the 16 column lanes, then the sweep's output
+  const float inv_n = 1.f / (float)n_tok;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const float s = row16_sum(rsum[t][jj]);
+      const int row = rw0 + 16 * t + 4 * g + jj;
+      if (c16 == 0 && row < n_tok) {
+        if (SWEEP == 1)
+          a.neg_log_l[col0 + row] = -__builtin_amdgcn_logf(s);  // log2
+        else
+          a.out[col0 + row] = s * inv_n;
+      }
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_token_redundancy(const TokRedArgs &a, hipStream_t st) {
+  const int64_t n_lh = (int64_t)a.n_layers * a.n_kv_heads;
+  if (n_lh == 0 || a.total_tokens == 0 || a.batch == 0) return hipSuccess;
+  const int64_t rows = n_lh * a.total_tokens;
+  const unsigned g0 = (unsigned)std::min<int64_t>((rows + 15) / 16, 1 << 16);
+  const int64_t items = n_lh * a.nrb_max;
+  const unsigned g1 = (unsigned)((items + 7) / 8 * 8);
+  if (a.dtype == SKIPKV_BF16) {
+    hipLaunchKernelGGL(k_key_scale<SKIPKV_BF16>, dim3(g0), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((k_tokred_sweep<SKIPKV_BF16, 1>), dim3(g1), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((k_tokred_sweep<SKIPKV_BF16, 2>), dim3(g1), dim3(256), 0, st, a);
+  } else {
+    hipLaunchKernelGGL(k_key_scale<SKIPKV_F32>, dim3(g0), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((k_tokred_sweep<SKIPKV_F32, 1>), dim3(g1), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((k_tokred_sweep<SKIPKV_F32, 2>), dim3(g1), dim3(256), 0, st, a);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace skipkv
