@@ -101,6 +101,41 @@ def calib_copy(reps: int = 3) -> int:
     return 0
 
 
+def time_redundancy(config: int, reps: int = 3) -> int:
+    """Times skipkv_token_redundancy (Eq.5, optional input of the step, quadratic in the cache
+    length) on a workload's keys; prints one JSON line of its own.  Not part of the headline step."""
+    import torch
+
+    from paper_2512_07993_amd import binding as B
+    from paper_2512_07993_amd import workloads as W
+    torch.cuda.set_device(0)
+    cfg = W.CONFIGS[config]
+    st = W.make_structure(cfg)
+    k0, v0, _ = W.fill_cache(cfg, st, device="cuda:0")
+    so = torch.from_numpy(st.seq_off).cuda()
+    sp = torch.from_numpy(st.sent_ptr).cuda()
+    sf = torch.from_numpy(st.sent_off).cuda()
+    cache = B.Cache(k0, v0, cfg.n_q_heads, so, sp, sf, st.total_tokens, st.total_sentences)
+    ws = torch.empty(B.skipkv_redundancy_workspace_bytes(cache), dtype=torch.uint8, device="cuda")
+    out = torch.empty((cfg.n_layers, cfg.n_kv_heads, st.total_tokens), dtype=torch.float32, device="cuda")
+    B.skipkv_token_redundancy(cache, out, ws)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        B.skipkv_token_redundancy(cache, out, ws)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    pairs = float((st.seq_len.astype("float64") ** 2).sum()) * cfg.n_layers * cfg.n_kv_heads
+    flops = 2 * pairs * 128 * 2          # two sweeps over the full cosine matrix
+    print(json.dumps({"op": "token_redundancy", "workload": "config %d: %s" % (cfg.config_id, cfg.name), "ms": ms,
+                      "key_pairs_per_sweep": pairs, "mfma_tflops": flops / (ms * 1e-3) / 1e12,
+                      "frac_of_bf16_mfma_peak": flops / (ms * 1e-3) / 2.5e15,
+                      "exp_per_s": 2 * pairs / (ms * 1e-3)}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -110,9 +145,12 @@ def main() -> int:
     ap.add_argument("--copies", type=int, default=5, help="pristine-copy working buffers (HBM: 2 x cache each)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy", action="store_true", help="run only the counter-calibration copy (see profiles/)")
+    ap.add_argument("--redundancy", action="store_true", help="time only skipkv_token_redundancy on the workload's keys")
     args = ap.parse_args()
     if args.calib_copy:
         return calib_copy()
+    if args.redundancy:
+        return time_redundancy(args.config)
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (heads are independent: more GPUs would only shard them); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
