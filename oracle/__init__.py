@@ -7,6 +7,8 @@ benchmark's ``cpu_baseline`` leg do.  It shares no code with the HIP kernels.
 from .skipkv_oracle import (  # noqa: F401
     token_importance,
     token_redundancy,
+    token_scores,
+    select_tokens,
     sentence_embeddings,
     sentence_redundancy,
     sentence_scores,

@@ -27,7 +27,11 @@ notes of the repository):
     the rows: R[t] is the average share of softmax mass the head's keys give to key t;
     the diagonal is kept, there is no causal mask and no padding (ragged layout), eps = 1e-12;
   * eviction is by whole sentences: rank by (score desc, index desc), keep the longest
-    prefix that fits the budget left after the protected recent window.
+    prefix that fits the budget left after the protected recent window;
+  * the token-level form of the same step (Eq.6 as printed: every token of a redundant sentence
+    carries the sentence's penalty): the protected recent window is always kept, the other
+    tokens are ranked by (score desc, index desc) and exactly budget - window of them survive;
+    sentence ranges follow Eq.11.
 
 Parity pins: every function below is pinned by tests/test_oracle_*.py against library
 routines, closed forms, brute force or invariants.  The whole-step result has no
@@ -47,6 +51,8 @@ __all__ = [
     "token_redundancy",
     "sentence_scores",
     "select_sentences",
+    "token_scores",
+    "select_tokens",
     "remap_ranges",
     "compact",
     "compress_head",
@@ -225,6 +231,52 @@ def select_sentences(score, candlen, off, budget, protect):
         "new_len": len(kept),
         "new_off": np.asarray(new_off, dtype=np.int64),
     }
+
+
+# --------------------------------------------------------------------------------------
+# Token-level form of Eq.6 and of the eviction rule that follows it
+# --------------------------------------------------------------------------------------
+def token_scores(imp, red, lam, off, sigma=0.1, tau=0.95):
+    """Eq.6 per token: sigma * I[t] - (1 - sigma) * R[t], minus lambda_s for every token of a
+    sentence s in the redundant set (lambda_s > tau).  red may be None (R = 0)."""
+    imp = np.asarray(imp, dtype=np.float64)
+    score = sigma * imp
+    if red is not None:
+        score = score - (1.0 - sigma) * np.asarray(red, dtype=np.float64)
+    score = score.copy()
+    for s in range(len(off) - 1):
+        if lam[s] > tau:
+            score[int(off[s]):int(off[s + 1])] -= lam[s]
+    return score
+
+
+def select_tokens(score, off, budget, protect):
+    """Token-level selection under a budget ("evict tokens in increasing order of the final score").
+
+    The last min(protect, N) tokens are kept.  If N <= budget everything is kept; otherwise the
+    remaining tokens are ranked by (score desc, index desc) and the first budget - window of them
+    are kept, so exactly `budget` tokens survive.  Returns dict(keep [N] bool, kept_idx
+    ascending, new_len, new_off): new_off are the offsets of the sentences that still have a
+    token, in the compacted cache (Eq.11; a sentence with no survivor is dropped).
+    """
+    score = np.asarray(score, dtype=np.float64)
+    off = np.asarray(off, dtype=np.int64)
+    n_tok = int(off[-1])
+    p = n_tok - min(protect, n_tok)
+    keep = np.ones(n_tok, dtype=bool)
+    if n_tok > budget:
+        room = budget - (n_tok - p)
+        order = sorted(range(p), key=lambda t: (-score[t], -t))
+        keep[:p] = False
+        for t in order[:room]:
+            keep[t] = True
+    kept = np.nonzero(keep)[0].astype(np.int64)
+    new_off = [0]
+    for s in range(len(off) - 1):
+        cnt = int(keep[int(off[s]):int(off[s + 1])].sum())
+        if cnt:
+            new_off.append(new_off[-1] + cnt)
+    return {"keep": keep, "kept_idx": kept, "new_len": len(kept), "new_off": np.asarray(new_off, dtype=np.int64)}
 
 
 def remap_ranges(off, kept_idx):
