@@ -61,7 +61,8 @@ enum {
 enum {
   SKIPKV_DEV_BAD_OFFSETS = 1,  /* sentence offsets not strictly ascending from 0 to N_b   */
   SKIPKV_DEV_TOO_MANY_SENT = 2, /* a sequence has more than SKIPKV_MAX_SENTENCES sentences */
-  SKIPKV_DEV_TIMEOUT = 4        /* a bounded cross-workgroup wait ran out: scores are invalid  */
+  SKIPKV_DEV_TIMEOUT = 4,       /* a bounded cross-workgroup wait ran out: scores are invalid  */
+  SKIPKV_DEV_TOO_MANY_TOK = 8   /* skipkv_select_tokens: a sequence is longer than SKIPKV_MAX_TOKENS_TOKEN_SELECT */
 };
 
 typedef enum { SKIPKV_F32 = 0, SKIPKV_BF16 = 1 } skipkv_dtype;
@@ -71,6 +72,7 @@ typedef enum { SKIPKV_F32 = 0, SKIPKV_BF16 = 1 } skipkv_dtype;
 #define SKIPKV_MAX_GROUP 8        /* n = n_q_heads / n_kv_heads                           */
 #define SKIPKV_MAX_OBS_WINDOW 32  /* alpha                                                */
 #define SKIPKV_MAX_SENTENCES 4096 /* per sequence                                         */
+#define SKIPKV_MAX_TOKENS_TOKEN_SELECT 131072 /* per sequence, token-level selection only   */
 
 /* The KV cache and its ragged structure (Sec. 4.1: K, V in R^{bs x H_k x N' x d}). */
 typedef struct skipkv_cache {
@@ -172,6 +174,26 @@ int skipkv_step(const skipkv_cache *cache, const skipkv_params *params, const vo
                 float *tok_importance, uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len,
                 int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride, void *ws,
                 size_t ws_bytes, void *stream);
+
+/*
+ * Token-level selection: Eq. 6 as printed and the rule after it ("evict tokens in increasing
+ * order of the final score").  Per head and token t of sentence s:
+ *   tok_score[t] = sigma * I[t] - (1 - sigma) * R[t] - (lambda_s if lambda_s > tau)
+ * The last min(protect_window, N) tokens are kept; if N > budget, the other tokens are ranked by
+ * (score descending, index descending) and exactly budget - window of them are kept.  Sentence
+ * ranges follow Eq. 11: new_sent_off / new_sent_cnt list the sentences that still have a token.
+ * The outputs have the layout of skipkv_select and feed skipkv_compact unchanged.
+ * tok_importance  device [n_layers, n_kv_heads, total_tokens] fp32 (from skipkv_score).
+ * tok_redundancy  device, same shape, or NULL (R = 0).   sent_lambda  device (from skipkv_score).
+ * tok_score       device out, same shape, required (also the kernel's working copy).
+ * tok_keep        device out [n_layers, n_kv_heads, total_tokens] u8, or NULL.
+ * A sequence longer than SKIPKV_MAX_TOKENS_TOKEN_SELECT gets new_len 0 and
+ * SKIPKV_DEV_TOO_MANY_TOK in dev_status.
+ */
+int skipkv_select_tokens(const skipkv_cache *cache, const skipkv_params *params, const float *tok_importance,
+                         const float *tok_redundancy, const float *sent_lambda, float *tok_score,
+                         uint8_t *tok_keep, int32_t *kept_idx, int32_t *new_len, int32_t *new_sent_off,
+                         int32_t *new_sent_cnt, int32_t kept_stride, void *stream);
 
 /*
  * Token redundancy (Sec. 4.1 "Token Redundancy Score", Eq. 5).  Per head, with Kbar the rows of

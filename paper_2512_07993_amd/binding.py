@@ -16,7 +16,7 @@ import torch
 
 F32, BF16 = 0, 1
 OK, EINVAL, EBUDGET, ECAPACITY, EWORKSPACE, EHIP = 0, -1, -2, -3, -4, -5
-DEV_BAD_OFFSETS, DEV_TOO_MANY_SENT, DEV_TIMEOUT = 1, 2, 4
+DEV_BAD_OFFSETS, DEV_TOO_MANY_SENT, DEV_TIMEOUT, DEV_TOO_MANY_TOK = 1, 2, 4, 8
 PROFILE_SLOTS = 16
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libskipkv.so")
@@ -59,6 +59,7 @@ def lib() -> C.CDLL:
         L.skipkv_select.argtypes = [cp, pp, vp, vp, vp, vp, vp, vp, i32, vp]
         L.skipkv_compact.argtypes = [cp, vp, vp, i32, vp]
         L.skipkv_step.argtypes = [cp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+        L.skipkv_select_tokens.argtypes = [cp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
         L.skipkv_redundancy_workspace_bytes.argtypes = [cp, C.POINTER(sz)]
         L.skipkv_token_redundancy.argtypes = [cp, vp, vp, sz, vp]
         L.skipkv_steer_add.argtypes = [vp, vp, vp, fl, vp, i32, i32, i32, vp]
@@ -70,6 +71,7 @@ def lib() -> C.CDLL:
         L.skipkv_version.argtypes = []
         for name in ("skipkv_workspace_bytes", "skipkv_score", "skipkv_select", "skipkv_compact", "skipkv_step",
                      "skipkv_steer_add", "skipkv_redundancy_workspace_bytes", "skipkv_token_redundancy",
+                     "skipkv_select_tokens",
                      "skipkv_profile_create", "skipkv_profile_read", "skipkv_profile_destroy",
                      "skipkv_version"):
             getattr(L, name).restype = C.c_int
@@ -183,6 +185,14 @@ def skipkv_select(cache: Cache, params: Params, sent_score, sent_keep, kept_idx,
     _check(lib().skipkv_select(C.byref(cache.c()), C.byref(params.c()), _ptr(sent_score), _ptr(sent_keep),
                                _ptr(kept_idx), _ptr(new_len), _ptr(new_sent_off), _ptr(new_sent_cnt),
                                kept_stride, _stream(stream)))
+
+
+def skipkv_select_tokens(cache: Cache, params: Params, tok_importance, tok_redundancy, sent_lambda, tok_score,
+                         tok_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride: int, stream=None) -> None:
+    _check(lib().skipkv_select_tokens(C.byref(cache.c()), C.byref(params.c()), _ptr(tok_importance),
+                                      _ptr(tok_redundancy), _ptr(sent_lambda), _ptr(tok_score), _ptr(tok_keep),
+                                      _ptr(kept_idx), _ptr(new_len), _ptr(new_sent_off), _ptr(new_sent_cnt),
+                                      kept_stride, _stream(stream)))
 
 
 def skipkv_compact(cache: Cache, kept_idx, new_len, kept_stride: int, stream=None) -> None:

@@ -284,6 +284,42 @@ int skipkv_select(const skipkv_cache *cache, const skipkv_params *params, const 
                    static_cast<hipStream_t>(stream));
 }
 
+int skipkv_select_tokens(const skipkv_cache *cache, const skipkv_params *params, const float *tok_importance,
+                         const float *tok_redundancy, const float *sent_lambda, float *tok_score,
+                         uint8_t *tok_keep, int32_t *kept_idx, int32_t *new_len, int32_t *new_sent_off,
+                         int32_t *new_sent_cnt, int32_t kept_stride, void *stream) {
+  RowLayout rl;
+  const int rc = check_select_args(cache, params, &rl, sent_lambda, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride);
+  if (rc) return rc;
+  if (is_empty(cache)) return SKIPKV_OK;
+  if (cache->total_tokens > 0 && (!tok_importance || !tok_score)) return SKIPKV_EINVAL;
+  TokSelectArgs a{};
+  a.n_lh = cache->n_layers * cache->n_kv_heads;
+  a.batch = cache->batch;
+  a.total_tokens = cache->total_tokens;
+  a.total_sentences = cache->total_sentences;
+  a.protect = params->protect_window;
+  a.budget_scalar = params->budget_scalar;
+  a.kept_stride = kept_stride;
+  a.sigma = params->sigma;
+  a.tau = params->tau;
+  a.budget = params->budget;
+  a.seq_off = cache->seq_off;
+  a.sent_ptr = cache->sent_ptr;
+  a.sent_off = cache->sent_off;
+  a.tok_imp = tok_importance;
+  a.tok_red = tok_redundancy;
+  a.sent_lambda = sent_lambda;
+  a.tok_score = tok_score;
+  a.tok_keep = tok_keep;
+  a.kept_idx = kept_idx;
+  a.new_len = new_len;
+  a.new_sent_off = new_sent_off;
+  a.new_sent_cnt = new_sent_cnt;
+  a.dev_status = params->dev_status;
+  return launch_select_tokens(a, static_cast<hipStream_t>(stream)) == hipSuccess ? SKIPKV_OK : SKIPKV_EHIP;
+}
+
 int skipkv_compact(const skipkv_cache *cache, const int32_t *kept_idx, const int32_t *new_len, int32_t kept_stride,
                    void *stream) {
   const int rc = check_cache(cache, false);

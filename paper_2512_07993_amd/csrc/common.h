@@ -141,6 +141,19 @@ struct SelectArgs {
 };
 hipError_t launch_select(const SelectArgs &a, hipStream_t st);
 
+struct TokSelectArgs {
+  int32_t n_lh, batch, total_tokens, total_sentences, protect, budget_scalar, kept_stride;
+  float sigma, tau;
+  const int32_t *budget;
+  const int32_t *seq_off, *sent_ptr, *sent_off;
+  const float *tok_imp, *tok_red, *sent_lambda;
+  float *tok_score;
+  uint8_t *tok_keep;
+  int32_t *kept_idx, *new_len, *new_sent_off, *new_sent_cnt;
+  int32_t *dev_status;
+};
+hipError_t launch_select_tokens(const TokSelectArgs &a, hipStream_t st);
+
 struct CompactArgs {
   void *k, *v;
   int64_t stride_layer, stride_head, stride_tok;

@@ -272,7 +272,186 @@ __global__ void __launch_bounds__(256) k_select(SelectArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Token-level form (Eq. 6 as printed, then "evict tokens in increasing order of the final score"):
+// every token carries sigma * I - (1 - sigma) * R, minus its sentence's lambda when the sentence
+// is in the redundant set; the protected recent window is kept and exactly budget - window of the
+// other tokens survive, ranked by (score descending, index descending).  Same search for the cut
+// key as above, with counts in place of lengths.  One workgroup per head.
+constexpr int kMaxTokens = SKIPKV_MAX_TOKENS_TOKEN_SELECT;
+
+__device__ __forceinline__ int block_sum(int v, int *slots /*[2][4]*/, int &call, int wave, int lane) {
+  const int s = wave_sum_i(v);
+  int *slot = slots + 4 * (call & 1);
+  ++call;
+  if (lane == 0) slot[wave] = s;
+  __syncthreads();
+  return slot[0] + slot[1] + slot[2] + slot[3];
+}
+__device__ __forceinline__ int block_scan_excl(int v, int *slots, int &call, int wave, int lane, int &total) {
+  const int incl = wave_scan_incl(v, lane);
+  const int wtot = __builtin_amdgcn_readlane(incl, 63);
+  int *slot = slots + 4 * (call & 1);
+  ++call;
+  if (lane == 0) slot[wave] = wtot;
+  __syncthreads();
+  int before = 0;
+#pragma unroll
+  for (int w = 0; w < 4; ++w)
+    if (w < wave) before += slot[w];
+  total = slot[0] + slot[1] + slot[2] + slot[3];
+  return before + incl - v;
+}
+__device__ __forceinline__ uint32_t score_order(float f) {  // order-preserving image; -0.0 ties with 0.0
+  uint32_t u = __float_as_uint(f);
+  if (u == 0x80000000u) u = 0;
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__global__ void __launch_bounds__(256) k_select_tokens(TokSelectArgs a) {
+  __shared__ uint32_t keep_bits[kMaxTokens / 32];
+  __shared__ int slots[8];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int lhb = blockIdx.x, lh = lhb / a.batch, b = lhb % a.batch;
+  const int tok0 = a.seq_off[b];
+  const int n_tok = a.seq_off[b + 1] - tok0;
+  const int sp = a.sent_ptr[b];
+  const int n_sent = a.sent_ptr[b + 1] - sp - 1;
+  const int32_t *off = a.sent_off + sp;
+  const int64_t tcol = (int64_t)lh * a.total_tokens + tok0;
+  const int64_t scol = (int64_t)lh * a.total_sentences + (sp - b);
+  int32_t *kept = a.kept_idx + (int64_t)lhb * a.kept_stride;
+  int32_t *noff = a.new_sent_off ? a.new_sent_off + (int64_t)lh * (a.total_sentences + a.batch) + sp : nullptr;
+  const int budget = a.budget ? a.budget[b] : a.budget_scalar;
+  int call = 0;
+
+  if (n_tok > kMaxTokens || n_sent < 0) {
+    if (tid == 0) {
+      if (a.dev_status) atomicOr(a.dev_status, SKIPKV_DEV_TOO_MANY_TOK);
+      a.new_len[lhb] = 0;
+      if (a.new_sent_cnt) a.new_sent_cnt[lhb] = 0;
+    }
+    return;
+  }
+
+  // ---- token scores (Eq. 6), sentence by sentence: waves take sentences, lanes their tokens
+  float *score = a.tok_score + tcol;
+  for (int s = wave; s < n_sent; s += 4) {
+    const float lam = a.sent_lambda[scol + s];
+    const float pen = lam > a.tau ? lam : 0.f;
+    for (int t = off[s] + lane; t < off[s + 1]; t += 64) {
+      float v = a.sigma * a.tok_imp[tcol + t];
+      if (a.tok_red) v -= (1.f - a.sigma) * a.tok_red[tcol + t];
+      score[t] = v - pen;
+    }
+  }
+  __syncthreads();  // the scores are read back by other threads of this workgroup
+
+  const int p_start = n_tok - min(a.protect, n_tok);
+  uint32_t H = 0xFFFFFFFFu;
+  int L = 0x7FFFFFFF;  // keep = key > (H, L): nothing unprotected
+  if (n_tok <= budget) {
+    H = 0;
+    L = -1;  // everything
+  } else {
+    const int room = budget - (n_tok - p_start);
+    // score part: the largest H such that more than `room` unprotected tokens have order >= H
+    H = 0;
+    for (int bit = 31; bit >= 0; --bit) {
+      const uint32_t th = H | (1u << bit);
+      int cnt = 0;
+      for (int t = tid; t < p_start; t += 256) cnt += score_order(score[t]) >= th;
+      if (block_sum(cnt, slots, call, wave, lane) > room) H = th;
+    }
+    int above = 0;
+    for (int t = tid; t < p_start; t += 256) above += score_order(score[t]) > H;
+    above = block_sum(above, slots, call, wave, lane);
+    // index part: the largest L such that, among the tokens with order == H, those with index >= L do not fit
+    L = 0;
+    for (int bit = 31 - __builtin_clz(max(p_start, 1)); bit >= 0; --bit) {
+      const int tl = L | (1 << bit);
+      int cnt = 0;
+      for (int t = max(tl, 0) + tid; t < p_start; t += 256) cnt += score_order(score[t]) == H;
+      if (above + block_sum(cnt, slots, call, wave, lane) > room) L = tl;
+    }
+  }
+
+  // ---- keep flags as a bit map; every thread owns a run of whole 32-token words
+  const int words = (n_tok + 31) / 32;
+  const int per_w = (words + 255) / 256;
+  int mine = 0;
+  for (int w = tid * per_w; w < min((tid + 1) * per_w, words); ++w) {
+    uint32_t bits = 0;
+    for (int i = 0; i < 32; ++i) {
+      const int t = 32 * w + i;
+      if (t < n_tok) {
+        bool k = t >= p_start;
+        if (!k) {
+          const uint32_t o = score_order(score[t]);
+          k = o > H || (o == H && t > L);
+        }
+        bits |= (uint32_t)k << i;
+        if (a.tok_keep) a.tok_keep[tcol + t] = k;
+      }
+    }
+    keep_bits[w] = bits;
+    mine += __popc(bits);
+  }
+  int total_tok;
+  int dst = block_scan_excl(mine, slots, call, wave, lane, total_tok);  // also makes the bit map visible
+  for (int w = tid * per_w; w < min((tid + 1) * per_w, words); ++w) {
+    uint32_t bits = keep_bits[w];
+    while (bits) {
+      const int i = __builtin_ctz(bits);
+      bits &= bits - 1;
+      kept[dst++] = 32 * w + i;
+    }
+  }
+
+  // ---- sentences that still have a token, and where they now start (Eq. 11)
+  const int per_s = (n_sent + 255) / 256;
+  const int s_lo = tid * per_s, s_hi = min(s_lo + per_s, n_sent);
+  auto survivors = [&](int s) -> int {
+    int cnt = 0;
+    const int bgn = off[s], end = off[s + 1];
+    for (int w = bgn >> 5; w <= (end - 1) >> 5; ++w) {
+      uint32_t m = keep_bits[w];
+      if (w == (bgn >> 5)) m &= 0xFFFFFFFFu << (bgn & 31);
+      if (w == ((end - 1) >> 5) && (end & 31)) m &= 0xFFFFFFFFu >> (32 - (end & 31));
+      cnt += __popc(m);
+    }
+    return cnt;
+  };
+  int sent_cnt = 0;
+  for (int s = s_lo; s < s_hi; ++s) sent_cnt += survivors(s) > 0;
+  int my_tok = 0;
+  for (int s = s_lo; s < s_hi; ++s) my_tok += survivors(s);
+  int tot_t, tot_s;
+  int tok_before = block_scan_excl(my_tok, slots, call, wave, lane, tot_t);  // kept tokens before this thread's first sentence
+  int sent_before = block_scan_excl(sent_cnt, slots, call, wave, lane, tot_s);
+  for (int s = s_lo; s < s_hi; ++s) {
+    const int c = survivors(s);
+    if (c > 0) {
+      if (noff) noff[sent_before] = tok_before;
+      ++sent_before;
+      tok_before += c;
+    }
+  }
+  if (tid == 0) {
+    a.new_len[lhb] = total_tok;
+    if (a.new_sent_cnt) a.new_sent_cnt[lhb] = tot_s;
+    if (noff) noff[tot_s] = total_tok;
+  }
+}
+
 }  // namespace
+
+hipError_t launch_select_tokens(const TokSelectArgs &a, hipStream_t st) {
+  const int heads = a.n_lh * a.batch;
+  if (heads == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_select_tokens, dim3(heads), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
 
 hipError_t launch_select(const SelectArgs &a, hipStream_t st) {
   const int heads = a.n_lh * a.batch;

@@ -1,0 +1,125 @@
+"""GPU parity of the token-level selection (Eq.6 as printed, the eviction rule after it, ranges per
+Eq.11) against the oracle.  The selection is integer work once the fp32 token scores are fixed:
+the scores are compared to the oracle's within rel 1e-6 (one fp32 fma and subtraction of fp32
+inputs), and the decision is compared exactly, both sides ranking the SAME fp32 scores."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2512_07993_amd import binding as B
+from paper_2512_07993_amd import workloads as W
+
+from helpers import make_cache, run_step
+from test_gpu_edges import _structure
+
+pytestmark = pytest.mark.gpu
+
+
+def _select_tokens(cfg, st, cache, imp, red, lam, budgets):
+    L, H, Bn, S, T = cfg.n_layers, cfg.n_kv_heads, cfg.batch, st.total_sentences, st.total_tokens
+    bud_t = torch.from_numpy(np.asarray(budgets, dtype=np.int32)).cuda()
+    max_budget = int(max(budgets))
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    params = B.Params(cfg.obs_window, cfg.protect_window, bud_t, max_budget=max_budget, dev_status=status)
+    kept_stride = max(1, min(max_budget, T))
+    out = dict(
+        tok_score=torch.full((L, H, T), float("nan"), dtype=torch.float32, device="cuda"),
+        tok_keep=torch.full((L, H, T), 77, dtype=torch.uint8, device="cuda"),
+        kept_idx=torch.full((L, H, Bn, kept_stride), -1, dtype=torch.int32, device="cuda"),
+        new_len=torch.full((L, H, Bn), -1, dtype=torch.int32, device="cuda"),
+        new_off=torch.full((L, H, S + Bn), -1, dtype=torch.int32, device="cuda"),
+        new_cnt=torch.full((L, H, Bn), -1, dtype=torch.int32, device="cuda"),
+        kept_stride=kept_stride, status=status)
+    B.skipkv_select_tokens(cache, params, imp, red, lam, out["tok_score"], out["tok_keep"], out["kept_idx"],
+                           out["new_len"], out["new_off"], out["new_cnt"], kept_stride)
+    torch.cuda.synchronize()
+    return out
+
+
+def _check_head(cfg, st, out, imp, red, lam, budgets, l, h, b, sigma=0.1, tau=0.95):
+    t0, t1 = int(st.seq_off[b]), int(st.seq_off[b + 1])
+    off = st.offsets(b).astype(np.int64)
+    sb, ns = st.sent_base(b), int(st.n_sent[b])
+    tag = "head (l=%d, h=%d, b=%d, N=%d, S=%d, B=%d)" % (l, h, b, t1 - t0, ns, budgets[b])
+    sc = out["tok_score"][l, h, t0:t1].cpu().numpy()
+    want_sc = oracle.token_scores(imp[l, h, t0:t1].cpu().numpy(), None if red is None else red[l, h, t0:t1].cpu().numpy(),
+                                  lam[l, h, sb:sb + ns].cpu().numpy().astype(np.float64), off, sigma, tau)
+    np.testing.assert_allclose(sc, want_sc, rtol=1e-6, atol=1e-9, err_msg="token scores " + tag)
+    ora = oracle.select_tokens(sc.astype(np.float64), off, int(budgets[b]), cfg.protect_window)
+    nl = int(out["new_len"][l, h, b])
+    assert nl == ora["new_len"], tag
+    np.testing.assert_array_equal(out["kept_idx"][l, h, b, :nl].cpu().numpy(), ora["kept_idx"], err_msg=tag)
+    np.testing.assert_array_equal(out["tok_keep"][l, h, t0:t1].cpu().numpy().astype(bool), ora["keep"], err_msg=tag)
+    cnt = int(out["new_cnt"][l, h, b])
+    assert cnt == len(ora["new_off"]) - 1, tag
+    p0 = int(st.sent_ptr[b])
+    np.testing.assert_array_equal(out["new_off"][l, h, p0:p0 + cnt + 1].cpu().numpy(), ora["new_off"], err_msg=tag)
+
+
+def test_crafted_scores_ties_and_all_sizes():
+    rng = np.random.default_rng(5)
+    n_sents = [1, 3, 40, 200, 1000, 4096]
+    offsets = []
+    for ns in n_sents:
+        offsets.append(np.concatenate([[0], np.cumsum(rng.integers(1, 9, size=ns))]).tolist())
+    offsets.append([0])  # an empty sequence
+    st = _structure(offsets)
+    cfg = W.Config("toksel", 9, len(offsets), 1, 2, 8, "bf16", 0, 0, 0, 8, 16, 4.0, 0.0)
+    k = torch.zeros((1, 2, st.total_tokens, 128), dtype=torch.bfloat16, device="cuda")
+    cache = make_cache(cfg, st, k, k.clone())
+    T, S = st.total_tokens, st.total_sentences
+    imp = np.empty((1, 2, T), dtype=np.float32)
+    imp[0, 0] = rng.choice(np.array([0.0, 0.25, 0.5, 1.0], dtype=np.float32), size=T)  # heavy ties
+    imp[0, 1] = rng.random(T).astype(np.float32)
+    red = rng.random((1, 2, T)).astype(np.float32) * 0.01
+    lam = np.where(rng.random((1, 2, S)) < 0.2, 0.97, 0.3).astype(np.float32)
+    imp_t, red_t, lam_t = (torch.from_numpy(x).cuda() for x in (imp, red, lam))
+    for frac in (0.1, 0.6, 1.5):
+        budgets = np.maximum(16, (st.seq_len * frac).astype(np.int32))
+        for use_red in (True, False):
+            out = _select_tokens(cfg, st, cache, imp_t, red_t if use_red else None, lam_t, budgets)
+            assert int(out["status"].item()) == 0
+            for h in range(2):
+                for b in range(cfg.batch):
+                    if st.seq_len[b] == 0:
+                        assert int(out["new_len"][0, h, b]) == 0 and int(out["new_cnt"][0, h, b]) == 0
+                        continue
+                    _check_head(cfg, st, out, imp_t, red_t if use_red else None, lam_t, budgets, 0, h, b)
+
+
+def test_token_level_step_end_to_end():
+    """score (token importance, lambda) -> token redundancy -> token-level selection -> compaction."""
+    cfg = W.CONFIGS[3].scaled(n_layers=1, batch=3)
+    st = W.make_structure(cfg)
+    k0, v0, q = W.fill_cache(cfg, st, device="cuda")
+    k, v = k0.clone(), v0.clone()
+    scored = run_step(cfg, st, k0.clone(), v0.clone(), q)  # for tok_imp and sent_lambda (its own compaction goes to a scratch copy)
+    cache = make_cache(cfg, st, k, v)
+    ws = torch.empty(B.skipkv_redundancy_workspace_bytes(cache) + 256, dtype=torch.uint8, device="cuda")
+    red = torch.empty((cfg.n_layers, cfg.n_kv_heads, st.total_tokens), dtype=torch.float32, device="cuda")
+    B.skipkv_token_redundancy(cache, red, ws)
+    budgets = np.full(cfg.batch, cfg.budget, dtype=np.int32)
+    out = _select_tokens(cfg, st, cache, scored.tok_imp, red, scored.sent_lambda, budgets)
+    assert int(out["status"].item()) == 0
+    B.skipkv_compact(cache, out["kept_idx"], out["new_len"], out["kept_stride"])
+    torch.cuda.synchronize()
+    for (l, h, b) in [(0, 0, 0), (0, 3, 1), (0, 7, 2)]:
+        _check_head(cfg, st, out, scored.tok_imp, red, scored.sent_lambda, budgets, l, h, b)
+        t0 = int(st.seq_off[b])
+        nl = int(out["new_len"][l, h, b])
+        assert nl == min(cfg.budget, int(st.seq_len[b]))
+        kept = out["kept_idx"][l, h, b, :nl].long()
+        assert torch.equal(k[l, h, t0:t0 + nl], k0[l, h, t0 + kept]) and torch.equal(v[l, h, t0:t0 + nl], v0[l, h, t0 + kept])
+
+
+def test_too_long_sequence_is_reported():
+    n = 131072 + 1  # SKIPKV_MAX_TOKENS_TOKEN_SELECT + 1
+    st = _structure([[0, n]])
+    cfg = W.Config("toksel", 9, 1, 1, 1, 4, "bf16", 0, 0, 0, 8, 16, 4.0, 0.0)
+    k = torch.zeros((1, 1, n, 128), dtype=torch.bfloat16, device="cuda")
+    cache = make_cache(cfg, st, k, k)
+    imp = torch.zeros((1, 1, n), dtype=torch.float32, device="cuda")
+    lam = torch.zeros((1, 1, 1), dtype=torch.float32, device="cuda")
+    out = _select_tokens(cfg, st, cache, imp, None, lam, [64])
+    assert int(out["status"].item()) & B.DEV_TOO_MANY_TOK and int(out["new_len"][0, 0, 0]) == 0
