@@ -272,3 +272,60 @@ def test_steer_add_matches_oracle_bit_for_bit(dtype):
     ref = oracle.steer_add(h0.double().cpu().numpy(), vec.double().cpu().numpy(), coefs.cpu().numpy(),
                            mask.cpu().numpy(), dtype=dtype)
     np.testing.assert_array_equal(h.double().cpu().numpy(), ref)
+
+
+def test_step_replays_from_a_hip_graph():
+    """The step allocates nothing, never synchronises and clears its counters with a fill kernel, so
+    it can be captured into a HIP graph: every replay (with eager work and synchronisations between
+    the replays) must reproduce the eager result bit for bit."""
+    cfg = W.CONFIGS[3].scaled(n_layers=1, batch=3)
+    st = W.make_structure(cfg)
+    k0, v0, q = W.fill_cache(cfg, st, device="cuda")
+    k, v = k0.clone(), v0.clone()
+    eager = run_step(cfg, st, k, v, q)
+    want = [t.clone() for t in (eager.sent_score, eager.sent_keep, eager.kept_idx, eager.new_len, k, v)]
+
+    kg, vg = k0.clone(), v0.clone()
+    cache = make_cache(cfg, st, kg, vg)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    params = B.Params(cfg.obs_window, cfg.protect_window, cfg.budget, dev_status=status)
+    ws = torch.empty(B.skipkv_workspace_bytes(cache, params), dtype=torch.uint8, device="cuda")
+    L, H, Bn, S, T = cfg.n_layers, cfg.n_kv_heads, cfg.batch, st.total_sentences, st.total_tokens
+    ks = min(cfg.budget, T)
+    sent_score = torch.empty((L, H, S), dtype=torch.float32, device="cuda")
+    sent_lambda = torch.empty_like(sent_score)
+    sent_keep = torch.empty((L, H, S), dtype=torch.uint8, device="cuda")
+    kept_idx = torch.empty((L, H, Bn, ks), dtype=torch.int32, device="cuda")
+    new_len = torch.empty((L, H, Bn), dtype=torch.int32, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            B.skipkv_step(cache, params, q, None, sent_score, sent_lambda, None, sent_keep, kept_idx, new_len,
+                          None, None, ks, ws)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        kg.copy_(k0)
+        vg.copy_(v0)
+        for t in (sent_score, kept_idx, new_len):
+            t.fill_(-7)                       # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert int(status.item()) == 0
+        got = (sent_score, sent_keep, kept_idx, new_len, kg, vg)
+        for name, g_, w_ in zip(("score", "keep", "kept_idx", "new_len", "K", "V"), got, want):
+            if name == "kept_idx":  # entries beyond new_len are unspecified
+                ar = torch.arange(ks, device="cuda")[None, None, None, :]
+                valid = ar < new_len[..., None]
+                assert torch.equal(g_[valid], w_[valid]), (rep, name)
+            elif name in ("K", "V"):  # rows beyond new_len are unspecified
+                for b in range(Bn):
+                    t0 = int(st.seq_off[b])
+                    for h in range(H):
+                        n = int(new_len[0, h, b])
+                        assert torch.equal(g_[0, h, t0:t0 + n], w_[0, h, t0:t0 + n]), (rep, name, h, b)
+            else:
+                assert torch.equal(g_.view(torch.uint8) if g_.dtype != torch.uint8 else g_,
+                                   w_.view(torch.uint8) if w_.dtype != torch.uint8 else w_), (rep, name)
