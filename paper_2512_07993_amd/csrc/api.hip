@@ -75,7 +75,7 @@ Workspace carve(const skipkv_cache *c, const RowLayout &rl, void *base) {
   w.rb_cnt = static_cast<int32_t *>(take(B * 4));
   w.seq_fused = static_cast<int32_t *>(take(B * 4));
   w.pair_cnt = static_cast<int32_t *>(take(B * 4));
-  w.pair_first = static_cast<int32_t *>(take((size_t)w.nc_max * 4));
+  w.pair_rec = static_cast<int32_t *>(take((size_t)w.nc_max * kPairRecInts * 4));
   w.arrive = static_cast<int32_t *>(take(2 * LH * B * 4));
   w.ready = w.arrive ? w.arrive + LH * B : nullptr;
   w.chunks = static_cast<Chunk *>(take((size_t)w.nc_max * sizeof(Chunk)));

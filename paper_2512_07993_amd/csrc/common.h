@@ -32,6 +32,25 @@ struct RowBlock {
 };
 
 // Device scalars at the head of the workspace.
+// Record of one work item of the single-pass scan (a pair of consecutive chunks of one sequence),
+// written by the plan so that a workgroup learns everything about an item from one 64-byte read.
+constexpr int kPairRecInts = 16;
+enum PairRec : int {
+  kPrB = 0,        // sequence
+  kPrNch,          // chunks in the pair: 1 or 2; 0 = the sequence takes the two-pass scan
+  kPrC0,           // index of the first chunk (its statistics record is filed there)
+  kPrTok0,         // first token of the sequence in the packed cache
+  kPrNTok,         // tokens of the sequence
+  kPrTBegin,       // first token of the pair, relative to the sequence
+  kPrLen0,         // tokens of the first chunk (the second one follows it directly)
+  kPrNs0,          // sentences of the first chunk
+  kPrSoffIdx,      // index of the first chunk's first sentence offset in sent_off
+  kPrLen1,
+  kPrNs1,
+  kPrNPairs,       // pairs of the sequence
+  kPrCFirst,       // first chunk of the sequence
+};
+
 struct PlanHeader {
   int32_t n_chunks;
   int32_t n_rowblocks;
@@ -48,7 +67,7 @@ struct Workspace {
   int32_t *rb_base;      // [B] first row block of each sequence
   int32_t *rb_cnt;       // [B]
   int32_t *seq_fused;    // [B] 1: the sequence goes through the single-pass scan
-  int32_t *pair_first;   // [nc_max] first chunk of every pair of consecutive chunks of one sequence
+  int32_t *pair_rec;     // [nc_max][kPairRecInts] one record per pair of consecutive chunks of one sequence (PairRec)
   int32_t *pair_cnt;     // [B] number of pairs of each sequence
   int32_t *arrive;       // [LH, B] chunks of the head that have published their row statistics
   int32_t *ready;        // [LH, B] 1 once the head's row normalisers are final

@@ -59,50 +59,74 @@ __global__ void __launch_bounds__(256) k_plan(PlanArgs a) {
     if (bad) s_bad = 1;
   }
   __syncthreads();
-  if (tid != 0) return;
-
-  if (reject || s_bad) {
-    if (a.dev_status) atomicOr(a.dev_status, reject ? SKIPKV_DEV_TOO_MANY_SENT : SKIPKV_DEV_BAD_OFFSETS);
-    a.ws.chunk_base[b] = 0;
-    a.ws.chunk_cnt[b] = 0;
-    a.ws.rb_base[b] = 0;
-    a.ws.rb_cnt[b] = 0;
-    a.ws.seq_fused[b] = 1;  // nothing to scan either way
-    a.ws.pair_cnt[b] = 0;
-    return;
+  __shared__ int s_base, s_nchunks, s_pbase, s_fused;
+  if (tid == 0) {
+    s_nchunks = -1;
+    if (reject || s_bad) {
+      if (a.dev_status) atomicOr(a.dev_status, reject ? SKIPKV_DEV_TOO_MANY_SENT : SKIPKV_DEV_BAD_OFFSETS);
+      a.ws.chunk_base[b] = 0;
+      a.ws.chunk_cnt[b] = 0;
+      a.ws.rb_base[b] = 0;
+      a.ws.rb_cnt[b] = 0;
+      a.ws.seq_fused[b] = 1;  // nothing to scan either way
+      a.ws.pair_cnt[b] = 0;
+    } else {
+      // pass 1: count chunks
+      int n_chunks = 0, longest = 0;
+      for (int start = 0; start < n_sent;) {
+        const int e = chunk_end(s_off, start, n_sent);
+        longest = max(longest, s_off[e] - s_off[start]);
+        ++n_chunks;
+        start = e;
+      }
+      const int base = atomicAdd(&a.ws.hdr->n_chunks, n_chunks);
+      a.ws.chunk_base[b] = base;
+      a.ws.chunk_cnt[b] = n_chunks;
+      const bool fused = longest <= kChunkCap && n_chunks <= kFuseMaxChunks;
+      a.ws.seq_fused[b] = fused;
+      if (!fused && n_chunks > 0) atomicAdd(&a.ws.hdr->n_unfused, 1);
+      // pass 2: emit
+      int idx = base;
+      for (int start = 0; start < n_sent;) {
+        const int e = chunk_end(s_off, start, n_sent);
+        a.ws.chunks[idx++] = Chunk{b, start, e - start, s_off[start], s_off[e] - s_off[start], sp + start, tok0, n_tok};
+        start = e;
+      }
+      // the single-pass scan works on pairs of consecutive chunks of a sequence
+      const int n_pairs = (n_chunks + 1) / 2;
+      a.ws.pair_cnt[b] = n_pairs;
+      const int nrb = (n_sent + kRowBlock - 1) / kRowBlock;
+      const int rb0 = atomicAdd(&a.ws.hdr->n_rowblocks, nrb);
+      a.ws.rb_base[b] = rb0;
+      a.ws.rb_cnt[b] = nrb;
+      for (int i = 0; i < nrb; ++i) a.ws.rowblocks[rb0 + i] = RowBlock{b, i * kRowBlock};
+      s_base = base;
+      s_nchunks = n_chunks;
+      s_pbase = atomicAdd(&a.ws.hdr->n_pairs, n_pairs);
+      s_fused = fused;
+    }
   }
-
-  // pass 1: count chunks
-  int n_chunks = 0, longest = 0;
-  for (int start = 0; start < n_sent;) {
-    const int e = chunk_end(s_off, start, n_sent);
-    longest = max(longest, s_off[e] - s_off[start]);
-    ++n_chunks;
-    start = e;
+  __syncthreads();  // the chunk records written above are read back below by the whole block
+  if (s_nchunks < 0) return;
+  const int base = s_base, n_chunks = s_nchunks, n_pairs = (n_chunks + 1) / 2;
+  for (int j = tid; j < n_pairs; j += 256) {  // one record per pair
+    const Chunk &c0 = a.ws.chunks[base + 2 * j];
+    const bool two = 2 * j + 1 < n_chunks;
+    int32_t *r = a.ws.pair_rec + (int64_t)(s_pbase + j) * kPairRecInts;
+    r[kPrB] = b;
+    r[kPrNch] = s_fused ? (two ? 2 : 1) : 0;
+    r[kPrC0] = base + 2 * j;
+    r[kPrTok0] = tok0;
+    r[kPrNTok] = n_tok;
+    r[kPrTBegin] = c0.t_begin;
+    r[kPrLen0] = c0.len;
+    r[kPrNs0] = c0.ns;
+    r[kPrSoffIdx] = c0.soff_idx;
+    r[kPrLen1] = two ? a.ws.chunks[base + 2 * j + 1].len : 0;
+    r[kPrNs1] = two ? a.ws.chunks[base + 2 * j + 1].ns : 0;
+    r[kPrNPairs] = n_pairs;
+    r[kPrCFirst] = base;
   }
-  const int base = atomicAdd(&a.ws.hdr->n_chunks, n_chunks);
-  a.ws.chunk_base[b] = base;
-  a.ws.chunk_cnt[b] = n_chunks;
-  const bool fused = longest <= kChunkCap && n_chunks <= kFuseMaxChunks;
-  a.ws.seq_fused[b] = fused;
-  if (!fused && n_chunks > 0) atomicAdd(&a.ws.hdr->n_unfused, 1);
-  // pass 2: emit
-  int idx = base;
-  for (int start = 0; start < n_sent;) {
-    const int e = chunk_end(s_off, start, n_sent);
-    a.ws.chunks[idx++] = Chunk{b, start, e - start, s_off[start], s_off[e] - s_off[start], sp + start, tok0, n_tok};
-    start = e;
-  }
-  // the single-pass scan works on pairs of consecutive chunks of a sequence
-  const int n_pairs = (n_chunks + 1) / 2;
-  const int pbase = atomicAdd(&a.ws.hdr->n_pairs, n_pairs);
-  a.ws.pair_cnt[b] = n_pairs;
-  for (int j = 0; j < n_pairs; ++j) a.ws.pair_first[pbase + j] = base + 2 * j;
-  const int nrb = (n_sent + kRowBlock - 1) / kRowBlock;
-  const int rb0 = atomicAdd(&a.ws.hdr->n_rowblocks, nrb);
-  a.ws.rb_base[b] = rb0;
-  a.ws.rb_cnt[b] = nrb;
-  for (int i = 0; i < nrb; ++i) a.ws.rowblocks[rb0 + i] = RowBlock{b, i * kRowBlock};
 }
 
 hipError_t launch_plan(const PlanArgs &a, hipStream_t st) {

@@ -48,7 +48,7 @@ struct ChunkD {  // one chunk as seen by one wave
 };
 struct Pair {  // one item
   uint32_t item;  // >= n_items: none
-  int lh, b, c0, nch, n_tok, tok0;
+  int lh, b, c0, nch, n_tok, tok0, np, c_first;
   const char *kbase;
   ChunkD ch[2];
 };
@@ -89,21 +89,15 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
   // The plan is constant while this kernel runs: reading it through the constant address space
   // lets the compiler use scalar loads, which do not queue behind the key loads in flight.
   typedef const __attribute__((address_space(4))) int32_t *ConstIntPtr;
-  static_assert(sizeof(Chunk) == 8 * sizeof(int32_t), "chunk records are read as 8 ints");
-  const ConstIntPtr chunks_c = (ConstIntPtr)a.ws.chunks;
-  const ConstIntPtr seq_fused_c = (ConstIntPtr)a.ws.seq_fused;
-  const ConstIntPtr chunk_cnt_c = (ConstIntPtr)a.ws.chunk_cnt;
-  const ConstIntPtr chunk_base_c = (ConstIntPtr)a.ws.chunk_base;
-  const ConstIntPtr pair_first_c = (ConstIntPtr)a.ws.pair_first;
-  const ConstIntPtr pair_cnt_c = (ConstIntPtr)a.ws.pair_cnt;
+  const ConstIntPtr pair_rec_c = (ConstIntPtr)a.ws.pair_rec;
 
-  // ---- item descriptors ------------------------------------------------------------------
-  auto load_chunk = [&](int c) -> ChunkD {
+  // ---- item descriptors: one 64-byte record per pair of chunks, written by the plan ----------
+  auto make_chunk = [&](int t_begin, int len, int ns, int soff_idx) -> ChunkD {
     ChunkD d;
-    d.ns = chunks_c[8 * c + 2];
-    d.t_begin = chunks_c[8 * c + 3];
-    d.t_end = d.t_begin + chunks_c[8 * c + 4];
-    d.soff_idx = chunks_c[8 * c + 5];
+    d.ns = ns;
+    d.t_begin = t_begin;
+    d.t_end = t_begin + len;
+    d.soff_idx = soff_idx;
     d.w0 = d.t_begin + wave * kCapW;
     d.w1 = min(d.w0 + kCapW, d.t_end);
     d.nst = d.w1 > d.w0 ? (d.w1 - d.w0 + kStageRows - 1) / kStageRows : 0;
@@ -112,17 +106,19 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
   auto load_pair = [&](uint32_t item) -> Pair {  // first fused item at or after `item` in this workgroup's sequence
     Pair it{};
     for (; item < n_items; item += gridDim.x) {
-      const int c0 = pair_first_c[item % n_pairs];
-      const int b = chunks_c[8 * c0 + 0];
-      if (!seq_fused_c[b]) continue;
+      const ConstIntPtr r = pair_rec_c + (int64_t)(item % n_pairs) * kPairRecInts;
+      const int nch = r[kPrNch];
+      if (nch == 0) continue;  // the sequence takes the two-pass scan
       it.lh = item / n_pairs;
-      it.b = b;
-      it.c0 = c0;
-      it.nch = (c0 + 1 - chunk_base_c[b] < chunk_cnt_c[b]) ? 2 : 1;
-      it.tok0 = chunks_c[8 * c0 + 6];
-      it.n_tok = chunks_c[8 * c0 + 7];
-      it.ch[0] = load_chunk(c0);
-      it.ch[1] = it.nch == 2 ? load_chunk(c0 + 1) : ChunkD{};
+      it.b = r[kPrB];
+      it.c0 = r[kPrC0];
+      it.nch = nch;
+      it.tok0 = r[kPrTok0];
+      it.n_tok = r[kPrNTok];
+      it.np = r[kPrNPairs];
+      it.c_first = r[kPrCFirst];
+      it.ch[0] = make_chunk(r[kPrTBegin], r[kPrLen0], r[kPrNs0], r[kPrSoffIdx]);
+      it.ch[1] = nch == 2 ? make_chunk(r[kPrTBegin] + r[kPrLen0], r[kPrLen1], r[kPrNs1], r[kPrSoffIdx] + r[kPrNs0]) : ChunkD{};
       const int l = it.lh / a.n_kv_heads, h = it.lh % a.n_kv_heads;
       it.kbase = static_cast<const char *>(a.k) +
                  ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head + (int64_t)it.tok0 * a.stride_tok) * ESZ;
@@ -449,13 +445,13 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     __builtin_amdgcn_s_barrier();
     if (tid == 0) {
       const int old = __hip_atomic_fetch_add(&a.ws.arrive[lhb], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      s_flag = (old == pair_cnt_c[b] - 1);
+      s_flag = (old == cur.np - 1);
     }
     lds_barrier();
     float *rn = a.ws.row_norm + (int64_t)lhb * R;
     if (s_flag) {  // last share of the head to arrive: merge the partials into the normalisers
       // lane = query row, wave w takes items w, w+4, ...; 8 independent loads in flight per lane
-      const int c_first = chunk_base_c[b], np = pair_cnt_c[b];
+      const int c_first = cur.c_first, np = cur.np;
       for (int r = lane; r < R; r += 64) {
         float m = kRefInit, s = 0.f;
         for (int pp = wave; pp < np; pp += 32) {
