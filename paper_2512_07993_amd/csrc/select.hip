@@ -11,6 +11,8 @@
 // A head with at most 1024 sentences is handled by ONE wave, 16 sentences per lane in registers,
 // without any workgroup barrier; four such heads share a workgroup.  A head with more sentences
 // (up to 4096) is handled afterwards by the four waves together, with the same code.
+#include <type_traits>
+
 #include "common.h"
 
 namespace skipkv {
@@ -310,6 +312,7 @@ __device__ __forceinline__ uint32_t score_order(float f) {  // order-preserving 
 
 __global__ void __launch_bounds__(256) k_select_tokens(TokSelectArgs a) {
   __shared__ uint32_t keep_bits[kMaxTokens / 32];
+  __shared__ int off_l[SKIPKV_MAX_SENTENCES + 1];
   __shared__ int slots[8];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int lhb = blockIdx.x, lh = lhb / a.batch, b = lhb % a.batch;
@@ -325,78 +328,99 @@ __global__ void __launch_bounds__(256) k_select_tokens(TokSelectArgs a) {
   const int budget = a.budget ? a.budget[b] : a.budget_scalar;
   int call = 0;
 
-  if (n_tok > kMaxTokens || n_sent < 0) {
+  if (n_tok > kMaxTokens || n_sent < 0 || n_sent > SKIPKV_MAX_SENTENCES) {
     if (tid == 0) {
-      if (a.dev_status) atomicOr(a.dev_status, SKIPKV_DEV_TOO_MANY_TOK);
+      if (a.dev_status) atomicOr(a.dev_status, n_sent > SKIPKV_MAX_SENTENCES ? SKIPKV_DEV_TOO_MANY_SENT : SKIPKV_DEV_TOO_MANY_TOK);
       a.new_len[lhb] = 0;
       if (a.new_sent_cnt) a.new_sent_cnt[lhb] = 0;
     }
     return;
   }
 
-  // ---- token scores (Eq. 6), sentence by sentence: waves take sentences, lanes their tokens
+  // ---- token scores (Eq. 6): thread t takes tokens t, t+256, ... (coalesced); the sentence of a
+  // token is found by bisection in the offsets, which sit in LDS
   float *score = a.tok_score + tcol;
-  for (int s = wave; s < n_sent; s += 4) {
-    const float lam = a.sent_lambda[scol + s];
-    const float pen = lam > a.tau ? lam : 0.f;
-    for (int t = off[s] + lane; t < off[s + 1]; t += 64) {
-      float v = a.sigma * a.tok_imp[tcol + t];
-      if (a.tok_red) v -= (1.f - a.sigma) * a.tok_red[tcol + t];
-      score[t] = v - pen;
+  for (int s = tid; s <= n_sent; s += 256) off_l[s] = off[s];
+  __syncthreads();
+  for (int t = tid; t < n_tok; t += 256) {
+    int lo = 0, hi = n_sent - 1;  // invariant: off_l[lo] <= t < off_l[hi + 1]
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (off_l[mid] <= t) lo = mid; else hi = mid - 1;
     }
+    const float lam = a.sent_lambda[scol + lo];
+    float v = a.sigma * a.tok_imp[tcol + t];
+    if (a.tok_red) v -= (1.f - a.sigma) * a.tok_red[tcol + t];
+    score[t] = v - (lam > a.tau ? lam : 0.f);
   }
   __syncthreads();  // the scores are read back by other threads of this workgroup
 
   const int p_start = n_tok - min(a.protect, n_tok);
-  uint32_t H = 0xFFFFFFFFu;
-  int L = 0x7FFFFFFF;  // keep = key > (H, L): nothing unprotected
-  if (n_tok <= budget) {
-    H = 0;
-    L = -1;  // everything
-  } else {
+  uint32_t H = 0;
+  int L = -1;  // keep = key > (H, L); (0, -1) keeps everything
+  if (n_tok > budget) {
     const int room = budget - (n_tok - p_start);
-    // score part: the largest H such that more than `room` unprotected tokens have order >= H
-    H = 0;
-    for (int bit = 31; bit >= 0; --bit) {
-      const uint32_t th = H | (1u << bit);
-      int cnt = 0;
-      for (int t = tid; t < p_start; t += 256) cnt += score_order(score[t]) >= th;
-      if (block_sum(cnt, slots, call, wave, lane) > room) H = th;
-    }
-    int above = 0;
-    for (int t = tid; t < p_start; t += 256) above += score_order(score[t]) > H;
-    above = block_sum(above, slots, call, wave, lane);
-    // index part: the largest L such that, among the tokens with order == H, those with index >= L do not fit
-    L = 0;
-    for (int bit = 31 - __builtin_clz(max(p_start, 1)); bit >= 0; --bit) {
-      const int tl = L | (1 << bit);
-      int cnt = 0;
-      for (int t = max(tl, 0) + tid; t < p_start; t += 256) cnt += score_order(score[t]) == H;
-      if (above + block_sum(cnt, slots, call, wave, lane) > room) L = tl;
-    }
+    // The order images of the unprotected tokens t = tid + 256 r stay in registers when the
+    // sequence is short enough (EPL per thread); longer sequences re-read the scores from L2.
+    auto search = [&](auto epl_tag) {
+      constexpr int EPL = decltype(epl_tag)::value;
+      uint32_t key[EPL > 0 ? EPL : 1];
+      if constexpr (EPL > 0) {
+#pragma unroll
+        for (int r = 0; r < EPL; ++r) {
+          const int t = tid + 256 * r;
+          key[r] = t < p_start ? score_order(score[t]) : 0u;
+        }
+      }
+      auto count = [&](auto pred) -> int {  // number of unprotected tokens with pred(order, index)
+        int cnt = 0;
+        if constexpr (EPL > 0) {
+#pragma unroll
+          for (int r = 0; r < EPL; ++r) cnt += (tid + 256 * r < p_start) && pred(key[r], tid + 256 * r);
+        } else {
+          for (int t = tid; t < p_start; t += 256) cnt += pred(score_order(score[t]), t);
+        }
+        return block_sum(cnt, slots, call, wave, lane);
+      };
+      // score part: the largest H such that more than `room` unprotected tokens have order >= H
+      for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t th = H | (1u << bit);
+        if (count([&](uint32_t o, int) { return o >= th; }) > room) H = th;
+      }
+      const int above = count([&](uint32_t o, int) { return o > H; });
+      // index part: the largest L such that, among the tokens with order == H, those with index >= L do not fit
+      L = 0;
+      for (int bit = 31 - __builtin_clz(max(p_start, 1)); bit >= 0; --bit) {
+        const int tl = L | (1 << bit);
+        if (above + count([&](uint32_t o, int t) { return o == H && t >= tl; }) > room) L = tl;
+      }
+    };
+    if (p_start <= 256 * 16)
+      search(std::integral_constant<int, 16>{});
+    else if (p_start <= 256 * 64)
+      search(std::integral_constant<int, 64>{});
+    else
+      search(std::integral_constant<int, 0>{});
   }
 
-  // ---- keep flags as a bit map; every thread owns a run of whole 32-token words
+  // ---- keep flags as a bit map in LDS, set token by token in the coalesced order; then every
+  // thread owns a run of whole 32-token words of it
   const int words = (n_tok + 31) / 32;
   const int per_w = (words + 255) / 256;
-  int mine = 0;
-  for (int w = tid * per_w; w < min((tid + 1) * per_w, words); ++w) {
-    uint32_t bits = 0;
-    for (int i = 0; i < 32; ++i) {
-      const int t = 32 * w + i;
-      if (t < n_tok) {
-        bool k = t >= p_start;
-        if (!k) {
-          const uint32_t o = score_order(score[t]);
-          k = o > H || (o == H && t > L);
-        }
-        bits |= (uint32_t)k << i;
-        if (a.tok_keep) a.tok_keep[tcol + t] = k;
-      }
+  for (int w = tid; w < words; w += 256) keep_bits[w] = 0;
+  __syncthreads();
+  for (int t = tid; t < n_tok; t += 256) {
+    bool k = t >= p_start;
+    if (!k) {
+      const uint32_t o = score_order(score[t]);
+      k = o > H || (o == H && t > L);
     }
-    keep_bits[w] = bits;
-    mine += __popc(bits);
+    if (k) atomicOr(&keep_bits[t >> 5], 1u << (t & 31));
+    if (a.tok_keep) a.tok_keep[tcol + t] = k;
   }
+  __syncthreads();
+  int mine = 0;
+  for (int w = tid * per_w; w < min((tid + 1) * per_w, words); ++w) mine += __popc(keep_bits[w]);
   int total_tok;
   int dst = block_scan_excl(mine, slots, call, wave, lane, total_tok);  // also makes the bit map visible
   for (int w = tid * per_w; w < min((tid + 1) * per_w, words); ++w) {
