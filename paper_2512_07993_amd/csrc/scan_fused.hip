@@ -441,11 +441,13 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
       coherent_store2(&a.ws.stat_part[((int64_t)lh * a.ws.nc_max + cur.c0) * R + r], make_float2(m, s));
     }
     if (nxt.item < n_items) q_commit(nxt, nq, par ^ 1);
-    wait_all();  // the statistics are acknowledged (and so are the loads already in flight)
-    __builtin_amdgcn_s_barrier();
-    if (tid == 0) {
-      const int old = __hip_atomic_fetch_add(&a.ws.arrive[lhb], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      s_flag = (old == cur.np - 1);
+    static_assert(R <= 64, "the record is written by wave 0 alone: only that wave waits for the acknowledgement");
+    if (wave == 0) {
+      wait_all();  // the statistics are acknowledged (the other waves keep their key loads in flight)
+      if (tid == 0) {
+        const int old = __hip_atomic_fetch_add(&a.ws.arrive[lhb], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_flag = (old == cur.np - 1);
+      }
     }
     lds_barrier();
     float *rn = a.ws.row_norm + (int64_t)lhb * R;
