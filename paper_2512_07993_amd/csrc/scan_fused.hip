@@ -482,11 +482,14 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
         float ss = 0.f;
 #pragma unroll
         for (int w = 0; w < 4; ++w) ss += wstat[w][r][1] * __builtin_amdgcn_exp2f(wstat[w][r][0] - mm);
-        coherent_store(&rn[r], ss > 0.f ? mm + __builtin_amdgcn_logf(ss) : INFINITY);
+        const float v = ss > 0.f ? mm + __builtin_amdgcn_logf(ss) : INFINITY;  // log2 of the softmax normaliser
+        coherent_store(&rn[r], v);
+        row_norm_l[r] = v;  // this workgroup uses its own copy
       }
-      wait_all();
-      __builtin_amdgcn_s_barrier();
-      if (tid == 0) __hip_atomic_store(&a.ws.ready[lhb], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (wave == 0) {  // rows are written by wave 0 alone (R <= 64)
+        wait_all();
+        if (tid == 0) __hip_atomic_store(&a.ws.ready[lhb], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
     } else {
       if (tid == 0) {
         int polls = 0;
@@ -499,12 +502,12 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
         }
       }
       __builtin_amdgcn_s_barrier();
+      // the head's normalisers come in once per workgroup (coherent loads are slow) and go round through LDS
+      if (tid < R) row_norm_l[tid] = coherent_load(&rn[tid]);
     }
+    lds_barrier();
 
     // =============== second phase: token importance from the logits still in registers =========
-    // the head's normalisers come in once per workgroup (coherent loads are slow) and go round through LDS
-    if (tid < R) row_norm_l[tid] = coherent_load(&rn[tid]);
-    lds_barrier();
     float cn[SLP];
 #pragma unroll
     for (int q = 0; q < SLP; ++q) {
