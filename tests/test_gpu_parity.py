@@ -81,3 +81,16 @@ def test_config3_full_size_sampled_heads():
     that bench.py times), checked on heads sampled across layers, heads and sequences."""
     stats = _run_and_compare(W.CONFIGS[3], 16, seed=3)
     assert stats["heads"] == 16
+
+
+def test_config4_full_size_sampled_heads():
+    """Qwen-7B shape at full size (64 sequences, 28 layers, GQA 7, alpha 8) on sampled heads."""
+    stats = _run_and_compare(W.CONFIGS[4], 12, seed=4)
+    assert stats["heads"] == 12
+
+
+def test_config5_full_size_sampled_heads():
+    """Long-CoT shape at full size (8 sequences of 32896 tokens, 48 layers, 160 query rows per head:
+    the two-pass scan) on sampled heads."""
+    stats = _run_and_compare(W.CONFIGS[5], 6, seed=5)
+    assert stats["heads"] == 6
