@@ -76,8 +76,7 @@ Workspace carve(const skipkv_cache *c, const RowLayout &rl, void *base) {
   w.seq_fused = static_cast<int32_t *>(take(B * 4));
   w.pair_cnt = static_cast<int32_t *>(take(B * 4));
   w.pair_rec = static_cast<int32_t *>(take((size_t)w.nc_max * kPairRecInts * 4));
-  w.arrive = static_cast<int32_t *>(take(2 * LH * B * 4));
-  w.ready = w.arrive ? w.arrive + LH * B : nullptr;
+  w.arrive = static_cast<int32_t *>(take(LH * B * 4));
   w.chunks = static_cast<Chunk *>(take((size_t)w.nc_max * sizeof(Chunk)));
   w.rowblocks = static_cast<RowBlock *>(take((size_t)w.nrb_max * sizeof(RowBlock)));
   w.stat_part = static_cast<float2 *>(take(LH * w.nc_max * rl.rows * sizeof(float2)));

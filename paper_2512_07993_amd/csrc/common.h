@@ -12,6 +12,7 @@ constexpr int kD = SKIPKV_HEAD_DIM;  // head dimension
 constexpr int kChunkCap = 256;       // a chunk of scan work = a maximal run of whole sentences of at most this many tokens
 constexpr int kChunkMaxSent = 32;    // ... and at most this many sentences (a single longer sentence is a chunk of its own)
 constexpr int kFuseMaxChunks = 512;  // sequences with more chunks than this take the two-pass scan (see scan_fused.hip)
+constexpr uint32_t kRowNormUnset = 0xFFFFFFFFu;  // bit pattern no computed normaliser has (a NaN with full payload)
 constexpr float kRefInit = -3.0e38f;  // "no key seen yet" softmax reference, finite so that -inf - ref stays -inf
 constexpr int kRowBlock = 128;       // sentences per row block of the redundancy kernel
 
@@ -70,11 +71,10 @@ struct Workspace {
   int32_t *pair_rec;     // [nc_max][kPairRecInts] one record per pair of consecutive chunks of one sequence (PairRec)
   int32_t *pair_cnt;     // [B] number of pairs of each sequence
   int32_t *arrive;       // [LH, B] chunks of the head that have published their row statistics
-  int32_t *ready;        // [LH, B] 1 once the head's row normalisers are final
   Chunk *chunks;         // [nc_max]
   RowBlock *rowblocks;   // [nrb_max]
   float2 *stat_part;     // [LH, nc_max, R]  per-chunk (max, sum) of every query row, log2 domain
-  float *row_norm;       // [LH, B, R]       log2 of the softmax normaliser of every query row
+  float *row_norm;       // [LH, B, R]       log2 of the softmax normaliser of every query row; preset to kRowNormUnset by the plan
   uint16_t *vhat_hi;     // [LH, S_total, 128] bf16 high part of the unit sentence embedding
   uint16_t *vhat_lo;     // [LH, S_total, 128] bf16 low part (residual)
   float *sent_imp;       // [LH, S_total]    mean token importance over the candidate span

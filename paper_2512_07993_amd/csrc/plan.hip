@@ -6,7 +6,7 @@
 
 namespace skipkv {
 
-__global__ void k_plan_reset(PlanHeader *hdr, int32_t *flags, int n_flags) {
+__global__ void k_plan_reset(PlanHeader *hdr, int32_t *flags, int n_flags, uint32_t *row_norm_bits, int n_norm) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i == 0) {
     hdr->n_chunks = 0;
@@ -15,6 +15,7 @@ __global__ void k_plan_reset(PlanHeader *hdr, int32_t *flags, int n_flags) {
     hdr->n_pairs = 0;
   }
   for (int j = i; j < n_flags; j += gridDim.x * blockDim.x) flags[j] = 0;
+  for (int j = i; j < n_norm; j += gridDim.x * blockDim.x) row_norm_bits[j] = kRowNormUnset;
 }
 
 // End (exclusive sentence index) of the chunk that starts at sentence `start`: the largest e in
@@ -130,8 +131,9 @@ __global__ void __launch_bounds__(256) k_plan(PlanArgs a) {
 }
 
 hipError_t launch_plan(const PlanArgs &a, hipStream_t st) {
-  const int n_flags = 2 * a.n_lh * a.batch;  // arrive and ready are one allocation
-  hipLaunchKernelGGL(k_plan_reset, dim3(64), dim3(256), 0, st, a.ws.hdr, a.ws.arrive, n_flags);
+  const int n_flags = a.n_lh * a.batch;  // arrive counters
+  hipLaunchKernelGGL(k_plan_reset, dim3(64), dim3(256), 0, st, a.ws.hdr, a.ws.arrive, n_flags,
+                     reinterpret_cast<uint32_t *>(a.ws.row_norm), a.n_lh * a.batch * a.ws.rows);
   if (a.batch > 0) hipLaunchKernelGGL(k_plan, dim3(a.batch), dim3(256), 0, st, a);
   return hipGetLastError();
 }

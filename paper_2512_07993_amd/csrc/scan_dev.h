@@ -10,7 +10,7 @@ typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
 
 // Cross-workgroup communication (the workgroups may sit on different XCDs, whose L2 caches are not
 // coherent with each other).  Everything that is communicated - share statistics, row normalisers,
-// the arrive counter and the ready flag - is accessed ONLY with device-scope relaxed atomics, which
+// the arrive counter - is accessed ONLY with device-scope relaxed atomics, which
 // are coherent by themselves; ordering comes from waiting until the data stores have been
 // acknowledged before the counter or flag is touched, and from program order plus a workgroup
 // barrier on the reading side.  No device-scope fence is used: on this chip such a fence writes

@@ -6,8 +6,9 @@
 // logits of its share in registers (they are MFMA accumulators anyway: per wave 64 tokens x all
 // query rows of the GQA group, for each of two consecutive chunks), publishes the (max, sum exp)
 // of every row over its share, and waits until the head's normalisers are final; the last
-// share of a head to arrive merges the partials and raises the head's ready flag.  Then each
-// workgroup finishes I[t] from its registers.  A unit of work ("item") is a PAIR of consecutive
+// share of a head to arrive merges the partials and writes the normalisers over the marker the
+// plan had preset them to, which is what the others poll for.  Then each workgroup finishes
+// I[t] from its registers.  A unit of work ("item") is a PAIR of consecutive
 // chunks of one head, so that the cross-workgroup round trips are paid once per 512 tokens.
 //
 // Forward progress.  The grid is persistent and no larger than what is co-resident on the chip
@@ -486,24 +487,21 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
         coherent_store(&rn[r], v);
         row_norm_l[r] = v;  // this workgroup uses its own copy
       }
-      if (wave == 0) {  // rows are written by wave 0 alone (R <= 64)
-        wait_all();
-        if (tid == 0) __hip_atomic_store(&a.ws.ready[lhb], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-    } else {
-      if (tid == 0) {
-        int polls = 0;
-        while (__hip_atomic_load(&a.ws.ready[lhb], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) {
-          __builtin_amdgcn_s_sleep(2);
-          if (++polls > a.spin_limit) {
-            if (a.dev_status) atomicOr(a.dev_status, SKIPKV_DEV_TIMEOUT);
-            break;
-          }
+      // no flag: the readers poll the rows themselves, which the plan has preset to a marker
+    } else if (wave == 0) {
+      // wait for the head's normalisers: one coherent load per row and poll, all rows at once;
+      // they go round the workgroup through LDS
+      const uint32_t *rn_bits = reinterpret_cast<const uint32_t *>(rn);
+      for (int polls = 0;; ++polls) {
+        const uint32_t u = lane < R ? __hip_atomic_load(&rn_bits[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+        const bool done = __all(u != kRowNormUnset);
+        if (done || polls > a.spin_limit) {
+          if (!done && lane == 0 && a.dev_status) atomicOr(a.dev_status, SKIPKV_DEV_TIMEOUT);
+          if (lane < R) row_norm_l[lane] = __uint_as_float(u);
+          break;
         }
+        __builtin_amdgcn_s_sleep(2);
       }
-      __builtin_amdgcn_s_barrier();
-      // the head's normalisers come in once per workgroup (coherent loads are slow) and go round through LDS
-      if (tid < R) row_norm_l[tid] = coherent_load(&rn[tid]);
     }
     lds_barrier();
 
