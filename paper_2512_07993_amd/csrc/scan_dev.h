@@ -32,6 +32,14 @@ __device__ __forceinline__ float2 coherent_load2(const float2 *p) {
 }
 
 // s_waitcnt immediates (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14)
+// A copy of a per-thread value that the compiler cannot trace back to its source: address parts
+// derived from it are computed where they are used instead of being kept in registers (or in
+// scratch, whose reloads would wait for every key load in flight) across a whole item.
+__device__ __forceinline__ int opaque(int x) {
+  asm volatile("" : "+v"(x));
+  return x;
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vm() {  // at most N vector-memory operations still outstanding
   __builtin_amdgcn_s_waitcnt((N & 0xF) | (0x7 << 4) | (0xF << 8) | ((N >> 4) << 14));

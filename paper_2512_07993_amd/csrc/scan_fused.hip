@@ -137,14 +137,15 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
   };
   auto q_fetch = [&](const Pair &it) -> QFetch {
     QFetch f;
+    const int t = opaque(tid);
     f.so = 0;
-    if (tid <= it.ch[0].ns) f.so = a.sent_off[it.ch[0].soff_idx + tid];
-    if (it.nch == 2 && tid >= 64 && tid - 64 <= it.ch[1].ns) f.so = a.sent_off[it.ch[1].soff_idx + tid - 64];
+    if (t <= it.ch[0].ns) f.so = a.sent_off[it.ch[0].soff_idx + t];
+    if (it.nch == 2 && t >= 64 && t - 64 <= it.ch[1].ns) f.so = a.sent_off[it.ch[1].soff_idx + t - 64];
     const char *qbase = static_cast<const char *>(a.q);
     const int l = it.lh / a.n_kv_heads, h = it.lh % a.n_kv_heads;
 #pragma unroll
     for (int u = 0; u < NQ; ++u) {
-      const int r = u * (256 / PPR) + tid / PPR, piece = tid % PPR;
+      const int r = u * (256 / PPR) + t / PPR, piece = t % PPR;
       const int slot = 4 * (r >> 4) + (r & 3), gq = (r >> 2) & 3;
       const int al = slot / NP, i = slot % NP, aq = gq + 4 * al;
       f.q[u] = make_uint4(0, 0, 0, 0);
@@ -156,11 +157,12 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     return f;
   };
   auto q_commit = [&](const Pair &it, const QFetch &f, int par) {
-    if (tid <= it.ch[0].ns) soff_buf[par][0][tid] = f.so;
-    if (it.nch == 2 && tid >= 64 && tid - 64 <= it.ch[1].ns) soff_buf[par][1][tid - 64] = f.so;
+    const int t = opaque(tid);
+    if (t <= it.ch[0].ns) soff_buf[par][0][t] = f.so;
+    if (it.nch == 2 && t >= 64 && t - 64 <= it.ch[1].ns) soff_buf[par][1][t - 64] = f.so;
 #pragma unroll
     for (int u = 0; u < NQ; ++u) {
-      const int r = u * (256 / PPR) + tid / PPR, piece = tid % PPR;
+      const int r = u * (256 / PPR) + t / PPR, piece = t % PPR;
       *reinterpret_cast<uint4 *>(qt + r * LSTR + piece * 16) = f.q[u];
     }
   };
@@ -397,10 +399,13 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     }
     // The next item is usually known already (the load stream has just moved on to it; after very
     // short items it may be further ahead, then the descriptor is read again).  Its queries and
-    // offsets are fetched now and committed once every wave is done with the current query tile.
+    // offsets are fetched now and committed before the second barrier below, so that their latency
+    // and the sentences pieced together below overlap with the round trips of the exchange.  After
+    // the last item the descriptor is all zero: the fetch then reads valid memory that nobody uses,
+    // which keeps fetch and commit free of conditions (a fetch that may stay uncommitted would
+    // make the compiler drain the load queue at the next fetch).
     const Pair nxt = (iss_from == cur.item) ? iss : load_pair(cur.item + gridDim.x);
-    QFetch nq;
-    if (nxt.item < n_items) nq = q_fetch(nxt);
+    const QFetch nq = q_fetch(nxt);
 #pragma unroll
     for (int q = 0; q < SLP; ++q) {
       const float tot = row16_sum_fast(lsum[q]);
@@ -412,44 +417,46 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     }
     lds_barrier();  // every wave is done with the query tile and has left its partials
 
+    // ---- publish the share's row statistics (one record per item, filed under its first chunk).
+    // The last wave does it, lane = query row: no sentence that crosses a wave boundary starts in
+    // its range, so it has nothing else to do while the other waves piece those together.
+    static_assert(R <= 64, "the record is written by one wave: only that wave waits for the acknowledgement");
+    int arrived = 0;
+    if (wave == 3) {
+      if (lane < R) {
+        float m = kRefInit;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) m = fmaxf(m, wstat[w][lane][0]);
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) s += wstat[w][lane][1] * __builtin_amdgcn_exp2f(wstat[w][lane][0] - m);
+        coherent_store2(&a.ws.stat_part[((int64_t)lh * a.ws.nc_max + cur.c0) * R + lane], make_float2(m, s));
+      }
+      wait_all();  // the statistics are acknowledged (the other waves keep their key loads in flight)
+      if (lane == 0) arrived = __hip_atomic_fetch_add(&a.ws.arrive[lhb], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     // ---- sentences that cross wave boundaries: the wave in whose range one starts pieces it together
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
       if (k < cur.nch) {
         const ChunkD &cd = cur.ch[k];
         const int *soff = soff_buf[par][k];
-        if (cd.w0 < cd.w1) {
+        if (cd.w0 < cd.w1 && wave < 3) {
           const int sl = __popcll(__ballot(lane < cd.ns && soff[lane + 1] <= cd.w1 - 1));  // sentence holding the wave's last token
           if (soff[sl] >= cd.w0 && soff[sl + 1] > cd.w1) {
-            float k0 = part_last[k][wave][2 * lane], k1 = part_last[k][wave][2 * lane + 1];
+            const int ln = opaque(lane);
+            float k0 = part_last[k][wave][2 * ln], k1 = part_last[k][wave][2 * ln + 1];
             for (int w = wave + 1; w < 4 && cd.t_begin + w * kCapW < soff[sl + 1]; ++w) {
-              k0 += part_first[k][w][2 * lane];
-              k1 += part_first[k][w][2 * lane + 1];
+              k0 += part_first[k][w][2 * ln];
+              k1 += part_first[k][w][2 * ln + 1];
             }
             emit_sentence(soff[sl + 1] - soff[sl], cd.soff_idx - b, sl, k0, k1);
           }
         }
       }
     }
-    // ---- publish the share's row statistics (one record per item, filed under its first chunk)
-    for (int r = tid; r < R; r += 256) {
-      float m = kRefInit;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) m = fmaxf(m, wstat[w][r][0]);
-      float s = 0.f;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) s += wstat[w][r][1] * __builtin_amdgcn_exp2f(wstat[w][r][0] - m);
-      coherent_store2(&a.ws.stat_part[((int64_t)lh * a.ws.nc_max + cur.c0) * R + r], make_float2(m, s));
-    }
-    if (nxt.item < n_items) q_commit(nxt, nq, par ^ 1);
-    static_assert(R <= 64, "the record is written by wave 0 alone: only that wave waits for the acknowledgement");
-    if (wave == 0) {
-      wait_all();  // the statistics are acknowledged (the other waves keep their key loads in flight)
-      if (tid == 0) {
-        const int old = __hip_atomic_fetch_add(&a.ws.arrive[lhb], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_flag = (old == cur.np - 1);
-      }
-    }
+    q_commit(nxt, nq, par ^ 1);
+    if (tid == 192) s_flag = (arrived == cur.np - 1);
     lds_barrier();
     float *rn = a.ws.row_norm + (int64_t)lhb * R;
     if (s_flag) {  // last share of the head to arrive: merge the partials into the normalisers
@@ -541,7 +548,8 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     const int64_t tok_col = (int64_t)lh * a.total_tokens + cur.tok0;
     {  // sentence means: 4 lanes per sentence; threads 0..127 take the first chunk, 128..255 the second
       static_assert(kChunkMaxSent * 4 <= 128, "4 lanes per sentence of a chunk");
-      const int k = tid >> 7, s_idx = (tid & 127) >> 2, part = tid & 3;
+      const int tl = opaque(tid);
+      const int k = tl >> 7, s_idx = (tl & 127) >> 2, part = tl & 3;
       const bool valid = k < cur.nch && s_idx < (k ? cur.ch[1].ns : cur.ch[0].ns);
       float sum_i = 0.f, sum_r = 0.f;
       int lo = 0, hi = 0;
@@ -568,13 +576,15 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
       }
     }
     if (a.tok_imp) {
+      const int tl = opaque(tid);
 #pragma unroll
       for (int k = 0; k < 2; ++k)
         if (k < cur.nch)
-          for (int i = tid; i < cur.ch[k].t_end - cur.ch[k].t_begin; i += 256)
+          for (int i = tl; i < cur.ch[k].t_end - cur.ch[k].t_begin; i += 256)
             a.tok_imp[tok_col + cur.ch[k].t_begin + i] = imp[k][i];
     }
-    lds_barrier();  // imp, the offsets and the partial buffers are free again; the next item's query tile is in place
+    // No barrier here: every buffer shared between waves is written next only after at least one
+    // of the next item's barriers, which no wave passes before all have finished reading above.
     cur = nxt;
     par ^= 1;
   }
