@@ -4,8 +4,9 @@
 // Per head the unit sentence embeddings form an S x 128 matrix; lambda_s is the row maximum of
 // the strictly upper triangle of its Gram matrix.  The Gram tiles run on the bf16 matrix cores;
 // to keep fp32-grade cosines (the ranking among near-duplicates depends on differences of
-// ~1e-3) each embedding is carried as bf16 hi + bf16 lo and a tile is the full product
-// (hi + lo)(hi + lo)^T: four bf16 MFMAs, small terms accumulated first.
+// ~1e-3) each embedding is carried as bf16 hi + bf16 lo and a tile is the product
+// (hi + lo)(hi + lo)^T without its lo*lo term (below 2^-16 of a unit cosine, i.e. fp32-grade
+// for the comparison with tau and for the ranking): three bf16 MFMAs, small terms first.
 // One workgroup owns kRowBlock = 128 rows (32 per wave, A operands in registers) and walks the
 // 64-column blocks at and to the right of the diagonal, staged through LDS and shared by the 4
 // waves; the next column block is fetched into registers while the current one is multiplied.
@@ -87,25 +88,38 @@ __global__ void __launch_bounds__(256) k_cosine(CosineArgs a) {
     for (int ct = 0; ct < kColBlock / 16; ++ct) {
       const int cbase = jb + 16 * ct;
       if (cbase >= n_sent) continue;
+      // both row tiles of the wave share the column fragments (one LDS read serves two products)
+      bool live[kRowTiles];
+      bool any_live = false;
 #pragma unroll
       for (int t = 0; t < kRowTiles; ++t) {
         const int rt0 = rw0 + 16 * t;
-        if (cbase + 15 <= rt0 || rt0 >= n_sent) continue;  // nothing right of the diagonal in this tile
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        live[t] = !(cbase + 15 <= rt0 || rt0 >= n_sent);  // something right of the diagonal in this tile
+        any_live |= live[t];
+      }
+      if (!any_live) continue;
+      f32x4 acc[kRowTiles];
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          const bf16x8 b_hi = *reinterpret_cast<const bf16x8 *>(col_hi + (16 * ct + c16) * LSTR + g * 64 + kk * 16);
-          const bf16x8 b_lo = *reinterpret_cast<const bf16x8 *>(col_lo + (16 * ct + c16) * LSTR + g * 64 + kk * 16);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo[t][kk], b_lo, acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo[t][kk], b_hi, acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi[t][kk], b_lo, acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi[t][kk], b_hi, acc, 0, 0, 0);
+      for (int t = 0; t < kRowTiles; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const bf16x8 b_hi = *reinterpret_cast<const bf16x8 *>(col_hi + (16 * ct + c16) * LSTR + g * 64 + kk * 16);
+        const bf16x8 b_lo = *reinterpret_cast<const bf16x8 *>(col_lo + (16 * ct + c16) * LSTR + g * 64 + kk * 16);
+#pragma unroll
+        for (int t = 0; t < kRowTiles; ++t) {
+          acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo[t][kk], b_hi, acc[t], 0, 0, 0);
+          acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi[t][kk], b_lo, acc[t], 0, 0, 0);
+          acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi[t][kk], b_hi, acc[t], 0, 0, 0);
         }
-        const int col = cbase + c16;
+      }
+      const int col = cbase + c16;
+#pragma unroll
+      for (int t = 0; t < kRowTiles; ++t) {
+        if (!live[t]) continue;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          const int row = rt0 + 4 * g + j;
-          if (col > row && col < n_sent) rmax[t][j] = fmaxf(rmax[t][j], acc[j]);
+          const int row = rw0 + 16 * t + 4 * g + j;
+          if (col > row && col < n_sent) rmax[t][j] = fmaxf(rmax[t][j], acc[t][j]);
         }
       }
     }

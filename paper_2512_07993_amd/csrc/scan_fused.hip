@@ -35,6 +35,10 @@
 // through LDS in a fixed order, so results are reproducible.
 #include "scan_dev.h"
 
+#ifndef SKIPKV_FRAG_AHEAD
+#define SKIPKV_FRAG_AHEAD 1  // slices of query fragments read ahead of the matrix instructions (2 needs more registers than there are)
+#endif
+
 namespace skipkv {
 
 namespace {
@@ -272,14 +276,32 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
 
             // ---- logits of this stage's 16 tokens against all query rows
             if constexpr (DT == SKIPKV_BF16) {
+              // Fragment reads run AHEAD slices of the head dimension ahead of the matrix
+              // instructions that use them (the order is pinned, the compiler would otherwise read
+              // each fragment right before its use and pay the LDS latency every time).
+              constexpr int AHEAD = SKIPKV_FRAG_AHEAD;
+              const char *brow = stage + c16 * ROWB;
+              const char *arow = qt + c16 * LSTR + g * 64;
+              bf16x8 bfr[4], afr[4][NT];
+#pragma unroll
+              for (int kk = 0; kk < 4; ++kk) bfr[kk] = *reinterpret_cast<const bf16x8 *>(brow + (((4 * g + kk) ^ c16) * 16));
+#pragma unroll
+              for (int kk = 0; kk < AHEAD; ++kk)
+#pragma unroll
+                for (int T = 0; T < NT; ++T) afr[kk][T] = *reinterpret_cast<const bf16x8 *>(arow + 16 * T * LSTR + kk * 16);
+              __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
               for (int kk = 0; kk < 4; ++kk) {
-                const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(stage + c16 * ROWB + (((4 * g + kk) ^ c16) * 16));
+                if (kk + AHEAD < 4) {
 #pragma unroll
-                for (int T = 0; T < NT; ++T) {
-                  const bf16x8 afrag = *reinterpret_cast<const bf16x8 *>(qt + (16 * T + c16) * LSTR + g * 64 + kk * 16);
-                  acc[k][st][T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag, acc[k][st][T], 0, 0, 0);
+                  for (int T = 0; T < NT; ++T)
+                    afr[kk + AHEAD][T] = *reinterpret_cast<const bf16x8 *>(arow + 16 * T * LSTR + (kk + AHEAD) * 16);
                 }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int T = 0; T < NT; ++T)
+                  acc[k][st][T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afr[kk][T], bfr[kk], acc[k][st][T], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
               }
             } else {
 #pragma unroll
