@@ -7,6 +7,7 @@
 namespace skipkv {
 
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short bf16x4_t;  // operand type of the 4x4x4 bf16 matrix instruction
 
 // Cross-workgroup communication (the workgroups may sit on different XCDs, whose L2 caches are not
 // coherent with each other).  Everything that is communicated - share statistics, row normalisers,

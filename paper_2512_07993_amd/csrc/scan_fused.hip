@@ -81,6 +81,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
   __shared__ float imp[2][kChunkCap];
   __shared__ int s_flag;
   __shared__ float row_norm_l[R];
+  __shared__ uint2 ind_tab[16];  // entry n: four bf16, element j = 1.0 if bit j of n is set (indicator rows of the pooling products)
 
   const int tid = threadIdx.x, lane = tid & 63, c16 = lane & 15, g = lane >> 4;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: everything derived from it is uniform control flow
@@ -208,6 +209,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
 
   Pair cur = load_pair(blockIdx.x);
   if (cur.item >= n_items) return;
+  if (tid < 16) ind_tab[tid] = make_uint2(((tid & 1) ? 0x3F80u : 0u) | ((tid & 2) ? 0x3F800000u : 0u), ((tid & 4) ? 0x3F80u : 0u) | ((tid & 8) ? 0x3F800000u : 0u));
 #pragma unroll
   for (int i = 0; i < NBUF - 1; ++i) issue_next();
   uint32_t cmp_cnt = 0;  // stages computed so far (ring position)
@@ -254,11 +256,13 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
         const int *soff = soff_buf[par][k];
         const int ns = cd.ns, w0 = cd.w0, w1 = cd.w1;
         const int sent_col0 = cd.soff_idx - b;
-        // sentence pooling state: current sentence, its running key sum (lane = 2 head-dim columns);
-        // lane i keeps offset i of the chunk, so that boundaries are fetched with v_readlane
+        // sentence pooling state: current sentence si and the running key sums of sentences si .. si+3
+        // (lane = 2 head-dim columns: pk0 the even one, pk1 the odd one; component j belongs to sentence
+        // si + j; the fp32 path only uses component 0); lane i keeps offset i of the chunk, so that
+        // boundaries are fetched with v_readlane
         const int soff_v = soff[min(lane, ns)];
         int si = 0;
-        float ps0 = 0.f, ps1 = 0.f;
+        f32x4 pk0 = {0.f, 0.f, 0.f, 0.f}, pk1 = {0.f, 0.f, 0.f, 0.f};
         if (w0 < w1) si = __popcll(__ballot(lane >= 1 && lane <= ns && soff_v <= w0));
         int s_bgn = __builtin_amdgcn_readlane(soff_v, si), s_end = __builtin_amdgcn_readlane(soff_v, min(si + 1, ns));
 
@@ -352,9 +356,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
             }
 
             // ---- sentence key sums over tokens [ts, te).  All rows of the stage come into registers
-            // with one LDS round trip (lane = 2 head-dim columns of every row); then every run of
-            // rows that belongs to one sentence is added with a 0/1 weight per row taken from a
-            // scalar bit mask, so there is no branch per row.
+            // with one LDS round trip (lane = 2 head-dim columns of every row).
             {
               float x0[kStageRows], x1[kStageRows];
               uint32_t xw[kStageRows];
@@ -372,41 +374,65 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
                   x1[i] = lds_read_f32((la ^ (i << 4)) + i * ROWB + 4);
                 }
               }
-              int t = ts;
-              while (t < te) {
-                const int run_end = min(s_end, te);
-                if (run_end <= t) break;  // cannot happen with validated offsets; never spin on bad ones
-                const uint32_t rows = ((1u << (run_end - ts)) - 1u) & ~((1u << (t - ts)) - 1u);  // rows of this run
-                if constexpr (DT == SKIPKV_BF16) {
-                  // dot2 with (1, 0) adds the low half of the pair, with (0, 1) the high half
-#pragma unroll
-                  for (int i = 0; i < kStageRows; ++i) {
-                    const bool on = (rows >> i) & 1u;
-                    ps0 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, xw[i]),
-                                                         __builtin_bit_cast(bf16x2_t, on ? 0x00003F80u : 0u), ps0, false);
-                    ps1 = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, xw[i]),
-                                                         __builtin_bit_cast(bf16x2_t, on ? 0x3F800000u : 0u), ps1, false);
-                  }
+              auto sentence_done = [&]() {  // sentence si ends: emit it (or leave its part), move the sums up one place
+                if (s_bgn >= w0) {
+                  emit_sentence(s_end - s_bgn, sent_col0, si, pk0[0], pk1[0]);
                 } else {
+                  part_first[k][wave][2 * lane] = pk0[0];
+                  part_first[k][wave][2 * lane + 1] = pk1[0];
+                }
+                pk0 = f32x4{pk0[1], pk0[2], pk0[3], 0.f};
+                pk1 = f32x4{pk1[1], pk1[2], pk1[3], 0.f};
+                ++si;
+                s_bgn = s_end;
+                s_end = __builtin_amdgcn_readlane(soff_v, min(si + 1, ns));
+              };
+              int t = ts;
+              if constexpr (DT == SKIPKV_BF16) {
+                // Segment sums on the matrix cores: [4 sentences x 16 tokens] 0/1 indicator times
+                // [16 tokens x 128 columns] keys, as 4x4x4 products in 16 independent blocks.  Every
+                // block gets the same indicator rows (lane % 4 = sentence si + lane % 4) and four
+                // columns of its own; a lane's B operand is its own column, so the result comes back
+                // in the lane that pools that column: register j = sentence si + j.  One product per
+                // 4 tokens and column parity, whatever the number of sentence ends in the stage; the
+                // loop below runs again only when more than 4 sentences meet in one stage.
+                while (t < te) {
+                  const int g_end = min(__builtin_amdgcn_readlane(soff_v, min(si + 4, ns)), te);
+                  if (g_end <= t) break;  // cannot happen with validated offsets; never spin on bad ones
+                  const int c = min(si + (lane & 3), ns), c1 = min(c + 1, ns);
+                  const int lo_t = max(soff[c], t), hi_t = min(soff[c1], g_end);
+                  uint32_t rows = 0;  // rows of the stage that belong to this lane's sentence
+                  if (hi_t > lo_t) rows = ((1u << (hi_t - ts)) - 1u) & ~((1u << (lo_t - ts)) - 1u);
+#pragma unroll
+                  for (int q = 0; q < kStageRows / 4; ++q) {
+                    const uint2 ind = ind_tab[(rows >> (4 * q)) & 15u];
+                    const bf16x4_t av = __builtin_bit_cast(bf16x4_t, ind);
+                    // tokens 4q .. 4q+3 of the even column (low halves) and of the odd column (high halves)
+                    const uint2 be = make_uint2(__builtin_amdgcn_perm(xw[4 * q + 1], xw[4 * q], 0x05040100u),
+                                                __builtin_amdgcn_perm(xw[4 * q + 3], xw[4 * q + 2], 0x05040100u));
+                    const uint2 bo = make_uint2(__builtin_amdgcn_perm(xw[4 * q + 1], xw[4 * q], 0x07060302u),
+                                                __builtin_amdgcn_perm(xw[4 * q + 3], xw[4 * q + 2], 0x07060302u));
+                    pk0 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(av, __builtin_bit_cast(bf16x4_t, be), pk0, 0, 0, 0);
+                    pk1 = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(av, __builtin_bit_cast(bf16x4_t, bo), pk1, 0, 0, 0);
+                  }
+                  t = g_end;
+                  while (si < ns && s_end <= t) sentence_done();
+                }
+              } else {
+                // fp32 keys: every run of rows that belongs to one sentence is added with a 0/1 weight
+                // per row taken from a scalar bit mask, so there is no branch per row
+                while (t < te) {
+                  const int run_end = min(s_end, te);
+                  if (run_end <= t) break;  // cannot happen with validated offsets; never spin on bad ones
+                  const uint32_t rows = ((1u << (run_end - ts)) - 1u) & ~((1u << (t - ts)) - 1u);  // rows of this run
 #pragma unroll
                   for (int i = 0; i < kStageRows; ++i) {
                     const float m = ((rows >> i) & 1u) ? 1.f : 0.f;
-                    ps0 = fmaf(x0[i], m, ps0);
-                    ps1 = fmaf(x1[i], m, ps1);
+                    pk0[0] = fmaf(x0[i], m, pk0[0]);
+                    pk1[0] = fmaf(x1[i], m, pk1[0]);
                   }
-                }
-                t = run_end;
-                if (t == s_end) {  // the sentence ends here
-                  if (s_bgn >= w0) {
-                    emit_sentence(s_end - s_bgn, sent_col0, si, ps0, ps1);
-                  } else {
-                    part_first[k][wave][2 * lane] = ps0;
-                    part_first[k][wave][2 * lane + 1] = ps1;
-                  }
-                  ps0 = ps1 = 0.f;
-                  ++si;
-                  s_bgn = s_end;
-                  s_end = __builtin_amdgcn_readlane(soff_v, min(si + 1, ns));
+                  t = run_end;
+                  if (t == s_end) sentence_done();
                 }
               }
             }
@@ -414,8 +440,8 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
         }
         if (w0 < w1 && si < ns && s_bgn < w1 && w1 < s_end) {  // a sentence is still running at the end of this wave's range
           float *dst = (s_bgn >= w0) ? part_last[k][wave] : part_first[k][wave];
-          dst[2 * lane] = ps0;
-          dst[2 * lane + 1] = ps1;
+          dst[2 * lane] = pk0[0];
+          dst[2 * lane + 1] = pk1[0];
         }
       }
     }
@@ -505,7 +531,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
         wstat[wave][r][1] = s;
       }
       lds_barrier();
-      for (int r = tid; r < R; r += 256) {
+      for (int r = opaque(tid); r < R; r += 256) {
         float mm = kRefInit;
 #pragma unroll
         for (int w = 0; w < 4; ++w) mm = fmaxf(mm, wstat[w][r][0]);
@@ -526,7 +552,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
         const bool done = __all(u != kRowNormUnset);
         if (done || polls > a.spin_limit) {
           if (!done && lane == 0 && a.dev_status) atomicOr(a.dev_status, SKIPKV_DEV_TIMEOUT);
-          if (lane < R) row_norm_l[lane] = __uint_as_float(u);
+          if (lane < R) row_norm_l[opaque(lane)] = __uint_as_float(u);
           break;
         }
         __builtin_amdgcn_s_sleep(2);
