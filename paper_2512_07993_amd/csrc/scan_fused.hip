@@ -232,11 +232,10 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     }
 
     auto emit_sentence = [&](int len, int sent_col0, int s_idx, float k0, float k1) {  // unit embedding, bf16 hi + lo
-      // 1-ulp reciprocal and square root: a common scale error of ~1e-7 on the unit vector
-      const float inv_len = __builtin_amdgcn_rcpf((float)len);
-      const float m0 = k0 * inv_len, m1 = k1 * inv_len;
-      const float inv = __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(wave_sum_fast(m0 * m0 + m1 * m1)) + 1e-12f);
-      const float u0 = m0 * inv, u1 = m1 * inv;
+      // mean / (|mean| + eps) = sum / (|sum| + eps * len): no division by the length.  1-ulp
+      // reciprocal and square root: a common scale error of ~1e-7 on the unit vector
+      const float inv = __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(wave_sum_fast(k0 * k0 + k1 * k1)) + 1e-12f * (float)len);
+      const float u0 = k0 * inv, u1 = k1 * inv;
       const uint32_t hi = pack_bf16x2(u0, u1);  // round to nearest even, both halves in one instruction
       const uint32_t lo = pack_bf16x2(u0 - __uint_as_float(hi << 16), u1 - __uint_as_float(hi & 0xFFFF0000u));
       const int64_t o = ((int64_t)lh * a.total_sentences + sent_col0 + s_idx) * (kD / 2) + lane;
