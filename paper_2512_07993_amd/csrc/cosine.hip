@@ -21,7 +21,7 @@ constexpr int kColBlock = 64;
 constexpr int kRowTiles = kRowBlock / 64;  // 16-row tiles per wave
 static_assert(kRowBlock % 64 == 0, "four waves, whole tiles");
 
-__global__ void __launch_bounds__(256) k_cosine(CosineArgs a) {
+__global__ void __launch_bounds__(256, 3) k_cosine(CosineArgs a) {
   __shared__ __align__(16) char col_hi[kColBlock * LSTR];
   __shared__ __align__(16) char col_lo[kColBlock * LSTR];
 
@@ -54,6 +54,20 @@ __global__ void __launch_bounds__(256) k_cosine(CosineArgs a) {
       a_hi[t][kk] = __builtin_bit_cast(bf16x8, vh);
       a_lo[t][kk] = __builtin_bit_cast(bf16x8, vl);
     }
+  }
+  // inputs of the epilogue, one row per lane (lanes c16 < 4 * kRowTiles), fetched now so that their
+  // latency is hidden behind the products
+  static_assert(4 * kRowTiles <= 16, "one epilogue row per lane of a 16-lane group");
+  const int my_row = rw0 + 16 * (c16 >> 2) + 4 * g + (c16 & 3);
+  const int tok0 = a.seq_off[b];
+  const int n_tok = a.seq_off[b + 1] - tok0;
+  const int p_start = n_tok - min(a.protect, n_tok);
+  float my_imp = 0.f, my_red = 0.f;
+  int my_off = 0;
+  if (c16 < 4 * kRowTiles && my_row < n_sent) {
+    my_off = a.sent_off[sp + my_row];
+    my_imp = a.ws.sent_imp[col0 + my_row];
+    if (a.has_red) my_red = a.ws.sent_red[col0 + my_row];
   }
   float rmax[kRowTiles][4];
 #pragma unroll
@@ -126,26 +140,22 @@ __global__ void __launch_bounds__(256) k_cosine(CosineArgs a) {
     __syncthreads();
   }
 
-  // row maxima across the 16 column lanes, then the fused score of Eq. 6
-  const int tok0 = a.seq_off[b];
-  const int n_tok = a.seq_off[b + 1] - tok0;
-  const int p_start = n_tok - min(a.protect, n_tok);
+  // row maxima across the 16 column lanes, then the fused score of Eq. 6: lane c16 = 4t + j of
+  // a lane group finishes row (tile t, register j), with the inputs it fetched at the start
 #pragma unroll
   for (int t = 0; t < kRowTiles; ++t) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const float lam = row16_max(rmax[t][j]);
-      const int row = rw0 + 16 * t + 4 * g + j;
-      if (c16 == 0 && row < n_sent) {
-        const int64_t o = col0 + row;
+      if (c16 == 4 * t + j && my_row < n_sent) {
         float score = INFINITY;
-        if (a.sent_off[sp + row] < p_start) {
-          score = a.sigma * a.ws.sent_imp[o];
-          if (a.has_red) score -= (1.f - a.sigma) * a.ws.sent_red[o];
+        if (my_off < p_start) {
+          score = a.sigma * my_imp;
+          if (a.has_red) score -= (1.f - a.sigma) * my_red;
           if (lam > a.tau) score -= lam;
         }
-        a.sent_lambda[o] = lam;
-        a.sent_score[o] = score;
+        a.sent_lambda[col0 + my_row] = lam;
+        a.sent_score[col0 + my_row] = score;
       }
     }
   }
