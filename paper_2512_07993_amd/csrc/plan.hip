@@ -61,9 +61,17 @@ __global__ void __launch_bounds__(256) k_plan(PlanArgs a) {
   }
   __syncthreads();
   __shared__ int s_base, s_nchunks, s_pbase, s_fused;
+  __shared__ int s_next[SKIPKV_MAX_SENTENCES];    // end of the chunk that would start at each sentence
+  __shared__ int s_first[SKIPKV_MAX_SENTENCES];   // first sentence of every chunk
+  const bool ok = !reject && !s_bad;
+  // the greedy packing is a walk along s -> chunk_end(s); the ends are found for all sentences at
+  // once, so that the (serial) walk is one LDS read per chunk
+  if (ok)
+    for (int s = tid; s < n_sent; s += 256) s_next[s] = chunk_end(s_off, s, n_sent);
+  __syncthreads();
   if (tid == 0) {
     s_nchunks = -1;
-    if (reject || s_bad) {
+    if (!ok) {
       if (a.dev_status) atomicOr(a.dev_status, reject ? SKIPKV_DEV_TOO_MANY_SENT : SKIPKV_DEV_BAD_OFFSETS);
       a.ws.chunk_base[b] = 0;
       a.ws.chunk_cnt[b] = 0;
@@ -72,12 +80,11 @@ __global__ void __launch_bounds__(256) k_plan(PlanArgs a) {
       a.ws.seq_fused[b] = 1;  // nothing to scan either way
       a.ws.pair_cnt[b] = 0;
     } else {
-      // pass 1: count chunks
       int n_chunks = 0, longest = 0;
       for (int start = 0; start < n_sent;) {
-        const int e = chunk_end(s_off, start, n_sent);
+        const int e = s_next[start];
         longest = max(longest, s_off[e] - s_off[start]);
-        ++n_chunks;
+        s_first[n_chunks++] = start;
         start = e;
       }
       const int base = atomicAdd(&a.ws.hdr->n_chunks, n_chunks);
@@ -86,13 +93,6 @@ __global__ void __launch_bounds__(256) k_plan(PlanArgs a) {
       const bool fused = longest <= kChunkCap && n_chunks <= kFuseMaxChunks;
       a.ws.seq_fused[b] = fused;
       if (!fused && n_chunks > 0) atomicAdd(&a.ws.hdr->n_unfused, 1);
-      // pass 2: emit
-      int idx = base;
-      for (int start = 0; start < n_sent;) {
-        const int e = chunk_end(s_off, start, n_sent);
-        a.ws.chunks[idx++] = Chunk{b, start, e - start, s_off[start], s_off[e] - s_off[start], sp + start, tok0, n_tok};
-        start = e;
-      }
       // the single-pass scan works on pairs of consecutive chunks of a sequence
       const int n_pairs = (n_chunks + 1) / 2;
       a.ws.pair_cnt[b] = n_pairs;
@@ -107,24 +107,29 @@ __global__ void __launch_bounds__(256) k_plan(PlanArgs a) {
       s_fused = fused;
     }
   }
-  __syncthreads();  // the chunk records written above are read back below by the whole block
+  __syncthreads();
   if (s_nchunks < 0) return;
   const int base = s_base, n_chunks = s_nchunks, n_pairs = (n_chunks + 1) / 2;
+  for (int j = tid; j < n_chunks; j += 256) {  // one record per chunk
+    const int s0 = s_first[j], e = s_next[s0];
+    a.ws.chunks[base + j] = Chunk{b, s0, e - s0, s_off[s0], s_off[e] - s_off[s0], sp + s0, tok0, n_tok};
+  }
   for (int j = tid; j < n_pairs; j += 256) {  // one record per pair
-    const Chunk &c0 = a.ws.chunks[base + 2 * j];
+    const int s0 = s_first[2 * j], e0 = s_next[s0];
     const bool two = 2 * j + 1 < n_chunks;
+    const int e1 = two ? s_next[e0] : e0;
     int32_t *r = a.ws.pair_rec + (int64_t)(s_pbase + j) * kPairRecInts;
     r[kPrB] = b;
     r[kPrNch] = s_fused ? (two ? 2 : 1) : 0;
     r[kPrC0] = base + 2 * j;
     r[kPrTok0] = tok0;
     r[kPrNTok] = n_tok;
-    r[kPrTBegin] = c0.t_begin;
-    r[kPrLen0] = c0.len;
-    r[kPrNs0] = c0.ns;
-    r[kPrSoffIdx] = c0.soff_idx;
-    r[kPrLen1] = two ? a.ws.chunks[base + 2 * j + 1].len : 0;
-    r[kPrNs1] = two ? a.ws.chunks[base + 2 * j + 1].ns : 0;
+    r[kPrTBegin] = s_off[s0];
+    r[kPrLen0] = s_off[e0] - s_off[s0];
+    r[kPrNs0] = e0 - s0;
+    r[kPrSoffIdx] = sp + s0;
+    r[kPrLen1] = s_off[e1] - s_off[e0];
+    r[kPrNs1] = e1 - e0;
     r[kPrNPairs] = n_pairs;
     r[kPrCFirst] = base;
   }
