@@ -196,6 +196,55 @@ int skipkv_select_tokens(const skipkv_cache *cache, const skipkv_params *params,
                          int32_t *new_sent_cnt, int32_t kept_stride, void *stream);
 
 /*
+ * Per-head sentence ranges across steps (Sec. 4.1 "Sentence-level eviction": the ranges M^(cs) and
+ * cache lengths l_t^(cs) of Eq. 9-11 and Alg. 1).  After a step every (layer, KV head, sequence)
+ * has evicted sentences of its own, so lengths and ranges are per head from then on:
+ *   len       device [n_layers, n_kv_heads, batch]   cache length N of every head's sequence
+ *   sent_cnt  device [n_layers, n_kv_heads, batch]   its number of sentences S
+ *   sent_off  device [n_layers, n_kv_heads, total_sentences + batch]   its S+1 offsets, stored where
+ *             the shared layout would keep those of sequence b (at sent_ptr[b] of the head's row)
+ * These are exactly the new_len / new_sent_cnt / new_sent_off outputs of the previous step (Eq. 11
+ * is applied there).  The cache's seq_off, sent_ptr, total_tokens and total_sentences keep their
+ * meaning as ROOM: sequence b of every head lives in rows seq_off[b] .. seq_off[b+1] and may hold at
+ * most sent_ptr[b+1]-sent_ptr[b]-1 sentences; cache->sent_off is not read.
+ */
+typedef struct skipkv_ranges {
+  int32_t *len;
+  int32_t *sent_cnt;
+  int32_t *sent_off;
+} skipkv_ranges;
+
+/*
+ * Eq. 10: n_new[b] tokens have been appended to sequence b of every head (the caller has written
+ * their K and V rows at rows seq_off[b] + len .. of each head).  bnd_off[bnd_ptr[b] .. bnd_ptr[b+1])
+ * lists, strictly ascending, the positions 0 <= p < n_new[b] inside the appended run at which a new
+ * sentence starts (the token after a delimiter); tokens before the first such position continue
+ * the head's last sentence.  Positions are cache positions: the shift by the number of evicted
+ * tokens that the paper writes out is contained in len.  Updates ranges in place.  A head whose
+ * room (tokens or sentences) would overflow, or bad boundaries, are reported in *dev_status
+ * (SKIPKV_DEV_TOO_MANY_SENT / SKIPKV_DEV_BAD_OFFSETS) and that head is left unchanged.
+ * n_new, bnd_ptr [batch+1], bnd_off: device.  dev_status: device, nullable.
+ */
+int skipkv_ranges_append(const skipkv_cache *cache, const skipkv_ranges *ranges, const int32_t *n_new,
+                         const int32_t *bnd_ptr, const int32_t *bnd_off, int32_t *dev_status, void *stream);
+
+/* Workspace of skipkv_step_ranges for this problem (larger than skipkv_workspace_bytes).       */
+int skipkv_ranges_workspace_bytes(const skipkv_cache *cache, const skipkv_params *params, size_t *out_bytes);
+
+/*
+ * skipkv_step for caches with per-head ranges: same computation, outputs and layouts, with every
+ * head's own length and sentence ranges as input.  Needs K and V contiguous over (layer, head,
+ * token): stride_head = total_tokens * stride_tok, stride_layer = n_kv_heads * stride_head, else
+ * SKIPKV_ECAPACITY.  params->budget, if not NULL, has one entry per (layer, KV head, sequence).
+ * The outputs new_len / new_sent_off / new_sent_cnt must not alias the input ranges.
+ */
+int skipkv_step_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_params *params,
+                       const void *q_obs, const float *tok_redundancy, float *sent_score, float *sent_lambda,
+                       float *tok_importance, uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len,
+                       int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride, void *ws, size_t ws_bytes,
+                       void *stream);
+
+/*
  * Token redundancy (Sec. 4.1 "Token Redundancy Score", Eq. 5).  Per head, with Kbar the rows of
  * K scaled to unit length (1e-12 added to the norm):
  *   R[t] = mean over rows i of softmax_j(Kbar Kbar^T)[i, t]

@@ -14,6 +14,7 @@ from .skipkv_oracle import (  # noqa: F401
     sentence_scores,
     select_sentences,
     remap_ranges,
+    append_ranges,
     compact,
     compress_head,
     steer_add,

@@ -31,7 +31,11 @@ notes of the repository):
   * the token-level form of the same step (Eq.6 as printed: every token of a redundant sentence
     carries the sentence's penalty): the protected recent window is always kept, the other
     tokens are ranked by (score desc, index desc) and exactly budget - window of them survive;
-    sentence ranges follow Eq.11.
+    sentence ranges follow Eq.11;
+  * across steps (Eq.9-10) ranges are kept in CACHE positions per head: the shift by the number
+    of evicted tokens that Eq.10 writes out is contained in the head's cache length; a token
+    that follows a delimiter starts a new sentence, any other appended token continues the
+    head's last sentence.
 
 Parity pins: every function below is pinned by tests/test_oracle_*.py against library
 routines, closed forms, brute force or invariants.  The whole-step result has no
@@ -54,6 +58,7 @@ __all__ = [
     "token_scores",
     "select_tokens",
     "remap_ranges",
+    "append_ranges",
     "compact",
     "compress_head",
     "steer_add",
@@ -291,6 +296,21 @@ def remap_ranges(off, kept_idx):
             continue
         out.append((min(ks_b), max(ks_e)))
     return out
+
+
+def append_ranges(off, n_new, starts):
+    """Eq.10 in cache positions: n_new tokens are appended to a cache of N = off[-1] tokens;
+    `starts` are the positions 0 <= p < n_new inside the appended run at which a new sentence
+    starts.  A sentence is the run of tokens from one start to the next: the starts of the new
+    cache are the old ones, the new ones shifted by N, and N itself if the cache was empty.
+    Returns the new offsets (starts, then the new length)."""
+    off = [int(x) for x in off]
+    n_old = off[-1]
+    begin = set(off[:-1])
+    begin |= {n_old + int(p) for p in starts}
+    if len(off) == 1:
+        begin.add(0)
+    return np.array(sorted(begin) + [n_old + int(n_new)], dtype=np.int64)
 
 
 def compact(k, v, kept_idx):

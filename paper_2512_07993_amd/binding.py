@@ -34,6 +34,10 @@ class CCache(C.Structure):
     ]
 
 
+class CRanges(C.Structure):
+    _fields_ = [("len", C.c_void_p), ("sent_cnt", C.c_void_p), ("sent_off", C.c_void_p)]
+
+
 class CParams(C.Structure):
     _fields_ = [
         ("obs_window", C.c_int32), ("protect_window", C.c_int32),
@@ -63,6 +67,10 @@ def lib() -> C.CDLL:
         L.skipkv_redundancy_workspace_bytes.argtypes = [cp, C.POINTER(sz)]
         L.skipkv_token_redundancy.argtypes = [cp, vp, vp, sz, vp]
         L.skipkv_steer_add.argtypes = [vp, vp, vp, fl, vp, i32, i32, i32, vp]
+        rp = C.POINTER(CRanges)
+        L.skipkv_ranges_workspace_bytes.argtypes = [cp, pp, C.POINTER(sz)]
+        L.skipkv_ranges_append.argtypes = [cp, rp, vp, vp, vp, vp, vp]
+        L.skipkv_step_ranges.argtypes = [cp, rp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
         L.skipkv_profile_create.argtypes = [C.POINTER(vp)]
         L.skipkv_profile_read.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_char_p), C.POINTER(fl)]
         L.skipkv_profile_destroy.argtypes = [vp]
@@ -71,7 +79,7 @@ def lib() -> C.CDLL:
         L.skipkv_version.argtypes = []
         for name in ("skipkv_workspace_bytes", "skipkv_score", "skipkv_select", "skipkv_compact", "skipkv_step",
                      "skipkv_steer_add", "skipkv_redundancy_workspace_bytes", "skipkv_token_redundancy",
-                     "skipkv_select_tokens",
+                     "skipkv_select_tokens", "skipkv_ranges_workspace_bytes", "skipkv_ranges_append", "skipkv_step_ranges",
                      "skipkv_profile_create", "skipkv_profile_read", "skipkv_profile_destroy",
                      "skipkv_version"):
             getattr(L, name).restype = C.c_int
@@ -205,6 +213,39 @@ def skipkv_step(cache: Cache, params: Params, q_obs, tok_redundancy, sent_score,
                              _ptr(sent_score), _ptr(sent_lambda), _ptr(tok_importance), _ptr(sent_keep),
                              _ptr(kept_idx), _ptr(new_len), _ptr(new_sent_off), _ptr(new_sent_cnt), kept_stride,
                              _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
+
+
+@dataclass
+class Ranges:
+    """Python mirror of skipkv_ranges: per-head lengths [L, Hk, B], sentence counts [L, Hk, B] and
+    offsets [L, Hk, S_total + B] (int32 device tensors)."""
+    len: torch.Tensor
+    sent_cnt: torch.Tensor
+    sent_off: torch.Tensor
+
+    def c(self) -> CRanges:
+        return CRanges(self.len.data_ptr(), self.sent_cnt.data_ptr(), self.sent_off.data_ptr())
+
+
+def skipkv_ranges_workspace_bytes(cache: Cache, params: Params) -> int:
+    out = C.c_size_t(0)
+    _check(lib().skipkv_ranges_workspace_bytes(C.byref(cache.c()), C.byref(params.c()), C.byref(out)))
+    return int(out.value)
+
+
+def skipkv_ranges_append(cache: Cache, ranges: Ranges, n_new, bnd_ptr, bnd_off, dev_status=None, stream=None) -> None:
+    _check(lib().skipkv_ranges_append(C.byref(cache.c()), C.byref(ranges.c()), _ptr(n_new), _ptr(bnd_ptr),
+                                      _ptr(bnd_off), _ptr(dev_status), _stream(stream)))
+
+
+def skipkv_step_ranges(cache: Cache, ranges: Ranges, params: Params, q_obs, tok_redundancy, sent_score, sent_lambda,
+                       tok_importance, sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride: int, ws,
+                       stream=None) -> None:
+    _check(lib().skipkv_step_ranges(C.byref(cache.c()), C.byref(ranges.c()), C.byref(params.c()), _ptr(q_obs),
+                                    _ptr(tok_redundancy), _ptr(sent_score), _ptr(sent_lambda), _ptr(tok_importance),
+                                    _ptr(sent_keep), _ptr(kept_idx), _ptr(new_len), _ptr(new_sent_off),
+                                    _ptr(new_sent_cnt), kept_stride, _ptr(ws),
+                                    ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
 
 
 def skipkv_redundancy_workspace_bytes(cache: Cache) -> int:

@@ -89,6 +89,13 @@ Workspace carve(const skipkv_cache *c, const RowLayout &rl, void *base) {
   return w;
 }
 
+// What a call with per-head ranges adds to the (virtual) cache description: explicit lengths and
+// sentence counts per virtual sequence, and how to find the query rows of the real head.
+struct HeadView {
+  const int32_t *len = nullptr, *cnt = nullptr;
+  int32_t virt_hk = 0, virt_b = 0;
+};
+
 struct Timer {
   Profile *p;
   hipStream_t st;
@@ -110,9 +117,10 @@ struct Timer {
 };
 
 int do_score(Timer &tm, const skipkv_cache *c, const skipkv_params *p, const RowLayout &rl, const void *q_obs,
-             const float *tok_red, float *sent_score, float *sent_lambda, float *tok_imp, void *ws, hipStream_t st) {
+             const float *tok_red, float *sent_score, float *sent_lambda, float *tok_imp, void *ws, hipStream_t st,
+             const HeadView &hv = HeadView()) {
   const Workspace w = carve(c, rl, ws);
-  PlanArgs pa{c->seq_off, c->sent_ptr, c->sent_off, c->batch, c->n_layers * c->n_kv_heads, w, p->dev_status};
+  PlanArgs pa{c->seq_off, c->sent_ptr, c->sent_off, c->batch, c->n_layers * c->n_kv_heads, w, p->dev_status, hv.len, hv.cnt};
   if (tm.run("plan", [&] { return launch_plan(pa, st); }) != hipSuccess) return SKIPKV_EHIP;
   ScanArgs sa{};
   sa.k = c->k;
@@ -143,6 +151,8 @@ int do_score(Timer &tm, const skipkv_cache *c, const skipkv_params *p, const Row
   sa.force_two_pass = (env_two && env_two[0] == '1') || !scan_fused_supported(rl);
   sa.spin_limit = env_spin ? std::atoi(env_spin) : 4000000;
   sa.dev_status = p->dev_status;
+  sa.virt_hk = hv.virt_hk;
+  sa.virt_b = hv.virt_b;
   if (tm.run("scan_fused", [&] { return launch_scan_fused(sa, st); }) != hipSuccess) return SKIPKV_EHIP;
   if (tm.run("scan_stats", [&] { return launch_scan_stats(sa, st); }) != hipSuccess) return SKIPKV_EHIP;
   if (tm.run("row_norm", [&] { return launch_row_norm(sa, st); }) != hipSuccess) return SKIPKV_EHIP;
@@ -161,13 +171,15 @@ int do_score(Timer &tm, const skipkv_cache *c, const skipkv_params *p, const Row
   ca.ws = w;
   ca.sent_score = sent_score;
   ca.sent_lambda = sent_lambda;
+  ca.len = hv.len;
+  ca.cnt = hv.cnt;
   if (tm.run("redundancy", [&] { return launch_cosine(ca, st); }) != hipSuccess) return SKIPKV_EHIP;
   return SKIPKV_OK;
 }
 
 int do_select(Timer &tm, const skipkv_cache *c, const skipkv_params *p, const float *sent_score, uint8_t *sent_keep,
               int32_t *kept_idx, int32_t *new_len, int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride,
-              hipStream_t st) {
+              hipStream_t st, const HeadView &hv = HeadView()) {
   SelectArgs a{};
   a.n_lh = c->n_layers * c->n_kv_heads;
   a.batch = c->batch;
@@ -186,6 +198,8 @@ int do_select(Timer &tm, const skipkv_cache *c, const skipkv_params *p, const fl
   a.new_sent_off = new_sent_off;
   a.new_sent_cnt = new_sent_cnt;
   a.dev_status = p->dev_status;
+  a.len = hv.len;
+  a.cnt = hv.cnt;
   if (tm.run("select", [&] { return launch_select(a, st); }) != hipSuccess) return SKIPKV_EHIP;
   return SKIPKV_OK;
 }
@@ -211,6 +225,50 @@ int do_compact(Timer &tm, const skipkv_cache *c, const int32_t *kept_idx, const 
 }
 
 bool is_empty(const skipkv_cache *c) { return c->n_layers == 0 || c->n_kv_heads == 0 || c->batch == 0; }
+
+// Per-head ranges.  Every (layer, KV head, sequence) triple becomes a sequence of its own of a
+// cache with ONE layer and ONE KV head: v = (l * H_k + h) * B + b, whose tokens start at packed
+// row (l * H_k + h) * T + seq_off[b] of the (contiguous) K and V and whose offsets start at
+// (l * H_k + h) * (S + B) + sent_ptr[b] of the per-head offset array.  With this numbering the
+// per-sentence, per-token and per-sequence outputs keep exactly their real layout, so the same
+// kernels serve; only lengths and counts become explicit and the query rows keep the real (l, b, h).
+struct VirtualView {
+  skipkv_cache c;
+  HeadView hv;
+  int32_t *seq_off, *sent_ptr;  // [LH * B + 1] each, at the head of the workspace
+  size_t head_bytes;            // bytes taken from the workspace for them
+};
+
+int make_virtual(const skipkv_cache *c, const skipkv_ranges *r, void *ws, VirtualView *out) {
+  if (!r || !r->len || !r->sent_cnt || !r->sent_off) return SKIPKV_EINVAL;
+  const int64_t LH = (int64_t)c->n_layers * c->n_kv_heads, B = c->batch;
+  const int64_t T = c->total_tokens, S = c->total_sentences;
+  if (LH * B >= (1ll << 31) - 1 || LH * T >= (1ll << 31) - 1 || LH * (S + B) >= (1ll << 31) - 1) return SKIPKV_ECAPACITY;
+  // K and V must be one flat array of rows over (layer, head, token)
+  if (T > 0 && (c->stride_head != T * c->stride_tok || c->stride_layer != c->n_kv_heads * c->stride_head)) return SKIPKV_ECAPACITY;
+  VirtualView v{};
+  v.c = *c;
+  v.c.n_layers = 1;
+  v.c.n_kv_heads = 1;
+  v.c.n_q_heads = c->n_q_heads / c->n_kv_heads;
+  v.c.batch = (int32_t)(LH * B);
+  v.c.total_tokens = (int32_t)(LH * T);
+  v.c.total_sentences = (int32_t)(LH * S);
+  v.c.stride_layer = 0;
+  v.c.stride_head = 0;
+  v.head_bytes = 2 * align_up((size_t)(LH * B + 1) * 4);
+  v.seq_off = static_cast<int32_t *>(ws);
+  v.sent_ptr = ws ? reinterpret_cast<int32_t *>(static_cast<char *>(ws) + v.head_bytes / 2) : nullptr;
+  v.c.seq_off = v.seq_off;
+  v.c.sent_ptr = v.sent_ptr;
+  v.c.sent_off = r->sent_off;
+  v.hv.len = r->len;
+  v.hv.cnt = r->sent_cnt;
+  v.hv.virt_hk = c->n_kv_heads;
+  v.hv.virt_b = c->batch;
+  *out = v;
+  return SKIPKV_OK;
+}
 
 int check_score_args(const skipkv_cache *c, const skipkv_params *p, RowLayout *rl, const void *q_obs, float *sent_score,
                      float *sent_lambda, void *ws, size_t ws_bytes) {
@@ -346,6 +404,82 @@ int skipkv_step(const skipkv_cache *cache, const skipkv_params *params, const vo
   rc = do_select(tm, cache, params, sent_score, sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride, st);
   if (rc) return rc;
   return do_compact(tm, cache, kept_idx, new_len, kept_stride, st);
+}
+
+int skipkv_ranges_workspace_bytes(const skipkv_cache *cache, const skipkv_params *params, size_t *out_bytes) {
+  if (!out_bytes) return SKIPKV_EINVAL;
+  int rc = check_cache(cache, true);
+  if (rc) return rc;
+  RowLayout rl;
+  rc = check_params(cache, params, &rl);
+  if (rc) return rc;
+  if (is_empty(cache)) {
+    *out_bytes = 0;
+    return SKIPKV_OK;
+  }
+  skipkv_ranges dummy{reinterpret_cast<int32_t *>(16), reinterpret_cast<int32_t *>(16), reinterpret_cast<int32_t *>(16)};
+  VirtualView v;
+  rc = make_virtual(cache, &dummy, nullptr, &v);
+  if (rc) return rc;
+  *out_bytes = v.head_bytes + carve(&v.c, rl, nullptr).bytes;
+  return SKIPKV_OK;
+}
+
+int skipkv_step_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_params *params,
+                       const void *q_obs, const float *tok_redundancy, float *sent_score, float *sent_lambda,
+                       float *tok_importance, uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len,
+                       int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride, void *ws, size_t ws_bytes,
+                       void *stream) {
+  RowLayout rl;
+  int rc = check_cache(cache, true);
+  if (rc) return rc;
+  rc = check_params(cache, params, &rl);
+  if (rc) return rc;
+  rc = check_select_args(cache, params, &rl, sent_score, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride);
+  if (rc) return rc;
+  if (is_empty(cache)) return SKIPKV_OK;
+  if (!q_obs || !aligned16(q_obs)) return SKIPKV_EINVAL;
+  if (cache->total_sentences > 0 && (!sent_score || !sent_lambda)) return SKIPKV_EINVAL;
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SKIPKV_EWORKSPACE;
+  VirtualView v;
+  rc = make_virtual(cache, ranges, ws, &v);
+  if (rc) return rc;
+  const Workspace w = carve(&v.c, rl, nullptr);
+  if (ws_bytes < v.head_bytes + w.bytes) return SKIPKV_EWORKSPACE;
+  if (ranges->sent_off == new_sent_off || ranges->len == new_len || ranges->sent_cnt == new_sent_cnt) return SKIPKV_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (launch_virtual_layout(cache->seq_off, cache->sent_ptr, cache->batch, cache->n_layers * cache->n_kv_heads,
+                            cache->total_tokens, cache->total_sentences, v.seq_off, v.sent_ptr, st) != hipSuccess)
+    return SKIPKV_EHIP;
+  void *ws2 = static_cast<char *>(ws) + v.head_bytes;
+  Timer tm(params->profile, st);
+  rc = do_score(tm, &v.c, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, ws2, st, v.hv);
+  if (rc) return rc;
+  rc = do_select(tm, &v.c, params, sent_score, sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride, st, v.hv);
+  if (rc) return rc;
+  return do_compact(tm, &v.c, kept_idx, new_len, kept_stride, st);
+}
+
+int skipkv_ranges_append(const skipkv_cache *cache, const skipkv_ranges *ranges, const int32_t *n_new,
+                         const int32_t *bnd_ptr, const int32_t *bnd_off, int32_t *dev_status, void *stream) {
+  const int rc = check_cache(cache, true);
+  if (rc) return rc;
+  if (is_empty(cache)) return SKIPKV_OK;
+  if (!ranges || !ranges->len || !ranges->sent_cnt || !ranges->sent_off || !n_new || !bnd_ptr) return SKIPKV_EINVAL;
+  RangesAppendArgs a{};
+  a.n_lh = cache->n_layers * cache->n_kv_heads;
+  a.batch = cache->batch;
+  a.total_sentences = cache->total_sentences;
+  a.seq_off = cache->seq_off;
+  a.sent_ptr = cache->sent_ptr;
+  a.len = ranges->len;
+  a.cnt = ranges->sent_cnt;
+  a.off = ranges->sent_off;
+  a.n_new = n_new;
+  a.bnd_ptr = bnd_ptr;
+  a.bnd_off = bnd_off;
+  a.dev_status = dev_status;
+  return launch_ranges_append(a, static_cast<hipStream_t>(stream)) == hipSuccess ? SKIPKV_OK : SKIPKV_EHIP;
 }
 
 int skipkv_redundancy_workspace_bytes(const skipkv_cache *cache, size_t *out_bytes) {

@@ -110,11 +110,34 @@ inline bool make_row_layout(int n, int alpha, RowLayout *out) {
 struct Profile;  // api.hip
 
 // ---- kernel launchers (one per .hip file) -------------------------------------------------
+// Eq. 10 on per-head ranges: n_new[b] tokens are appended to sequence b of every head; bnd_off
+// (CSR over sequences, bnd_ptr) lists the positions inside the appended run at which a new
+// sentence starts.
+struct RangesAppendArgs {
+  int32_t n_lh, batch, total_sentences;
+  const int32_t *seq_off, *sent_ptr;  // capacities
+  int32_t *len, *cnt, *off;           // [n_lh, batch], [n_lh, batch], [n_lh, total_sentences + batch], updated in place
+  const int32_t *n_new, *bnd_ptr, *bnd_off;
+  int32_t *dev_status;
+};
+hipError_t launch_ranges_append(const RangesAppendArgs &a, hipStream_t st);
+hipError_t launch_virtual_layout(const int32_t *seq_off, const int32_t *sent_ptr, int32_t batch, int32_t n_lh, int32_t total_tokens,
+                                 int32_t total_sentences, int32_t *v_seq_off, int32_t *v_sent_ptr, hipStream_t st);
+
+// Length and sentence count of sequence b: explicit where given, else from the CSR arrays.
+__device__ __forceinline__ int seq_tokens(const int32_t *seq_off, const int32_t *len, int b) {
+  return len ? len[b] : seq_off[b + 1] - seq_off[b];
+}
+__device__ __forceinline__ int seq_sentences(const int32_t *sent_ptr, const int32_t *cnt, int b) {
+  return cnt ? cnt[b] : sent_ptr[b + 1] - sent_ptr[b] - 1;
+}
+
 struct PlanArgs {
   const int32_t *seq_off, *sent_ptr, *sent_off;
   int32_t batch, n_lh;
   Workspace ws;
   int32_t *dev_status;
+  const int32_t *len, *cnt;  // nullable [batch]: explicit lengths and sentence counts (then seq_off / sent_ptr only give capacities)
 };
 hipError_t launch_plan(const PlanArgs &a, hipStream_t st);
 
@@ -132,6 +155,10 @@ struct ScanArgs {
   int32_t force_two_pass;  // debugging aid: send every sequence through the two-pass scan
   int32_t spin_limit;      // bound on the polls of a cross-workgroup wait in the single-pass scan
   int32_t *dev_status;
+  // Per-head ranges: every (layer, KV head, sequence) triple is presented to the kernels as a
+  // sequence of its own of ONE layer with ONE KV head (v = (l * H_k + h) * B + b); only the query
+  // rows are still laid out by the real (l, b, h).  virt_hk = real H_k (0: off), virt_b = real B.
+  int32_t virt_hk, virt_b;
 };
 bool scan_fused_supported(const RowLayout &rl);
 hipError_t launch_scan_fused(const ScanArgs &a, hipStream_t st);    // single pass over K (sequences the plan marked fused)
@@ -146,6 +173,7 @@ struct CosineArgs {
   const int32_t *seq_off, *sent_ptr, *sent_off;
   Workspace ws;
   float *sent_score, *sent_lambda;
+  const int32_t *len, *cnt;  // nullable, see PlanArgs
 };
 hipError_t launch_cosine(const CosineArgs &a, hipStream_t st);
 
@@ -157,6 +185,7 @@ struct SelectArgs {
   uint8_t *sent_keep;
   int32_t *kept_idx, *new_len, *new_sent_off, *new_sent_cnt;
   int32_t *dev_status;
+  const int32_t *len, *cnt;  // nullable, see PlanArgs
 };
 hipError_t launch_select(const SelectArgs &a, hipStream_t st);
 

@@ -33,7 +33,7 @@ __global__ void __launch_bounds__(256, 3) k_cosine(CosineArgs a) {
   const RowBlock blk = a.ws.rowblocks[rb];
   const int b = blk.b, r0 = blk.r0;
   const int sp = a.sent_ptr[b];
-  const int n_sent = a.sent_ptr[b + 1] - sp - 1;
+  const int n_sent = seq_sentences(a.sent_ptr, a.cnt, b);
   const int64_t col0 = (int64_t)lh * a.total_sentences + (sp - b);
   const char *hi = reinterpret_cast<const char *>(a.ws.vhat_hi) + col0 * 256;
   const char *lo = reinterpret_cast<const char *>(a.ws.vhat_lo) + col0 * 256;
@@ -59,8 +59,7 @@ __global__ void __launch_bounds__(256, 3) k_cosine(CosineArgs a) {
   // latency is hidden behind the products
   static_assert(4 * kRowTiles <= 16, "one epilogue row per lane of a 16-lane group");
   const int my_row = rw0 + 16 * (c16 >> 2) + 4 * g + (c16 & 3);
-  const int tok0 = a.seq_off[b];
-  const int n_tok = a.seq_off[b + 1] - tok0;
+  const int n_tok = seq_tokens(a.seq_off, a.len, b);
   const int p_start = n_tok - min(a.protect, n_tok);
   float my_imp = 0.f, my_red = 0.f;
   int my_off = 0;

@@ -37,9 +37,9 @@ __global__ void __launch_bounds__(256) k_plan(PlanArgs a) {
   const int b = blockIdx.x;
   const int tid = threadIdx.x;
   const int tok0 = a.seq_off[b];
-  const int n_tok = a.seq_off[b + 1] - tok0;
+  const int n_tok = seq_tokens(a.seq_off, a.len, b);
   const int sp = a.sent_ptr[b];
-  const int n_sent = a.sent_ptr[b + 1] - sp - 1;
+  const int n_sent = seq_sentences(a.sent_ptr, a.cnt, b);
   const int32_t *off = a.sent_off + sp;
 
   __shared__ int s_off[SKIPKV_MAX_SENTENCES + 1];
@@ -48,7 +48,11 @@ __global__ void __launch_bounds__(256) k_plan(PlanArgs a) {
   __syncthreads();
 
   bool reject = n_sent > SKIPKV_MAX_SENTENCES || n_sent < 0;
-  if (!reject) {
+  // explicit lengths and counts must fit the room that the CSR arrays describe
+  const bool overflow = !reject && (n_tok < 0 || n_tok > a.seq_off[b + 1] - tok0 || n_sent > a.sent_ptr[b + 1] - sp - 1);
+  if (overflow) {
+    if (tid == 0) s_bad = 1;
+  } else if (!reject) {
     // validation: o[0] = 0, o[S] = N, strictly ascending
     int bad = 0;
     for (int s = tid; s <= n_sent; s += 256) {

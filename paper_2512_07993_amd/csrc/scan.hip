@@ -66,13 +66,23 @@ __global__ void __launch_bounds__(256) k_scan(ScanArgs a) {
   // ---- queries of the group -> LDS, one padded row per (lane group, slot)
   {
     const char *qbase = static_cast<const char *>(a.q);
+    // layer, KV head and sequence that address the query rows (the real ones under per-head ranges)
+    int ql = l, qh = h, qb = b, q_batch = a.batch, q_heads = a.n_q_heads;
+    if (a.virt_hk > 0) {
+      const int lh_r = b / a.virt_b;
+      qb = b % a.virt_b;
+      ql = lh_r / a.virt_hk;
+      qh = lh_r % a.virt_hk;
+      q_batch = a.virt_b;
+      q_heads = a.virt_hk * n;
+    }
     for (int r0 = 0; r0 < R; r0 += 256 / PPR) {
       const int r = r0 + tid / PPR, piece = tid % PPR;
       const int slot = 4 * (r >> 4) + (r & 3), gq = (r >> 2) & 3;
       const int al = slot / NP, i = slot % NP, aq = gq + 4 * al;
       uint4 val = make_uint4(0, 0, 0, 0);
       if (slot < SL && i < n && aq < a.alpha) {
-        const int64_t row = (((int64_t)l * a.batch + b) * a.n_q_heads + (h * n + i)) * a.alpha + aq;
+        const int64_t row = (((int64_t)ql * q_batch + qb) * q_heads + (qh * n + i)) * a.alpha + aq;
         val = *reinterpret_cast<const uint4 *>(qbase + row * ROWB + piece * 16);
       }
       *reinterpret_cast<uint4 *>(qt + r * LSTR + piece * 16) = val;

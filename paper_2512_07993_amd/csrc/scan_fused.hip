@@ -147,7 +147,16 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     if (t <= it.ch[0].ns) f.so = a.sent_off[it.ch[0].soff_idx + t];
     if (it.nch == 2 && t >= 64 && t - 64 <= it.ch[1].ns) f.so = a.sent_off[it.ch[1].soff_idx + t - 64];
     const char *qbase = static_cast<const char *>(a.q);
-    const int l = it.lh / a.n_kv_heads, h = it.lh % a.n_kv_heads;
+    // layer, KV head and sequence that address the query rows (the real ones under per-head ranges)
+    int l = it.lh / a.n_kv_heads, h = it.lh % a.n_kv_heads, qb = it.b, q_batch = a.batch, q_heads = a.n_q_heads;
+    if (a.virt_hk > 0) {
+      const int lh_r = it.b / a.virt_b;
+      qb = it.b % a.virt_b;
+      l = lh_r / a.virt_hk;
+      h = lh_r % a.virt_hk;
+      q_batch = a.virt_b;
+      q_heads = a.virt_hk * n;
+    }
 #pragma unroll
     for (int u = 0; u < NQ; ++u) {
       const int r = u * (256 / PPR) + t / PPR, piece = t % PPR;
@@ -155,7 +164,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
       const int al = slot / NP, i = slot % NP, aq = gq + 4 * al;
       f.q[u] = make_uint4(0, 0, 0, 0);
       if (slot < SL && i < n && aq < a.alpha) {
-        const int64_t row = (((int64_t)l * a.batch + it.b) * a.n_q_heads + (h * n + i)) * a.alpha + aq;
+        const int64_t row = (((int64_t)l * q_batch + qb) * q_heads + (h * n + i)) * a.alpha + aq;
         f.q[u] = *reinterpret_cast<const uint4 *>(qbase + row * ROWB + piece * 16);
       }
     }

@@ -99,9 +99,10 @@ __device__ __forceinline__ void select_head(const SelectArgs &a, int lhb, int gt
   constexpr int G = 64 * NW;
   const int lane = gt & 63;
   const int lh = lhb / a.batch, b = lhb % a.batch;
-  const int n_tok = a.seq_off[b + 1] - a.seq_off[b];
+  // explicit lengths and counts are clamped to the room the CSR arrays describe (the plan reports them)
+  const int n_tok = min(seq_tokens(a.seq_off, a.len, b), a.seq_off[b + 1] - a.seq_off[b]);
   const int sp = a.sent_ptr[b];
-  const int n_sent = a.sent_ptr[b + 1] - sp - 1;
+  const int n_sent = min(seq_sentences(a.sent_ptr, a.cnt, b), a.sent_ptr[b + 1] - sp - 1);
   const int32_t *off = a.sent_off + sp;
   const int64_t col0 = (int64_t)lh * a.total_sentences + (sp - b);
   int32_t *kept = a.kept_idx + (int64_t)lhb * a.kept_stride;
@@ -238,10 +239,10 @@ __device__ __forceinline__ void select_head(const SelectArgs &a, int lhb, int gt
 
 __device__ __forceinline__ int head_sentences(const SelectArgs &a, int lhb) {
   const int b = lhb % a.batch;
-  return a.sent_ptr[b + 1] - a.sent_ptr[b] - 1;
+  return min(seq_sentences(a.sent_ptr, a.cnt, b), a.sent_ptr[b + 1] - a.sent_ptr[b] - 1);
 }
 
-__global__ void __launch_bounds__(256) k_select(SelectArgs a) {
+__global__ void __launch_bounds__(256, 4) k_select(SelectArgs a) {
   __shared__ __align__(16) uint8_t keep_l[4 * kWaveSent];
   __shared__ int slots[8];
   const int tid = threadIdx.x, lane = tid & 63;
