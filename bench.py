@@ -153,6 +153,67 @@ def time_redundancy(config: int, reps: int = 3) -> int:
     return 0
 
 
+def time_ranges(config_id: int, steps: int = 5) -> int:
+    """Times skipkv_step_ranges (per-head sentence ranges, Eq. 9-11) on the workload, with ranges that
+    describe the same cache as the shared structure, next to skipkv_step on the same data."""
+    import torch
+
+    from paper_2512_07993_amd import binding as B
+    from paper_2512_07993_amd import workloads as W
+
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    cfg = W.CONFIGS[config_id]
+    st = W.make_structure(cfg)
+    k0, v0, q = W.fill_cache(cfg, st, device=dev)
+    L, H, Bn, S, T = cfg.n_layers, cfg.n_kv_heads, cfg.batch, st.total_sentences, st.total_tokens
+    so, sp, sf = (torch.from_numpy(x).to(dev) for x in (st.seq_off, st.sent_ptr, st.sent_off))
+    k, v = torch.empty_like(k0), torch.empty_like(v0)
+    cache = B.Cache(k, v, cfg.n_q_heads, so, sp, sf, T, S)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    prof = B.skipkv_profile_create()
+    params = B.Params(cfg.obs_window, cfg.protect_window, cfg.budget, dev_status=status, profile=prof)
+    ws = torch.empty(B.skipkv_ranges_workspace_bytes(cache, params), dtype=torch.uint8, device=dev)
+    ranges = B.Ranges(torch.from_numpy(st.seq_len.astype("int32")).to(dev).expand(L, H, Bn).contiguous(),
+                      torch.from_numpy(st.n_sent.astype("int32")).to(dev).expand(L, H, Bn).contiguous(),
+                      sf.expand(L, H, sf.numel()).contiguous())
+    kept_stride = min(cfg.budget, T)
+    sent_score = torch.empty((L, H, S), dtype=torch.float32, device=dev)
+    sent_lambda = torch.empty_like(sent_score)
+    sent_keep = torch.empty((L, H, S), dtype=torch.uint8, device=dev)
+    kept_idx = torch.empty((L, H, Bn, kept_stride), dtype=torch.int32, device=dev)
+    new_len = torch.empty((L, H, Bn), dtype=torch.int32, device=dev)
+    new_off = torch.empty((L, H, S + Bn), dtype=torch.int32, device=dev)
+    new_cnt = torch.empty((L, H, Bn), dtype=torch.int32, device=dev)
+    out = {}
+    for name in ("step_ranges", "step"):
+        times = []
+        for i in range(steps + 1):
+            k.copy_(k0)
+            v.copy_(v0)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            if name == "step_ranges":
+                B.skipkv_step_ranges(cache, ranges, params, q, None, sent_score, sent_lambda, None, sent_keep, kept_idx,
+                                     new_len, new_off, new_cnt, kept_stride, ws)
+            else:
+                B.skipkv_step(cache, params, q, None, sent_score, sent_lambda, None, sent_keep, kept_idx, new_len,
+                              new_off, new_cnt, kept_stride, ws)
+            e1.record()
+            torch.cuda.synchronize()
+            if i:
+                times.append(e0.elapsed_time(e1))
+        out[name] = sum(times) / len(times)
+        out[name + "_kernels"] = {n: round(t, 4) for n, t in B.skipkv_profile_read(prof)}  # of the last call
+    assert int(status.item()) == 0, "device status %d" % int(status.item())
+    B.skipkv_profile_destroy(prof)
+    print(json.dumps({"op": "step_ranges", "workload": "config %d: %s" % (cfg.config_id, cfg.name),
+                      "ms_per_step_per_head_ranges": out["step_ranges"], "ms_per_step_shared_ranges": out["step"],
+                      "kernel_ms_per_head_ranges": out["step_ranges_kernels"], "kernel_ms_shared_ranges": out["step_kernels"],
+                      "steps": steps}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -163,11 +224,14 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy", action="store_true", help="run only the counter-calibration copy (see profiles/)")
     ap.add_argument("--redundancy", action="store_true", help="time only skipkv_token_redundancy on the workload's keys")
+    ap.add_argument("--ranges", action="store_true", help="time skipkv_step_ranges (per-head sentence ranges) next to skipkv_step")
     args = ap.parse_args()
     if args.calib_copy:
         return calib_copy()
     if args.redundancy:
         return time_redundancy(args.config)
+    if args.ranges:
+        return time_ranges(args.config)
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (heads are independent: more GPUs would only shard them); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
