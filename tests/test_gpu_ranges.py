@@ -81,6 +81,47 @@ def test_per_head_step_equals_shared_step_on_the_same_cache(config_id, kw):
                 assert torch.equal(ka[l, h, t0:t0 + n], kb[l, h, t0:t0 + n]) and torch.equal(va[l, h, t0:t0 + n], vb[l, h, t0:t0 + n])
 
 
+def _assert_same_step(cfg, st, a, ka, va, b, kb, vb):
+    for name in ("sent_score", "sent_lambda", "tok_imp", "sent_keep", "new_len", "new_sent_cnt"):
+        x, y = getattr(a, name), getattr(b, name)
+        assert torch.equal(x.view(torch.uint8), y.view(torch.uint8)), name
+    for l in range(cfg.n_layers):
+        for h in range(cfg.n_kv_heads):
+            for s in range(cfg.batch):
+                n = int(a.new_len[l, h, s])
+                assert torch.equal(a.kept_idx[l, h, s, :n], b.kept_idx[l, h, s, :n])
+                t0 = int(st.seq_off[s])
+                assert torch.equal(ka[l, h, t0:t0 + n], kb[l, h, t0:t0 + n]) and torch.equal(va[l, h, t0:t0 + n], vb[l, h, t0:t0 + n])
+
+
+def test_per_head_step_through_the_two_pass_scan(monkeypatch):
+    monkeypatch.setenv("SKIPKV_FORCE_TWO_PASS", "1")
+    cfg = W.CONFIGS[4].scaled(n_layers=1, batch=3, len_lo=500, len_hi=1300, budget=384)
+    st = W.make_structure(cfg)
+    k0, v0, q = W.fill_cache(cfg, st, device="cuda")
+    ka, va = k0.clone(), v0.clone()
+    a = run_step(cfg, st, ka, va, q)
+    kb, vb = k0.clone(), v0.clone()
+    b = run_step_ranges(cfg, st, kb, vb, q, shared_as_ranges(cfg, st), cfg.budget)
+    assert int(a.dev_status.item()) == 0 and int(b.dev_status.item()) == 0
+    _assert_same_step(cfg, st, a, ka, va, b, kb, vb)
+
+
+def test_per_head_step_on_degenerate_sequences():
+    # empty sequence, shorter than the window, fits the budget, a 700-token sentence (two-pass scan),
+    # 300 one-token sentences
+    from test_gpu_edges import _edge_cfg, _edge_offsets, _random_kvq, _structure
+    cfg = _edge_cfg("bf16")
+    st = _structure(_edge_offsets())
+    k0, v0, q = _random_kvq(cfg, st, 11)
+    ka, va = k0.clone(), v0.clone()
+    a = run_step(cfg, st, ka, va, q)
+    kb, vb = k0.clone(), v0.clone()
+    b = run_step_ranges(cfg, st, kb, vb, q, shared_as_ranges(cfg, st), cfg.budget)
+    assert int(a.dev_status.item()) == 0 and int(b.dev_status.item()) == 0
+    _assert_same_step(cfg, st, a, ka, va, b, kb, vb)
+
+
 def test_ranges_append_matches_oracle_and_reports_overflow():
     rng = np.random.default_rng(11)
     L, H, Bn = 2, 3, 4
