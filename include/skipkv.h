@@ -245,6 +245,33 @@ int skipkv_step_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, c
                        void *stream);
 
 /*
+ * Sentence similarity from the last layer's hidden states (Sec. 4.1 "Sentence Similarity Score",
+ * Eq. 1-3 as printed): v_s = mean of the hidden states over the tokens of sentence s,
+ * shared_lambda[s] = largest cosine between v_s and the embedding of a LATER sentence of the same
+ * sequence (-inf for the last one): one value per sentence, shared by all layers and heads.
+ * Uses cache->batch, seq_off, sent_ptr, sent_off, total_tokens, total_sentences (at most
+ * SKIPKV_MAX_SENTENCES sentences per sequence; K and V are not touched).
+ * hidden         device [total_tokens, d_model], rows packed like the cache's token axis; dtype is
+ *                SKIPKV_BF16 or SKIPKV_F32; d_model a multiple of 128; 16-byte aligned.
+ * shared_lambda  device out [total_sentences] fp32 (sentence s of sequence b at sent_ptr[b]-b+s).
+ * ws             device workspace, 256-byte aligned, >= skipkv_similarity_workspace_bytes().
+ */
+int skipkv_similarity_workspace_bytes(const skipkv_cache *cache, int32_t d_model, size_t *out_bytes);
+int skipkv_sentence_similarity(const skipkv_cache *cache, const void *hidden, int32_t d_model, int32_t dtype,
+                               float *shared_lambda, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * skipkv_score with the similarity term taken from shared_lambda (one value per sentence of a
+ * sequence, e.g. from skipkv_sentence_similarity) instead of per-head key embeddings: the key
+ * scan only computes the token importance, no per-head Gram matrices are formed.  sent_lambda
+ * (nullable) receives a per-head copy of shared_lambda.  Everything else as skipkv_score, same
+ * workspace; follow with skipkv_select and skipkv_compact.
+ */
+int skipkv_score_shared(const skipkv_cache *cache, const skipkv_params *params, const void *q_obs,
+                        const float *tok_redundancy, const float *shared_lambda, float *sent_score,
+                        float *sent_lambda, float *tok_importance, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Token redundancy (Sec. 4.1 "Token Redundancy Score", Eq. 5).  Per head, with Kbar the rows of
  * K scaled to unit length (1e-12 added to the norm):
  *   R[t] = mean over rows i of softmax_j(Kbar Kbar^T)[i, t]
@@ -272,6 +299,14 @@ int skipkv_token_redundancy(const skipkv_cache *cache, float *tok_redundancy, vo
 int skipkv_steer_add(void *hidden, const void *vec, const float *coef, float coef_scalar,
                      const uint8_t *row_mask, int32_t rows, int32_t d_model, int32_t dtype,
                      void *stream);
+
+/*
+ * Adaptive steering strength (Sec. 4.2): coef[b] = alpha0 + gamma * n_nonexec[b], with n_nonexec[b]
+ * the sample's running count of non-execution thoughts (kept by the caller, who labels the
+ * thoughts).  coef is what skipkv_steer_add takes.  n_nonexec, coef: device [rows]; computed in fp32
+ * with one rounding.
+ */
+int skipkv_steer_strength(const int32_t *n_nonexec, float alpha0, float gamma, float *coef, int32_t rows, void *stream);
 
 /*
  * Optional per-kernel timing.  A profile owns HIP events; when params->profile is set the

@@ -18,5 +18,6 @@ from .skipkv_oracle import (  # noqa: F401
     compact,
     compress_head,
     steer_add,
+    steer_strength,
     round_to_bf16,
 )

@@ -62,6 +62,7 @@ __all__ = [
     "compact",
     "compress_head",
     "steer_add",
+    "steer_strength",
     "round_to_bf16",
 ]
 
@@ -361,6 +362,11 @@ def round_to_bf16(x):
     bits32 = (best_bits | sign).astype(np.uint32)
     vals = bits32.view(np.float32).astype(np.float64)
     return vals, (bits32 >> 16).astype(np.uint16)
+
+
+def steer_strength(n_nonexec, alpha0, gamma):
+    """Sec. 4.2: alpha_t = alpha_0 + gamma * N_o per sample (float64)."""
+    return float(alpha0) + float(gamma) * np.asarray(n_nonexec, dtype=np.float64)
 
 
 def steer_add(h, vec, coef, row_mask=None, dtype="bf16"):

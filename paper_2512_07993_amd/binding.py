@@ -67,6 +67,10 @@ def lib() -> C.CDLL:
         L.skipkv_redundancy_workspace_bytes.argtypes = [cp, C.POINTER(sz)]
         L.skipkv_token_redundancy.argtypes = [cp, vp, vp, sz, vp]
         L.skipkv_steer_add.argtypes = [vp, vp, vp, fl, vp, i32, i32, i32, vp]
+        L.skipkv_similarity_workspace_bytes.argtypes = [cp, i32, C.POINTER(sz)]
+        L.skipkv_sentence_similarity.argtypes = [cp, vp, i32, i32, vp, vp, sz, vp]
+        L.skipkv_score_shared.argtypes = [cp, pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.skipkv_steer_strength.argtypes = [vp, fl, fl, vp, i32, vp]
         rp = C.POINTER(CRanges)
         L.skipkv_ranges_workspace_bytes.argtypes = [cp, pp, C.POINTER(sz)]
         L.skipkv_ranges_append.argtypes = [cp, rp, vp, vp, vp, vp, vp]
@@ -80,6 +84,7 @@ def lib() -> C.CDLL:
         for name in ("skipkv_workspace_bytes", "skipkv_score", "skipkv_select", "skipkv_compact", "skipkv_step",
                      "skipkv_steer_add", "skipkv_redundancy_workspace_bytes", "skipkv_token_redundancy",
                      "skipkv_select_tokens", "skipkv_ranges_workspace_bytes", "skipkv_ranges_append", "skipkv_step_ranges",
+                     "skipkv_similarity_workspace_bytes", "skipkv_sentence_similarity", "skipkv_score_shared", "skipkv_steer_strength",
                      "skipkv_profile_create", "skipkv_profile_read", "skipkv_profile_destroy",
                      "skipkv_version"):
             getattr(L, name).restype = C.c_int
@@ -248,6 +253,26 @@ def skipkv_step_ranges(cache: Cache, ranges: Ranges, params: Params, q_obs, tok_
                                     ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
 
 
+def skipkv_similarity_workspace_bytes(cache: Cache, d_model: int) -> int:
+    out = C.c_size_t(0)
+    _check(lib().skipkv_similarity_workspace_bytes(C.byref(cache.c()), d_model, C.byref(out)))
+    return int(out.value)
+
+
+def skipkv_sentence_similarity(cache: Cache, hidden, shared_lambda, ws, stream=None) -> None:
+    assert hidden.dim() == 2 and hidden.is_contiguous()
+    _check(lib().skipkv_sentence_similarity(C.byref(cache.c()), _ptr(hidden), hidden.shape[1], dtype_code(hidden.dtype),
+                                            _ptr(shared_lambda), _ptr(ws),
+                                            ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
+
+
+def skipkv_score_shared(cache: Cache, params: Params, q_obs, tok_redundancy, shared_lambda, sent_score, sent_lambda,
+                        tok_importance, ws, stream=None) -> None:
+    _check(lib().skipkv_score_shared(C.byref(cache.c()), C.byref(params.c()), _ptr(q_obs), _ptr(tok_redundancy),
+                                     _ptr(shared_lambda), _ptr(sent_score), _ptr(sent_lambda), _ptr(tok_importance),
+                                     _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
+
+
 def skipkv_redundancy_workspace_bytes(cache: Cache) -> int:
     out = C.c_size_t(0)
     _check(lib().skipkv_redundancy_workspace_bytes(C.byref(cache.c()), C.byref(out)))
@@ -264,6 +289,10 @@ def skipkv_steer_add(hidden, vec, coef, coef_scalar: float, row_mask, stream=Non
     assert hidden.is_contiguous() and vec.is_contiguous() and vec.dtype == hidden.dtype
     _check(lib().skipkv_steer_add(_ptr(hidden), _ptr(vec), _ptr(coef), float(coef_scalar), _ptr(row_mask),
                                   rows, d_model, dtype_code(hidden.dtype), _stream(stream)))
+
+
+def skipkv_steer_strength(n_nonexec, alpha0: float, gamma: float, coef, stream=None) -> None:
+    _check(lib().skipkv_steer_strength(_ptr(n_nonexec), float(alpha0), float(gamma), _ptr(coef), n_nonexec.numel(), _stream(stream)))
 
 
 def skipkv_profile_create() -> int:

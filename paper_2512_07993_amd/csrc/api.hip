@@ -118,7 +118,7 @@ struct Timer {
 
 int do_score(Timer &tm, const skipkv_cache *c, const skipkv_params *p, const RowLayout &rl, const void *q_obs,
              const float *tok_red, float *sent_score, float *sent_lambda, float *tok_imp, void *ws, hipStream_t st,
-             const HeadView &hv = HeadView()) {
+             const HeadView &hv = HeadView(), const float *shared_lambda = nullptr) {
   const Workspace w = carve(c, rl, ws);
   PlanArgs pa{c->seq_off, c->sent_ptr, c->sent_off, c->batch, c->n_layers * c->n_kv_heads, w, p->dev_status, hv.len, hv.cnt};
   if (tm.run("plan", [&] { return launch_plan(pa, st); }) != hipSuccess) return SKIPKV_EHIP;
@@ -153,10 +153,31 @@ int do_score(Timer &tm, const skipkv_cache *c, const skipkv_params *p, const Row
   sa.dev_status = p->dev_status;
   sa.virt_hk = hv.virt_hk;
   sa.virt_b = hv.virt_b;
+  sa.no_pool = shared_lambda != nullptr;
   if (tm.run("scan_fused", [&] { return launch_scan_fused(sa, st); }) != hipSuccess) return SKIPKV_EHIP;
   if (tm.run("scan_stats", [&] { return launch_scan_stats(sa, st); }) != hipSuccess) return SKIPKV_EHIP;
   if (tm.run("row_norm", [&] { return launch_row_norm(sa, st); }) != hipSuccess) return SKIPKV_EHIP;
   if (tm.run("scan_scores", [&] { return launch_scan_scores(sa, st); }) != hipSuccess) return SKIPKV_EHIP;
+  if (shared_lambda) {  // lambda per sequence (hidden-state similarity): no Gram matrices per head
+    FuseSharedArgs fa{};
+    fa.n_lh = c->n_layers * c->n_kv_heads;
+    fa.batch = c->batch;
+    fa.total_sentences = c->total_sentences;
+    fa.protect = p->protect_window;
+    fa.sigma = p->sigma;
+    fa.tau = p->tau;
+    fa.has_red = tok_red != nullptr;
+    fa.seq_off = c->seq_off;
+    fa.sent_ptr = c->sent_ptr;
+    fa.sent_off = c->sent_off;
+    fa.sent_imp = w.sent_imp;
+    fa.sent_red = w.sent_red;
+    fa.shared_lambda = shared_lambda;
+    fa.sent_score = sent_score;
+    fa.sent_lambda = sent_lambda;
+    if (tm.run("fuse", [&] { return launch_fuse_shared(fa, st); }) != hipSuccess) return SKIPKV_EHIP;
+    return SKIPKV_OK;
+  }
   CosineArgs ca{};
   ca.n_lh = c->n_layers * c->n_kv_heads;
   ca.batch = c->batch;
@@ -482,6 +503,56 @@ int skipkv_ranges_append(const skipkv_cache *cache, const skipkv_ranges *ranges,
   return launch_ranges_append(a, static_cast<hipStream_t>(stream)) == hipSuccess ? SKIPKV_OK : SKIPKV_EHIP;
 }
 
+int skipkv_similarity_workspace_bytes(const skipkv_cache *cache, int32_t d_model, size_t *out_bytes) {
+  if (!out_bytes || d_model <= 0 || d_model % 128) return SKIPKV_EINVAL;
+  const int rc = check_cache(cache, true);
+  if (rc) return rc;
+  const size_t n = (size_t)cache->total_sentences * (size_t)d_model;
+  *out_bytes = align_up(n * 4) + 2 * align_up(n * 2);
+  return SKIPKV_OK;
+}
+
+int skipkv_sentence_similarity(const skipkv_cache *cache, const void *hidden, int32_t d_model, int32_t dtype,
+                               float *shared_lambda, void *ws, size_t ws_bytes, void *stream) {
+  if (d_model <= 0 || d_model % 128) return SKIPKV_EINVAL;
+  if (dtype != SKIPKV_F32 && dtype != SKIPKV_BF16) return SKIPKV_EINVAL;
+  const int rc = check_cache(cache, true);
+  if (rc) return rc;
+  if (cache->batch == 0 || cache->total_sentences == 0) return SKIPKV_OK;
+  if (!hidden || !aligned16(hidden) || !shared_lambda) return SKIPKV_EINVAL;
+  const size_t n = (size_t)cache->total_sentences * (size_t)d_model;
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < align_up(n * 4) + 2 * align_up(n * 2)) return SKIPKV_EWORKSPACE;
+  HiddenSimArgs a{};
+  a.batch = cache->batch;
+  a.total_sentences = cache->total_sentences;
+  a.d_model = d_model;
+  a.dtype = dtype;
+  a.seq_off = cache->seq_off;
+  a.sent_ptr = cache->sent_ptr;
+  a.sent_off = cache->sent_off;
+  a.hidden = hidden;
+  char *p = static_cast<char *>(ws);
+  a.sum_scratch = reinterpret_cast<float *>(p);
+  a.vhat_hi = reinterpret_cast<uint16_t *>(p + align_up(n * 4));
+  a.vhat_lo = reinterpret_cast<uint16_t *>(p + align_up(n * 4) + align_up(n * 2));
+  a.sent_lambda = shared_lambda;
+  return launch_hidden_similarity(a, static_cast<hipStream_t>(stream)) == hipSuccess ? SKIPKV_OK : SKIPKV_EHIP;
+}
+
+int skipkv_score_shared(const skipkv_cache *cache, const skipkv_params *params, const void *q_obs,
+                        const float *tok_redundancy, const float *shared_lambda, float *sent_score, float *sent_lambda,
+                        float *tok_importance, void *ws, size_t ws_bytes, void *stream) {
+  RowLayout rl;
+  float dummy = 0.f;
+  const int rc = check_score_args(cache, params, &rl, q_obs, sent_score, sent_lambda ? sent_lambda : &dummy, ws, ws_bytes);
+  if (rc) return rc;
+  if (is_empty(cache)) return SKIPKV_OK;
+  if (cache->total_sentences > 0 && !shared_lambda) return SKIPKV_EINVAL;
+  Timer tm(params->profile, static_cast<hipStream_t>(stream));
+  return do_score(tm, cache, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, ws,
+                  static_cast<hipStream_t>(stream), HeadView(), shared_lambda);
+}
+
 int skipkv_redundancy_workspace_bytes(const skipkv_cache *cache, size_t *out_bytes) {
   if (!out_bytes) return SKIPKV_EINVAL;
   const int rc = check_cache(cache, false);
@@ -525,6 +596,13 @@ int skipkv_steer_add(void *hidden, const void *vec, const float *coef, float coe
   if (rows > 65535) return SKIPKV_ECAPACITY;
   SteerArgs a{hidden, vec, coef, coef_scalar, row_mask, rows, d_model, dtype};
   return launch_steer(a, static_cast<hipStream_t>(stream)) == hipSuccess ? SKIPKV_OK : SKIPKV_EHIP;
+}
+
+int skipkv_steer_strength(const int32_t *n_nonexec, float alpha0, float gamma, float *coef, int32_t rows, void *stream) {
+  if (rows < 0) return SKIPKV_EINVAL;
+  if (rows == 0) return SKIPKV_OK;
+  if (!n_nonexec || !coef) return SKIPKV_EINVAL;
+  return launch_steer_strength(n_nonexec, alpha0, gamma, coef, rows, static_cast<hipStream_t>(stream)) == hipSuccess ? SKIPKV_OK : SKIPKV_EHIP;
 }
 
 int skipkv_profile_create(void **out_profile) {

@@ -159,6 +159,7 @@ struct ScanArgs {
   // sequence of its own of ONE layer with ONE KV head (v = (l * H_k + h) * B + b); only the query
   // rows are still laid out by the real (l, b, h).  virt_hk = real H_k (0: off), virt_b = real B.
   int32_t virt_hk, virt_b;
+  int32_t no_pool;  // 1: sentence embeddings are not needed (lambda comes from elsewhere): skip the key pooling
 };
 bool scan_fused_supported(const RowLayout &rl);
 hipError_t launch_scan_fused(const ScanArgs &a, hipStream_t st);    // single pass over K (sequences the plan marked fused)
@@ -222,6 +223,28 @@ struct TokRedArgs {
 };
 hipError_t launch_token_redundancy(const TokRedArgs &a, hipStream_t st);
 
+// Sentence similarity from hidden states (Eq. 1-3 as printed), shared by all layers and heads.
+struct HiddenSimArgs {
+  int32_t batch, total_sentences, d_model, dtype;
+  const int32_t *seq_off, *sent_ptr, *sent_off;
+  const void *hidden;    // [total_tokens, d_model]
+  float *sum_scratch;    // [total_sentences, d_model]
+  uint16_t *vhat_hi, *vhat_lo;  // [total_sentences, d_model] unit embeddings, bf16 high part and residual
+  float *sent_lambda;    // out [total_sentences]
+};
+hipError_t launch_hidden_similarity(const HiddenSimArgs &a, hipStream_t st);
+
+// Eq. 6 with a lambda that is given per sequence instead of computed per head.
+struct FuseSharedArgs {
+  int32_t n_lh, batch, total_sentences, protect;
+  float sigma, tau;
+  bool has_red;
+  const int32_t *seq_off, *sent_ptr, *sent_off;
+  const float *sent_imp, *sent_red, *shared_lambda;
+  float *sent_score, *sent_lambda;  // sent_lambda nullable
+};
+hipError_t launch_fuse_shared(const FuseSharedArgs &a, hipStream_t st);
+
 struct SteerArgs {
   void *hidden;
   const void *vec;
@@ -231,6 +254,7 @@ struct SteerArgs {
   int32_t rows, d_model, dtype;
 };
 hipError_t launch_steer(const SteerArgs &a, hipStream_t st);
+hipError_t launch_steer_strength(const int32_t *n_nonexec, float alpha0, float gamma, float *coef, int32_t rows, hipStream_t st);
 
 // ---- device helpers -----------------------------------------------------------------------
 #if defined(__HIPCC__)

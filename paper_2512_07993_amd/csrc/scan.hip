@@ -253,7 +253,7 @@ __global__ void __launch_bounds__(256) k_scan(ScanArgs a) {
 
   if constexpr (!PASSB) {
     // ---- unit sentence embeddings, split into bf16 hi + lo, one wave per sentence
-    for (int si = wave; si < ns; si += 4) {
+    for (int si = wave; si < ns && !a.no_pool; si += 4) {
       const float inv_len = 1.f / (float)(soff[si + 1] - soff[si]);
       const float m0 = sbuf[si * kD + 2 * lane] * inv_len, m1 = sbuf[si * kD + 2 * lane + 1] * inv_len;
       const float nrm = sqrtf(wave_sum(m0 * m0 + m1 * m1));

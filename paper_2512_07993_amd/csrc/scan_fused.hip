@@ -365,7 +365,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
 
             // ---- sentence key sums over tokens [ts, te).  All rows of the stage come into registers
             // with one LDS round trip (lane = 2 head-dim columns of every row).
-            {
+            if (!a.no_pool) {
               float x0[kStageRows], x1[kStageRows];
               uint32_t xw[kStageRows];
               // the stage buffers are 256-byte aligned, so the swizzle (piece ^ row) is an XOR on bits
@@ -446,7 +446,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
             }
           }
         }
-        if (w0 < w1 && si < ns && s_bgn < w1 && w1 < s_end) {  // a sentence is still running at the end of this wave's range
+        if (!a.no_pool && w0 < w1 && si < ns && s_bgn < w1 && w1 < s_end) {  // a sentence is still running at the end of this wave's range
           float *dst = (s_bgn >= w0) ? part_last[k][wave] : part_first[k][wave];
           dst[2 * lane] = pk0[0];
           dst[2 * lane + 1] = pk1[0];
@@ -497,7 +497,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
       if (k < cur.nch) {
         const ChunkD &cd = cur.ch[k];
         const int *soff = soff_buf[par][k];
-        if (cd.w0 < cd.w1 && wave < 3) {
+        if (cd.w0 < cd.w1 && wave < 3 && !a.no_pool) {
           const int sl = __popcll(__ballot(lane < cd.ns && soff[lane + 1] <= cd.w1 - 1));  // sentence holding the wave's last token
           if (soff[sl] >= cd.w0 && soff[sl + 1] > cd.w1) {
             const int ln = opaque(lane);

@@ -43,7 +43,20 @@ __global__ void __launch_bounds__(256) k_steer(SteerArgs a) {
   }
 }
 
+// Adaptive strength (Sec. 4.2): alpha_t = alpha_0 + gamma * N_o per sample, N_o the running
+// count of non-execution thoughts.  One rounding (fused multiply-add).
+__global__ void __launch_bounds__(256) k_steer_strength(const int32_t *n_nonexec, float alpha0, float gamma, float *coef, int rows) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < rows) coef[i] = fmaf(gamma, (float)n_nonexec[i], alpha0);
+}
+
 }  // namespace
+
+hipError_t launch_steer_strength(const int32_t *n_nonexec, float alpha0, float gamma, float *coef, int32_t rows, hipStream_t st) {
+  if (rows == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_steer_strength, dim3((rows + 255) / 256), dim3(256), 0, st, n_nonexec, alpha0, gamma, coef, rows);
+  return hipGetLastError();
+}
 
 hipError_t launch_steer(const SteerArgs &a, hipStream_t st) {
   if (a.rows == 0 || a.d_model == 0) return hipSuccess;

@@ -264,8 +264,11 @@ def test_steer_add_matches_oracle_bit_for_bit(dtype):
     ref = oracle.steer_add(h0.double().cpu().numpy(), vec.double().cpu().numpy(), coef, dtype=dtype)
     np.testing.assert_array_equal(h.double().cpu().numpy(), ref)
     # adaptive per-sample strength alpha_0 + gamma * N_o and a delimiter-row mask
-    n_o = torch.arange(64, device="cuda", dtype=torch.float32)
-    coefs = (1.0 + 0.02 * n_o).contiguous()
+    n_o = torch.arange(64, device="cuda", dtype=torch.int32)
+    coefs = torch.empty(64, dtype=torch.float32, device="cuda")
+    B.skipkv_steer_strength(n_o, 1.0, 0.02, coefs)
+    want = oracle.steer_strength(n_o.cpu().numpy(), np.float32(1.0), np.float32(0.02)).astype(np.float32)
+    np.testing.assert_array_equal(coefs.cpu().numpy(), want)
     mask = (torch.arange(64, device="cuda") % 3 != 1).to(torch.uint8)
     h = h0.clone()
     B.skipkv_steer_add(h, vec, coefs, 0.0, mask)

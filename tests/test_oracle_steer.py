@@ -63,3 +63,13 @@ def test_steer_bf16_per_row_coefficients_and_mask():
     lib = torch.from_numpy(exact).to(torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
     diff = np.abs(lib[rows] - got[rows])
     assert np.all(diff <= ulp * 1.0000001) and (diff > 0).mean() < 1e-2
+
+
+def test_adaptive_strength_is_the_initial_strength_plus_gamma_per_non_execution_thought():
+    from oracle import steer_strength
+    # Sec. 4.2: alpha_t = alpha_0 + gamma * N_o: alpha_0 with no non-execution thought so far,
+    # one gamma more for every one counted, independently per sample
+    np.testing.assert_array_equal(steer_strength([0, 0], 1.5, 0.25), [1.5, 1.5])
+    np.testing.assert_array_equal(steer_strength([0, 1, 2, 8], 1.0, 0.5), [1.0, 1.5, 2.0, 5.0])
+    a = steer_strength(np.arange(10), 0.3, 0.07)
+    np.testing.assert_allclose(np.diff(a), 0.07, rtol=1e-12)
