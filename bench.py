@@ -214,6 +214,62 @@ def time_ranges(config_id: int, steps: int = 5) -> int:
     return 0
 
 
+def time_shared_lambda(config_id: int, d_model: int = 4096, steps: int = 5) -> int:
+    """Times the paper-literal variant of the step: sentence similarity from hidden states once per
+    sequence (Eq. 1-3), then scores with that shared lambda, selection and compaction."""
+    import torch
+
+    from paper_2512_07993_amd import binding as B
+    from paper_2512_07993_amd import workloads as W
+
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    cfg = W.CONFIGS[config_id]
+    st = W.make_structure(cfg)
+    k0, v0, q = W.fill_cache(cfg, st, device=dev)
+    L, H, Bn, S, T = cfg.n_layers, cfg.n_kv_heads, cfg.batch, st.total_sentences, st.total_tokens
+    so, sp, sf = (torch.from_numpy(x).to(dev) for x in (st.seq_off, st.sent_ptr, st.sent_off))
+    k, v = torch.empty_like(k0), torch.empty_like(v0)
+    cache = B.Cache(k, v, cfg.n_q_heads, so, sp, sf, T, S)
+    g = torch.Generator(device=dev)
+    g.manual_seed(cfg.seed)
+    hidden = torch.randn((T, d_model), generator=g, device=dev).to(k0.dtype)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    prof = B.skipkv_profile_create()
+    params = B.Params(cfg.obs_window, cfg.protect_window, cfg.budget, dev_status=status, profile=prof)
+    ws = torch.empty(B.skipkv_workspace_bytes(cache, params), dtype=torch.uint8, device=dev)
+    ws_sim = torch.empty(B.skipkv_similarity_workspace_bytes(cache, d_model), dtype=torch.uint8, device=dev)
+    kept_stride = min(cfg.budget, T)
+    shared = torch.empty((S,), dtype=torch.float32, device=dev)
+    sent_score = torch.empty((L, H, S), dtype=torch.float32, device=dev)
+    sent_keep = torch.empty((L, H, S), dtype=torch.uint8, device=dev)
+    kept_idx = torch.empty((L, H, Bn, kept_stride), dtype=torch.int32, device=dev)
+    new_len = torch.empty((L, H, Bn), dtype=torch.int32, device=dev)
+    t_sim, t_rest = [], []
+    for i in range(steps + 1):
+        k.copy_(k0)
+        v.copy_(v0)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        ev[0].record()
+        B.skipkv_sentence_similarity(cache, hidden, shared, ws_sim)
+        ev[1].record()
+        B.skipkv_score_shared(cache, params, q, None, shared, sent_score, None, None, ws)
+        B.skipkv_select(cache, params, sent_score, sent_keep, kept_idx, new_len, None, None, kept_stride)
+        B.skipkv_compact(cache, kept_idx, new_len, kept_stride)
+        ev[2].record()
+        torch.cuda.synchronize()
+        if i:
+            t_sim.append(ev[0].elapsed_time(ev[1]))
+            t_rest.append(ev[1].elapsed_time(ev[2]))
+    assert int(status.item()) == 0, "device status %d" % int(status.item())
+    kern = {n: round(t, 4) for n, t in B.skipkv_profile_read(prof)}  # of the last skipkv_score_shared
+    B.skipkv_profile_destroy(prof)
+    print(json.dumps({"op": "step_shared_lambda", "workload": "config %d: %s" % (cfg.config_id, cfg.name),
+                      "d_model": d_model, "sentence_similarity_ms": sum(t_sim) / len(t_sim),
+                      "score_select_compact_ms": sum(t_rest) / len(t_rest), "score_kernel_ms": kern, "steps": steps}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -224,6 +280,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy", action="store_true", help="run only the counter-calibration copy (see profiles/)")
     ap.add_argument("--redundancy", action="store_true", help="time only skipkv_token_redundancy on the workload's keys")
+    ap.add_argument("--shared-lambda", action="store_true", help="time the variant with hidden-state sentence similarity shared by all heads")
     ap.add_argument("--ranges", action="store_true", help="time skipkv_step_ranges (per-head sentence ranges) next to skipkv_step")
     args = ap.parse_args()
     if args.calib_copy:
@@ -232,6 +289,8 @@ def main() -> int:
         return time_redundancy(args.config)
     if args.ranges:
         return time_ranges(args.config)
+    if args.shared_lambda:
+        return time_shared_lambda(args.config)
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (heads are independent: more GPUs would only shard them); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)

@@ -3,6 +3,8 @@
 // with a later sentence, computed once per sequence and shared by all layers and heads - and
 // the scores of Eq. 6 with that shared lambda, so that the per-head key pooling and Gram
 // matrices drop out of the step.
+#include <algorithm>
+
 #include "common.h"
 
 namespace skipkv {
@@ -43,6 +45,7 @@ __global__ void __launch_bounds__(256) k_hidden_pool(HiddenSimArgs a) {
   float *sum_row = a.sum_scratch + (int64_t)c * a.d_model;
   for (int g8 = tid; g8 * 8 < a.d_model; g8 += 256) {
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
     for (int t = t0; t < t1; ++t) {
       const char *p = h + t * pitch + (int64_t)g8 * 8 * ESZ;
       if constexpr (DT == SKIPKV_BF16) {
@@ -69,6 +72,7 @@ __global__ void __launch_bounds__(256) k_hidden_pool(HiddenSimArgs a) {
   if ((tid & 63) == 0) red[tid >> 6] = ssq;
   __syncthreads();
   const float inv = 1.f / (sqrtf(red[0] + red[1] + red[2] + red[3]) + 1e-12f * (float)(t1 - t0));
+  if (tid == 0) a.sent_lambda[c] = -INFINITY;  // the Gram kernel folds its row maxima into this
   uint16_t *hi = a.vhat_hi + (int64_t)c * a.d_model, *lo = a.vhat_lo + (int64_t)c * a.d_model;
   for (int g8 = tid; g8 * 8 < a.d_model; g8 += 256) {
 #pragma unroll
@@ -81,21 +85,37 @@ __global__ void __launch_bounds__(256) k_hidden_pool(HiddenSimArgs a) {
   }
 }
 
-// lambda of 64 rows of one sequence: Gram tiles against all columns at and right of the diagonal,
-// accumulated over 128-dim slices of the embedding (A and B slices staged through LDS, bf16 hi + lo,
-// three products per slice step as in the per-head kernel), running row maximum in registers.
+// atomic max on a float that may be negative (order of the bit patterns: ints for >= 0, reversed uints for < 0)
+__device__ __forceinline__ void atomic_max_float(float *addr, float v) {
+  if (v >= 0.f)
+    atomicMax(reinterpret_cast<int *>(addr), __float_as_int(v));
+  else
+    atomicMin(reinterpret_cast<unsigned int *>(addr), __float_as_uint(v));
+}
+
+// One 64 x 64 block of a sequence's Gram matrix at or right of the diagonal: accumulated over the
+// 128-dim slices of the embedding (A and B slices staged through LDS, bf16 hi + lo, three products
+// per slice step as in the per-head kernel), then folded into the row maxima (lambda, preset to
+// -inf by the pooling kernel) with atomics, so that all blocks of a sequence run side by side.
 __global__ void __launch_bounds__(256) k_cosine_wide(HiddenSimArgs a) {
   __shared__ __align__(16) char sa_hi[64 * LSTR], sa_lo[64 * LSTR], sb_hi[64 * LSTR], sb_lo[64 * LSTR];
-  const int b = blockIdx.x, r0 = blockIdx.y * 64;
+  const int b = blockIdx.x;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, c16 = lane & 15, g = lane >> 4;
   const int sp = a.sent_ptr[b];
-  const int n_sent = a.sent_ptr[b + 1] - sp - 1;
-  if (r0 >= n_sent) return;
+  const int n_sent = min(a.sent_ptr[b + 1] - sp - 1, SKIPKV_MAX_SENTENCES);
+  const int nb = (n_sent + 63) / 64;
+  // blockIdx.y enumerates the pairs (rb, cb), cb >= rb, row by row
+  int rb = 0, rest = blockIdx.y;
+  while (rb < nb && rest >= nb - rb) {
+    rest -= nb - rb;
+    ++rb;
+  }
+  if (rb >= nb) return;
+  const int r0 = 64 * rb, jb = 64 * (rb + rest);
   const int64_t col0 = sp - b;
   const char *hi = reinterpret_cast<const char *>(a.vhat_hi + col0 * a.d_model);
   const char *lo = reinterpret_cast<const char *>(a.vhat_lo + col0 * a.d_model);
   const int64_t pitch = (int64_t)a.d_model * 2;
-  float rmax[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
   auto stage = [&](char *dst_hi, char *dst_lo, int row0, int d0) {  // 64 rows x 128 dims, hi and lo: 8 pieces of 16 bytes per thread
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
@@ -105,44 +125,43 @@ __global__ void __launch_bounds__(256) k_cosine_wide(HiddenSimArgs a) {
       *reinterpret_cast<uint4 *>((half ? dst_lo : dst_hi) + row * LSTR + piece * 16) = v;
     }
   };
-  for (int jb = r0; jb < n_sent; jb += 64) {
-    f32x4 acc[4];
+  f32x4 acc[4];
 #pragma unroll
-    for (int ct = 0; ct < 4; ++ct) acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int d0 = 0; d0 < a.d_model; d0 += 128) {
-      __syncthreads();  // the previous slice is consumed
-      stage(sa_hi, sa_lo, r0, d0);
-      stage(sb_hi, sb_lo, jb, d0);
-      __syncthreads();
+  for (int ct = 0; ct < 4; ++ct) acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int d0 = 0; d0 < a.d_model; d0 += 128) {
+    __syncthreads();  // the previous slice is consumed
+    stage(sa_hi, sa_lo, r0, d0);
+    stage(sb_hi, sb_lo, jb, d0);
+    __syncthreads();
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const bf16x8 a_hi = *reinterpret_cast<const bf16x8 *>(sa_hi + (16 * wave + c16) * LSTR + g * 64 + kk * 16);
-        const bf16x8 a_lo = *reinterpret_cast<const bf16x8 *>(sa_lo + (16 * wave + c16) * LSTR + g * 64 + kk * 16);
+    for (int kk = 0; kk < 4; ++kk) {
+      const bf16x8 a_hi = *reinterpret_cast<const bf16x8 *>(sa_hi + (16 * wave + c16) * LSTR + g * 64 + kk * 16);
+      const bf16x8 a_lo = *reinterpret_cast<const bf16x8 *>(sa_lo + (16 * wave + c16) * LSTR + g * 64 + kk * 16);
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct) {
-          const bf16x8 b_hi = *reinterpret_cast<const bf16x8 *>(sb_hi + (16 * ct + c16) * LSTR + g * 64 + kk * 16);
-          const bf16x8 b_lo = *reinterpret_cast<const bf16x8 *>(sb_lo + (16 * ct + c16) * LSTR + g * 64 + kk * 16);
-          acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo, b_hi, acc[ct], 0, 0, 0);
-          acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi, b_lo, acc[ct], 0, 0, 0);
-          acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi, b_hi, acc[ct], 0, 0, 0);
-        }
+      for (int ct = 0; ct < 4; ++ct) {
+        const bf16x8 b_hi = *reinterpret_cast<const bf16x8 *>(sb_hi + (16 * ct + c16) * LSTR + g * 64 + kk * 16);
+        const bf16x8 b_lo = *reinterpret_cast<const bf16x8 *>(sb_lo + (16 * ct + c16) * LSTR + g * 64 + kk * 16);
+        acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo, b_hi, acc[ct], 0, 0, 0);
+        acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi, b_lo, acc[ct], 0, 0, 0);
+        acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi, b_hi, acc[ct], 0, 0, 0);
       }
     }
+  }
+  float rmax[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
 #pragma unroll
-    for (int ct = 0; ct < 4; ++ct) {
-      const int col = jb + 16 * ct + c16;
+  for (int ct = 0; ct < 4; ++ct) {
+    const int col = jb + 16 * ct + c16;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int row = r0 + 16 * wave + 4 * g + j;
-        if (col > row && col < n_sent) rmax[j] = fmaxf(rmax[j], acc[ct][j]);
-      }
+    for (int j = 0; j < 4; ++j) {
+      const int row = r0 + 16 * wave + 4 * g + j;
+      if (col > row && col < n_sent) rmax[j] = fmaxf(rmax[j], acc[ct][j]);
     }
   }
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const float lam = row16_max(rmax[j]);
     const int row = r0 + 16 * wave + 4 * g + j;
-    if (c16 == 0 && row < n_sent) a.sent_lambda[col0 + row] = lam;
+    if (c16 == 0 && row < n_sent && lam > -INFINITY) atomic_max_float(&a.sent_lambda[col0 + row], lam);
   }
 }
 
@@ -177,7 +196,9 @@ hipError_t launch_hidden_similarity(const HiddenSimArgs &a, hipStream_t st) {
     hipLaunchKernelGGL(k_hidden_pool<SKIPKV_F32>, dim3(a.total_sentences), dim3(256), 0, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_cosine_wide, dim3(a.batch, (SKIPKV_MAX_SENTENCES + 63) / 64), dim3(256), 0, st, a);
+  // a sequence has at most min(total_sentences, SKIPKV_MAX_SENTENCES) sentences: that many 64-row blocks, all pairs of them
+  const int nb = (std::min(a.total_sentences, SKIPKV_MAX_SENTENCES) + 63) / 64;
+  hipLaunchKernelGGL(k_cosine_wide, dim3(a.batch, nb * (nb + 1) / 2), dim3(256), 0, st, a);
   return hipGetLastError();
 }
 
