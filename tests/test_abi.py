@@ -125,3 +125,36 @@ def test_binding_refuses_to_run_without_the_library(monkeypatch):
     monkeypatch.setattr(B, "_LIB_PATH", "/nonexistent/libskipkv.so")
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         B.lib()
+
+
+def test_ranges_and_similarity_entry_points_validate_on_the_host():
+    lib, cache, params = B.lib(), _cache(), _params()
+    out = C.c_size_t(0)
+    # per-head ranges: workspace larger than the shared one, contiguous K/V required, ranges required
+    assert lib.skipkv_ranges_workspace_bytes(C.byref(cache), C.byref(params), C.byref(out)) == B.OK
+    assert out.value > _ws_bytes(cache, params)[1]
+    need = out.value
+    strided = _cache(stride_head=8192 * 128, stride_layer=8 * 8192 * 128)
+    assert lib.skipkv_ranges_workspace_bytes(C.byref(strided), C.byref(params), C.byref(out)) == B.ECAPACITY
+    rng = B.CRanges(0x6000, 0x6100, 0x6200)
+    step = lambda r, ws=0x10000, n=need, noff=0xB000, ncnt=0xC000: lib.skipkv_step_ranges(
+        C.byref(cache), r, C.byref(params), 0x6400, None, 0x7000, 0x8000, None, None, 0x9000, 0xA000, noff, ncnt,
+        2048, ws, n, None)
+    assert step(None) == B.EINVAL
+    assert step(C.byref(B.CRanges(0x6000, None, 0x6200))) == B.EINVAL
+    assert step(C.byref(rng), n=need - 1) == B.EWORKSPACE
+    assert step(C.byref(rng), noff=0x6200) == B.EINVAL     # outputs must not alias the input ranges
+    assert lib.skipkv_ranges_append(C.byref(cache), None, 0x6300, 0x6400, 0x6500, None, None) == B.EINVAL
+    assert lib.skipkv_ranges_append(C.byref(cache), C.byref(rng), None, 0x6400, 0x6500, None, None) == B.EINVAL
+    # hidden-state similarity: d_model a multiple of 128, workspace, pointers
+    assert lib.skipkv_similarity_workspace_bytes(C.byref(cache), 4096, C.byref(out)) == B.OK
+    assert out.value >= 200 * 4096 * 8
+    assert lib.skipkv_similarity_workspace_bytes(C.byref(cache), 100, C.byref(out)) == B.EINVAL
+    sim = lambda h=0x6400, d=4096, dt=B.BF16, lam=0x7000, ws=0x10000, n=1 << 30: lib.skipkv_sentence_similarity(
+        C.byref(cache), h, d, dt, lam, ws, n, None)
+    assert sim(h=None) == B.EINVAL and sim(lam=None) == B.EINVAL and sim(d=130) == B.EINVAL and sim(dt=7) == B.EINVAL
+    assert sim(n=1024) == B.EWORKSPACE and sim(ws=0x10010) == B.EWORKSPACE
+    assert lib.skipkv_score_shared(C.byref(cache), C.byref(params), 0x6400, None, None, 0x7000, None, None, 0x10000,
+                                   1 << 40, None) == B.EINVAL  # lambda missing
+    assert lib.skipkv_steer_strength(None, 1.0, 0.1, 0x7000, 4, None) == B.EINVAL
+    assert lib.skipkv_steer_strength(None, 1.0, 0.1, None, 0, None) == B.OK

@@ -122,6 +122,16 @@ def test_per_head_step_on_degenerate_sequences():
     _assert_same_step(cfg, st, a, ka, va, b, kb, vb)
 
 
+def test_per_head_length_beyond_the_room_is_reported():
+    cfg = W.CONFIGS[3].scaled(n_layers=1, n_kv_heads=2, n_q_heads=8, batch=2, len_lo=400, len_hi=700, budget=256)
+    st = W.make_structure(cfg)
+    k0, v0, q = W.fill_cache(cfg, st, device="cuda")
+    r = shared_as_ranges(cfg, st)
+    r.len[0, 1, 0] += 5  # more tokens than the sequence's rows can hold
+    out = run_step_ranges(cfg, st, k0.clone(), v0.clone(), q, r, cfg.budget)
+    assert int(out.dev_status.item()) & B.DEV_BAD_OFFSETS
+
+
 def test_ranges_append_matches_oracle_and_reports_overflow():
     rng = np.random.default_rng(11)
     L, H, Bn = 2, 3, 4
