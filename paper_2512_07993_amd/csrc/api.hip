@@ -60,6 +60,7 @@ Workspace carve(const skipkv_cache *c, const RowLayout &rl, void *base) {
   const size_t T = (size_t)c->total_tokens, S = (size_t)c->total_sentences;
   w.nc_max = (int32_t)(2 * ((T + kChunkCap - 1) / kChunkCap) + B + (S + kChunkMaxSent - 1) / kChunkMaxSent);
   w.nrb_max = (int32_t)((S + kRowBlock - 1) / kRowBlock + B);
+  w.fits = w.nc_max <= kHdrMaxChunks && w.nc_max / 2 + (int64_t)B <= kHdrMaxPairs && w.nrb_max <= kHdrMaxRowBlocks;
   w.rows = rl.rows;
   size_t off = 0;
   char *p = static_cast<char *>(base);
@@ -301,6 +302,7 @@ int check_score_args(const skipkv_cache *c, const skipkv_params *p, RowLayout *r
   if (!q_obs || !aligned16(q_obs)) return SKIPKV_EINVAL;
   if (c->total_sentences > 0 && (!sent_score || !sent_lambda)) return SKIPKV_EINVAL;
   const Workspace w = carve(c, *rl, nullptr);
+  if (!w.fits) return SKIPKV_ECAPACITY;
   if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < w.bytes) return SKIPKV_EWORKSPACE;
   return SKIPKV_OK;
 }
@@ -334,7 +336,9 @@ int skipkv_workspace_bytes(const skipkv_cache *cache, const skipkv_params *param
   RowLayout rl;
   rc = check_params(cache, params, &rl);
   if (rc) return rc;
-  *out_bytes = carve(cache, rl, nullptr).bytes;
+  const Workspace w = carve(cache, rl, nullptr);
+  if (!w.fits) return SKIPKV_ECAPACITY;
+  *out_bytes = w.bytes;
   return SKIPKV_OK;
 }
 
@@ -442,7 +446,9 @@ int skipkv_ranges_workspace_bytes(const skipkv_cache *cache, const skipkv_params
   VirtualView v;
   rc = make_virtual(cache, &dummy, nullptr, &v);
   if (rc) return rc;
-  *out_bytes = v.head_bytes + carve(&v.c, rl, nullptr).bytes;
+  const Workspace w = carve(&v.c, rl, nullptr);
+  if (!w.fits) return SKIPKV_ECAPACITY;
+  *out_bytes = v.head_bytes + w.bytes;
   return SKIPKV_OK;
 }
 
@@ -466,6 +472,7 @@ int skipkv_step_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, c
   rc = make_virtual(cache, ranges, ws, &v);
   if (rc) return rc;
   const Workspace w = carve(&v.c, rl, nullptr);
+  if (!w.fits) return SKIPKV_ECAPACITY;
   if (ws_bytes < v.head_bytes + w.bytes) return SKIPKV_EWORKSPACE;
   if (ranges->sent_off == new_sent_off || ranges->len == new_len || ranges->sent_cnt == new_sent_cnt) return SKIPKV_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(stream);

@@ -53,12 +53,19 @@ enum PairRec : int {
 };
 
 struct PlanHeader {
-  int32_t n_chunks;
-  int32_t n_rowblocks;
+  // The three range counters that every plan block draws from, packed into one word so that a
+  // block needs ONE atomic (with thousands of blocks the same-address atomics are what the plan
+  // costs): chunks in bits 0..21, chunk pairs (units of the single-pass scan) in bits 22..42,
+  // row blocks in bits 43..63.
+  unsigned long long ranges;
   int32_t n_unfused;  // number of sequences that take the two-pass scan
-  int32_t n_pairs;    // number of chunk pairs (units of the single-pass scan)
-  int32_t pad[60];
+  int32_t pad[61];
 };
+constexpr int kHdrPairShift = 22, kHdrRbShift = 43;
+constexpr int64_t kHdrMaxChunks = (1ll << 22) - 1, kHdrMaxPairs = (1ll << 21) - 1, kHdrMaxRowBlocks = (1ll << 21) - 1;
+__host__ __device__ inline int32_t hdr_chunks(unsigned long long r) { return (int32_t)(r & ((1ull << kHdrPairShift) - 1)); }
+__host__ __device__ inline int32_t hdr_pairs(unsigned long long r) { return (int32_t)((r >> kHdrPairShift) & ((1ull << (kHdrRbShift - kHdrPairShift)) - 1)); }
+__host__ __device__ inline int32_t hdr_rowblocks(unsigned long long r) { return (int32_t)(r >> kHdrRbShift); }
 
 // Carved-up view of the caller's workspace.  All sections 256-byte aligned.
 struct Workspace {
@@ -80,6 +87,7 @@ struct Workspace {
   float *sent_imp;       // [LH, S_total]    mean token importance over the candidate span
   float *sent_red;       // [LH, S_total]    mean token redundancy over the candidate span
   int32_t nc_max, nrb_max, rows;  // rows = R, padded query rows per head
+  bool fits;                      // the counts fit the packed range counters of the plan header
   size_t bytes;
 };
 

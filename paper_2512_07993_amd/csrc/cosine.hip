@@ -26,10 +26,15 @@ __global__ void __launch_bounds__(256, 3) k_cosine(CosineArgs a) {
   __shared__ __align__(16) char col_lo[kColBlock * LSTR];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, c16 = lane & 15, g = lane >> 4;
-  const uint32_t item = xcd_contiguous_item(blockIdx.x, gridDim.x);
-  if (item >= (uint32_t)a.n_lh * (uint32_t)a.ws.nrb_max) return;
-  const int lh = item / a.ws.nrb_max, rb = item % a.ws.nrb_max;
-  if (rb >= a.ws.hdr->n_rowblocks) return;
+  // the grid is sized for the largest possible number of row blocks; the work items that exist
+  // are numbered densely (head-major) and dealt to the XCDs in contiguous ranges
+  const uint32_t n_rb = (uint32_t)hdr_rowblocks(a.ws.hdr->ranges);
+  const uint32_t n_items = (uint32_t)a.n_lh * n_rb;
+  const uint32_t per_xcd = (n_items + 7u) / 8u;
+  if (blockIdx.x >= 8u * per_xcd) return;
+  const uint32_t item = xcd_contiguous_item(blockIdx.x, 8u * per_xcd);
+  if (item >= n_items) return;
+  const int lh = item / n_rb, rb = item % n_rb;
   const RowBlock blk = a.ws.rowblocks[rb];
   const int b = blk.b, r0 = blk.r0;
   const int sp = a.sent_ptr[b];

@@ -9,10 +9,8 @@ namespace skipkv {
 __global__ void k_plan_reset(PlanHeader *hdr, int32_t *flags, int n_flags, uint32_t *row_norm_bits, int n_norm) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i == 0) {
-    hdr->n_chunks = 0;
-    hdr->n_rowblocks = 0;
+    hdr->ranges = 0;
     hdr->n_unfused = 0;
-    hdr->n_pairs = 0;
   }
   for (int j = i; j < n_flags; j += gridDim.x * blockDim.x) flags[j] = 0;
   for (int j = i; j < n_norm; j += gridDim.x * blockDim.x) row_norm_bits[j] = kRowNormUnset;
@@ -65,13 +63,14 @@ __global__ void __launch_bounds__(256) k_plan(PlanArgs a) {
   }
   __syncthreads();
   __shared__ int s_base, s_nchunks, s_pbase, s_fused;
-  __shared__ int s_next[SKIPKV_MAX_SENTENCES];    // end of the chunk that would start at each sentence
-  __shared__ int s_first[SKIPKV_MAX_SENTENCES];   // first sentence of every chunk
+  static_assert(SKIPKV_MAX_SENTENCES <= 65535, "sentence indices are kept in 16 bits here");
+  __shared__ uint16_t s_next[SKIPKV_MAX_SENTENCES];    // end of the chunk that would start at each sentence
+  __shared__ uint16_t s_first[SKIPKV_MAX_SENTENCES];   // first sentence of every chunk
   const bool ok = !reject && !s_bad;
   // the greedy packing is a walk along s -> chunk_end(s); the ends are found for all sentences at
   // once, so that the (serial) walk is one LDS read per chunk
   if (ok)
-    for (int s = tid; s < n_sent; s += 256) s_next[s] = chunk_end(s_off, s, n_sent);
+    for (int s = tid; s < n_sent; s += 256) s_next[s] = (uint16_t)chunk_end(s_off, s, n_sent);
   __syncthreads();
   if (tid == 0) {
     s_nchunks = -1;
@@ -88,26 +87,28 @@ __global__ void __launch_bounds__(256) k_plan(PlanArgs a) {
       for (int start = 0; start < n_sent;) {
         const int e = s_next[start];
         longest = max(longest, s_off[e] - s_off[start]);
-        s_first[n_chunks++] = start;
+        s_first[n_chunks++] = (uint16_t)start;
         start = e;
       }
-      const int base = atomicAdd(&a.ws.hdr->n_chunks, n_chunks);
+      // one atomic draws the block's ranges of chunks, pairs and row blocks
+      const int n_pairs = (n_chunks + 1) / 2;
+      const int nrb = (n_sent + kRowBlock - 1) / kRowBlock;
+      const unsigned long long old = atomicAdd(&a.ws.hdr->ranges, (unsigned long long)n_chunks | ((unsigned long long)n_pairs << kHdrPairShift) |
+                                                                      ((unsigned long long)nrb << kHdrRbShift));
+      const int base = hdr_chunks(old), pbase = hdr_pairs(old), rb0 = hdr_rowblocks(old);
       a.ws.chunk_base[b] = base;
       a.ws.chunk_cnt[b] = n_chunks;
       const bool fused = longest <= kChunkCap && n_chunks <= kFuseMaxChunks;
       a.ws.seq_fused[b] = fused;
       if (!fused && n_chunks > 0) atomicAdd(&a.ws.hdr->n_unfused, 1);
       // the single-pass scan works on pairs of consecutive chunks of a sequence
-      const int n_pairs = (n_chunks + 1) / 2;
       a.ws.pair_cnt[b] = n_pairs;
-      const int nrb = (n_sent + kRowBlock - 1) / kRowBlock;
-      const int rb0 = atomicAdd(&a.ws.hdr->n_rowblocks, nrb);
       a.ws.rb_base[b] = rb0;
       a.ws.rb_cnt[b] = nrb;
       for (int i = 0; i < nrb; ++i) a.ws.rowblocks[rb0 + i] = RowBlock{b, i * kRowBlock};
       s_base = base;
       s_nchunks = n_chunks;
-      s_pbase = atomicAdd(&a.ws.hdr->n_pairs, n_pairs);
+      s_pbase = pbase;
       s_fused = fused;
     }
   }

@@ -46,7 +46,7 @@ __global__ void __launch_bounds__(256) k_scan(ScanArgs a) {
   // a chunk, or too many chunks), unless the caller forces this path for everything.
   if (!a.force_two_pass && a.ws.hdr->n_unfused == 0) return;
   const int n_lh = a.n_layers * a.n_kv_heads;
-  const int n_chunks = a.ws.hdr->n_chunks;
+  const int n_chunks = hdr_chunks(a.ws.hdr->ranges);
   const uint32_t n_items = (uint32_t)n_lh * (uint32_t)n_chunks;
   const int n = a.n_q_heads / a.n_kv_heads;
   for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {

@@ -86,7 +86,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
   const int tid = threadIdx.x, lane = tid & 63, c16 = lane & 15, g = lane >> 4;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: everything derived from it is uniform control flow
   const int n_lh = a.n_layers * a.n_kv_heads;
-  const int n_pairs = a.ws.hdr->n_pairs;
+  const int n_pairs = hdr_pairs(a.ws.hdr->ranges);
   const uint32_t n_items = (uint32_t)n_lh * (uint32_t)n_pairs;
   const int n = a.n_q_heads / a.n_kv_heads;
   const int64_t tok_pitch = a.stride_tok * ESZ;
