@@ -12,6 +12,7 @@ constexpr int kD = SKIPKV_HEAD_DIM;  // head dimension
 constexpr int kChunkCap = 256;       // a chunk of scan work = a maximal run of whole sentences of at most this many tokens
 constexpr int kChunkMaxSent = 32;    // ... and at most this many sentences (a single longer sentence is a chunk of its own)
 constexpr int kFuseMaxChunks = 512;  // sequences with more chunks than this take the two-pass scan (see scan_fused.hip)
+constexpr int kAllMergeMax = 128;    // heads with at most this many scan items: every workgroup merges the head's records itself (see scan_fused.hip)
 constexpr uint32_t kRowNormUnset = 0xFFFFFFFFu;  // bit pattern no computed normaliser has (a NaN with full payload)
 constexpr float kRefInit = -3.0e38f;  // "no key seen yet" softmax reference, finite so that -inf - ref stays -inf
 constexpr int kRowBlock = 128;       // sentences per row block of the redundancy kernel
@@ -80,7 +81,7 @@ struct Workspace {
   int32_t *arrive;       // [LH, B] chunks of the head that have published their row statistics
   Chunk *chunks;         // [nc_max]
   RowBlock *rowblocks;   // [nrb_max]
-  float2 *stat_part;     // [LH, nc_max, R]  per-chunk (max, sum) of every query row, log2 domain
+  float2 *stat_part;     // [LH, nc_max, R]  per-chunk (max, sum) of every query row, log2 domain; the plan presets .x of the used records to kRowNormUnset
   float *row_norm;       // [LH, B, R]       log2 of the softmax normaliser of every query row; preset to kRowNormUnset by the plan
   uint16_t *vhat_hi;     // [LH, S_total, 128] bf16 high part of the unit sentence embedding
   uint16_t *vhat_lo;     // [LH, S_total, 128] bf16 low part (residual)

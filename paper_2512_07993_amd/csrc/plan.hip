@@ -4,6 +4,8 @@
 // layers and heads of the batch, so it is tiny.
 #include "common.h"
 
+#include <algorithm>
+
 namespace skipkv {
 
 __global__ void k_plan_reset(PlanHeader *hdr, int32_t *flags, int n_flags, uint32_t *row_norm_bits, int n_norm) {
@@ -140,11 +142,26 @@ __global__ void __launch_bounds__(256) k_plan(PlanArgs a) {
   }
 }
 
+// Marks the statistics records of all chunks of this step as "not written yet": the single-pass
+// scan polls them.  The number of chunks is only known on the device, so the grid covers the
+// capacity and the surplus exits.  grid = (x, LH); one thread writes two rows of a record at a time.
+__global__ void __launch_bounds__(256) k_plan_preset(Workspace ws) {
+  const int64_t n16 = (int64_t)hdr_chunks(ws.hdr->ranges) * ws.rows / 2;  // 16-byte pieces per head
+  uint4 *dst = reinterpret_cast<uint4 *>(ws.stat_part + (int64_t)blockIdx.y * ws.nc_max * ws.rows);
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (int64_t)gridDim.x * 256)
+    dst[i] = make_uint4(kRowNormUnset, 0u, kRowNormUnset, 0u);
+}
+
 hipError_t launch_plan(const PlanArgs &a, hipStream_t st) {
   const int n_flags = a.n_lh * a.batch;  // arrive counters
   hipLaunchKernelGGL(k_plan_reset, dim3(64), dim3(256), 0, st, a.ws.hdr, a.ws.arrive, n_flags,
                      reinterpret_cast<uint32_t *>(a.ws.row_norm), a.n_lh * a.batch * a.ws.rows);
-  if (a.batch > 0) hipLaunchKernelGGL(k_plan, dim3(a.batch), dim3(256), 0, st, a);
+  if (a.batch > 0) {
+    hipLaunchKernelGGL(k_plan, dim3(a.batch), dim3(256), 0, st, a);
+    const int64_t cap16 = (int64_t)a.ws.nc_max * a.ws.rows / 2;
+    const int gx = (int)std::min<int64_t>((cap16 + 255) / 256, std::max(32, 8192 / std::max(1, a.n_lh)));  // ~8192 workgroups in all
+    if (a.n_lh > 0 && cap16 > 0) hipLaunchKernelGGL(k_plan_preset, dim3(gx, a.n_lh), dim3(256), 0, st, a.ws);
+  }
   return hipGetLastError();
 }
 

@@ -36,7 +36,7 @@
 #include "scan_dev.h"
 
 #ifndef SKIPKV_FRAG_AHEAD
-#define SKIPKV_FRAG_AHEAD 1  // slices of query fragments read ahead of the matrix instructions (2 needs more registers than there are)
+#define SKIPKV_FRAG_AHEAD 3  // query fragments are read this many matrix instructions ahead of their use
 #endif
 
 namespace skipkv {
@@ -247,7 +247,9 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
       const float u0 = k0 * inv, u1 = k1 * inv;
       const uint32_t hi = pack_bf16x2(u0, u1);  // round to nearest even, both halves in one instruction
       const uint32_t lo = pack_bf16x2(u0 - __uint_as_float(hi << 16), u1 - __uint_as_float(hi & 0xFFFF0000u));
-      const int64_t o = ((int64_t)lh * a.total_sentences + sent_col0 + s_idx) * (kD / 2) + lane;
+      // the lane's part of the address is formed here, from an opaque copy: kept across the item it
+      // could be spilled, and its reload would wait for every key load in flight
+      const int64_t o = ((int64_t)lh * a.total_sentences + sent_col0 + s_idx) * (kD / 2) + opaque(lane);
       reinterpret_cast<uint32_t *>(a.ws.vhat_hi)[o] = hi;
       reinterpret_cast<uint32_t *>(a.ws.vhat_lo)[o] = lo;
     };
@@ -288,31 +290,30 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
 
             // ---- logits of this stage's 16 tokens against all query rows
             if constexpr (DT == SKIPKV_BF16) {
-              // Fragment reads run AHEAD slices of the head dimension ahead of the matrix
-              // instructions that use them (the order is pinned, the compiler would otherwise read
-              // each fragment right before its use and pay the LDS latency every time).
-              constexpr int AHEAD = SKIPKV_FRAG_AHEAD;
-              const char *brow = stage + c16 * ROWB;
+              // Fragment reads run AHEAD matrix instructions ahead of their use (the order is
+              // pinned: the compiler would otherwise read each fragment right before its use and pay
+              // the LDS latency every time, or read all of them first and run out of registers).
+              // Step i multiplies slice i / NT of the head dimension into row tile i % NT.
+              constexpr int AHEAD = SKIPKV_FRAG_AHEAD, NSTEP = 4 * NT;
+              // key row c16, piece (4g + kk) ^ c16: the stage buffers are 256-byte aligned, so the slice
+              // index is an XOR on bits 4..5 of one address per lane (no address register per slice)
+              const uint32_t baddr = lds_addr(stage) + c16 * ROWB + (((4 * g) ^ c16) << 4);
               const char *arow = qt + c16 * LSTR + g * 64;
-              bf16x8 bfr[4], afr[4][NT];
+              auto rd_a = [&](int i) { return *reinterpret_cast<const bf16x8 *>(arow + 16 * (i % NT) * LSTR + (i / NT) * 16); };
+              auto rd_b = [&](int kk) {
+                return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8 *>((uintptr_t)(baddr ^ (kk << 4)));
+              };
+              bf16x8 bfr[4], afr[NSTEP];
+              bfr[0] = rd_b(0);
 #pragma unroll
-              for (int kk = 0; kk < 4; ++kk) bfr[kk] = *reinterpret_cast<const bf16x8 *>(brow + (((4 * g + kk) ^ c16) * 16));
-#pragma unroll
-              for (int kk = 0; kk < AHEAD; ++kk)
-#pragma unroll
-                for (int T = 0; T < NT; ++T) afr[kk][T] = *reinterpret_cast<const bf16x8 *>(arow + 16 * T * LSTR + kk * 16);
+              for (int i = 0; i < AHEAD && i < NSTEP; ++i) afr[i] = rd_a(i);
               __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-              for (int kk = 0; kk < 4; ++kk) {
-                if (kk + AHEAD < 4) {
-#pragma unroll
-                  for (int T = 0; T < NT; ++T)
-                    afr[kk + AHEAD][T] = *reinterpret_cast<const bf16x8 *>(arow + 16 * T * LSTR + (kk + AHEAD) * 16);
-                }
+              for (int i = 0; i < NSTEP; ++i) {
+                if (i + AHEAD < NSTEP) afr[i + AHEAD] = rd_a(i + AHEAD);
+                if (i % NT == 0 && i / NT + 1 < 4) bfr[i / NT + 1] = rd_b(i / NT + 1);
                 __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int T = 0; T < NT; ++T)
-                  acc[k][st][T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afr[kk][T], bfr[kk], acc[k][st][T], 0, 0, 0);
+                acc[k][st][i % NT] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afr[i], bfr[i / NT], acc[k][st][i % NT], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
               }
             } else {
@@ -477,6 +478,11 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     // The last wave does it, lane = query row: no sentence that crosses a wave boundary starts in
     // its range, so it has nothing else to do while the other waves piece those together.
     static_assert(R <= 64, "the record is written by one wave: only that wave waits for the acknowledgement");
+    // Heads of at most kAllMergeMax items: no arrive counter and no merging workgroup.  Every
+    // workgroup of the head polls the head's records (the plan has preset them to a marker) and
+    // merges them itself, so nobody waits for one workgroup's merge and there is no
+    // acknowledgement + counter + publication chain between the last record and the readers.
+    const bool all_merge = cur.np <= kAllMergeMax;
     int arrived = 0;
     if (wave == 3) {
       if (lane < R) {
@@ -488,8 +494,10 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
         for (int w = 0; w < 4; ++w) s += wstat[w][lane][1] * __builtin_amdgcn_exp2f(wstat[w][lane][0] - m);
         coherent_store2(&a.ws.stat_part[((int64_t)lh * a.ws.nc_max + cur.c0) * R + lane], make_float2(m, s));
       }
-      wait_all();  // the statistics are acknowledged (the other waves keep their key loads in flight)
-      if (lane == 0) arrived = __hip_atomic_fetch_add(&a.ws.arrive[lhb], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (!all_merge) {
+        wait_all();  // the statistics are acknowledged (the other waves keep their key loads in flight)
+        if (lane == 0) arrived = __hip_atomic_fetch_add(&a.ws.arrive[lhb], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
     }
     // ---- sentences that cross wave boundaries: the wave in whose range one starts pieces it together
 #pragma unroll
@@ -512,21 +520,32 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
       }
     }
     q_commit(nxt, nq, par ^ 1);
-    if (tid == 192) s_flag = (arrived == cur.np - 1);
+    if (tid == 192) s_flag = all_merge || (arrived == cur.np - 1);
     lds_barrier();
     float *rn = a.ws.row_norm + (int64_t)lhb * R;
-    if (s_flag) {  // last share of the head to arrive: merge the partials into the normalisers
-      // lane = query row, wave w takes items w, w+4, ...; 8 independent loads in flight per lane
+    if (s_flag) {  // merge the head's partials into the normalisers (every share, or the last one to arrive)
+      // lane = query row, wave w takes items w, w+4, ...; 8 independent loads in flight per lane.
+      // A record that has not been written yet still holds the plan's marker: load again.
       const int c_first = cur.c_first, np = cur.np;
-      for (int r = lane; r < R; r += 64) {
+      for (int r = opaque(lane); r < R; r += 64) {
         float m = kRefInit, s = 0.f;
         for (int pp = wave; pp < np; pp += 32) {
           float2 pv[8];
+          for (int polls = 0;; ++polls) {
+            bool ok = true;
 #pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            pv[u] = make_float2(kRefInit, 0.f);
-            if (pp + 4 * u < np)
-              pv[u] = coherent_load2(&a.ws.stat_part[((int64_t)lh * a.ws.nc_max + c_first + 2 * (pp + 4 * u)) * R + r]);
+            for (int u = 0; u < 8; ++u) {
+              pv[u] = make_float2(kRefInit, 0.f);
+              if (pp + 4 * u < np)
+                pv[u] = coherent_load2(&a.ws.stat_part[((int64_t)lh * a.ws.nc_max + c_first + 2 * (pp + 4 * u)) * R + r]);
+              ok = ok && __float_as_uint(pv[u].x) != kRowNormUnset;
+            }
+            if (__all(ok)) break;
+            if (polls >= a.spin_limit) {
+              if (lane == 0 && a.dev_status) atomicOr(a.dev_status, SKIPKV_DEV_TIMEOUT);
+              break;
+            }
+            __builtin_amdgcn_s_sleep(1);
           }
 #pragma unroll
           for (int u = 0; u < 8; ++u) {
@@ -547,7 +566,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
 #pragma unroll
         for (int w = 0; w < 4; ++w) ss += wstat[w][r][1] * __builtin_amdgcn_exp2f(wstat[w][r][0] - mm);
         const float v = ss > 0.f ? mm + __builtin_amdgcn_logf(ss) : INFINITY;  // log2 of the softmax normaliser
-        coherent_store(&rn[r], v);
+        if (!all_merge) coherent_store(&rn[r], v);  // for the workgroups that poll
         row_norm_l[r] = v;  // this workgroup uses its own copy
       }
       // no flag: the readers poll the rows themselves, which the plan has preset to a marker
@@ -558,7 +577,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
       for (int polls = 0;; ++polls) {
         const uint32_t u = lane < R ? __hip_atomic_load(&rn_bits[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
         const bool done = __all(u != kRowNormUnset);
-        if (done || polls > a.spin_limit) {
+        if (done || polls >= a.spin_limit) {
           if (!done && lane == 0 && a.dev_status) atomicOr(a.dev_status, SKIPKV_DEV_TIMEOUT);
           if (lane < R) row_norm_l[opaque(lane)] = __uint_as_float(u);
           break;
