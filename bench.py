@@ -27,7 +27,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch measured with rocprofv3 counters (FETCH_SIZE and WRITE_SIZE, each scaled by what
 # the same counter reads for a copy of known size; profiles/scan_fused_config3_hbm_traffic.txt).
 # Only for the workload they were measured on.
-MEASURED_TRAFFIC = {(3, "scan_fused"): 11.80e9, (3, "compact"): 8.40e9}
+MEASURED_TRAFFIC = {(3, "scan_fused"): 12.18e9, (3, "compact"): 8.40e9}
 
 
 def _oracle_worker(args):

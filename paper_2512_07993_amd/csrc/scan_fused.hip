@@ -71,6 +71,10 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
   constexpr int RPL = 64 / PPR;                       // rows covered by one direct load
   constexpr int NBUF = (DT == SKIPKV_BF16) ? 3 : 2;   // stage buffers per wave
   constexpr int STAGEB = kStageRows * ROWB;
+  // bf16 keys are pooled by matrix products with an indicator whose ones are written as 2.0 (a
+  // single bit, cheap to build from a row mask): all key sums of that path carry this factor,
+  // which the normalisation to a unit vector removes.
+  constexpr float kPoolScale = (DT == SKIPKV_BF16) ? 2.f : 1.f;
 
   __shared__ __align__(256) char kt[4][NBUF][STAGEB];  // 256-byte aligned: the row swizzle is applied as an XOR on address bits
   __shared__ __align__(16) char qt[R * LSTR];
@@ -81,7 +85,6 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
   __shared__ float imp[2][kChunkCap];
   __shared__ int s_flag;
   __shared__ float row_norm_l[R];
-  __shared__ uint2 ind_tab[16];  // entry n: four bf16, element j = 1.0 if bit j of n is set (indicator rows of the pooling products)
 
   const int tid = threadIdx.x, lane = tid & 63, c16 = lane & 15, g = lane >> 4;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: everything derived from it is uniform control flow
@@ -218,7 +221,6 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
 
   Pair cur = load_pair(blockIdx.x);
   if (cur.item >= n_items) return;
-  if (tid < 16) ind_tab[tid] = make_uint2(((tid & 1) ? 0x3F80u : 0u) | ((tid & 2) ? 0x3F800000u : 0u), ((tid & 4) ? 0x3F80u : 0u) | ((tid & 8) ? 0x3F800000u : 0u));
 #pragma unroll
   for (int i = 0; i < NBUF - 1; ++i) issue_next();
   uint32_t cmp_cnt = 0;  // stages computed so far (ring position)
@@ -243,7 +245,8 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     auto emit_sentence = [&](int len, int sent_col0, int s_idx, float k0, float k1) {  // unit embedding, bf16 hi + lo
       // mean / (|mean| + eps) = sum / (|sum| + eps * len): no division by the length.  1-ulp
       // reciprocal and square root: a common scale error of ~1e-7 on the unit vector
-      const float inv = __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(wave_sum_fast(k0 * k0 + k1 * k1)) + 1e-12f * (float)len);
+      // (bf16 keys: the sums arrive scaled by kPoolScale, and so does the epsilon)
+      const float inv = __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(wave_sum_fast(k0 * k0 + k1 * k1)) + (1e-12f * kPoolScale) * (float)len);
       const float u0 = k0 * inv, u1 = k1 * inv;
       const uint32_t hi = pack_bf16x2(u0, u1);  // round to nearest even, both halves in one instruction
       const uint32_t lo = pack_bf16x2(u0 - __uint_as_float(hi << 16), u1 - __uint_as_float(hi & 0xFFFF0000u));
@@ -414,7 +417,11 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
                   if (hi_t > lo_t) rows = ((1u << (hi_t - ts)) - 1u) & ~((1u << (lo_t - ts)) - 1u);
 #pragma unroll
                   for (int q = 0; q < kStageRows / 4; ++q) {
-                    const uint2 ind = ind_tab[(rows >> (4 * q)) & 15u];
+                    // indicator of rows 4q .. 4q+3 as four bf16 values 2.0 (= bit 14 alone) or 0: row bits
+                    // 4q, 4q+1 go to bits 14 and 30 of the first word, 4q+2, 4q+3 of the second one, by
+                    // shifts and one mask each (every other bit that the shifts bring along is masked off)
+                    const uint2 ind = make_uint2(((rows << (14 - 4 * q)) | (rows << (29 - 4 * q))) & 0x40004000u,
+                                                 ((rows << (12 - 4 * q)) | (rows << (27 - 4 * q))) & 0x40004000u);
                     const bf16x4_t av = __builtin_bit_cast(bf16x4_t, ind);
                     // tokens 4q .. 4q+3 of the even column (low halves) and of the odd column (high halves)
                     const uint2 be = make_uint2(__builtin_amdgcn_perm(xw[4 * q + 1], xw[4 * q], 0x05040100u),
