@@ -94,3 +94,13 @@ def test_config5_full_size_sampled_heads():
     the two-pass scan) on sampled heads."""
     stats = _run_and_compare(W.CONFIGS[5], 6, seed=5)
     assert stats["heads"] == 6
+
+
+def test_long_sequences_counter_protocol_next_to_short_ones():
+    """Sequences of more than 128 scan items (here 75 K and 99 K tokens: 160 and 211 items) exchange
+    their row statistics through the arrive counter and one merging workgroup, shorter ones (55 K
+    tokens: 118 items) have every workgroup merge the records itself; one launch holds both."""
+    cfg = W.CONFIGS[3].scaled(n_layers=1, batch=3, n_kv_heads=2, n_q_heads=8, len_lo=30000, len_hi=100000,
+                              sent_mean=40.0)
+    stats = _run_and_compare(cfg, 6, seed=7)
+    assert stats["heads"] == 6
