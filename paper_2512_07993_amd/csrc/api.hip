@@ -149,7 +149,7 @@ int do_score(Timer &tm, const skipkv_cache *c, const skipkv_params *p, const Row
   // two-pass scan; SKIPKV_SPIN_LIMIT bounds the polls of the single-pass scan's wait.
   const char *env_two = std::getenv("SKIPKV_FORCE_TWO_PASS");
   const char *env_spin = std::getenv("SKIPKV_SPIN_LIMIT");
-  sa.force_two_pass = (env_two && env_two[0] == '1') || !scan_fused_supported(rl);
+  sa.force_two_pass = (env_two && env_two[0] == '1') || !scan_fused_supported(rl, c->stride_tok * (c->dtype == SKIPKV_BF16 ? 2 : 4));
   sa.spin_limit = env_spin ? std::atoi(env_spin) : 4000000;
   sa.dev_status = p->dev_status;
   sa.virt_hk = hv.virt_hk;

@@ -170,7 +170,7 @@ struct ScanArgs {
   int32_t virt_hk, virt_b;
   int32_t no_pool;  // 1: sentence embeddings are not needed (lambda comes from elsewhere): skip the key pooling
 };
-bool scan_fused_supported(const RowLayout &rl);
+bool scan_fused_supported(const RowLayout &rl, int64_t row_pitch_bytes);
 hipError_t launch_scan_fused(const ScanArgs &a, hipStream_t st);    // single pass over K (sequences the plan marked fused)
 hipError_t launch_scan_stats(const ScanArgs &a, hipStream_t st);    // pass A: row statistics + sentence embeddings
 hipError_t launch_row_norm(const ScanArgs &a, hipStream_t st);      // combine the per-chunk statistics

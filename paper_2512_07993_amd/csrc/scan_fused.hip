@@ -69,7 +69,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
   constexpr int PPR = ROWB / 16;                      // 16-byte pieces per row
   constexpr int GL = kStageRows * PPR / 64;           // direct loads per stage
   constexpr int RPL = 64 / PPR;                       // rows covered by one direct load
-  constexpr int NBUF = (DT == SKIPKV_BF16) ? 3 : 2;   // stage buffers per wave
+  constexpr int NBUF = 2;                             // stage buffers per wave (a third one gains nothing: memory latency does not pace the waves)
   constexpr int STAGEB = kStageRows * ROWB;
   // bf16 keys are pooled by matrix products with an indicator whose ones are written as 2.0 (a
   // single bit, cheap to build from a row mask): all key sums of that path carry this factor,
@@ -207,12 +207,17 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     const int w1 = iss_k ? iss.ch[1].w1 : iss.ch[0].w1;
     int ln = lane;
     asm volatile("" : "+v"(ln));  // opaque copy: the per-load address parts are recomputed here rather than kept live across the item
+    // scalar 64-bit base of the stage + a 32-bit offset per lane (one 24-bit multiply; the launcher
+    // only takes this kernel for row pitches below 2^24 bytes): no 64-bit multiplies per load
+    const char *sbase = iss.kbase + (int64_t)ts * tok_pitch;
+    const int last = w1 - 1 - ts;  // rows past the range re-read its last row (masked later)
+    const uint32_t pitch32 = (uint32_t)tok_pitch;
 #pragma unroll
     for (int j = 0; j < GL; ++j) {
       const int row = j * RPL + ln / PPR;         // row of the stage this lane's 16 bytes belong to
       const int piece = (ln % PPR) ^ (row & 15);    // swizzle: LDS position (lane % PPR) holds this global piece
-      const int t = min(ts + row, w1 - 1);          // rows past the range re-read its last row (masked later)
-      load_to_lds_16(iss.kbase + (int64_t)t * tok_pitch + piece * 16, dst + j * 1024);
+      const uint32_t off = __umul24((uint32_t)min(row, last), pitch32) + (uint32_t)piece * 16u;
+      load_to_lds_16(sbase + off, dst + j * 1024);
     }
     ++iss_st;
     ++iss_cnt;
@@ -689,7 +694,9 @@ hipError_t launch_one(const ScanArgs &a, hipStream_t st) {
 
 }  // namespace
 
-bool scan_fused_supported(const RowLayout &rl) { return rl.nt <= 4; }
+bool scan_fused_supported(const RowLayout &rl, int64_t row_pitch_bytes) {
+  return rl.nt <= 4 && row_pitch_bytes > 0 && row_pitch_bytes < (1 << 24);  // the key loads form lane offsets with a 24-bit multiply
+}
 
 hipError_t launch_scan_fused(const ScanArgs &a, hipStream_t st) {
   if ((int64_t)a.n_layers * a.n_kv_heads * a.batch == 0 || a.force_two_pass) return hipSuccess;
