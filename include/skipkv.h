@@ -62,7 +62,8 @@ enum {
   SKIPKV_DEV_BAD_OFFSETS = 1,  /* sentence offsets not strictly ascending from 0 to N_b   */
   SKIPKV_DEV_TOO_MANY_SENT = 2, /* a sequence has more than SKIPKV_MAX_SENTENCES sentences */
   SKIPKV_DEV_TIMEOUT = 4,       /* a bounded cross-workgroup wait ran out: scores are invalid  */
-  SKIPKV_DEV_TOO_MANY_TOK = 8   /* skipkv_select_tokens: a sequence is longer than SKIPKV_MAX_TOKENS_TOKEN_SELECT */
+  SKIPKV_DEV_TOO_MANY_TOK = 8,  /* skipkv_select_tokens: a sequence is longer than SKIPKV_MAX_TOKENS_TOKEN_SELECT */
+  SKIPKV_DEV_BAD_BLOCK_TABLE = 16 /* paged cache: a block id outside [0, n_blocks); that sequence's K/V are left untouched */
 };
 
 typedef enum { SKIPKV_F32 = 0, SKIPKV_BF16 = 1 } skipkv_dtype;
@@ -287,6 +288,45 @@ int skipkv_score_shared(const skipkv_cache *cache, const skipkv_params *params, 
 int skipkv_redundancy_workspace_bytes(const skipkv_cache *cache, size_t *out_bytes);
 int skipkv_token_redundancy(const skipkv_cache *cache, float *tok_redundancy, void *ws, size_t ws_bytes,
                             void *stream);
+
+/*
+ * Paged KV cache (Appendix, "System-Level Evaluation on vLLM": continuous batching with a paged
+ * KV cache).  K and V are pools of blocks of block_size token slots, and logical token t of
+ * sequence b lives in block block_table[b * table_stride + t / block_size] at slot
+ * t % block_size:
+ *   element offset of (layer l, KV head h, block p, slot s) =
+ *       l * cache->stride_layer + h * cache->stride_head + p * stride_block + s * cache->stride_tok
+ * with cache->k and cache->v pointing at the pools.  This covers [blocks, slots, heads, 128]
+ * (stride_tok = heads * 128, stride_head = 128) as well as [blocks, heads, slots, 128].  Everything
+ * else in skipkv_cache keeps its meaning: seq_off numbers the LOGICAL tokens of the batch
+ * consecutively, and every per-token and per-sentence array uses that numbering.
+ */
+typedef struct skipkv_paging {
+  const int32_t *block_table; /* device [batch, table_stride]; the first ceil(N_b / block_size) entries of row b are read */
+  int32_t table_stride;       /* entries per row                                               */
+  int32_t block_size;         /* token slots per block, >= 1                                   */
+  int32_t n_blocks;           /* blocks in the pools: valid ids are 0 .. n_blocks-1            */
+  int64_t stride_block;       /* elements; a multiple of cache->stride_tok                     */
+} skipkv_paging;
+
+/* Device scratch for skipkv_step_paged (the workspace of skipkv_step plus the row map).       */
+int skipkv_paged_workspace_bytes(const skipkv_cache *cache, const skipkv_paging *paging, const skipkv_params *params,
+                                 size_t *out_bytes);
+
+/*
+ * skipkv_step on a paged cache: same scores, same selection, and the compaction moves rows between
+ * slots, K[slot of k] <- K[slot of kept_idx[k]] for k < new_len, bit for bit; the block table is
+ * not changed (afterwards the caller may release the blocks that lie wholly beyond the new
+ * lengths).  Outputs and their layouts are those of skipkv_step.  A row map (logical token ->
+ * slot) is built first; a block id outside [0, n_blocks) raises SKIPKV_DEV_BAD_BLOCK_TABLE, is
+ * read as block 0, and the sequence's K and V are not touched.  The key scan takes its two-pass
+ * form on a paged cache.
+ */
+int skipkv_step_paged(const skipkv_cache *cache, const skipkv_paging *paging, const skipkv_params *params,
+                      const void *q_obs, const float *tok_redundancy, float *sent_score, float *sent_lambda,
+                      float *tok_importance, uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len,
+                      int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride, void *ws, size_t ws_bytes,
+                      void *stream);
 
 /*
  * Steering injection (Sec. 4.2): hidden[b, :] <- hidden[b, :] + coef_b * vec for every row b

@@ -16,7 +16,7 @@ import torch
 
 F32, BF16 = 0, 1
 OK, EINVAL, EBUDGET, ECAPACITY, EWORKSPACE, EHIP = 0, -1, -2, -3, -4, -5
-DEV_BAD_OFFSETS, DEV_TOO_MANY_SENT, DEV_TIMEOUT, DEV_TOO_MANY_TOK = 1, 2, 4, 8
+DEV_BAD_OFFSETS, DEV_TOO_MANY_SENT, DEV_TIMEOUT, DEV_TOO_MANY_TOK, DEV_BAD_BLOCK_TABLE = 1, 2, 4, 8, 16
 PROFILE_SLOTS = 16
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libskipkv.so")
@@ -36,6 +36,11 @@ class CCache(C.Structure):
 
 class CRanges(C.Structure):
     _fields_ = [("len", C.c_void_p), ("sent_cnt", C.c_void_p), ("sent_off", C.c_void_p)]
+
+
+class CPaging(C.Structure):
+    _fields_ = [("block_table", C.c_void_p), ("table_stride", C.c_int32), ("block_size", C.c_int32),
+                ("n_blocks", C.c_int32), ("stride_block", C.c_int64)]
 
 
 class CParams(C.Structure):
@@ -75,6 +80,9 @@ def lib() -> C.CDLL:
         L.skipkv_ranges_workspace_bytes.argtypes = [cp, pp, C.POINTER(sz)]
         L.skipkv_ranges_append.argtypes = [cp, rp, vp, vp, vp, vp, vp]
         L.skipkv_step_ranges.argtypes = [cp, rp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+        gp = C.POINTER(CPaging)
+        L.skipkv_paged_workspace_bytes.argtypes = [cp, gp, pp, C.POINTER(sz)]
+        L.skipkv_step_paged.argtypes = [cp, gp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
         L.skipkv_profile_create.argtypes = [C.POINTER(vp)]
         L.skipkv_profile_read.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_char_p), C.POINTER(fl)]
         L.skipkv_profile_destroy.argtypes = [vp]
@@ -85,6 +93,7 @@ def lib() -> C.CDLL:
                      "skipkv_steer_add", "skipkv_redundancy_workspace_bytes", "skipkv_token_redundancy",
                      "skipkv_select_tokens", "skipkv_ranges_workspace_bytes", "skipkv_ranges_append", "skipkv_step_ranges",
                      "skipkv_similarity_workspace_bytes", "skipkv_sentence_similarity", "skipkv_score_shared", "skipkv_steer_strength",
+                     "skipkv_paged_workspace_bytes", "skipkv_step_paged",
                      "skipkv_profile_create", "skipkv_profile_read", "skipkv_profile_destroy",
                      "skipkv_version"):
             getattr(L, name).restype = C.c_int
@@ -251,6 +260,49 @@ def skipkv_step_ranges(cache: Cache, ranges: Ranges, params: Params, q_obs, tok_
                                     _ptr(sent_keep), _ptr(kept_idx), _ptr(new_len), _ptr(new_sent_off),
                                     _ptr(new_sent_cnt), kept_stride, _ptr(ws),
                                     ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
+
+
+@dataclass
+class PagedCache:
+    """Python mirror of skipkv_cache + skipkv_paging for pools laid out [L, blocks, slots, Hk, D]
+    (any strides with D contiguous); seq_off numbers the logical tokens."""
+    k: torch.Tensor
+    v: torch.Tensor
+    block_table: torch.Tensor  # int32 device [B, table_stride]
+    n_q_heads: int
+    seq_off: torch.Tensor
+    sent_ptr: torch.Tensor
+    sent_off: torch.Tensor
+    total_tokens: int
+    total_sentences: int
+
+    def c(self) -> CCache:
+        k = self.k
+        assert k.dim() == 5 and k.stride(4) == 1 and self.v.stride() == k.stride() and self.v.shape == k.shape
+        return CCache(k.data_ptr(), self.v.data_ptr(), k.stride(0), k.stride(3), k.stride(2), dtype_code(k.dtype),
+                      k.shape[0], k.shape[3], self.n_q_heads, k.shape[4], int(self.seq_off.numel()) - 1,
+                      self.total_tokens, self.total_sentences,
+                      _ptr(self.seq_off), _ptr(self.sent_ptr), _ptr(self.sent_off))
+
+    def paging(self) -> CPaging:
+        bt = self.block_table
+        assert bt.dim() == 2 and bt.dtype == torch.int32 and bt.stride(1) == 1
+        return CPaging(bt.data_ptr(), bt.stride(0), self.k.shape[2], self.k.shape[1], self.k.stride(1))
+
+
+def skipkv_paged_workspace_bytes(cache: PagedCache, params: Params) -> int:
+    out = C.c_size_t(0)
+    _check(lib().skipkv_paged_workspace_bytes(C.byref(cache.c()), C.byref(cache.paging()), C.byref(params.c()), C.byref(out)))
+    return int(out.value)
+
+
+def skipkv_step_paged(cache: PagedCache, params: Params, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance,
+                      sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride: int, ws, stream=None) -> None:
+    _check(lib().skipkv_step_paged(C.byref(cache.c()), C.byref(cache.paging()), C.byref(params.c()), _ptr(q_obs),
+                                   _ptr(tok_redundancy), _ptr(sent_score), _ptr(sent_lambda), _ptr(tok_importance),
+                                   _ptr(sent_keep), _ptr(kept_idx), _ptr(new_len), _ptr(new_sent_off),
+                                   _ptr(new_sent_cnt), kept_stride, _ptr(ws),
+                                   ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
 
 
 def skipkv_similarity_workspace_bytes(cache: Cache, d_model: int) -> int:

@@ -13,7 +13,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libskipkv.so")
-SOURCES = ["api.hip", "plan.hip", "scan.hip", "scan_fused.hip", "cosine.hip", "select.hip", "tokred.hip", "compact.hip", "steer.hip", "ranges.hip", "hidden.hip"]
+SOURCES = ["api.hip", "plan.hip", "scan.hip", "scan_fused.hip", "cosine.hip", "select.hip", "tokred.hip", "compact.hip", "steer.hip", "ranges.hip", "hidden.hip", "paged.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -95,6 +95,7 @@ Workspace carve(const skipkv_cache *c, const RowLayout &rl, void *base) {
 struct HeadView {
   const int32_t *len = nullptr, *cnt = nullptr;
   int32_t virt_hk = 0, virt_b = 0;
+  const int32_t *row_map = nullptr;  // paged cache: logical token -> slot row
 };
 
 struct Timer {
@@ -149,7 +150,8 @@ int do_score(Timer &tm, const skipkv_cache *c, const skipkv_params *p, const Row
   // two-pass scan; SKIPKV_SPIN_LIMIT bounds the polls of the single-pass scan's wait.
   const char *env_two = std::getenv("SKIPKV_FORCE_TWO_PASS");
   const char *env_spin = std::getenv("SKIPKV_SPIN_LIMIT");
-  sa.force_two_pass = (env_two && env_two[0] == '1') || !scan_fused_supported(rl, c->stride_tok * (c->dtype == SKIPKV_BF16 ? 2 : 4));
+  sa.row_map = hv.row_map;
+  sa.force_two_pass = hv.row_map != nullptr || (env_two && env_two[0] == '1') || !scan_fused_supported(rl, c->stride_tok * (c->dtype == SKIPKV_BF16 ? 2 : 4));
   sa.spin_limit = env_spin ? std::atoi(env_spin) : 4000000;
   sa.dev_status = p->dev_status;
   sa.virt_hk = hv.virt_hk;
@@ -227,8 +229,10 @@ int do_select(Timer &tm, const skipkv_cache *c, const skipkv_params *p, const fl
 }
 
 int do_compact(Timer &tm, const skipkv_cache *c, const int32_t *kept_idx, const int32_t *new_len, int32_t kept_stride,
-               hipStream_t st) {
+               hipStream_t st, const int32_t *row_map = nullptr, const int32_t *seq_bad = nullptr) {
   CompactArgs a{};
+  a.row_map = row_map;
+  a.seq_bad = seq_bad;
   a.k = c->k;
   a.v = c->v;
   a.stride_layer = c->stride_layer;
@@ -429,6 +433,85 @@ int skipkv_step(const skipkv_cache *cache, const skipkv_params *params, const vo
   rc = do_select(tm, cache, params, sent_score, sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride, st);
   if (rc) return rc;
   return do_compact(tm, cache, kept_idx, new_len, kept_stride, st);
+}
+
+namespace {
+// Validation of a paged cache's description, and where the row map and the per-sequence flags sit
+// behind the step's workspace.
+struct PagedView {
+  size_t step_bytes, map_bytes, total;
+  int32_t rows_per_block;
+};
+int check_paging(const skipkv_cache *c, const skipkv_paging *pg, const RowLayout &rl, PagedView *v) {
+  if (!pg) return SKIPKV_EINVAL;
+  if (pg->block_size < 1 || pg->n_blocks < 1 || pg->table_stride < 0 || pg->stride_block < 0) return SKIPKV_EINVAL;
+  if (!pg->block_table && c->total_tokens > 0) return SKIPKV_EINVAL;
+  if (c->stride_tok <= 0 || pg->stride_block % c->stride_tok) return SKIPKV_EINVAL;
+  const int64_t rpb = pg->stride_block / c->stride_tok;
+  if (rpb < pg->block_size) return SKIPKV_EINVAL;  // the slots of a block must not reach into the next one
+  if ((int64_t)pg->n_blocks * rpb > 0x7FFFFFFFll) return SKIPKV_ECAPACITY;  // slot rows are 32-bit
+  v->rows_per_block = (int32_t)rpb;
+  const Workspace w = carve(c, rl, nullptr);
+  if (!w.fits) return SKIPKV_ECAPACITY;
+  v->step_bytes = align_up(w.bytes);
+  v->map_bytes = align_up((size_t)c->total_tokens * 4);
+  v->total = v->step_bytes + v->map_bytes + align_up((size_t)c->batch * 4);
+  return SKIPKV_OK;
+}
+}  // namespace
+
+int skipkv_paged_workspace_bytes(const skipkv_cache *cache, const skipkv_paging *paging, const skipkv_params *params,
+                                 size_t *out_bytes) {
+  if (!out_bytes) return SKIPKV_EINVAL;
+  int rc = check_cache(cache, true);
+  if (rc) return rc;
+  RowLayout rl;
+  rc = check_params(cache, params, &rl);
+  if (rc) return rc;
+  if (is_empty(cache)) {
+    *out_bytes = 0;
+    return SKIPKV_OK;
+  }
+  PagedView pv;
+  rc = check_paging(cache, paging, rl, &pv);
+  if (rc) return rc;
+  *out_bytes = pv.total;
+  return SKIPKV_OK;
+}
+
+int skipkv_step_paged(const skipkv_cache *cache, const skipkv_paging *paging, const skipkv_params *params,
+                      const void *q_obs, const float *tok_redundancy, float *sent_score, float *sent_lambda,
+                      float *tok_importance, uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len,
+                      int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride, void *ws, size_t ws_bytes,
+                      void *stream) {
+  RowLayout rl;
+  int rc = check_cache(cache, true);
+  if (rc) return rc;
+  rc = check_params(cache, params, &rl);
+  if (rc) return rc;
+  rc = check_select_args(cache, params, &rl, sent_score, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride);
+  if (rc) return rc;
+  if (is_empty(cache)) return SKIPKV_OK;
+  if (!q_obs || !aligned16(q_obs)) return SKIPKV_EINVAL;
+  if (cache->total_sentences > 0 && (!sent_score || !sent_lambda)) return SKIPKV_EINVAL;
+  PagedView pv;
+  rc = check_paging(cache, paging, rl, &pv);
+  if (rc) return rc;
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < pv.total) return SKIPKV_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Timer tm(params->profile, st);
+  int32_t *row_map = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + pv.step_bytes);
+  int32_t *seq_bad = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + pv.step_bytes + pv.map_bytes);
+  RowMapArgs ra{cache->seq_off, paging->block_table, cache->batch, paging->table_stride, paging->block_size,
+                paging->n_blocks, pv.rows_per_block, row_map, seq_bad, params->dev_status};
+  if (tm.run("row_map", [&] { return launch_row_map(ra, st); }) != hipSuccess) return SKIPKV_EHIP;
+  HeadView hv;
+  hv.row_map = row_map;
+  rc = do_score(tm, cache, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, ws, st, hv);
+  if (rc) return rc;
+  rc = do_select(tm, cache, params, sent_score, sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride, st);
+  if (rc) return rc;
+  return do_compact(tm, cache, kept_idx, new_len, kept_stride, st, row_map, seq_bad);
 }
 
 int skipkv_ranges_workspace_bytes(const skipkv_cache *cache, const skipkv_params *params, size_t *out_bytes) {

@@ -169,6 +169,9 @@ struct ScanArgs {
   // rows are still laid out by the real (l, b, h).  virt_hk = real H_k (0: off), virt_b = real B.
   int32_t virt_hk, virt_b;
   int32_t no_pool;  // 1: sentence embeddings are not needed (lambda comes from elsewhere): skip the key pooling
+  // Paged cache (two-pass scan only): row_map[seq_off[b] + t] = slot row of logical token t, in units of
+  // stride_tok from the head's base; null for a contiguous cache.
+  const int32_t *row_map;
 };
 bool scan_fused_supported(const RowLayout &rl, int64_t row_pitch_bytes);
 hipError_t launch_scan_fused(const ScanArgs &a, hipStream_t st);    // single pass over K (sequences the plan marked fused)
@@ -217,8 +220,19 @@ struct CompactArgs {
   int64_t stride_layer, stride_head, stride_tok;
   int32_t dtype, n_layers, n_kv_heads, batch, kept_stride;
   const int32_t *seq_off, *kept_idx, *new_len;
+  const int32_t *row_map;  // paged cache: logical token -> slot row (see ScanArgs); null: contiguous
+  const int32_t *seq_bad;  // paged cache, [batch]: nonzero = invalid block table, leave the sequence alone
 };
 hipError_t launch_compact(const CompactArgs &a, hipStream_t st);
+
+// Paged cache: row_map[seq_off[b] + t] = block_table[b][t / block_size] * rows_per_block + t % block_size
+// for every logical token; block ids outside [0, n_blocks) are flagged (dev_status, seq_bad[b]) and read as 0.
+struct RowMapArgs {
+  const int32_t *seq_off, *block_table;
+  int32_t batch, table_stride, block_size, n_blocks, rows_per_block;
+  int32_t *row_map, *seq_bad, *dev_status;
+};
+hipError_t launch_row_map(const RowMapArgs &a, hipStream_t st);
 
 struct TokRedArgs {
   const void *k;

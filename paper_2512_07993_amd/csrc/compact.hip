@@ -107,12 +107,63 @@ __global__ void __launch_bounds__(256) k_compact(CompactArgs a) {
 #undef SKIPKV_STORE_TILE
 }
 
+// Paged cache: the same movement with every row addressed through the row map (logical token ->
+// slot row).  Logical positions still only move forward and distinct logical rows are distinct
+// slots, so the order argument above holds unchanged.  Kept simple: a tile of 32 rows is loaded
+// completely, then stored, no overlap between tiles.
+template <int ROWB>
+__global__ void __launch_bounds__(256) k_compact_paged(CompactArgs a) {
+  constexpr int PPR = ROWB / 16, RPI = 64 / PPR, U = 8, TR = U * RPI, ESZ = ROWB / kD;
+  static_assert(TR <= 64, "one lane per row of a tile");
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int64_t sid = (int64_t)blockIdx.x * 4 + wave;
+  const int64_t n_lhb = (int64_t)a.n_layers * a.n_kv_heads * a.batch;
+  if (sid >= 2 * n_lhb) return;
+  const int64_t lhb = sid >> 1;
+  const int b = (int)(lhb % a.batch);
+  if (a.seq_bad[b]) return;
+  const int lh = (int)(lhb / a.batch), l = lh / a.n_kv_heads, h = lh % a.n_kv_heads;
+  char *base = static_cast<char *>((sid & 1) ? a.v : a.k) + ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head) * ESZ;
+  const int64_t pitch = a.stride_tok * ESZ;
+  const int32_t *kept = a.kept_idx + lhb * a.kept_stride;
+  const int32_t *rmap = a.row_map + a.seq_off[b];
+  const int nl = a.new_len[lhb];
+  const int sub = lane / PPR, piece = lane % PPR;
+  for (int k0 = 0; k0 < nl; k0 += TR) {
+    // lane i < TR: logical source and the two slot rows of row k0 + i
+    const int k = min(k0 + lane, nl - 1);
+    const int src = kept[k];
+    const int src_row = rmap[src], dst_row = rmap[k];
+    if (!__any(lane < TR && k0 + lane < nl && src != k)) continue;  // nothing in this tile moves
+    uint4 r[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) r[u] = *reinterpret_cast<const uint4 *>(base + (int64_t)__shfl(src_row, u * RPI + sub) * pitch + piece * 16);
+    // the loads above are complete before the first store below: the stores depend on their data
+    // only, so the order is forced with an explicit wait
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int i = u * RPI + sub;
+      const int dr = __shfl(dst_row, i);  // taken by all lanes: a shuffle must not read from a lane that a branch has switched off
+      if (k0 + i < nl) *reinterpret_cast<uint4 *>(base + (int64_t)dr * pitch + piece * 16) = r[u];
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // and the stores are acknowledged before the next tile's loads
+  }
+}
+
 }  // namespace
 
 hipError_t launch_compact(const CompactArgs &a, hipStream_t st) {
   const int64_t streams = 2LL * a.n_layers * a.n_kv_heads * a.batch;
   if (streams == 0) return hipSuccess;
   const unsigned grid = (unsigned)((streams + 3) / 4);
+  if (a.row_map) {
+    if (a.dtype == SKIPKV_BF16)
+      hipLaunchKernelGGL(k_compact_paged<256>, dim3(grid), dim3(256), 0, st, a);
+    else
+      hipLaunchKernelGGL(k_compact_paged<512>, dim3(grid), dim3(256), 0, st, a);
+    return hipGetLastError();
+  }
   if (a.dtype == SKIPKV_BF16)
     hipLaunchKernelGGL(k_compact<256>, dim3(grid), dim3(256), 0, st, a);
   else

@@ -91,8 +91,10 @@ __global__ void __launch_bounds__(256) k_scan(ScanArgs a) {
   __syncthreads();
 
   const int t_begin = soff[0], t_end = soff[ns];
+  // contiguous cache: row t of the sequence is row tok0 + t of the head; paged cache: the row map says where it is
+  const int32_t *rmap = a.row_map ? a.row_map + tok0 : nullptr;
   const char *kbase = static_cast<const char *>(a.k) +
-                      ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head + (int64_t)tok0 * a.stride_tok) * ESZ;
+                      ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head + (rmap ? 0 : (int64_t)tok0 * a.stride_tok)) * ESZ;
   const int64_t tok_pitch = a.stride_tok * ESZ;
   const int last_free = n_tok - a.alpha;  // keys t <= last_free are visible to every window query
 
@@ -120,11 +122,18 @@ __global__ void __launch_bounds__(256) k_scan(ScanArgs a) {
     // ---- stream the tile into LDS
     {
       uint4 regs[LOADS];
+      int rows[LOADS];
+#pragma unroll
+      for (int it = 0; it < LOADS; ++it) {
+        const int t = tile_t + (it * 256 + tid) / PPR;
+        rows[it] = t;
+        if (rmap && t < t_end) rows[it] = rmap[t];
+      }
 #pragma unroll
       for (int it = 0; it < LOADS; ++it) {
         const int idx = it * 256 + tid, row = idx / PPR, piece = idx % PPR, t = tile_t + row;
         regs[it] = make_uint4(0, 0, 0, 0);
-        if (t < t_end) regs[it] = *reinterpret_cast<const uint4 *>(kbase + (int64_t)t * tok_pitch + piece * 16);
+        if (t < t_end) regs[it] = *reinterpret_cast<const uint4 *>(kbase + (int64_t)rows[it] * tok_pitch + piece * 16);
       }
 #pragma unroll
       for (int it = 0; it < LOADS; ++it) {

@@ -158,3 +158,28 @@ def test_ranges_and_similarity_entry_points_validate_on_the_host():
                                    1 << 40, None) == B.EINVAL  # lambda missing
     assert lib.skipkv_steer_strength(None, 1.0, 0.1, 0x7000, 4, None) == B.EINVAL
     assert lib.skipkv_steer_strength(None, 1.0, 0.1, None, 0, None) == B.OK
+
+
+def test_paged_entry_points_validate_on_the_host():
+    lib, cache, params = B.lib(), _cache(), _params()
+    out = C.c_size_t(0)
+    good = dict(block_table=0x6000, table_stride=600, block_size=16, n_blocks=700, stride_block=16 * cache.stride_tok)
+    pg = lambda **kw: B.CPaging(**{**good, **kw})
+    size = lambda p: lib.skipkv_paged_workspace_bytes(C.byref(cache), p, C.byref(params), C.byref(out))
+    assert size(C.byref(pg())) == B.OK
+    need = out.value
+    assert need >= _ws_bytes(cache, params)[1] + 4 * cache.total_tokens   # the step's workspace plus the row map
+    assert size(None) == B.EINVAL
+    assert size(C.byref(pg(block_size=0))) == B.EINVAL
+    assert size(C.byref(pg(n_blocks=0))) == B.EINVAL
+    assert size(C.byref(pg(block_table=None))) == B.EINVAL
+    assert size(C.byref(pg(stride_block=16 * cache.stride_tok + 8))) == B.EINVAL   # not a whole number of rows
+    assert size(C.byref(pg(stride_block=8 * cache.stride_tok))) == B.EINVAL        # blocks would overlap
+    assert size(C.byref(pg(n_blocks=1 << 30))) == B.ECAPACITY                      # slot rows are 32-bit
+    step = lambda p, ws=0x10000, n=need, q=0x6400: lib.skipkv_step_paged(
+        C.byref(cache), p, C.byref(params), q, None, 0x7000, 0x8000, None, None, 0x9000, 0xA000, 0xB000, 0xC000,
+        2048, ws, n, None)
+    assert step(None) == B.EINVAL
+    assert step(C.byref(pg()), q=None) == B.EINVAL
+    assert step(C.byref(pg()), n=need - 1) == B.EWORKSPACE
+    assert step(C.byref(pg()), ws=0x10010) == B.EWORKSPACE

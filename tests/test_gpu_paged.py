@@ -1,0 +1,160 @@
+"""GPU parity of the step on a paged KV cache (block table): against the same step on the
+contiguous cache (through the same two-pass scan: token importance, selection and the compacted
+rows bit for bit) and against the oracle on sampled heads.  The pools are filled by scattering a seeded contiguous cache into randomly
+permuted blocks; slots that hold no token carry a sentinel that must survive the step."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_07993_amd import binding as B
+from paper_2512_07993_amd import workloads as W
+
+from helpers import GpuStep, compare_head, device_structure, oracle_head, run_step, sample_heads
+
+pytestmark = pytest.mark.gpu
+
+SENTINEL = -7.0
+
+
+def _to_pages(cfg, st, k, v, block_size, seed, heads_before_slots=False, spare=3):
+    """Pools [L, blocks, slots, Hk, D] (or the same shape as a view of [L, blocks, Hk, slots, D]) and
+    the block table [B, max blocks per sequence] of a random placement."""
+    L, H, T, D = k.shape
+    lens = [int(st.seq_off[b + 1] - st.seq_off[b]) for b in range(cfg.batch)]
+    nblk = [(n + block_size - 1) // block_size for n in lens]
+    n_blocks = sum(nblk) + spare
+    rng = np.random.default_rng(seed)
+    perm = rng.permutation(n_blocks)
+    table = np.full((cfg.batch, max(1, max(nblk)) + 2), -1, dtype=np.int32)
+    pos = 0
+    for b in range(cfg.batch):
+        table[b, :nblk[b]] = perm[pos:pos + nblk[b]]
+        pos += nblk[b]
+    if heads_before_slots:
+        kp = torch.full((L, n_blocks, H, block_size, D), SENTINEL, dtype=k.dtype, device=k.device).permute(0, 1, 3, 2, 4)
+        vp = torch.full((L, n_blocks, H, block_size, D), SENTINEL, dtype=k.dtype, device=k.device).permute(0, 1, 3, 2, 4)
+    else:
+        kp = torch.full((L, n_blocks, block_size, H, D), SENTINEL, dtype=k.dtype, device=k.device)
+        vp = torch.full((L, n_blocks, block_size, H, D), SENTINEL, dtype=k.dtype, device=k.device)
+    blk, slot = _token_slots(cfg, st, table, block_size, k.device)
+    kp[:, blk, slot] = k.permute(0, 2, 1, 3)
+    vp[:, blk, slot] = v.permute(0, 2, 1, 3)
+    return kp, vp, torch.from_numpy(table).to(k.device)
+
+
+def _token_slots(cfg, st, table, block_size, device):
+    blk = np.empty(st.total_tokens, dtype=np.int64)
+    slot = np.empty(st.total_tokens, dtype=np.int64)
+    for b in range(cfg.batch):
+        t0, t1 = int(st.seq_off[b]), int(st.seq_off[b + 1])
+        t = np.arange(t1 - t0)
+        blk[t0:t1] = table[b, t // block_size]
+        slot[t0:t1] = t % block_size
+    return torch.from_numpy(blk).to(device), torch.from_numpy(slot).to(device)
+
+
+def _from_pages(cfg, st, kp, table, block_size):
+    blk, slot = _token_slots(cfg, st, table.cpu().numpy(), block_size, kp.device)
+    return kp[:, blk, slot].permute(0, 2, 1, 3).contiguous()
+
+
+def _run_paged(cfg, st, kp, vp, table, q):
+    dev = kp.device
+    so, sp, sf = device_structure(st, dev)
+    cache = B.PagedCache(kp, vp, table, cfg.n_q_heads, so, sp, sf, st.total_tokens, st.total_sentences)
+    L, H, Bn = cfg.n_layers, cfg.n_kv_heads, cfg.batch
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    params = B.Params(cfg.obs_window, cfg.protect_window, cfg.budget, dev_status=status)
+    ws = torch.empty(B.skipkv_paged_workspace_bytes(cache, params) + 256, dtype=torch.uint8, device=dev)
+    S, T = st.total_sentences, st.total_tokens
+    kept_stride = max(1, min(cfg.budget, T))
+    out = GpuStep(
+        cache, params,
+        torch.full((L, H, S), float("nan"), dtype=torch.float32, device=dev),
+        torch.full((L, H, S), float("nan"), dtype=torch.float32, device=dev),
+        torch.full((L, H, T), float("nan"), dtype=torch.float32, device=dev),
+        torch.full((L, H, S), 77, dtype=torch.uint8, device=dev),
+        torch.full((L, H, Bn, kept_stride), -1, dtype=torch.int32, device=dev),
+        torch.full((L, H, Bn), -1, dtype=torch.int32, device=dev),
+        torch.full((L, H, S + Bn), -1, dtype=torch.int32, device=dev),
+        torch.full((L, H, Bn), -1, dtype=torch.int32, device=dev),
+        kept_stride, status)
+    B.skipkv_step_paged(cache, params, q, None, out.sent_score, out.sent_lambda, out.tok_imp, out.sent_keep,
+                        out.kept_idx, out.new_len, out.new_sent_off, out.new_sent_cnt, kept_stride, ws)
+    torch.cuda.synchronize()
+    return out
+
+
+def _check_against_contiguous(cfg, block_size, heads_before_slots, monkeypatch, n_oracle_heads=4):
+    st = W.make_structure(cfg)
+    k0, v0, q = W.fill_cache(cfg, st, device="cuda")
+    kp, vp, table = _to_pages(cfg, st, k0, v0, block_size, seed=block_size, heads_before_slots=heads_before_slots)
+    kp0 = kp.clone()
+    print("paged", cfg.name, "block", block_size, "blocks", kp.shape[1], "tokens", st.total_tokens, flush=True)
+    out = _run_paged(cfg, st, kp, vp, table, q)
+    assert int(out.dev_status.item()) == 0
+    # the same step on the contiguous cache, through the same (two-pass) scan
+    monkeypatch.setenv("SKIPKV_FORCE_TWO_PASS", "1")
+    k, v = k0.clone(), v0.clone()
+    ref = run_step(cfg, st, k, v, q)
+    monkeypatch.delenv("SKIPKV_FORCE_TWO_PASS")
+    for name in ("tok_imp", "sent_keep", "kept_idx", "new_len", "new_sent_off", "new_sent_cnt"):
+        a, b = getattr(out, name), getattr(ref, name)
+        assert torch.equal(a.view(torch.uint8) if a.dtype != torch.uint8 else a, b.view(torch.uint8) if b.dtype != torch.uint8 else b), name
+    # the two-pass scan adds a sentence's keys up in an order that varies from run to run (LDS atomics):
+    # embeddings, lambda and scores agree to rounding, not bit for bit
+    for name in ("sent_lambda", "sent_score"):
+        torch.testing.assert_close(getattr(out, name), getattr(ref, name), rtol=1e-5, atol=1e-6, equal_nan=True)
+    kg, vg = _from_pages(cfg, st, kp, table, block_size), _from_pages(cfg, st, vp, table, block_size)
+    new_len = out.new_len.cpu().numpy()
+    for b in range(cfg.batch):
+        t0 = int(st.seq_off[b])
+        for l in range(cfg.n_layers):
+            for h in range(cfg.n_kv_heads):
+                n = int(new_len[l, h, b])
+                assert torch.equal(kg[l, h, t0:t0 + n].view(torch.uint8), k[l, h, t0:t0 + n].view(torch.uint8)), (l, h, b)
+                assert torch.equal(vg[l, h, t0:t0 + n].view(torch.uint8), v[l, h, t0:t0 + n].view(torch.uint8)), (l, h, b)
+    # slots that hold no token were not written
+    blk, slot = _token_slots(cfg, st, table.cpu().numpy(), block_size, kp.device)
+    free = torch.ones(kp.shape[1], kp.shape[2], dtype=torch.bool, device=kp.device)
+    free[blk, slot] = False
+    assert torch.equal(kp[:, free].view(torch.uint8), kp0[:, free].view(torch.uint8))
+    assert bool((vp[:, free] == SENTINEL).all())
+    # and against the oracle
+    stats = {}
+    for (l, h, b) in sample_heads(cfg, st, n_oracle_heads, seed=block_size):
+        ora = oracle_head(cfg, st, k0, v0, q, l, h, b)
+        compare_head(cfg, st, out, kg, vg, k0, v0, ora, l, h, b, stats)
+    print(stats, flush=True)
+
+
+@pytest.mark.parametrize("block_size,heads_before_slots", [(16, False), (16, True), (24, False), (128, True)])
+def test_paged_step_matches_contiguous_and_oracle(block_size, heads_before_slots, monkeypatch):
+    _check_against_contiguous(W.CONFIGS[3].scaled(n_layers=2, batch=4), block_size, heads_before_slots, monkeypatch)
+
+
+def test_paged_step_fp32(monkeypatch):
+    _check_against_contiguous(W.CONFIGS[1], 16, False, monkeypatch, n_oracle_heads=3)
+
+
+def test_paged_step_gqa7(monkeypatch):
+    _check_against_contiguous(W.CONFIGS[4].scaled(n_layers=1, batch=3), 32, False, monkeypatch, n_oracle_heads=3)
+
+
+def test_bad_block_id_is_reported_and_that_sequence_left_alone():
+    cfg = W.CONFIGS[3].scaled(n_layers=1, batch=3)
+    st = W.make_structure(cfg)
+    k0, v0, q = W.fill_cache(cfg, st, device="cuda")
+    kp, vp, table = _to_pages(cfg, st, k0, v0, 16, seed=5)
+    table[1, 3] = kp.shape[1] + 9          # out of range
+    kp0, vp0 = kp.clone(), vp.clone()
+    out = _run_paged(cfg, st, kp, vp, table, q)
+    assert int(out.dev_status.item()) & B.DEV_BAD_BLOCK_TABLE
+    # the blocks of sequence 1 hold what they held
+    n1 = (int(st.seq_off[2] - st.seq_off[1]) + 15) // 16
+    own = table[1, :n1].cpu().numpy()
+    own = torch.from_numpy(own[(own >= 0) & (own < kp.shape[1])].astype(np.int64)).to(kp.device)
+    assert torch.equal(kp[:, own].view(torch.uint8), kp0[:, own].view(torch.uint8))
+    assert torch.equal(vp[:, own].view(torch.uint8), vp0[:, own].view(torch.uint8))
+    new_len = out.new_len.cpu().numpy()
+    assert (new_len >= 0).all() and (new_len <= cfg.budget).all()
