@@ -214,6 +214,94 @@ def time_ranges(config_id: int, steps: int = 5) -> int:
     return 0
 
 
+def time_paged(config_id: int, block_size: int = 16, heads_first: bool = False, steps: int = 5) -> int:
+    """Times skipkv_step_paged on the workload scattered into a pool of blocks of `block_size` token
+    slots ([layers, blocks, slots, KV heads, 128], or [layers, blocks, KV heads, slots, 128] with
+    heads_first; blocks in random order), next to skipkv_step on the contiguous cache."""
+    import numpy as np
+    import torch
+
+    from paper_2512_07993_amd import binding as B
+    from paper_2512_07993_amd import workloads as W
+
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    cfg = W.CONFIGS[config_id]
+    st = W.make_structure(cfg)
+    k0, v0, q = W.fill_cache(cfg, st, device=dev)
+    L, H, Bn, S, T = cfg.n_layers, cfg.n_kv_heads, cfg.batch, st.total_sentences, st.total_tokens
+    so, sp, sf = (torch.from_numpy(x).to(dev) for x in (st.seq_off, st.sent_ptr, st.sent_off))
+    # placement: the blocks of all sequences in one random permutation
+    nblk = [(int(n) + block_size - 1) // block_size for n in st.seq_len]
+    n_blocks = sum(nblk)
+    perm = np.random.default_rng(cfg.seed).permutation(n_blocks)
+    table = np.full((Bn, max(nblk)), -1, dtype=np.int32)
+    blk, slot, pos = np.empty(T, dtype=np.int64), np.empty(T, dtype=np.int64), 0
+    for b in range(Bn):
+        table[b, :nblk[b]] = perm[pos:pos + nblk[b]]
+        pos += nblk[b]
+        t = np.arange(int(st.seq_len[b]))
+        blk[int(st.seq_off[b]):int(st.seq_off[b + 1])] = table[b, t // block_size]
+        slot[int(st.seq_off[b]):int(st.seq_off[b + 1])] = t % block_size
+    blk, slot = torch.from_numpy(blk).to(dev), torch.from_numpy(slot).to(dev)
+    if heads_first:
+        kp0 = torch.zeros((L, n_blocks, H, block_size, cfg.head_dim), dtype=k0.dtype, device=dev).permute(0, 1, 3, 2, 4)
+        vp0 = torch.zeros((L, n_blocks, H, block_size, cfg.head_dim), dtype=k0.dtype, device=dev).permute(0, 1, 3, 2, 4)
+    else:
+        kp0 = torch.zeros((L, n_blocks, block_size, H, cfg.head_dim), dtype=k0.dtype, device=dev)
+        vp0 = torch.zeros_like(kp0)
+    kp0[:, blk, slot] = k0.permute(0, 2, 1, 3)
+    vp0[:, blk, slot] = v0.permute(0, 2, 1, 3)
+    kp, vp = torch.empty_like(kp0), torch.empty_like(vp0)  # (keeps the strides of a permuted pool)
+    assert kp.stride() == kp0.stride()
+    k, v = torch.empty_like(k0), torch.empty_like(v0)
+    paged = B.PagedCache(kp, vp, torch.from_numpy(table).to(dev), cfg.n_q_heads, so, sp, sf, T, S)
+    cache = B.Cache(k, v, cfg.n_q_heads, so, sp, sf, T, S)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    prof = B.skipkv_profile_create()
+    params = B.Params(cfg.obs_window, cfg.protect_window, cfg.budget, dev_status=status, profile=prof)
+    ws = torch.empty(B.skipkv_paged_workspace_bytes(paged, params), dtype=torch.uint8, device=dev)
+    kept_stride = min(cfg.budget, T)
+    sent_score = torch.empty((L, H, S), dtype=torch.float32, device=dev)
+    sent_lambda = torch.empty_like(sent_score)
+    sent_keep = torch.empty((L, H, S), dtype=torch.uint8, device=dev)
+    kept_idx = torch.empty((L, H, Bn, kept_stride), dtype=torch.int32, device=dev)
+    new_len = torch.empty((L, H, Bn), dtype=torch.int32, device=dev)
+    new_off = torch.empty((L, H, S + Bn), dtype=torch.int32, device=dev)
+    new_cnt = torch.empty((L, H, Bn), dtype=torch.int32, device=dev)
+    out = {}
+    for name in ("step_paged", "step"):
+        times = []
+        for i in range(steps + 1):
+            if name == "step_paged":
+                kp.copy_(kp0)
+                vp.copy_(vp0)
+            else:
+                k.copy_(k0)
+                v.copy_(v0)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            if name == "step_paged":
+                B.skipkv_step_paged(paged, params, q, None, sent_score, sent_lambda, None, sent_keep, kept_idx, new_len,
+                                    new_off, new_cnt, kept_stride, ws)
+            else:
+                B.skipkv_step(cache, params, q, None, sent_score, sent_lambda, None, sent_keep, kept_idx, new_len,
+                              new_off, new_cnt, kept_stride, ws)
+            e1.record()
+            torch.cuda.synchronize()
+            if i:
+                times.append(e0.elapsed_time(e1))
+        out[name] = sum(times) / len(times)
+        out[name + "_kernels"] = {n: round(t, 4) for n, t in B.skipkv_profile_read(prof)}  # of the last call
+    assert int(status.item()) == 0, "device status %d" % int(status.item())
+    B.skipkv_profile_destroy(prof)
+    print(json.dumps({"op": "step_paged", "workload": "config %d: %s" % (cfg.config_id, cfg.name), "block_size": block_size,
+                      "layout": "[blocks, heads, slots, 128]" if heads_first else "[blocks, slots, heads, 128]", "blocks": n_blocks, "ms_per_step_paged": out["step_paged"], "ms_per_step_contiguous": out["step"],
+                      "kernel_ms_paged": out["step_paged_kernels"], "kernel_ms_contiguous": out["step_kernels"],
+                      "steps": steps}))
+    return 0
+
+
 def time_shared_lambda(config_id: int, d_model: int = 4096, steps: int = 5) -> int:
     """Times the paper-literal variant of the step: sentence similarity from hidden states once per
     sequence (Eq. 1-3), then scores with that shared lambda, selection and compaction."""
@@ -282,11 +370,15 @@ def main() -> int:
     ap.add_argument("--redundancy", action="store_true", help="time only skipkv_token_redundancy on the workload's keys")
     ap.add_argument("--shared-lambda", action="store_true", help="time the variant with hidden-state sentence similarity shared by all heads")
     ap.add_argument("--ranges", action="store_true", help="time skipkv_step_ranges (per-head sentence ranges) next to skipkv_step")
+    ap.add_argument("--paged", type=int, default=0, metavar="BLOCK", help="time skipkv_step_paged with blocks of BLOCK token slots next to skipkv_step")
+    ap.add_argument("--paged-heads-first", action="store_true", help="with --paged: pools laid out [blocks, heads, slots, 128] instead of [blocks, slots, heads, 128]")
     args = ap.parse_args()
     if args.calib_copy:
         return calib_copy()
     if args.redundancy:
         return time_redundancy(args.config)
+    if args.paged:
+        return time_paged(args.config, args.paged, args.paged_heads_first)
     if args.ranges:
         return time_ranges(args.config)
     if args.shared_lambda:

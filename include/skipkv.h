@@ -319,8 +319,9 @@ int skipkv_paged_workspace_bytes(const skipkv_cache *cache, const skipkv_paging 
  * not changed (afterwards the caller may release the blocks that lie wholly beyond the new
  * lengths).  Outputs and their layouts are those of skipkv_step.  A row map (logical token ->
  * slot) is built first; a block id outside [0, n_blocks) raises SKIPKV_DEV_BAD_BLOCK_TABLE, is
- * read as block 0, and the sequence's K and V are not touched.  The key scan takes its two-pass
- * form on a paged cache.
+ * read as block 0, and the sequence's K and V are not touched.  The key scan keeps its single-pass
+ * form when block_size is a power of two >= 16 (a 16-token stage then spans at most two blocks)
+ * and takes the two-pass form otherwise.
  */
 int skipkv_step_paged(const skipkv_cache *cache, const skipkv_paging *paging, const skipkv_params *params,
                       const void *q_obs, const float *tok_redundancy, float *sent_score, float *sent_lambda,

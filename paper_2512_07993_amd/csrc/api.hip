@@ -96,6 +96,7 @@ struct HeadView {
   const int32_t *len = nullptr, *cnt = nullptr;
   int32_t virt_hk = 0, virt_b = 0;
   const int32_t *row_map = nullptr;  // paged cache: logical token -> slot row
+  int32_t page_size = 0;             // ... and its slots per block
 };
 
 struct Timer {
@@ -151,7 +152,9 @@ int do_score(Timer &tm, const skipkv_cache *c, const skipkv_params *p, const Row
   const char *env_two = std::getenv("SKIPKV_FORCE_TWO_PASS");
   const char *env_spin = std::getenv("SKIPKV_SPIN_LIMIT");
   sa.row_map = hv.row_map;
-  sa.force_two_pass = hv.row_map != nullptr || (env_two && env_two[0] == '1') || !scan_fused_supported(rl, c->stride_tok * (c->dtype == SKIPKV_BF16 ? 2 : 4));
+  sa.page_size = hv.page_size;
+  const bool pages_fit_stages = hv.page_size >= 16 && (hv.page_size & (hv.page_size - 1)) == 0;
+  sa.force_two_pass = (hv.row_map != nullptr && !pages_fit_stages) || (env_two && env_two[0] == '1') || !scan_fused_supported(rl, c->stride_tok * (c->dtype == SKIPKV_BF16 ? 2 : 4));
   sa.spin_limit = env_spin ? std::atoi(env_spin) : 4000000;
   sa.dev_status = p->dev_status;
   sa.virt_hk = hv.virt_hk;
@@ -507,6 +510,7 @@ int skipkv_step_paged(const skipkv_cache *cache, const skipkv_paging *paging, co
   if (tm.run("row_map", [&] { return launch_row_map(ra, st); }) != hipSuccess) return SKIPKV_EHIP;
   HeadView hv;
   hv.row_map = row_map;
+  hv.page_size = paging->block_size;
   rc = do_score(tm, cache, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, ws, st, hv);
   if (rc) return rc;
   rc = do_select(tm, cache, params, sent_score, sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride, st);

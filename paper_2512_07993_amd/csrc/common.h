@@ -172,6 +172,7 @@ struct ScanArgs {
   // Paged cache (two-pass scan only): row_map[seq_off[b] + t] = slot row of logical token t, in units of
   // stride_tok from the head's base; null for a contiguous cache.
   const int32_t *row_map;
+  int32_t page_size;  // token slots per block of a paged cache (the single-pass scan needs a power of two >= 16)
 };
 bool scan_fused_supported(const RowLayout &rl, int64_t row_pitch_bytes);
 hipError_t launch_scan_fused(const ScanArgs &a, hipStream_t st);    // single pass over K (sequences the plan marked fused)

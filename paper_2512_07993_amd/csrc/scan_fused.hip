@@ -99,6 +99,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
   // lets the compiler use scalar loads, which do not queue behind the key loads in flight.
   typedef const __attribute__((address_space(4))) int32_t *ConstIntPtr;
   const ConstIntPtr pair_rec_c = (ConstIntPtr)a.ws.pair_rec;
+  const ConstIntPtr row_map_c = (ConstIntPtr)a.row_map;  // written by an earlier kernel, constant here
 
   // ---- item descriptors: one 64-byte record per pair of chunks, written by the plan ----------
   auto make_chunk = [&](int t_begin, int len, int ns, int soff_idx) -> ChunkD {
@@ -129,8 +130,9 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
       it.ch[0] = make_chunk(r[kPrTBegin], r[kPrLen0], r[kPrNs0], r[kPrSoffIdx]);
       it.ch[1] = nch == 2 ? make_chunk(r[kPrTBegin] + r[kPrLen0], r[kPrLen1], r[kPrNs1], r[kPrSoffIdx] + r[kPrNs0]) : ChunkD{};
       const int l = it.lh / a.n_kv_heads, h = it.lh % a.n_kv_heads;
+      // contiguous cache: first row of the sequence; paged cache: the head's base, rows come from the row map
       it.kbase = static_cast<const char *>(a.k) +
-                 ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head + (int64_t)it.tok0 * a.stride_tok) * ESZ;
+                 ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head + (a.row_map ? 0 : (int64_t)it.tok0 * a.stride_tok)) * ESZ;
       break;
     }
     it.item = item;
@@ -209,15 +211,34 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     asm volatile("" : "+v"(ln));  // opaque copy: the per-load address parts are recomputed here rather than kept live across the item
     // scalar 64-bit base of the stage + a 32-bit offset per lane (one 24-bit multiply; the launcher
     // only takes this kernel for row pitches below 2^24 bytes): no 64-bit multiplies per load
-    const char *sbase = iss.kbase + (int64_t)ts * tok_pitch;
     const int last = w1 - 1 - ts;  // rows past the range re-read its last row (masked later)
     const uint32_t pitch32 = (uint32_t)tok_pitch;
+    if (a.row_map == nullptr) {
+      const char *sbase = iss.kbase + (int64_t)ts * tok_pitch;
 #pragma unroll
-    for (int j = 0; j < GL; ++j) {
-      const int row = j * RPL + ln / PPR;         // row of the stage this lane's 16 bytes belong to
-      const int piece = (ln % PPR) ^ (row & 15);    // swizzle: LDS position (lane % PPR) holds this global piece
-      const uint32_t off = __umul24((uint32_t)min(row, last), pitch32) + (uint32_t)piece * 16u;
-      load_to_lds_16(sbase + off, dst + j * 1024);
+      for (int j = 0; j < GL; ++j) {
+        const int row = j * RPL + ln / PPR;         // row of the stage this lane's 16 bytes belong to
+        const int piece = (ln % PPR) ^ (row & 15);    // swizzle: LDS position (lane % PPR) holds this global piece
+        const uint32_t off = __umul24((uint32_t)min(row, last), pitch32) + (uint32_t)piece * 16u;
+        load_to_lds_16(sbase + off, dst + j * 1024);
+      }
+    } else {
+      // Paged cache, blocks of a power of two >= 16 slots: the stage's 16 tokens lie in at most two
+      // blocks, in consecutive slots within each.  Two scalar reads of the row map give the slot
+      // row of the stage's first token and of the first token of the next block.
+      const int jb = a.page_size - (ts & (a.page_size - 1));  // rows of the stage before the next block begins (may be >= 16)
+      const int r0 = row_map_c[iss.tok0 + ts];
+      const int r1 = row_map_c[iss.tok0 + min(ts + jb, iss.n_tok - 1)];
+      const char *base0 = iss.kbase + (int64_t)r0 * tok_pitch;
+      const char *base1 = iss.kbase + ((int64_t)r1 - jb) * tok_pitch;
+#pragma unroll
+      for (int j = 0; j < GL; ++j) {
+        const int row = j * RPL + ln / PPR;
+        const int piece = (ln % PPR) ^ (row & 15);
+        const int jr = min(row, last);
+        const uint32_t off = __umul24((uint32_t)jr, pitch32) + (uint32_t)piece * 16u;
+        load_to_lds_16((jr >= jb ? base1 : base0) + off, dst + j * 1024);
+      }
     }
     ++iss_st;
     ++iss_cnt;
