@@ -1,5 +1,6 @@
 // Host side of libskipkv: argument validation, workspace carving, kernel sequencing, timing.
 // No device work happens here and nothing is allocated on the device.
+#include <algorithm>
 #include <cstdlib>
 #include <new>
 
@@ -232,10 +233,13 @@ int do_select(Timer &tm, const skipkv_cache *c, const skipkv_params *p, const fl
 }
 
 int do_compact(Timer &tm, const skipkv_cache *c, const int32_t *kept_idx, const int32_t *new_len, int32_t kept_stride,
-               hipStream_t st, const int32_t *row_map = nullptr, const int32_t *seq_bad = nullptr) {
+               hipStream_t st, const int32_t *row_map = nullptr, const int32_t *seq_bad = nullptr,
+               int32_t *src_rows = nullptr, int32_t src_stride = 0) {
   CompactArgs a{};
   a.row_map = row_map;
   a.seq_bad = seq_bad;
+  a.src_rows = src_rows;
+  a.src_stride = src_stride;
   a.k = c->k;
   a.v = c->v;
   a.stride_layer = c->stride_layer;
@@ -442,10 +446,10 @@ namespace {
 // Validation of a paged cache's description, and where the row map and the per-sequence flags sit
 // behind the step's workspace.
 struct PagedView {
-  size_t step_bytes, map_bytes, total;
-  int32_t rows_per_block;
+  size_t step_bytes, map_bytes, bad_bytes, total;
+  int32_t rows_per_block, src_stride;
 };
-int check_paging(const skipkv_cache *c, const skipkv_paging *pg, const RowLayout &rl, PagedView *v) {
+int check_paging(const skipkv_cache *c, const skipkv_paging *pg, const skipkv_params *p, const RowLayout &rl, PagedView *v) {
   if (!pg) return SKIPKV_EINVAL;
   if (pg->block_size < 1 || pg->n_blocks < 1 || pg->table_stride < 0 || pg->stride_block < 0) return SKIPKV_EINVAL;
   if (!pg->block_table && c->total_tokens > 0) return SKIPKV_EINVAL;
@@ -458,7 +462,11 @@ int check_paging(const skipkv_cache *c, const skipkv_paging *pg, const RowLayout
   if (!w.fits) return SKIPKV_ECAPACITY;
   v->step_bytes = align_up(w.bytes);
   v->map_bytes = align_up((size_t)c->total_tokens * 4);
-  v->total = v->step_bytes + v->map_bytes + align_up((size_t)c->batch * 4);
+  v->bad_bytes = align_up((size_t)c->batch * 4);
+  // slot rows of the kept tokens of every head: no head keeps more than its budget, nor more than there is
+  v->src_stride = std::max(1, std::min(p->max_budget, c->total_tokens));
+  v->total = v->step_bytes + v->map_bytes + v->bad_bytes +
+             align_up((size_t)c->n_layers * c->n_kv_heads * c->batch * v->src_stride * 4);
   return SKIPKV_OK;
 }
 }  // namespace
@@ -476,7 +484,7 @@ int skipkv_paged_workspace_bytes(const skipkv_cache *cache, const skipkv_paging 
     return SKIPKV_OK;
   }
   PagedView pv;
-  rc = check_paging(cache, paging, rl, &pv);
+  rc = check_paging(cache, paging, params, rl, &pv);
   if (rc) return rc;
   *out_bytes = pv.total;
   return SKIPKV_OK;
@@ -498,7 +506,7 @@ int skipkv_step_paged(const skipkv_cache *cache, const skipkv_paging *paging, co
   if (!q_obs || !aligned16(q_obs)) return SKIPKV_EINVAL;
   if (cache->total_sentences > 0 && (!sent_score || !sent_lambda)) return SKIPKV_EINVAL;
   PagedView pv;
-  rc = check_paging(cache, paging, rl, &pv);
+  rc = check_paging(cache, paging, params, rl, &pv);
   if (rc) return rc;
   if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < pv.total) return SKIPKV_EWORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -515,7 +523,8 @@ int skipkv_step_paged(const skipkv_cache *cache, const skipkv_paging *paging, co
   if (rc) return rc;
   rc = do_select(tm, cache, params, sent_score, sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride, st);
   if (rc) return rc;
-  return do_compact(tm, cache, kept_idx, new_len, kept_stride, st, row_map, seq_bad);
+  int32_t *src_rows = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + pv.step_bytes + pv.map_bytes + pv.bad_bytes);
+  return do_compact(tm, cache, kept_idx, new_len, kept_stride, st, row_map, seq_bad, src_rows, pv.src_stride);
 }
 
 int skipkv_ranges_workspace_bytes(const skipkv_cache *cache, const skipkv_params *params, size_t *out_bytes) {

@@ -223,6 +223,8 @@ struct CompactArgs {
   const int32_t *seq_off, *kept_idx, *new_len;
   const int32_t *row_map;  // paged cache: logical token -> slot row (see ScanArgs); null: contiguous
   const int32_t *seq_bad;  // paged cache, [batch]: nonzero = invalid block table, leave the sequence alone
+  int32_t *src_rows;       // paged cache, workspace [heads, src_stride]: slot row of every kept token
+  int32_t src_stride;      // >= every new_len
 };
 hipError_t launch_compact(const CompactArgs &a, hipStream_t st);
 

@@ -12,7 +12,11 @@ namespace skipkv {
 
 namespace {
 
-template <int ROWB>
+// Paged cache (PAGED): rows live in block slots.  Sources come pre-translated (src_rows: slot row of
+// kept_idx[k], written by k_kept_rows below), destinations are read from the row map one coalesced
+// load per tile, issued right before the tile's row loads.  Logical positions still only move
+// forward and distinct logical rows are distinct slots, so the order argument above holds.
+template <int ROWB, bool PAGED>
 __global__ void __launch_bounds__(256) k_compact(CompactArgs a) {
   constexpr int PPR = ROWB / 16;   // 16-byte pieces per row
   constexpr int RPI = 64 / PPR;    // rows moved by one wave-wide instruction
@@ -24,11 +28,14 @@ __global__ void __launch_bounds__(256) k_compact(CompactArgs a) {
   if (sid >= 2 * n_lhb) return;
   const int64_t lhb = sid >> 1;
   const int b = (int)(lhb % a.batch);
+  if (PAGED && a.seq_bad[b]) return;  // invalid block table: leave the sequence alone
   const int lh = (int)(lhb / a.batch), l = lh / a.n_kv_heads, h = lh % a.n_kv_heads;
   char *base = static_cast<char *>((sid & 1) ? a.v : a.k) +
-               ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head + (int64_t)a.seq_off[b] * a.stride_tok) * ESZ;
+               ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head + (PAGED ? 0 : (int64_t)a.seq_off[b] * a.stride_tok)) * ESZ;
   const int64_t pitch = a.stride_tok * ESZ;
   const int32_t *kept = a.kept_idx + lhb * a.kept_stride;
+  const int32_t *srcs = PAGED ? a.src_rows + lhb * a.src_stride : kept;  // what the row loads are addressed with
+  const int32_t *rmap = PAGED ? a.row_map + a.seq_off[b] : nullptr;
   const int nl = a.new_len[lhb];
 
   // first row that actually moves
@@ -52,7 +59,10 @@ __global__ void __launch_bounds__(256) k_compact(CompactArgs a) {
   constexpr int TR = U * RPI;  // rows per tile
   static_assert(TR <= 64, "one lane per row index of a tile");
   auto load_idx = [&](int k0) -> int {  // unconditional (clamped), so that it always counts as one outstanding load
-    return kept[min(k0 + lane, nl - 1)];
+    return srcs[min(k0 + lane, nl - 1)];
+  };
+  auto load_dst = [&](int k0) -> int {  // paged: slot rows of the tile's destinations (same rule)
+    return PAGED ? rmap[min(k0 + lane, nl - 1)] : 0;
   };
   if (first >= nl) return;
   // The two tiles are written out as named registers (A0..A7, B0..B7): arrays carried around the
@@ -63,12 +73,16 @@ __global__ void __launch_bounds__(256) k_compact(CompactArgs a) {
   // always U loads per tile: rows past the end re-read the last kept row (index loads are clamped)
 #define SKIPKV_LOAD(T, u) \
   T##u = *reinterpret_cast<const uint4 *>(base + (int64_t)__shfl(idx_##T, u * RPI + sub) * pitch + piece * 16);
-#define SKIPKV_STORE(T, u) *reinterpret_cast<uint4 *>(base + (int64_t)(ks + u * RPI + sub) * pitch + piece * 16) = T##u;
+  // destination row of the lane's piece: position in the sequence, or (paged) its slot row; the shuffle
+  // is taken by all lanes, outside any condition
+#define SKIPKV_DROW(T, u) const int64_t dr_##u = PAGED ? (int64_t)__shfl(dst_##T, u * RPI + sub) : (int64_t)(ks + u * RPI + sub);
+#define SKIPKV_STORE(T, u) *reinterpret_cast<uint4 *>(base + dr_##u * pitch + piece * 16) = T##u;
 #define SKIPKV_STORE_TAIL(T, u) \
-  if (ks + u * RPI + sub < nl) *reinterpret_cast<uint4 *>(base + (int64_t)(ks + u * RPI + sub) * pitch + piece * 16) = T##u;
+  if (ks + u * RPI + sub < nl) *reinterpret_cast<uint4 *>(base + dr_##u * pitch + piece * 16) = T##u;
 #define SKIPKV_STORE_TILE(T, K0)        \
   {                                     \
     const int ks = (K0);                \
+    SKIPKV_EACH(SKIPKV_DROW, T)         \
     if (ks + TR <= nl) {                \
       SKIPKV_EACH(SKIPKV_STORE, T)      \
     } else {                            \
@@ -77,25 +91,29 @@ __global__ void __launch_bounds__(256) k_compact(CompactArgs a) {
   }
   // Wait until the loads of the tile about to be stored have landed.  Behind them in the queue
   // are the previous tile's U stores (none for the first tile), one index load and the next
-  // tile's U loads.  The next tile is always loaded, also past the end (clamped, one tile of
+  // tile's U loads (paged: plus the load of the next tile's destination rows, NX = 1).  The next tile is always loaded, also past the end (clamped, one tile of
   // wasted reads per stream): unconditional loads keep the counts exact and the registers in place.
   SKIPKV_EACH(SKIPKV_DECL, A)
   SKIPKV_EACH(SKIPKV_DECL, B)
+  constexpr int NX = PAGED ? 1 : 0;
   int idx_A = load_idx(first);
   int idx_B = load_idx(first + TR);
+  int dst_A = load_dst(first), dst_B = 0;
   SKIPKV_EACH(SKIPKV_LOAD, A)
   for (int k0 = first;; k0 += 2 * TR) {
     idx_A = load_idx(k0 + 2 * TR);
+    dst_B = load_dst(k0 + TR);
     SKIPKV_EACH(SKIPKV_LOAD, B)
     if (k0 != first)
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * U + 1) : "memory");
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * U + 1 + NX) : "memory");
     else
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(U + 1) : "memory");
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(U + 1 + NX) : "memory");
     SKIPKV_STORE_TILE(A, k0)
     if (k0 + TR >= nl) break;
     idx_B = load_idx(k0 + 3 * TR);
+    dst_A = load_dst(k0 + 2 * TR);
     SKIPKV_EACH(SKIPKV_LOAD, A)
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * U + 1) : "memory");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * U + 1 + NX) : "memory");
     SKIPKV_STORE_TILE(B, k0 + TR)
     if (k0 + 2 * TR >= nl) break;
   }
@@ -103,71 +121,43 @@ __global__ void __launch_bounds__(256) k_compact(CompactArgs a) {
 #undef SKIPKV_DECL
 #undef SKIPKV_LOAD
 #undef SKIPKV_STORE
+#undef SKIPKV_DROW
 #undef SKIPKV_STORE_TAIL
 #undef SKIPKV_STORE_TILE
 }
 
-// Paged cache: the same movement with every row addressed through the row map (logical token ->
-// slot row).  Logical positions still only move forward and distinct logical rows are distinct
-// slots, so the order argument above holds unchanged.  Kept simple: a tile of 32 rows is loaded
-// completely, then stored, no overlap between tiles.
-template <int ROWB>
-__global__ void __launch_bounds__(256) k_compact_paged(CompactArgs a) {
-  constexpr int PPR = ROWB / 16, RPI = 64 / PPR, U = 8, TR = U * RPI, ESZ = ROWB / kD;
-  static_assert(TR <= 64, "one lane per row of a tile");
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int64_t sid = (int64_t)blockIdx.x * 4 + wave;
-  const int64_t n_lhb = (int64_t)a.n_layers * a.n_kv_heads * a.batch;
-  if (sid >= 2 * n_lhb) return;
-  const int64_t lhb = sid >> 1;
-  const int b = (int)(lhb % a.batch);
+// Paged cache: src_rows[head, k] = slot row of the head's kept token k, for k < new_len (one wave
+// per head; shared by the K and the V stream of the head).
+__global__ void __launch_bounds__(256) k_kept_rows(CompactArgs a) {
+  const int64_t lhb = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (lhb >= (int64_t)a.n_layers * a.n_kv_heads * a.batch) return;
+  const int b = (int)(lhb % a.batch), lane = threadIdx.x & 63;
   if (a.seq_bad[b]) return;
-  const int lh = (int)(lhb / a.batch), l = lh / a.n_kv_heads, h = lh % a.n_kv_heads;
-  char *base = static_cast<char *>((sid & 1) ? a.v : a.k) + ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head) * ESZ;
-  const int64_t pitch = a.stride_tok * ESZ;
   const int32_t *kept = a.kept_idx + lhb * a.kept_stride;
   const int32_t *rmap = a.row_map + a.seq_off[b];
-  const int nl = a.new_len[lhb];
-  const int sub = lane / PPR, piece = lane % PPR;
-  for (int k0 = 0; k0 < nl; k0 += TR) {
-    // lane i < TR: logical source and the two slot rows of row k0 + i
-    const int k = min(k0 + lane, nl - 1);
-    const int src = kept[k];
-    const int src_row = rmap[src], dst_row = rmap[k];
-    if (!__any(lane < TR && k0 + lane < nl && src != k)) continue;  // nothing in this tile moves
-    uint4 r[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) r[u] = *reinterpret_cast<const uint4 *>(base + (int64_t)__shfl(src_row, u * RPI + sub) * pitch + piece * 16);
-    // the loads above are complete before the first store below: the stores depend on their data
-    // only, so the order is forced with an explicit wait
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int i = u * RPI + sub;
-      const int dr = __shfl(dst_row, i);  // taken by all lanes: a shuffle must not read from a lane that a branch has switched off
-      if (k0 + i < nl) *reinterpret_cast<uint4 *>(base + (int64_t)dr * pitch + piece * 16) = r[u];
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // and the stores are acknowledged before the next tile's loads
-  }
+  int32_t *out = a.src_rows + lhb * a.src_stride;
+  const int nl = min(a.new_len[lhb], a.src_stride);
+  for (int k = lane; k < nl; k += 64) out[k] = rmap[kept[k]];
 }
 
 }  // namespace
 
 hipError_t launch_compact(const CompactArgs &a, hipStream_t st) {
-  const int64_t streams = 2LL * a.n_layers * a.n_kv_heads * a.batch;
+  const int64_t heads = (int64_t)a.n_layers * a.n_kv_heads * a.batch, streams = 2 * heads;
   if (streams == 0) return hipSuccess;
   const unsigned grid = (unsigned)((streams + 3) / 4);
   if (a.row_map) {
+    hipLaunchKernelGGL(k_kept_rows, dim3((unsigned)((heads + 3) / 4)), dim3(256), 0, st, a);
     if (a.dtype == SKIPKV_BF16)
-      hipLaunchKernelGGL(k_compact_paged<256>, dim3(grid), dim3(256), 0, st, a);
+      hipLaunchKernelGGL((k_compact<256, true>), dim3(grid), dim3(256), 0, st, a);
     else
-      hipLaunchKernelGGL(k_compact_paged<512>, dim3(grid), dim3(256), 0, st, a);
+      hipLaunchKernelGGL((k_compact<512, true>), dim3(grid), dim3(256), 0, st, a);
     return hipGetLastError();
   }
   if (a.dtype == SKIPKV_BF16)
-    hipLaunchKernelGGL(k_compact<256>, dim3(grid), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((k_compact<256, false>), dim3(grid), dim3(256), 0, st, a);
   else
-    hipLaunchKernelGGL(k_compact<512>, dim3(grid), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((k_compact<512, false>), dim3(grid), dim3(256), 0, st, a);
   return hipGetLastError();
 }
 
