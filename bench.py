@@ -405,6 +405,10 @@ def main() -> int:
     sp = torch.from_numpy(st.sent_ptr).to(dev)
     sf = torch.from_numpy(st.sent_off).to(dev)
     n_copies = max(1, min(args.copies, max(args.steps, args.warmup)))
+    # working copies of K and V (restored from the pristine pair before each group of steps): as many as fit
+    free_bytes, _ = torch.cuda.mem_get_info()
+    pair_bytes = 2 * k0.numel() * esz
+    n_copies = max(1, min(n_copies, int(0.8 * free_bytes // pair_bytes)))
     bufs = [(torch.empty_like(k0), torch.empty_like(v0)) for _ in range(n_copies)]
     caches = [B.Cache(k, v, cfg.n_q_heads, so, sp, sf, T, S) for (k, v) in bufs]
     status = torch.zeros(1, dtype=torch.int32, device=dev)
