@@ -5,11 +5,12 @@
 // chunks, i.e. many workgroups.  Instead of a second pass over K, every workgroup keeps the
 // logits of its share in registers (they are MFMA accumulators anyway: per wave 64 tokens x all
 // query rows of the GQA group, for each of two consecutive chunks), publishes the (max, sum exp)
-// of every row over its share, and waits until the head's normalisers are final; the last
-// share of a head to arrive merges the partials and writes the normalisers over the marker the
-// plan had preset them to, which is what the others poll for.  Then each workgroup finishes
-// I[t] from its registers.  A unit of work ("item") is a PAIR of consecutive
-// chunks of one head, so that the cross-workgroup round trips are paid once per 512 tokens.
+// of every row over its share as one record, and then merges the records of ALL shares of the
+// head itself, loading them again while any still holds the marker that the plan preset it to.
+// (Heads of more than kAllMergeMax items keep an older protocol: an arrive counter, the last share
+// to arrive merges and writes the normalisers over their marker, the others poll those.)  Then
+// each workgroup finishes I[t] from its registers.  A unit of work ("item") is a PAIR of
+// consecutive chunks of one head, so that the exchange is paid once per 512 tokens.
 //
 // Forward progress.  The grid is persistent and no larger than what is co-resident on the chip
 // (occupancy query on the host).  Workgroup w takes items w, w+G, w+2G, ... in increasing order,
@@ -30,7 +31,11 @@
 // piece p of row r is kept at piece position p ^ (r & 15), which each lane arranges by choosing
 // which global piece it fetches.
 //
-// Pooling.  A sentence that lies inside one wave's range is normalised and written straight from
+// Paged cache.  With a row map (logical token -> block slot) and blocks of a power of two >= 16
+// slots, a stage spans at most two blocks: two scalar reads of the map give two bases per stage.
+//
+// Pooling.  Key sums per sentence come from 4x4x4 matrix products of a 0/1 indicator with the
+// stage's rows.  A sentence that lies inside one wave's range is normalised and written straight from
 // registers; the (at most 3 per chunk) sentences that cross wave boundaries are pieced together
 // through LDS in a fixed order, so results are reproducible.
 #include "scan_dev.h"
