@@ -22,7 +22,7 @@ namespace skipkv {
 namespace {
 
 template <int DT, int NP, int AL, int NSUB, bool PASSB>
-__global__ void __launch_bounds__(256) k_scan(ScanArgs a) {
+__global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan(ScanArgs a) {
   constexpr int SL = NP * AL;        // used (a, i) slots per lane group
   constexpr int NT = (SL + 3) / 4;   // row tiles
   constexpr int SLP = 4 * NT;        // slots incl. padding
@@ -38,7 +38,7 @@ __global__ void __launch_bounds__(256) k_scan(ScanArgs a) {
   __shared__ int soff[kChunkMaxSent + 1];
   // pass A: sentence key sums [kChunkMaxSent][128] then per-wave row statistics [4][R][2]
   // pass B: token importance of the tile [TT], sentence sums of I and of R [2][kChunkMaxSent]
-  constexpr int SBUF = PASSB ? (TT + 2 * kChunkMaxSent) : (kChunkMaxSent * kD + 8 * R);
+  constexpr int SBUF = PASSB ? (TT + 2 * kChunkMaxSent) : (kChunkMaxSent * kD);
   __shared__ float sbuf[SBUF];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, c16 = lane & 15, g = lane >> 4;
@@ -275,7 +275,10 @@ __global__ void __launch_bounds__(256) k_scan(ScanArgs a) {
       reinterpret_cast<uint32_t *>(a.ws.vhat_lo)[o] = l0 | (l1 << 16);
     }
     // ---- merge the row statistics of the 4 waves and publish the chunk's partial
-    float *wstat = sbuf + kChunkMaxSent * kD;
+    // (in the key tile's buffer, which nobody reads after the last tile: with 160 query rows this keeps
+    // the workgroup under half of the CU's LDS)
+    static_assert(8 * R * sizeof(float) <= sizeof(kt), "the statistics of the 4 waves fit the key tile");
+    float *wstat = reinterpret_cast<float *>(kt);
 #pragma unroll
     for (int q = 0; q < SLP; ++q) {
       const float tot = row16_sum(lsum[q]);
