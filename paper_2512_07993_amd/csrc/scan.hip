@@ -22,7 +22,8 @@ namespace skipkv {
 namespace {
 
 template <int DT, int NP, int AL, int NSUB, bool PASSB>
-__global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan(ScanArgs a) {
+// (two workgroups per CU are asked for where the query tile leaves room for them in LDS: bf16, up to 160 rows)
+__global__ void __launch_bounds__(256, ((DT == SKIPKV_BF16 && NP * AL <= 40) ? 2 : 1)) k_scan(ScanArgs a) {
   constexpr int SL = NP * AL;        // used (a, i) slots per lane group
   constexpr int NT = (SL + 3) / 4;   // row tiles
   constexpr int SLP = 4 * NT;        // slots incl. padding
