@@ -51,6 +51,7 @@ int check_params(const skipkv_cache *c, const skipkv_params *p, RowLayout *rl) {
   const int n = c->n_kv_heads > 0 ? c->n_q_heads / c->n_kv_heads : 1;
   if (!make_row_layout(n, p->obs_window, rl)) return SKIPKV_ECAPACITY;
   if (c->dtype == SKIPKV_F32 && rl->rows > 160) return SKIPKV_ECAPACITY;  // fp32 query tile would not fit in LDS
+  rl->rows = scan_two_pass_rows(*rl, c->dtype);
   return SKIPKV_OK;
 }
 

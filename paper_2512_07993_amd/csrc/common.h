@@ -176,6 +176,7 @@ struct ScanArgs {
 };
 bool scan_fused_supported(const RowLayout &rl, int64_t row_pitch_bytes);
 hipError_t launch_scan_fused(const ScanArgs &a, hipStream_t st);    // single pass over K (sequences the plan marked fused)
+int scan_two_pass_rows(const RowLayout &rl, int dtype);  // rows of the statistics arrays that the two-pass scan of this shape needs (>= rl.rows)
 hipError_t launch_scan_stats(const ScanArgs &a, hipStream_t st);    // pass A: row statistics + sentence embeddings
 hipError_t launch_row_norm(const ScanArgs &a, hipStream_t st);      // combine the per-chunk statistics
 hipError_t launch_scan_scores(const ScanArgs &a, hipStream_t st);   // pass B: token importance, sentence means

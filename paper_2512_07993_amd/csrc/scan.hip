@@ -17,6 +17,8 @@
 // exp() is evaluated in base 2: logits are scaled by log2(e)/sqrt(d).
 #include "scan_common.h"
 
+#include <algorithm>
+
 namespace skipkv {
 
 namespace {
@@ -310,6 +312,306 @@ __global__ void __launch_bounds__(256, ((DT == SKIPKV_BF16 && NP * AL <= 40) ? 2
   }  // item loop
 }
 
+// ---- many query rows (more than four row tiles; bf16) ------------------------------------------
+// With n * alpha > 64 query rows the kernel above reads every query fragment from LDS again for
+// every 16 tokens, and that LDS traffic is what bounds it.  Here the rows are split over the
+// waves instead of the tokens: wave w owns the window queries al = w*APW .. w*APW+APW-1 of every
+// lane group (all NP heads of each, so that the maximum over the group's heads stays inside a
+// lane), keeps their query fragments in registers for the whole chunk (loaded straight from
+// global memory: no query tile in LDS), and multiplies them with all 64 tokens of a key tile.
+// Row statistics need no merge across waves (a row belongs to one wave); token importance does
+// (a token's window queries are spread over the waves) and goes through a small LDS array.
+// Row ids: r = wave * RW + 16 * T + 4 * g + j for local row tile T, lane group g, register j.
+template <int NP, int AL>
+struct WideShape {
+  static constexpr int APW = AL / 4;            // window-query slots per wave and lane group
+  static constexpr int SPW = APW * NP;          // used (a, i) slots per wave
+  static constexpr int TPW = (SPW + 3) / 4;     // row tiles per wave
+  static constexpr int SLW = 4 * TPW;           // slots per wave incl. padding
+  static constexpr int RW = 16 * TPW;           // query rows per wave
+  static constexpr int R = 4 * RW;              // rows of the statistics arrays
+};
+
+template <int NP, int AL, bool PASSB>
+__global__ void __launch_bounds__(256, 2) k_scan_wide(ScanArgs a) {
+  using WS = WideShape<NP, AL>;
+  constexpr int APW = WS::APW, SPW = WS::SPW, TPW = WS::TPW, SLW = WS::SLW, RW = WS::RW;
+  constexpr int TT = 64;             // tokens per key tile: four sub-tiles of 16
+  constexpr int LSTR = Tr<SKIPKV_BF16>::LSTR, ROWB = Tr<SKIPKV_BF16>::ROWB, ESZ = 2;
+  constexpr int PPR = ROWB / 16, LOADS = TT * PPR / 256;
+  static_assert(AL % 4 == 0, "the window-query slots are dealt out to four waves");
+
+  __shared__ __align__(16) char kt[TT * LSTR];
+  __shared__ int soff[kChunkMaxSent + 1];
+  // pass A: sentence key sums [kChunkMaxSent][128]
+  // pass B: token importance of the tile [TT], sentence sums of I and of R [2][kChunkMaxSent], per-wave parts [4][TT]
+  constexpr int SBUF = PASSB ? (TT + 2 * kChunkMaxSent + 4 * TT) : (kChunkMaxSent * kD);
+  __shared__ float sbuf[SBUF];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, c16 = lane & 15, g = lane >> 4;
+  if (!a.force_two_pass && a.ws.hdr->n_unfused == 0) return;
+  const int R = a.ws.rows;  // stride of the statistics arrays (>= WS::R)
+  const int n_lh = a.n_layers * a.n_kv_heads;
+  const int n_chunks = hdr_chunks(a.ws.hdr->ranges);
+  const uint32_t n_items = (uint32_t)n_lh * (uint32_t)n_chunks;
+  const int n = a.n_q_heads / a.n_kv_heads;
+  for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+  const int lh = item / n_chunks, c = item % n_chunks;
+  const Chunk ch = a.ws.chunks[c];
+  const int b = ch.b, ns = ch.ns;
+  if (!a.force_two_pass && a.ws.seq_fused[b]) continue;
+  const int l = lh / a.n_kv_heads, h = lh % a.n_kv_heads;
+  const int tok0 = ch.tok0;
+  const int n_tok = ch.n_tok;
+  const int sent_col0 = ch.soff_idx - b;
+  __syncthreads();  // the previous item's readers of LDS are done
+
+  if (tid <= ns) soff[tid] = a.sent_off[ch.soff_idx + tid];
+  for (int i = tid; i < SBUF; i += 256) sbuf[i] = 0.f;
+
+  // ---- the wave's query fragments: lane (row c16 of a tile, head-dim slice g), as the A operand wants them
+  bf16x8 afr[TPW][4];
+  {
+    const char *qbase = static_cast<const char *>(a.q);
+    // layer, KV head and sequence that address the query rows (the real ones under per-head ranges)
+    int ql = l, qh = h, qb = b, q_batch = a.batch, q_heads = a.n_q_heads;
+    if (a.virt_hk > 0) {
+      const int lh_r = b / a.virt_b;
+      qb = b % a.virt_b;
+      ql = lh_r / a.virt_hk;
+      qh = lh_r % a.virt_hk;
+      q_batch = a.virt_b;
+      q_heads = a.virt_hk * n;
+    }
+#pragma unroll
+    for (int T = 0; T < TPW; ++T) {
+      // row c16 of a tile is register (c16 & 3) of lane group c16 / 4 in the output
+      const int slot = 4 * T + (c16 & 3), gq = c16 >> 2;
+      const int al = wave * APW + slot / NP, i = slot % NP, aq = gq + 4 * al;
+      const bool used = slot < SPW && i < n && aq < a.alpha;
+      const int64_t row = (((int64_t)ql * q_batch + qb) * q_heads + (qh * n + (used ? i : 0))) * a.alpha + (used ? aq : 0);
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (used) v = *reinterpret_cast<const uint4 *>(qbase + row * ROWB + g * 64 + kk * 16);
+        afr[T][kk] = __builtin_bit_cast(bf16x8, v);
+      }
+    }
+  }
+  __syncthreads();
+
+  const int t_begin = soff[0], t_end = soff[ns];
+  // contiguous cache: row t of the sequence is row tok0 + t of the head; paged cache: the row map says where it is
+  const int32_t *rmap = a.row_map ? a.row_map + tok0 : nullptr;
+  const char *kbase = static_cast<const char *>(a.k) +
+                      ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head + (rmap ? 0 : (int64_t)tok0 * a.stride_tok)) * ESZ;
+  const int64_t tok_pitch = a.stride_tok * ESZ;
+  const int last_free = n_tok - a.alpha;  // keys t <= last_free are visible to every window query
+
+  // per-lane state; slot q = 4 * T + j of this wave: window query g + 4 * (wave * APW + q / NP), head q % NP
+  float ref[SLW], lsum[SLW], cn[SLW];
+  const int64_t lhb = (int64_t)lh * a.batch + b;
+#pragma unroll
+  for (int q = 0; q < SLW; ++q) {
+    ref[q] = kRefInit;
+    lsum[q] = 0.f;
+    cn[q] = INFINITY;  // pass B: log2 normaliser of the slot's query row (+inf: unused slot)
+    if constexpr (PASSB) {
+      const int i = q % NP, aq = g + 4 * (wave * APW + q / NP);
+      const bool used = q < SPW && i < n && aq < a.alpha;
+      if (used) cn[q] = a.ws.row_norm[lhb * R + wave * RW + 16 * (q >> 2) + 4 * g + (q & 3)];
+    }
+  }
+  const int p_start = n_tok - min(a.protect, n_tok);  // first protected token
+
+  for (int tile_t = t_begin; tile_t < t_end; tile_t += TT) {
+    // ---- stream the tile into LDS
+    {
+      uint4 regs[LOADS];
+      int rows[LOADS];
+#pragma unroll
+      for (int it = 0; it < LOADS; ++it) {
+        const int t = tile_t + (it * 256 + tid) / PPR;
+        rows[it] = t;
+        if (rmap && t < t_end) rows[it] = rmap[t];
+      }
+#pragma unroll
+      for (int it = 0; it < LOADS; ++it) {
+        const int idx = it * 256 + tid, row = idx / PPR, piece = idx % PPR, t = tile_t + row;
+        regs[it] = make_uint4(0, 0, 0, 0);
+        if (t < t_end) regs[it] = *reinterpret_cast<const uint4 *>(kbase + (int64_t)rows[it] * tok_pitch + piece * 16);
+      }
+#pragma unroll
+      for (int it = 0; it < LOADS; ++it) {
+        const int idx = it * 256 + tid, row = idx / PPR, piece = idx % PPR;
+        *reinterpret_cast<uint4 *>(kt + row * LSTR + piece * 16) = regs[it];
+      }
+    }
+    __syncthreads();
+
+    // ---- logits of the wave's rows against all 64 tokens: acc[s][T][j] = row 4g+j of tile T, token 16s + c16
+    f32x4 acc[4][TPW];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+#pragma unroll
+      for (int T = 0; T < TPW; ++T) acc[s][T] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (tile_t + 16 * s < t_end) {
+        const char *krow = kt + (16 * s + c16) * LSTR + g * 64;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(krow + kk * 16);
+#pragma unroll
+          for (int T = 0; T < TPW; ++T) acc[s][T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afr[T][kk], bfrag, acc[s][T], 0, 0, 0);
+        }
+      }
+    }
+
+    if constexpr (!PASSB) {
+      // ---- running softmax statistics of the wave's query rows over the tile's tokens
+      float tmax[SLW];
+#pragma unroll
+      for (int q = 0; q < SLW; ++q) tmax[q] = -INFINITY;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const int t = tile_t + 16 * s + c16;
+        const bool edge = (tile_t + 16 * s + 15 >= t_end) || (tile_t + 16 * s + 15 > last_free);
+#pragma unroll
+        for (int q = 0; q < SLW; ++q) {
+          float x = acc[s][q >> 2][q & 3] * kScale2;
+          if (edge) {
+            const int aq = g + 4 * (wave * APW + q / NP);
+            if (!(t < t_end && t <= last_free + aq)) x = -INFINITY;
+          }
+          acc[s][q >> 2][q & 3] = x;
+          tmax[q] = fmaxf(tmax[q], x);
+        }
+      }
+      bool need = false;
+#pragma unroll
+      for (int q = 0; q < SLW; ++q) need |= tmax[q] > ref[q] + kRescaleSlack;
+      if (__any(need)) {
+#pragma unroll
+        for (int q = 0; q < SLW; ++q) {
+          const float nr = fmaxf(ref[q], row16_max(tmax[q]));
+          lsum[q] *= __builtin_amdgcn_exp2f(ref[q] - nr);
+          ref[q] = nr;
+        }
+      }
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int q = 0; q < SLW; ++q) lsum[q] += __builtin_amdgcn_exp2f(acc[s][q >> 2][q & 3] - ref[q]);
+
+      // ---- sentence key sums: wave w takes tokens 16w .. 16w+15 of the tile, lane = 2 head-dim columns.
+      // The 16 rows come into registers with one LDS round trip (rows past the end of the chunk hold
+      // zeros); every run of rows that belongs to one sentence is added with a 0/1 weight per row.
+      {
+        const int t_lo = tile_t + 16 * wave, t_hi = min(t_lo + 16, t_end);
+        if (t_lo < t_hi) {
+          uint32_t xw[16];
+#pragma unroll
+          for (int i = 0; i < 16; ++i) xw[i] = *reinterpret_cast<const uint32_t *>(kt + (16 * wave + i) * LSTR + lane * 4);
+          int t = t_lo;
+          int si = __popcll(__ballot(lane < ns && soff[lane + 1] <= t));
+          while (t < t_hi) {
+            const int run_end = min(soff[si + 1], t_hi);
+            if (run_end <= t) break;  // cannot happen with validated offsets; never spin on bad ones
+            const uint32_t rows = ((1u << (run_end - t_lo)) - 1u) & ~((1u << (t - t_lo)) - 1u);  // run_end - t_lo <= 16
+            float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const float m = ((rows >> i) & 1u) ? 1.f : 0.f;
+              s0 = fmaf(__uint_as_float(xw[i] << 16), m, s0);
+              s1 = fmaf(__uint_as_float(xw[i] & 0xFFFF0000u), m, s1);
+            }
+            atomicAdd(&sbuf[si * kD + 2 * lane], s0);
+            atomicAdd(&sbuf[si * kD + 2 * lane + 1], s1);
+            ++si;
+            t = run_end;
+          }
+        }
+      }
+    } else {
+      // ---- token importance: max over the group's heads in registers, exp2, sum over the wave's window
+      // queries; the four waves' parts are added in a fixed order through LDS
+      float *imp = sbuf, *part = sbuf + TT + 2 * kChunkMaxSent;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const int t = tile_t + 16 * s + c16;
+        const bool edge = (tile_t + 16 * s + 15 > last_free);
+        float sum = 0.f;
+#pragma unroll
+        for (int al = 0; al < APW; ++al) {
+          float gm = -INFINITY;
+#pragma unroll
+          for (int i = 0; i < NP; ++i) {
+            const int q = al * NP + i;
+            gm = fmaxf(gm, fmaf(acc[s][q >> 2][q & 3], kScale2, -cn[q]));
+          }
+          if (edge && t > last_free + g + 4 * (wave * APW + al)) gm = -INFINITY;
+          sum += __builtin_amdgcn_exp2f(gm);
+        }
+        sum += __shfl_xor(sum, 16);
+        sum += __shfl_xor(sum, 32);
+        if (g == 0) part[wave * TT + 16 * s + c16] = sum;
+      }
+      __syncthreads();
+      if (tid < TT) {
+        const float tot = ((part[tid] + part[TT + tid]) + part[2 * TT + tid]) + part[3 * TT + tid];
+        imp[tid] = (tile_t + tid < t_end) ? tot / (float)a.alpha : 0.f;
+      }
+      __syncthreads();
+      // sentence sums over the unprotected part, and the optional per-token outputs / inputs
+      const int64_t tok_col = (int64_t)lh * a.total_tokens + tok0;
+      if (tid < ns) {
+        const int lo = max(soff[tid], tile_t), hi = min(min(soff[tid + 1], p_start), tile_t + TT);
+        float si = 0.f, sr = 0.f;
+        for (int t = lo; t < hi; ++t) {
+          si += imp[t - tile_t];
+          if (a.tok_red) sr += a.tok_red[tok_col + t];
+        }
+        sbuf[TT + tid] += si;
+        sbuf[TT + kChunkMaxSent + tid] += sr;
+      }
+      if (a.tok_imp) {
+        for (int i = tid; i < TT && tile_t + i < t_end; i += 256) a.tok_imp[tok_col + tile_t + i] = imp[i];
+      }
+    }
+    __syncthreads();  // the next tile overwrites kt / imp / part
+  }
+
+  if constexpr (!PASSB) {
+    // ---- unit sentence embeddings, split into bf16 hi + lo, one wave per sentence
+    for (int si = wave; si < ns && !a.no_pool; si += 4) {
+      const float inv_len = 1.f / (float)(soff[si + 1] - soff[si]);
+      const float m0 = sbuf[si * kD + 2 * lane] * inv_len, m1 = sbuf[si * kD + 2 * lane + 1] * inv_len;
+      const float nrm = sqrtf(wave_sum(m0 * m0 + m1 * m1));
+      const float inv = 1.f / (nrm + 1e-12f);
+      const float u0 = m0 * inv, u1 = m1 * inv;
+      const uint32_t h0 = f32_to_bf16_bits(u0), h1 = f32_to_bf16_bits(u1);
+      const uint32_t l0 = f32_to_bf16_bits(u0 - bf16_bits_to_f32(h0)), l1 = f32_to_bf16_bits(u1 - bf16_bits_to_f32(h1));
+      const int64_t o = ((int64_t)lh * a.total_sentences + sent_col0 + si) * (kD / 2) + lane;
+      reinterpret_cast<uint32_t *>(a.ws.vhat_hi)[o] = h0 | (h1 << 16);
+      reinterpret_cast<uint32_t *>(a.ws.vhat_lo)[o] = l0 | (l1 << 16);
+    }
+    // ---- the chunk's partial statistics: every row belongs to one wave, nothing to merge
+#pragma unroll
+    for (int q = 0; q < SLW; ++q) {
+      const float tot = row16_sum(lsum[q]);
+      if (c16 == 0)
+        a.ws.stat_part[((int64_t)lh * a.ws.nc_max + c) * R + wave * RW + 16 * (q >> 2) + 4 * g + (q & 3)] = make_float2(ref[q], tot);
+    }
+  } else {
+    if (tid < ns) {
+      const int len = min(soff[tid + 1], p_start) - soff[tid];
+      const int64_t o = (int64_t)lh * a.total_sentences + sent_col0 + tid;
+      a.ws.sent_imp[o] = len > 0 ? sbuf[TT + tid] / (float)len : 0.f;
+      a.ws.sent_red[o] = len > 0 ? sbuf[TT + kChunkMaxSent + tid] / (float)len : 0.f;
+    }
+  }
+  }  // item loop
+}
+
 // log2 of the softmax normaliser of every query row: merge the chunk partials of a head.
 __global__ void k_row_norm(ScanArgs a, int R) {
   const int lhb = blockIdx.x, lh = lhb / a.batch, b = lhb % a.batch;
@@ -338,8 +640,24 @@ hipError_t launch_one(const ScanArgs &a, hipStream_t st) {
   return hipGetLastError();
 }
 
+template <int NP, int AL, bool PASSB>
+hipError_t launch_wide(const ScanArgs &a, hipStream_t st) {
+  if (a.ws.rows < WideShape<NP, AL>::R) return hipErrorInvalidValue;
+  const int64_t items = (int64_t)a.n_layers * a.n_kv_heads * a.ws.nc_max;
+  if (items == 0) return hipSuccess;
+  const int64_t grid = items < 4096 ? items : 4096;  // grid-stride over the items
+  hipLaunchKernelGGL((k_scan_wide<NP, AL, PASSB>), dim3((unsigned)grid), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
 template <bool PASSB>
 hipError_t dispatch(const ScanArgs &a, hipStream_t st) {
+  if (a.dtype == SKIPKV_BF16 && a.rl.nt > 4) {  // many query rows: rows split over the waves
+    if (a.rl.np == 4 && a.rl.al == 8) return launch_wide<4, 8, PASSB>(a, st);
+    if (a.rl.np == 8 && a.rl.al == 4) return launch_wide<8, 4, PASSB>(a, st);
+    if (a.rl.np == 8 && a.rl.al == 8) return launch_wide<8, 8, PASSB>(a, st);
+    if (a.rl.np == 5 && a.rl.al == 8) return launch_wide<5, 8, PASSB>(a, st);
+  }
 #define SKIPKV_CASE(NP_, AL_)                                                       \
   if (a.rl.np == NP_ && a.rl.al == AL_)                                             \
     return a.dtype == SKIPKV_BF16 ? launch_one<SKIPKV_BF16, NP_, AL_, PASSB>(a, st) \
@@ -358,6 +676,14 @@ hipError_t dispatch(const ScanArgs &a, hipStream_t st) {
 }
 
 }  // namespace
+
+int scan_two_pass_rows(const RowLayout &rl, int dtype) {
+  if (dtype == SKIPKV_BF16 && rl.nt > 4 && rl.al % 4 == 0) {
+    const int tiles_per_wave = ((rl.al / 4) * rl.np + 3) / 4;
+    return std::max(rl.rows, 64 * tiles_per_wave);
+  }
+  return rl.rows;
+}
 
 hipError_t launch_scan_stats(const ScanArgs &a, hipStream_t st) { return dispatch<false>(a, st); }
 hipError_t launch_scan_scores(const ScanArgs &a, hipStream_t st) { return dispatch<true>(a, st); }
