@@ -449,59 +449,73 @@ __global__ void __launch_bounds__(256, 2) k_scan_wide(ScanArgs a) {
     }
     __syncthreads();
 
-    // ---- logits of the wave's rows against all 64 tokens: acc[s][T][j] = row 4g+j of tile T, token 16s + c16
-    f32x4 acc[4][TPW];
+    // ---- per sub-tile of 16 tokens: logits of the wave's rows (acc[T][j] = row 4g+j of tile T, token 16s + c16),
+    // then straight away what the pass needs from them, so that only one sub-tile's logits are live
+    [[maybe_unused]] float *part = sbuf + TT + 2 * kChunkMaxSent;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-#pragma unroll
-      for (int T = 0; T < TPW; ++T) acc[s][T] = f32x4{0.f, 0.f, 0.f, 0.f};
-      if (tile_t + 16 * s < t_end) {
-        const char *krow = kt + (16 * s + c16) * LSTR + g * 64;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(krow + kk * 16);
-#pragma unroll
-          for (int T = 0; T < TPW; ++T) acc[s][T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afr[T][kk], bfrag, acc[s][T], 0, 0, 0);
-        }
+      if (tile_t + 16 * s >= t_end) {
+        if constexpr (PASSB)
+          if (g == 0) part[wave * TT + 16 * s + c16] = 0.f;
+        continue;
       }
-    }
-
-    if constexpr (!PASSB) {
-      // ---- running softmax statistics of the wave's query rows over the tile's tokens
-      float tmax[SLW];
+      f32x4 acc[TPW];
 #pragma unroll
-      for (int q = 0; q < SLW; ++q) tmax[q] = -INFINITY;
+      for (int T = 0; T < TPW; ++T) acc[T] = f32x4{0.f, 0.f, 0.f, 0.f};
+      const char *krow = kt + (16 * s + c16) * LSTR + g * 64;
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        const int t = tile_t + 16 * s + c16;
+      for (int kk = 0; kk < 4; ++kk) {
+        const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(krow + kk * 16);
+#pragma unroll
+        for (int T = 0; T < TPW; ++T) acc[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afr[T][kk], bfrag, acc[T], 0, 0, 0);
+      }
+      const int t = tile_t + 16 * s + c16;
+      if constexpr (!PASSB) {
+        // running softmax statistics of the wave's query rows
         const bool edge = (tile_t + 16 * s + 15 >= t_end) || (tile_t + 16 * s + 15 > last_free);
+        bool need = false;
 #pragma unroll
         for (int q = 0; q < SLW; ++q) {
-          float x = acc[s][q >> 2][q & 3] * kScale2;
+          float x = acc[q >> 2][q & 3] * kScale2;
           if (edge) {
             const int aq = g + 4 * (wave * APW + q / NP);
             if (!(t < t_end && t <= last_free + aq)) x = -INFINITY;
           }
-          acc[s][q >> 2][q & 3] = x;
-          tmax[q] = fmaxf(tmax[q], x);
+          acc[q >> 2][q & 3] = x;
+          need |= x > ref[q] + kRescaleSlack;
         }
-      }
-      bool need = false;
+        if (__any(need)) {
 #pragma unroll
-      for (int q = 0; q < SLW; ++q) need |= tmax[q] > ref[q] + kRescaleSlack;
-      if (__any(need)) {
-#pragma unroll
-        for (int q = 0; q < SLW; ++q) {
-          const float nr = fmaxf(ref[q], row16_max(tmax[q]));
-          lsum[q] *= __builtin_amdgcn_exp2f(ref[q] - nr);
-          ref[q] = nr;
+          for (int q = 0; q < SLW; ++q) {
+            const float nr = fmaxf(ref[q], row16_max(acc[q >> 2][q & 3]));
+            lsum[q] *= __builtin_amdgcn_exp2f(ref[q] - nr);
+            ref[q] = nr;
+          }
         }
+#pragma unroll
+        for (int q = 0; q < SLW; ++q) lsum[q] += __builtin_amdgcn_exp2f(acc[q >> 2][q & 3] - ref[q]);
+      } else {
+        // token importance: max over the group's heads in registers, exp2, sum over the wave's window queries
+        const bool edge = (tile_t + 16 * s + 15 > last_free);
+        float sum = 0.f;
+#pragma unroll
+        for (int al = 0; al < APW; ++al) {
+          float gm = -INFINITY;
+#pragma unroll
+          for (int i = 0; i < NP; ++i) {
+            const int q = al * NP + i;
+            gm = fmaxf(gm, fmaf(acc[q >> 2][q & 3], kScale2, -cn[q]));
+          }
+          if (edge && t > last_free + g + 4 * (wave * APW + al)) gm = -INFINITY;
+          sum += __builtin_amdgcn_exp2f(gm);
+        }
+        sum += __shfl_xor(sum, 16);
+        sum += __shfl_xor(sum, 32);
+        if (g == 0) part[wave * TT + 16 * s + c16] = sum;
       }
-#pragma unroll
-      for (int s = 0; s < 4; ++s)
-#pragma unroll
-        for (int q = 0; q < SLW; ++q) lsum[q] += __builtin_amdgcn_exp2f(acc[s][q >> 2][q & 3] - ref[q]);
+    }
 
+    if constexpr (!PASSB) {
       // ---- sentence key sums: wave w takes tokens 16w .. 16w+15 of the tile, lane = 2 head-dim columns.
       // The 16 rows come into registers with one LDS round trip (rows past the end of the chunk hold
       // zeros); every run of rows that belongs to one sentence is added with a 0/1 weight per row.
@@ -532,29 +546,8 @@ __global__ void __launch_bounds__(256, 2) k_scan_wide(ScanArgs a) {
         }
       }
     } else {
-      // ---- token importance: max over the group's heads in registers, exp2, sum over the wave's window
-      // queries; the four waves' parts are added in a fixed order through LDS
-      float *imp = sbuf, *part = sbuf + TT + 2 * kChunkMaxSent;
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        const int t = tile_t + 16 * s + c16;
-        const bool edge = (tile_t + 16 * s + 15 > last_free);
-        float sum = 0.f;
-#pragma unroll
-        for (int al = 0; al < APW; ++al) {
-          float gm = -INFINITY;
-#pragma unroll
-          for (int i = 0; i < NP; ++i) {
-            const int q = al * NP + i;
-            gm = fmaxf(gm, fmaf(acc[s][q >> 2][q & 3], kScale2, -cn[q]));
-          }
-          if (edge && t > last_free + g + 4 * (wave * APW + al)) gm = -INFINITY;
-          sum += __builtin_amdgcn_exp2f(gm);
-        }
-        sum += __shfl_xor(sum, 16);
-        sum += __shfl_xor(sum, 32);
-        if (g == 0) part[wave * TT + 16 * s + c16] = sum;
-      }
+      // ---- the four waves' parts of the token importance are added in a fixed order through LDS
+      float *imp = sbuf;
       __syncthreads();
       if (tid < TT) {
         const float tot = ((part[tid] + part[TT + tid]) + part[2 * TT + tid]) + part[3 * TT + tid];
