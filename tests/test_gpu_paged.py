@@ -162,3 +162,28 @@ def test_bad_block_id_is_reported_and_that_sequence_left_alone():
     assert torch.equal(vp[:, own].view(torch.uint8), vp0[:, own].view(torch.uint8))
     new_len = out.new_len.cpu().numpy()
     assert (new_len >= 0).all() and (new_len <= cfg.budget).all()
+
+
+@pytest.mark.parametrize("block_size", [16, 1])
+def test_paged_degenerate_batch(block_size):
+    """The ragged and degenerate sequences of the edge tests (an empty sequence, one shorter than the
+    observation window, one that fits its budget, a 700-token sentence that takes its sequence to the
+    two-pass scan, 300 one-token sentences) on a paged cache, every head against the oracle."""
+    from test_gpu_edges import _compare_all, _edge_cfg, _edge_offsets, _random_kvq, _structure
+    cfg = _edge_cfg("bf16")
+    st = _structure(_edge_offsets())
+    k0, v0, q = _random_kvq(cfg, st, 11)
+    kp, vp, table = _to_pages(cfg, st, k0, v0, block_size, seed=3)
+    kp0 = kp.clone()
+    out = _run_paged(cfg, st, kp, vp, table, q)
+    assert int(out.dev_status.item()) == 0
+    kg, vg = _from_pages(cfg, st, kp, table, block_size), _from_pages(cfg, st, vp, table, block_size)
+    stats = _compare_all(cfg, st, out, kg, vg, k0, v0, q)
+    assert stats["heads"] == 8
+    for b in (1, 2):     # sequences that fit are untouched, bit for bit
+        t0, t1 = int(st.seq_off[b]), int(st.seq_off[b + 1])
+        assert torch.equal(kg[:, :, t0:t1], k0[:, :, t0:t1]) and torch.equal(vg[:, :, t0:t1], v0[:, :, t0:t1])
+    blk, slot = _token_slots(cfg, st, table.cpu().numpy(), block_size, kp.device)
+    free = torch.ones(kp.shape[1], kp.shape[2], dtype=torch.bool, device=kp.device)
+    free[blk, slot] = False
+    assert torch.equal(kp[:, free].view(torch.uint8), kp0[:, free].view(torch.uint8))
