@@ -215,7 +215,7 @@ def time_ranges(config_id: int, steps: int = 5) -> int:
 
 
 def time_paged(config_id: int, block_size: int = 16, heads_first: bool = False, steps: int = 5) -> int:
-    """Times skipkv_step_paged on the workload scattered into a pool of blocks of `block_size` token
+    """Times skipkv_step_paged (and skipkv_step_ranges_paged on the same cache described per head) on the workload scattered into a pool of blocks of `block_size` token
     slots ([layers, blocks, slots, KV heads, 128], or [layers, blocks, KV heads, slots, 128] with
     heads_first; blocks in random order), next to skipkv_step on the contiguous cache."""
     import numpy as np
@@ -261,6 +261,11 @@ def time_paged(config_id: int, block_size: int = 16, heads_first: bool = False, 
     prof = B.skipkv_profile_create()
     params = B.Params(cfg.obs_window, cfg.protect_window, cfg.budget, dev_status=status, profile=prof)
     ws = torch.empty(B.skipkv_paged_workspace_bytes(paged, params), dtype=torch.uint8, device=dev)
+    # the same cache described head by head (the form every step after the first takes)
+    ranges = B.Ranges(torch.from_numpy(st.seq_len.astype(np.int32)).to(dev).expand(L, H, Bn).contiguous(),
+                      torch.from_numpy(st.n_sent.astype(np.int32)).to(dev).expand(L, H, Bn).contiguous(),
+                      sf.expand(L, H, sf.numel()).contiguous())
+    ws_rp = torch.empty(B.skipkv_ranges_paged_workspace_bytes(paged, params), dtype=torch.uint8, device=dev)
     kept_stride = min(cfg.budget, T)
     sent_score = torch.empty((L, H, S), dtype=torch.float32, device=dev)
     sent_lambda = torch.empty_like(sent_score)
@@ -270,10 +275,10 @@ def time_paged(config_id: int, block_size: int = 16, heads_first: bool = False, 
     new_off = torch.empty((L, H, S + Bn), dtype=torch.int32, device=dev)
     new_cnt = torch.empty((L, H, Bn), dtype=torch.int32, device=dev)
     out = {}
-    for name in ("step_paged", "step"):
+    for name in ("step_paged", "step_ranges_paged", "step"):
         times = []
         for i in range(steps + 1):
-            if name == "step_paged":
+            if name != "step":
                 kp.copy_(kp0)
                 vp.copy_(vp0)
             else:
@@ -284,6 +289,9 @@ def time_paged(config_id: int, block_size: int = 16, heads_first: bool = False, 
             if name == "step_paged":
                 B.skipkv_step_paged(paged, params, q, None, sent_score, sent_lambda, None, sent_keep, kept_idx, new_len,
                                     new_off, new_cnt, kept_stride, ws)
+            elif name == "step_ranges_paged":
+                B.skipkv_step_ranges_paged(paged, ranges, params, q, None, sent_score, sent_lambda, None, sent_keep,
+                                           kept_idx, new_len, new_off, new_cnt, kept_stride, ws_rp)
             else:
                 B.skipkv_step(cache, params, q, None, sent_score, sent_lambda, None, sent_keep, kept_idx, new_len,
                               new_off, new_cnt, kept_stride, ws)
@@ -296,8 +304,9 @@ def time_paged(config_id: int, block_size: int = 16, heads_first: bool = False, 
     assert int(status.item()) == 0, "device status %d" % int(status.item())
     B.skipkv_profile_destroy(prof)
     print(json.dumps({"op": "step_paged", "workload": "config %d: %s" % (cfg.config_id, cfg.name), "block_size": block_size,
-                      "layout": "[blocks, heads, slots, 128]" if heads_first else "[blocks, slots, heads, 128]", "blocks": n_blocks, "ms_per_step_paged": out["step_paged"], "ms_per_step_contiguous": out["step"],
-                      "kernel_ms_paged": out["step_paged_kernels"], "kernel_ms_contiguous": out["step_kernels"],
+                      "layout": "[blocks, heads, slots, 128]" if heads_first else "[blocks, slots, heads, 128]", "blocks": n_blocks, "ms_per_step_paged": out["step_paged"], "ms_per_step_ranges_paged": out["step_ranges_paged"], "ms_per_step_contiguous": out["step"],
+                      "kernel_ms_paged": out["step_paged_kernels"], "kernel_ms_ranges_paged": out["step_ranges_paged_kernels"],
+                      "kernel_ms_contiguous": out["step_kernels"],
                       "steps": steps}))
     return 0
 

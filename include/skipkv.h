@@ -330,6 +330,29 @@ int skipkv_step_paged(const skipkv_cache *cache, const skipkv_paging *paging, co
                       void *stream);
 
 /*
+ * skipkv_step_ranges on a paged cache: the step of every decode-time compression after the
+ * first, when the heads of a sequence have their own lengths and sentence ranges (Sec. 4.1
+ * "Multi-step Sentence Range Monitoring", Eq. 9-11) and the cache is paged (Appendix,
+ * "System-Level Evaluation on vLLM").  ranges, the outputs and their layouts are those of
+ * skipkv_step_ranges; paging is that of skipkv_step_paged, with the block table shared by the
+ * layers and heads of a sequence and sized for the sequence's extent in cache->seq_off (a head
+ * with len below the extent simply leaves the tail slots unused).  Instead of requiring K and V
+ * contiguous over (layer, head, token), every (layer, head) gets a row map of its own in units
+ * of one head row, so cache->stride_tok, stride_head, stride_layer and paging->stride_block must
+ * all be multiples of head_dim, and the last slot row must fit 31 bits (SKIPKV_ECAPACITY).
+ * Device errors are those of both calls; an invalid block id leaves K and V of all heads of that
+ * sequence untouched.
+ * ws, ws_bytes: device scratch of at least skipkv_ranges_paged_workspace_bytes, 256-byte aligned.
+ */
+int skipkv_ranges_paged_workspace_bytes(const skipkv_cache *cache, const skipkv_paging *paging,
+                                        const skipkv_params *params, size_t *out_bytes);
+int skipkv_step_ranges_paged(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_paging *paging,
+                             const skipkv_params *params, const void *q_obs, const float *tok_redundancy,
+                             float *sent_score, float *sent_lambda, float *tok_importance, uint8_t *sent_keep,
+                             int32_t *kept_idx, int32_t *new_len, int32_t *new_sent_off, int32_t *new_sent_cnt,
+                             int32_t kept_stride, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Steering injection (Sec. 4.2): hidden[b, :] <- hidden[b, :] + coef_b * vec for every row b
  * with row_mask[b] != 0 (all rows when row_mask is NULL).  coef_b = coef[b] when coef is
  * non-NULL, else coef_scalar.  The sum is formed in fp64 and rounded once (nearest even)

@@ -83,6 +83,8 @@ def lib() -> C.CDLL:
         gp = C.POINTER(CPaging)
         L.skipkv_paged_workspace_bytes.argtypes = [cp, gp, pp, C.POINTER(sz)]
         L.skipkv_step_paged.argtypes = [cp, gp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+        L.skipkv_ranges_paged_workspace_bytes.argtypes = [cp, gp, pp, C.POINTER(sz)]
+        L.skipkv_step_ranges_paged.argtypes = [cp, rp, gp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
         L.skipkv_profile_create.argtypes = [C.POINTER(vp)]
         L.skipkv_profile_read.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_char_p), C.POINTER(fl)]
         L.skipkv_profile_destroy.argtypes = [vp]
@@ -303,6 +305,23 @@ def skipkv_step_paged(cache: PagedCache, params: Params, q_obs, tok_redundancy, 
                                    _ptr(sent_keep), _ptr(kept_idx), _ptr(new_len), _ptr(new_sent_off),
                                    _ptr(new_sent_cnt), kept_stride, _ptr(ws),
                                    ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
+
+
+def skipkv_ranges_paged_workspace_bytes(cache: PagedCache, params: Params) -> int:
+    out = C.c_size_t(0)
+    _check(lib().skipkv_ranges_paged_workspace_bytes(C.byref(cache.c()), C.byref(cache.paging()), C.byref(params.c()),
+                                                     C.byref(out)))
+    return int(out.value)
+
+
+def skipkv_step_ranges_paged(cache: PagedCache, ranges: Ranges, params: Params, q_obs, tok_redundancy, sent_score,
+                             sent_lambda, tok_importance, sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt,
+                             kept_stride: int, ws, stream=None) -> None:
+    _check(lib().skipkv_step_ranges_paged(C.byref(cache.c()), C.byref(ranges.c()), C.byref(cache.paging()),
+                                          C.byref(params.c()), _ptr(q_obs), _ptr(tok_redundancy), _ptr(sent_score),
+                                          _ptr(sent_lambda), _ptr(tok_importance), _ptr(sent_keep), _ptr(kept_idx),
+                                          _ptr(new_len), _ptr(new_sent_off), _ptr(new_sent_cnt), kept_stride, _ptr(ws),
+                                          ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
 
 
 def skipkv_similarity_workspace_bytes(cache: Cache, d_model: int) -> int:

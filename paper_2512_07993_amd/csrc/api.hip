@@ -99,6 +99,7 @@ struct HeadView {
   int32_t virt_hk = 0, virt_b = 0;
   const int32_t *row_map = nullptr;  // paged cache: logical token -> slot row
   int32_t page_size = 0;             // ... and its slots per block
+  int64_t map_stride = 0;            // ... and the elements per unit of the map (0: stride_tok)
 };
 
 struct Timer {
@@ -155,6 +156,7 @@ int do_score(Timer &tm, const skipkv_cache *c, const skipkv_params *p, const Row
   const char *env_spin = std::getenv("SKIPKV_SPIN_LIMIT");
   sa.row_map = hv.row_map;
   sa.page_size = hv.page_size;
+  sa.map_stride = hv.map_stride ? hv.map_stride : c->stride_tok;
   const bool pages_fit_stages = hv.page_size >= 16 && (hv.page_size & (hv.page_size - 1)) == 0;
   sa.force_two_pass = (hv.row_map != nullptr && !pages_fit_stages) || (env_two && env_two[0] == '1') || !scan_fused_supported(rl, c->stride_tok * (c->dtype == SKIPKV_BF16 ? 2 : 4));
   sa.spin_limit = env_spin ? std::atoi(env_spin) : 4000000;
@@ -235,8 +237,9 @@ int do_select(Timer &tm, const skipkv_cache *c, const skipkv_params *p, const fl
 
 int do_compact(Timer &tm, const skipkv_cache *c, const int32_t *kept_idx, const int32_t *new_len, int32_t kept_stride,
                hipStream_t st, const int32_t *row_map = nullptr, const int32_t *seq_bad = nullptr,
-               int32_t *src_rows = nullptr, int32_t src_stride = 0) {
+               int32_t *src_rows = nullptr, int32_t src_stride = 0, int64_t map_stride = 0) {
   CompactArgs a{};
+  a.map_stride = map_stride ? map_stride : c->stride_tok;
   a.row_map = row_map;
   a.seq_bad = seq_bad;
   a.src_rows = src_rows;
@@ -273,13 +276,13 @@ struct VirtualView {
   size_t head_bytes;            // bytes taken from the workspace for them
 };
 
-int make_virtual(const skipkv_cache *c, const skipkv_ranges *r, void *ws, VirtualView *out) {
+int make_virtual(const skipkv_cache *c, const skipkv_ranges *r, void *ws, VirtualView *out, bool paged = false) {
   if (!r || !r->len || !r->sent_cnt || !r->sent_off) return SKIPKV_EINVAL;
   const int64_t LH = (int64_t)c->n_layers * c->n_kv_heads, B = c->batch;
   const int64_t T = c->total_tokens, S = c->total_sentences;
   if (LH * B >= (1ll << 31) - 1 || LH * T >= (1ll << 31) - 1 || LH * (S + B) >= (1ll << 31) - 1) return SKIPKV_ECAPACITY;
-  // K and V must be one flat array of rows over (layer, head, token)
-  if (T > 0 && (c->stride_head != T * c->stride_tok || c->stride_layer != c->n_kv_heads * c->stride_head)) return SKIPKV_ECAPACITY;
+  // K and V must be one flat array of rows over (layer, head, token), unless a row map says where the rows are
+  if (!paged && T > 0 && (c->stride_head != T * c->stride_tok || c->stride_layer != c->n_kv_heads * c->stride_head)) return SKIPKV_ECAPACITY;
   VirtualView v{};
   v.c = *c;
   v.c.n_layers = 1;
@@ -450,13 +453,20 @@ struct PagedView {
   size_t step_bytes, map_bytes, bad_bytes, total;
   int32_t rows_per_block, src_stride;
 };
-int check_paging(const skipkv_cache *c, const skipkv_paging *pg, const skipkv_params *p, const RowLayout &rl, PagedView *v) {
+int check_paging_desc(const skipkv_cache *c, const skipkv_paging *pg, int64_t *rows_per_block) {
   if (!pg) return SKIPKV_EINVAL;
   if (pg->block_size < 1 || pg->n_blocks < 1 || pg->table_stride < 0 || pg->stride_block < 0) return SKIPKV_EINVAL;
   if (!pg->block_table && c->total_tokens > 0) return SKIPKV_EINVAL;
   if (c->stride_tok <= 0 || pg->stride_block % c->stride_tok) return SKIPKV_EINVAL;
   const int64_t rpb = pg->stride_block / c->stride_tok;
   if (rpb < pg->block_size) return SKIPKV_EINVAL;  // the slots of a block must not reach into the next one
+  *rows_per_block = rpb;
+  return SKIPKV_OK;
+}
+int check_paging(const skipkv_cache *c, const skipkv_paging *pg, const skipkv_params *p, const RowLayout &rl, PagedView *v) {
+  int64_t rpb = 0;
+  const int rc = check_paging_desc(c, pg, &rpb);
+  if (rc) return rc;
   if ((int64_t)pg->n_blocks * rpb > 0x7FFFFFFFll) return SKIPKV_ECAPACITY;  // slot rows are 32-bit
   v->rows_per_block = (int32_t)rpb;
   const Workspace w = carve(c, rl, nullptr);
@@ -515,7 +525,7 @@ int skipkv_step_paged(const skipkv_cache *cache, const skipkv_paging *paging, co
   int32_t *row_map = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + pv.step_bytes);
   int32_t *seq_bad = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + pv.step_bytes + pv.map_bytes);
   RowMapArgs ra{cache->seq_off, paging->block_table, cache->batch, paging->table_stride, paging->block_size,
-                paging->n_blocks, pv.rows_per_block, row_map, seq_bad, params->dev_status};
+                paging->n_blocks, 1, 1, cache->total_tokens, 0, 0, pv.rows_per_block, 1, row_map, seq_bad, params->dev_status};
   if (tm.run("row_map", [&] { return launch_row_map(ra, st); }) != hipSuccess) return SKIPKV_EHIP;
   HeadView hv;
   hv.row_map = row_map;
@@ -583,6 +593,113 @@ int skipkv_step_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, c
   rc = do_select(tm, &v.c, params, sent_score, sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride, st, v.hv);
   if (rc) return rc;
   return do_compact(tm, &v.c, kept_idx, new_len, kept_stride, st);
+}
+
+namespace {
+// Per-head ranges on a paged cache.  The virtual cache of make_virtual has one layer and one head,
+// so the (layer, head) part of an address moves into the row map: every (layer, head) gets a map
+// of its own whose unit is one head row (head_dim elements), which every stride must be a
+// multiple of.  Behind the virtual layout and the step's workspace sit these maps, the
+// per-(head, sequence) flags and the slot rows of the kept tokens.
+struct RangesPagedView {
+  VirtualView v;
+  size_t step_bytes, map_bytes, bad_bytes, total;
+  int32_t src_stride;
+  int64_t unit_layer, unit_head, unit_block, unit_tok;
+};
+int check_ranges_paging(const skipkv_cache *c, const skipkv_ranges *r, const skipkv_paging *pg, const skipkv_params *p,
+                        const RowLayout &rl, void *ws, RangesPagedView *o) {
+  int64_t rpb = 0;
+  int rc = check_paging_desc(c, pg, &rpb);
+  if (rc) return rc;
+  const int64_t D = c->head_dim;
+  if ((c->stride_tok % D) || (c->stride_head % D) || (c->stride_layer % D) || (pg->stride_block % D)) return SKIPKV_EINVAL;
+  o->unit_layer = c->stride_layer / D;
+  o->unit_head = c->stride_head / D;
+  o->unit_block = pg->stride_block / D;
+  o->unit_tok = c->stride_tok / D;
+  const int64_t last_row = (int64_t)(c->n_layers - 1) * o->unit_layer + (int64_t)(c->n_kv_heads - 1) * o->unit_head +
+                           (int64_t)(pg->n_blocks - 1) * o->unit_block + (int64_t)(pg->block_size - 1) * o->unit_tok;
+  if (last_row > 0x7FFFFFFFll) return SKIPKV_ECAPACITY;  // slot rows are 32-bit
+  rc = make_virtual(c, r, ws, &o->v, true);
+  if (rc) return rc;
+  const Workspace w = carve(&o->v.c, rl, nullptr);
+  if (!w.fits) return SKIPKV_ECAPACITY;
+  const size_t LH = (size_t)c->n_layers * c->n_kv_heads;
+  o->step_bytes = align_up(w.bytes);
+  o->map_bytes = align_up(LH * c->total_tokens * 4);
+  o->bad_bytes = align_up(LH * c->batch * 4);
+  o->src_stride = std::max(1, std::min(p->max_budget, c->total_tokens));
+  o->total = o->v.head_bytes + o->step_bytes + o->map_bytes + o->bad_bytes + align_up(LH * c->batch * o->src_stride * 4);
+  return SKIPKV_OK;
+}
+}  // namespace
+
+int skipkv_ranges_paged_workspace_bytes(const skipkv_cache *cache, const skipkv_paging *paging,
+                                        const skipkv_params *params, size_t *out_bytes) {
+  if (!out_bytes) return SKIPKV_EINVAL;
+  int rc = check_cache(cache, true);
+  if (rc) return rc;
+  RowLayout rl;
+  rc = check_params(cache, params, &rl);
+  if (rc) return rc;
+  if (is_empty(cache)) {
+    *out_bytes = 0;
+    return SKIPKV_OK;
+  }
+  skipkv_ranges dummy{reinterpret_cast<int32_t *>(16), reinterpret_cast<int32_t *>(16), reinterpret_cast<int32_t *>(16)};
+  RangesPagedView pv;
+  rc = check_ranges_paging(cache, &dummy, paging, params, rl, nullptr, &pv);
+  if (rc) return rc;
+  *out_bytes = pv.total;
+  return SKIPKV_OK;
+}
+
+int skipkv_step_ranges_paged(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_paging *paging,
+                             const skipkv_params *params, const void *q_obs, const float *tok_redundancy,
+                             float *sent_score, float *sent_lambda, float *tok_importance, uint8_t *sent_keep,
+                             int32_t *kept_idx, int32_t *new_len, int32_t *new_sent_off, int32_t *new_sent_cnt,
+                             int32_t kept_stride, void *ws, size_t ws_bytes, void *stream) {
+  RowLayout rl;
+  int rc = check_cache(cache, true);
+  if (rc) return rc;
+  rc = check_params(cache, params, &rl);
+  if (rc) return rc;
+  rc = check_select_args(cache, params, &rl, sent_score, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride);
+  if (rc) return rc;
+  if (is_empty(cache)) return SKIPKV_OK;
+  if (!q_obs || !aligned16(q_obs)) return SKIPKV_EINVAL;
+  if (cache->total_sentences > 0 && (!sent_score || !sent_lambda)) return SKIPKV_EINVAL;
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SKIPKV_EWORKSPACE;
+  RangesPagedView pv;
+  rc = check_ranges_paging(cache, ranges, paging, params, rl, ws, &pv);
+  if (rc) return rc;
+  if (ws_bytes < pv.total) return SKIPKV_EWORKSPACE;
+  if (ranges->sent_off == new_sent_off || ranges->len == new_len || ranges->sent_cnt == new_sent_cnt) return SKIPKV_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const VirtualView &v = pv.v;
+  const int32_t n_lh = cache->n_layers * cache->n_kv_heads;
+  if (launch_virtual_layout(cache->seq_off, cache->sent_ptr, cache->batch, n_lh, cache->total_tokens,
+                            cache->total_sentences, v.seq_off, v.sent_ptr, st) != hipSuccess)
+    return SKIPKV_EHIP;
+  char *ws2 = static_cast<char *>(ws) + v.head_bytes;
+  int32_t *row_map = reinterpret_cast<int32_t *>(ws2 + pv.step_bytes);
+  int32_t *seq_bad = reinterpret_cast<int32_t *>(ws2 + pv.step_bytes + pv.map_bytes);
+  int32_t *src_rows = reinterpret_cast<int32_t *>(ws2 + pv.step_bytes + pv.map_bytes + pv.bad_bytes);
+  Timer tm(params->profile, st);
+  RowMapArgs ra{cache->seq_off, paging->block_table, cache->batch, paging->table_stride, paging->block_size,
+                paging->n_blocks, n_lh, cache->n_kv_heads, cache->total_tokens, pv.unit_layer, pv.unit_head,
+                pv.unit_block, pv.unit_tok, row_map, seq_bad, params->dev_status};
+  if (tm.run("row_map", [&] { return launch_row_map(ra, st); }) != hipSuccess) return SKIPKV_EHIP;
+  HeadView hv = v.hv;
+  hv.row_map = row_map;
+  hv.page_size = paging->block_size;
+  hv.map_stride = cache->head_dim;
+  rc = do_score(tm, &v.c, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, ws2, st, hv);
+  if (rc) return rc;
+  rc = do_select(tm, &v.c, params, sent_score, sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride, st, hv);
+  if (rc) return rc;
+  return do_compact(tm, &v.c, kept_idx, new_len, kept_stride, st, row_map, seq_bad, src_rows, pv.src_stride, cache->head_dim);
 }
 
 int skipkv_ranges_append(const skipkv_cache *cache, const skipkv_ranges *ranges, const int32_t *n_new,

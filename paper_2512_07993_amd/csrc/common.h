@@ -169,10 +169,12 @@ struct ScanArgs {
   // rows are still laid out by the real (l, b, h).  virt_hk = real H_k (0: off), virt_b = real B.
   int32_t virt_hk, virt_b;
   int32_t no_pool;  // 1: sentence embeddings are not needed (lambda comes from elsewhere): skip the key pooling
-  // Paged cache (two-pass scan only): row_map[seq_off[b] + t] = slot row of logical token t, in units of
-  // stride_tok from the head's base; null for a contiguous cache.
+  // Paged cache: row_map[seq_off[b] + t] = slot row of logical token t, in units of map_stride elements
+  // from the head's base (consecutive slots of a block are still stride_tok apart); null for a
+  // contiguous cache.
   const int32_t *row_map;
-  int32_t page_size;  // token slots per block of a paged cache (the single-pass scan needs a power of two >= 16)
+  int32_t page_size;   // token slots per block of a paged cache (the single-pass scan needs a power of two >= 16)
+  int64_t map_stride;  // stride_tok, or one head row when every (layer, head) has a map of its own
 };
 bool scan_fused_supported(const RowLayout &rl, int64_t row_pitch_bytes);
 hipError_t launch_scan_fused(const ScanArgs &a, hipStream_t st);    // single pass over K (sequences the plan marked fused)
@@ -226,14 +228,21 @@ struct CompactArgs {
   const int32_t *seq_bad;  // paged cache, [batch]: nonzero = invalid block table, leave the sequence alone
   int32_t *src_rows;       // paged cache, workspace [heads, src_stride]: slot row of every kept token
   int32_t src_stride;      // >= every new_len
+  int64_t map_stride;      // paged cache: elements per unit of the row map (stride_tok unless the map is per head)
 };
 hipError_t launch_compact(const CompactArgs &a, hipStream_t st);
 
-// Paged cache: row_map[seq_off[b] + t] = block_table[b][t / block_size] * rows_per_block + t % block_size
-// for every logical token; block ids outside [0, n_blocks) are flagged (dev_status, seq_bad[b]) and read as 0.
+// Paged cache: for every logical token the row of its slot, in units of the map's row pitch:
+//   row_map[lh * total_tokens + seq_off[b] + t] = l * unit_layer + h * unit_head
+//       + block_table[b][t / block_size] * unit_block + (t % block_size) * unit_tok.
+// One map serves all heads when the unit is the token pitch (n_lh = 1, unit_layer = unit_head = 0,
+// unit_tok = 1); with per-head ranges every (layer, head) gets its own map in units of one head row.
+// Block ids outside [0, n_blocks) are flagged (dev_status, seq_bad[lh * batch + b]) and read as 0.
 struct RowMapArgs {
   const int32_t *seq_off, *block_table;
-  int32_t batch, table_stride, block_size, n_blocks, rows_per_block;
+  int32_t batch, table_stride, block_size, n_blocks;
+  int32_t n_lh, n_kv_heads, total_tokens;
+  int64_t unit_layer, unit_head, unit_block, unit_tok;
   int32_t *row_map, *seq_bad, *dev_status;
 };
 hipError_t launch_row_map(const RowMapArgs &a, hipStream_t st);

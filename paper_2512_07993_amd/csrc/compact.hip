@@ -32,7 +32,7 @@ __global__ void __launch_bounds__(256) k_compact(CompactArgs a) {
   const int lh = (int)(lhb / a.batch), l = lh / a.n_kv_heads, h = lh % a.n_kv_heads;
   char *base = static_cast<char *>((sid & 1) ? a.v : a.k) +
                ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head + (PAGED ? 0 : (int64_t)a.seq_off[b] * a.stride_tok)) * ESZ;
-  const int64_t pitch = a.stride_tok * ESZ;
+  const int64_t pitch = (PAGED ? a.map_stride : a.stride_tok) * ESZ;  // paged: rows are addressed in units of the row map
   const int32_t *kept = a.kept_idx + lhb * a.kept_stride;
   const int32_t *srcs = PAGED ? a.src_rows + lhb * a.src_stride : kept;  // what the row loads are addressed with
   const int32_t *rmap = PAGED ? a.row_map + a.seq_off[b] : nullptr;

@@ -98,7 +98,7 @@ __global__ void __launch_bounds__(256, ((DT == SKIPKV_BF16 && NP * AL <= 40) ? 2
   const int32_t *rmap = a.row_map ? a.row_map + tok0 : nullptr;
   const char *kbase = static_cast<const char *>(a.k) +
                       ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head + (rmap ? 0 : (int64_t)tok0 * a.stride_tok)) * ESZ;
-  const int64_t tok_pitch = a.stride_tok * ESZ;
+  const int64_t tok_pitch = (a.row_map ? a.map_stride : a.stride_tok) * ESZ;  // paged: bytes per unit of the row map
   const int last_free = n_tok - a.alpha;  // keys t <= last_free are visible to every window query
 
   // per-lane state
@@ -405,7 +405,7 @@ __global__ void __launch_bounds__(256, 2) k_scan_wide(ScanArgs a) {
   const int32_t *rmap = a.row_map ? a.row_map + tok0 : nullptr;
   const char *kbase = static_cast<const char *>(a.k) +
                       ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head + (rmap ? 0 : (int64_t)tok0 * a.stride_tok)) * ESZ;
-  const int64_t tok_pitch = a.stride_tok * ESZ;
+  const int64_t tok_pitch = (a.row_map ? a.map_stride : a.stride_tok) * ESZ;  // paged: bytes per unit of the row map
   const int last_free = n_tok - a.alpha;  // keys t <= last_free are visible to every window query
 
   // per-lane state; slot q = 4 * T + j of this wave: window query g + 4 * (wave * APW + q / NP), head q % NP

@@ -234,8 +234,9 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
       const int jb = a.page_size - (ts & (a.page_size - 1));  // rows of the stage before the next block begins (may be >= 16)
       const int r0 = row_map_c[iss.tok0 + ts];
       const int r1 = row_map_c[iss.tok0 + min(ts + jb, iss.n_tok - 1)];
-      const char *base0 = iss.kbase + (int64_t)r0 * tok_pitch;
-      const char *base1 = iss.kbase + ((int64_t)r1 - jb) * tok_pitch;
+      const int64_t map_pitch = a.map_stride * ESZ;  // bytes per unit of the row map
+      const char *base0 = iss.kbase + (int64_t)r0 * map_pitch;
+      const char *base1 = iss.kbase + (int64_t)r1 * map_pitch - (int64_t)jb * tok_pitch;
 #pragma unroll
       for (int j = 0; j < GL; ++j) {
         const int row = j * RPL + ln / PPR;

@@ -183,3 +183,32 @@ def test_paged_entry_points_validate_on_the_host():
     assert step(C.byref(pg()), q=None) == B.EINVAL
     assert step(C.byref(pg()), n=need - 1) == B.EWORKSPACE
     assert step(C.byref(pg()), ws=0x10010) == B.EWORKSPACE
+
+
+def test_paged_ranges_entry_points_validate_on_the_host():
+    lib, params = B.lib(), _params()
+    # pools laid out [layers, blocks, slots, heads, 128]: 700 blocks of 16 slots
+    cache = _cache(stride_tok=8 * 128, stride_head=128, stride_layer=700 * 16 * 8 * 128)
+    out = C.c_size_t(0)
+    good = dict(block_table=0x6000, table_stride=600, block_size=16, n_blocks=700, stride_block=16 * cache.stride_tok)
+    pg = lambda **kw: B.CPaging(**{**good, **kw})
+    size = lambda p, c=cache: lib.skipkv_ranges_paged_workspace_bytes(C.byref(c), p, C.byref(params), C.byref(out))
+    assert size(C.byref(pg())) == B.OK
+    need = out.value
+    n_lh = cache.n_layers * cache.n_kv_heads
+    assert need >= 4 * n_lh * cache.total_tokens               # one row map per (layer, head)
+    assert size(None) == B.EINVAL
+    assert size(C.byref(pg(block_size=0))) == B.EINVAL
+    assert size(C.byref(pg(stride_block=8 * cache.stride_tok))) == B.EINVAL        # blocks would overlap
+    assert size(C.byref(pg()), _cache(stride_tok=8 * 128, stride_head=128 + 8, stride_layer=700 * 16 * 8 * 128)) == B.EINVAL  # head rows off the 128-element grid
+    assert size(C.byref(pg(n_blocks=1 << 30))) == B.ECAPACITY                      # slot rows are 32-bit
+    rng = B.CRanges(0x6000, 0x6100, 0x6200)
+    step = lambda r, p, ws=0x10000, n=need, q=0x6400, noff=0xB000: lib.skipkv_step_ranges_paged(
+        C.byref(cache), r, p, C.byref(params), q, None, 0x7000, 0x8000, None, None, 0x9000, 0xA000, noff, 0xC000,
+        2048, ws, n, None)
+    assert step(None, C.byref(pg())) == B.EINVAL
+    assert step(C.byref(rng), None) == B.EINVAL
+    assert step(C.byref(rng), C.byref(pg()), q=None) == B.EINVAL
+    assert step(C.byref(rng), C.byref(pg()), n=need - 1) == B.EWORKSPACE
+    assert step(C.byref(rng), C.byref(pg()), ws=0x10010) == B.EWORKSPACE
+    assert step(C.byref(rng), C.byref(pg()), noff=0x6200) == B.EINVAL               # outputs must not alias the input ranges

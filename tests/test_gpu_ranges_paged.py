@@ -1,0 +1,129 @@
+"""Per-head ranges (Sec. 4.1, Eq. 9-11) on a paged KV cache (Appendix, "System-Level Evaluation on
+vLLM") through the C ABI.  A first step on the contiguous cache leaves every head with its own
+length and sentence ranges; the second step then runs twice on the same numbers, once on the
+contiguous cache (whose parity with the oracle test_gpu_ranges.py establishes) and once on pools of
+blocks that the cache was scattered into, and the two must agree: token importance, selection and
+the compacted rows bit for bit, scores bit for bit through the single-pass scan and to rounding
+through the two-pass one (whose pooling order varies from run to run)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_07993_amd import binding as B
+from paper_2512_07993_amd import workloads as W
+
+from helpers import GpuStep, device_structure, run_step
+from test_gpu_paged import SENTINEL, _from_pages, _to_pages, _token_slots
+from test_gpu_ranges import _outputs, run_step_ranges
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_ranges_paged(cfg, st, kp, vp, table, q, ranges, budget):
+    dev = kp.device
+    so, sp, sf = device_structure(st, dev)
+    cache = B.PagedCache(kp, vp, table, cfg.n_q_heads, so, sp, sf, st.total_tokens, st.total_sentences)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    params = B.Params(cfg.obs_window, cfg.protect_window, budget, dev_status=status)
+    ws = torch.empty(B.skipkv_ranges_paged_workspace_bytes(cache, params) + 256, dtype=torch.uint8, device=dev)
+    kept_stride = max(1, min(budget, st.total_tokens))
+    o = _outputs(cfg, st, kept_stride)
+    B.skipkv_step_ranges_paged(cache, ranges, params, q, None, o["sent_score"], o["sent_lambda"], o["tok_imp"],
+                               o["sent_keep"], o["kept_idx"], o["new_len"], o["new_sent_off"], o["new_sent_cnt"],
+                               kept_stride, ws)
+    torch.cuda.synchronize()
+    return GpuStep(cache, params, o["sent_score"], o["sent_lambda"], o["tok_imp"], o["sent_keep"], o["kept_idx"],
+                   o["new_len"], o["new_sent_off"], o["new_sent_cnt"], kept_stride, status)
+
+
+def _first_step(cfg):
+    st = W.make_structure(cfg)
+    k, v, q = W.fill_cache(cfg, st, device="cuda")
+    s1 = run_step(cfg, st, k, v, q)
+    assert int(s1.dev_status.item()) == 0
+    assert len({int(x) for x in s1.new_len.flatten()}) > 1  # heads really differ after the first step
+    g = torch.Generator(device="cuda")
+    g.manual_seed(17)
+    q2 = torch.randn(q.shape, generator=g, device="cuda").to(q.dtype)
+    return st, k, v, q2, s1
+
+
+def _ranges_of(s1):
+    return B.Ranges(s1.new_len.clone(), s1.new_sent_cnt.clone(), s1.new_sent_off.clone())
+
+
+@pytest.mark.parametrize("config_id,kw,block_size,heads_before_slots", [
+    (3, dict(n_layers=2, batch=4, len_lo=900, len_hi=3000, budget=768), 16, False),
+    (3, dict(n_layers=2, batch=4, len_lo=900, len_hi=3000, budget=768), 32, True),
+    (3, dict(n_layers=1, batch=3, len_lo=700, len_hi=1800, budget=512), 24, False),
+    (4, dict(n_layers=2, batch=3, len_lo=700, len_hi=1800, budget=512), 16, False),
+    (1, dict(), 16, False),
+])
+def test_paged_per_head_step_equals_the_contiguous_one(config_id, kw, block_size, heads_before_slots, monkeypatch):
+    cfg = W.CONFIGS[config_id].scaled(**kw) if kw else W.CONFIGS[config_id]
+    st, k1, v1, q2, s1 = _first_step(cfg)
+    budget2 = cfg.budget // 2
+    print("paged ranges", cfg.name, "block", block_size, "tokens", st.total_tokens, flush=True)
+    kp, vp, table = _to_pages(cfg, st, k1, v1, block_size, seed=block_size + 1, heads_before_slots=heads_before_slots)
+    kp0 = kp.clone()
+    out = _run_ranges_paged(cfg, st, kp, vp, table, q2, _ranges_of(s1), budget2)
+    assert int(out.dev_status.item()) == 0
+    two_pass = block_size < 16 or (block_size & (block_size - 1)) != 0
+    if two_pass:
+        monkeypatch.setenv("SKIPKV_FORCE_TWO_PASS", "1")
+    k, v = k1.clone(), v1.clone()
+    ref = run_step_ranges(cfg, st, k, v, q2, _ranges_of(s1), budget2)
+    if two_pass:
+        monkeypatch.delenv("SKIPKV_FORCE_TWO_PASS")
+    assert int(ref.dev_status.item()) == 0
+    # per-token and per-sentence arrays are defined inside every head's own ranges only
+    len1, cnt1 = s1.new_len.cpu().numpy(), s1.new_sent_cnt.cpu().numpy()
+    new_len, new_cnt = out.new_len.cpu().numpy(), out.new_sent_cnt.cpu().numpy()
+    assert np.array_equal(new_len, ref.new_len.cpu().numpy()) and np.array_equal(new_cnt, ref.new_sent_cnt.cpu().numpy())
+    assert (new_len <= budget2).all() and (new_len < len1).any()
+    exact = not two_pass and cfg.dtype != "fp32"
+    kg, vg = _from_pages(cfg, st, kp, table, block_size), _from_pages(cfg, st, vp, table, block_size)
+    for l in range(cfg.n_layers):
+        for h in range(cfg.n_kv_heads):
+            for b in range(cfg.batch):
+                t0, p0 = int(st.seq_off[b]), int(st.sent_ptr[b])
+                n1, c1, n2, c2 = int(len1[l, h, b]), int(cnt1[l, h, b]), int(new_len[l, h, b]), int(new_cnt[l, h, b])
+                tag = (l, h, b)
+                assert torch.equal(out.tok_imp[l, h, t0:t0 + n1].view(torch.int32), ref.tok_imp[l, h, t0:t0 + n1].view(torch.int32)), tag
+                s0 = p0 - b
+                assert torch.equal(out.sent_keep[l, h, s0:s0 + c1], ref.sent_keep[l, h, s0:s0 + c1]), tag
+                for name in ("sent_lambda", "sent_score"):
+                    x, y = getattr(out, name)[l, h, s0:s0 + c1], getattr(ref, name)[l, h, s0:s0 + c1]
+                    if exact:
+                        assert torch.equal(x.view(torch.int32), y.view(torch.int32)), (name, tag)
+                    else:
+                        torch.testing.assert_close(x, y, rtol=1e-5, atol=1e-6)
+                assert torch.equal(out.kept_idx[l, h, b, :n2], ref.kept_idx[l, h, b, :n2]), tag
+                assert torch.equal(out.new_sent_off[l, h, p0:p0 + c2 + 1], ref.new_sent_off[l, h, p0:p0 + c2 + 1]), tag
+                assert torch.equal(kg[l, h, t0:t0 + n2].view(torch.uint8), k[l, h, t0:t0 + n2].view(torch.uint8)), tag
+                assert torch.equal(vg[l, h, t0:t0 + n2].view(torch.uint8), v[l, h, t0:t0 + n2].view(torch.uint8)), tag
+    # slots that hold no token were not written
+    blk, slot = _token_slots(cfg, st, table.cpu().numpy(), block_size, kp.device)
+    free = torch.ones(kp.shape[1], kp.shape[2], dtype=torch.bool, device=kp.device)
+    free[blk, slot] = False
+    assert torch.equal(kp[:, free].view(torch.uint8), kp0[:, free].view(torch.uint8))
+    assert bool((vp[:, free] == SENTINEL).all())
+
+
+def test_paged_per_head_step_reports_a_bad_block_id_and_leaves_the_sequence_alone():
+    cfg = W.CONFIGS[3].scaled(n_layers=2, batch=3, len_lo=900, len_hi=2000, budget=512)
+    st, k1, v1, q2, s1 = _first_step(cfg)
+    kp, vp, table = _to_pages(cfg, st, k1, v1, 16, seed=9)
+    table[2, 1] = -4
+    kp0, vp0 = kp.clone(), vp.clone()
+    out = _run_ranges_paged(cfg, st, kp, vp, table, q2, _ranges_of(s1), cfg.budget // 2)
+    assert int(out.dev_status.item()) & B.DEV_BAD_BLOCK_TABLE
+    n2 = (int(st.seq_off[3] - st.seq_off[2]) + 15) // 16
+    own = table[2, :n2].cpu().numpy()
+    own = torch.from_numpy(own[(own >= 0) & (own < kp.shape[1])].astype(np.int64)).to(kp.device)
+    assert torch.equal(kp[:, own].view(torch.uint8), kp0[:, own].view(torch.uint8))
+    assert torch.equal(vp[:, own].view(torch.uint8), vp0[:, own].view(torch.uint8))
+    # the other sequences were compacted
+    new_len = out.new_len.cpu().numpy()
+    assert (new_len >= 0).all() and (new_len <= cfg.budget // 2).all()
+    assert not torch.equal(kp.view(torch.uint8), kp0.view(torch.uint8))
