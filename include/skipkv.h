@@ -330,6 +330,27 @@ int skipkv_step_paged(const skipkv_cache *cache, const skipkv_paging *paging, co
                       void *stream);
 
 /*
+ * The two halves of skipkv_step_paged that touch K and V, for callers that select in between
+ * themselves (skipkv_select and skipkv_select_tokens only read scores and the ragged structure, so
+ * they serve a paged cache as they are).
+ * skipkv_score_paged: skipkv_score on a paged cache; ws as for skipkv_step_paged
+ * (skipkv_paged_workspace_bytes).
+ * skipkv_compact_paged: skipkv_compact on a paged cache, K[slot of k] <- K[slot of kept_idx[k]]
+ * for k < new_len <= kept_stride, bit for bit; a sequence with an invalid block id is left alone
+ * and SKIPKV_DEV_BAD_BLOCK_TABLE is raised in dev_status (device int32, OR-ed into; may be NULL).
+ * ws: device scratch of at least skipkv_compact_paged_workspace_bytes (row map + slot rows of the
+ * kept tokens), 256-byte aligned.
+ */
+int skipkv_score_paged(const skipkv_cache *cache, const skipkv_paging *paging, const skipkv_params *params,
+                       const void *q_obs, const float *tok_redundancy, float *sent_score, float *sent_lambda,
+                       float *tok_importance, void *ws, size_t ws_bytes, void *stream);
+int skipkv_compact_paged_workspace_bytes(const skipkv_cache *cache, const skipkv_paging *paging, int32_t kept_stride,
+                                         size_t *out_bytes);
+int skipkv_compact_paged(const skipkv_cache *cache, const skipkv_paging *paging, const int32_t *kept_idx,
+                         const int32_t *new_len, int32_t kept_stride, int32_t *dev_status, void *ws, size_t ws_bytes,
+                         void *stream);
+
+/*
  * skipkv_step_ranges on a paged cache: the step of every decode-time compression after the
  * first, when the heads of a sequence have their own lengths and sentence ranges (Sec. 4.1
  * "Multi-step Sentence Range Monitoring", Eq. 9-11) and the cache is paged (Appendix,

@@ -83,6 +83,9 @@ def lib() -> C.CDLL:
         gp = C.POINTER(CPaging)
         L.skipkv_paged_workspace_bytes.argtypes = [cp, gp, pp, C.POINTER(sz)]
         L.skipkv_step_paged.argtypes = [cp, gp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+        L.skipkv_score_paged.argtypes = [cp, gp, pp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.skipkv_compact_paged_workspace_bytes.argtypes = [cp, gp, i32, C.POINTER(sz)]
+        L.skipkv_compact_paged.argtypes = [cp, gp, vp, vp, i32, vp, vp, sz, vp]
         L.skipkv_ranges_paged_workspace_bytes.argtypes = [cp, gp, pp, C.POINTER(sz)]
         L.skipkv_step_ranges_paged.argtypes = [cp, rp, gp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
         L.skipkv_profile_create.argtypes = [C.POINTER(vp)]
@@ -305,6 +308,25 @@ def skipkv_step_paged(cache: PagedCache, params: Params, q_obs, tok_redundancy, 
                                    _ptr(sent_keep), _ptr(kept_idx), _ptr(new_len), _ptr(new_sent_off),
                                    _ptr(new_sent_cnt), kept_stride, _ptr(ws),
                                    ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
+
+
+def skipkv_score_paged(cache: PagedCache, params: Params, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance,
+                       ws, stream=None) -> None:
+    _check(lib().skipkv_score_paged(C.byref(cache.c()), C.byref(cache.paging()), C.byref(params.c()), _ptr(q_obs),
+                                    _ptr(tok_redundancy), _ptr(sent_score), _ptr(sent_lambda), _ptr(tok_importance),
+                                    _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
+
+
+def skipkv_compact_paged_workspace_bytes(cache: PagedCache, kept_stride: int) -> int:
+    out = C.c_size_t(0)
+    _check(lib().skipkv_compact_paged_workspace_bytes(C.byref(cache.c()), C.byref(cache.paging()), kept_stride, C.byref(out)))
+    return int(out.value)
+
+
+def skipkv_compact_paged(cache: PagedCache, kept_idx, new_len, kept_stride: int, dev_status, ws, stream=None) -> None:
+    _check(lib().skipkv_compact_paged(C.byref(cache.c()), C.byref(cache.paging()), _ptr(kept_idx), _ptr(new_len),
+                                      kept_stride, _ptr(dev_status), _ptr(ws),
+                                      ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
 
 
 def skipkv_ranges_paged_workspace_bytes(cache: PagedCache, params: Params) -> int:

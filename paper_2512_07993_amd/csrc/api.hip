@@ -501,6 +501,93 @@ int skipkv_paged_workspace_bytes(const skipkv_cache *cache, const skipkv_paging 
   return SKIPKV_OK;
 }
 
+int skipkv_score_paged(const skipkv_cache *cache, const skipkv_paging *paging, const skipkv_params *params,
+                       const void *q_obs, const float *tok_redundancy, float *sent_score, float *sent_lambda,
+                       float *tok_importance, void *ws, size_t ws_bytes, void *stream) {
+  RowLayout rl;
+  int rc = check_cache(cache, true);
+  if (rc) return rc;
+  rc = check_params(cache, params, &rl);
+  if (rc) return rc;
+  if (is_empty(cache)) return SKIPKV_OK;
+  if (!q_obs || !aligned16(q_obs)) return SKIPKV_EINVAL;
+  if (cache->total_sentences > 0 && (!sent_score || !sent_lambda)) return SKIPKV_EINVAL;
+  PagedView pv;
+  rc = check_paging(cache, paging, params, rl, &pv);
+  if (rc) return rc;
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < pv.total) return SKIPKV_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Timer tm(params->profile, st);
+  int32_t *row_map = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + pv.step_bytes);
+  int32_t *seq_bad = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + pv.step_bytes + pv.map_bytes);
+  RowMapArgs ra{cache->seq_off, paging->block_table, cache->batch, paging->table_stride, paging->block_size,
+                paging->n_blocks, 1, 1, cache->total_tokens, 0, 0, pv.rows_per_block, 1, row_map, seq_bad, params->dev_status};
+  if (tm.run("row_map", [&] { return launch_row_map(ra, st); }) != hipSuccess) return SKIPKV_EHIP;
+  HeadView hv;
+  hv.row_map = row_map;
+  hv.page_size = paging->block_size;
+  return do_score(tm, cache, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, ws, st, hv);
+}
+
+namespace {
+// Workspace of skipkv_compact_paged: the row map, the per-sequence flags, the slot rows of the kept tokens.
+struct CompactPagedView {
+  size_t map_bytes, bad_bytes, total;
+  int32_t rows_per_block, src_stride;
+};
+int check_compact_paging(const skipkv_cache *c, const skipkv_paging *pg, int32_t kept_stride, CompactPagedView *v) {
+  int64_t rpb = 0;
+  const int rc = check_paging_desc(c, pg, &rpb);
+  if (rc) return rc;
+  if ((int64_t)pg->n_blocks * rpb > 0x7FFFFFFFll) return SKIPKV_ECAPACITY;  // slot rows are 32-bit
+  if (kept_stride < 0) return SKIPKV_EINVAL;
+  v->rows_per_block = (int32_t)rpb;
+  v->src_stride = std::max(1, kept_stride);
+  v->map_bytes = align_up((size_t)c->total_tokens * 4);
+  v->bad_bytes = align_up((size_t)c->batch * 4);
+  v->total = v->map_bytes + v->bad_bytes + align_up((size_t)c->n_layers * c->n_kv_heads * c->batch * v->src_stride * 4);
+  return SKIPKV_OK;
+}
+}  // namespace
+
+int skipkv_compact_paged_workspace_bytes(const skipkv_cache *cache, const skipkv_paging *paging, int32_t kept_stride,
+                                         size_t *out_bytes) {
+  if (!out_bytes) return SKIPKV_EINVAL;
+  const int rc = check_cache(cache, false);
+  if (rc) return rc;
+  if (is_empty(cache)) {
+    *out_bytes = 0;
+    return SKIPKV_OK;
+  }
+  CompactPagedView v;
+  const int rc2 = check_compact_paging(cache, paging, kept_stride, &v);
+  if (rc2) return rc2;
+  *out_bytes = v.total;
+  return SKIPKV_OK;
+}
+
+int skipkv_compact_paged(const skipkv_cache *cache, const skipkv_paging *paging, const int32_t *kept_idx,
+                         const int32_t *new_len, int32_t kept_stride, int32_t *dev_status, void *ws, size_t ws_bytes,
+                         void *stream) {
+  int rc = check_cache(cache, false);
+  if (rc) return rc;
+  if (is_empty(cache)) return SKIPKV_OK;
+  if (!new_len || kept_stride < 0 || (!kept_idx && cache->total_tokens > 0)) return SKIPKV_EINVAL;
+  CompactPagedView v;
+  rc = check_compact_paging(cache, paging, kept_stride, &v);
+  if (rc) return rc;
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < v.total) return SKIPKV_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int32_t *row_map = static_cast<int32_t *>(ws);
+  int32_t *seq_bad = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + v.map_bytes);
+  int32_t *src_rows = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + v.map_bytes + v.bad_bytes);
+  RowMapArgs ra{cache->seq_off, paging->block_table, cache->batch, paging->table_stride, paging->block_size,
+                paging->n_blocks, 1, 1, cache->total_tokens, 0, 0, v.rows_per_block, 1, row_map, seq_bad, dev_status};
+  if (launch_row_map(ra, st) != hipSuccess) return SKIPKV_EHIP;
+  Timer tm(nullptr, st);
+  return do_compact(tm, cache, kept_idx, new_len, kept_stride, st, row_map, seq_bad, src_rows, v.src_stride);
+}
+
 int skipkv_step_paged(const skipkv_cache *cache, const skipkv_paging *paging, const skipkv_params *params,
                       const void *q_obs, const float *tok_redundancy, float *sent_score, float *sent_lambda,
                       float *tok_importance, uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len,

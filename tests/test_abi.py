@@ -212,3 +212,26 @@ def test_paged_ranges_entry_points_validate_on_the_host():
     assert step(C.byref(rng), C.byref(pg()), n=need - 1) == B.EWORKSPACE
     assert step(C.byref(rng), C.byref(pg()), ws=0x10010) == B.EWORKSPACE
     assert step(C.byref(rng), C.byref(pg()), noff=0x6200) == B.EINVAL               # outputs must not alias the input ranges
+
+
+def test_paged_score_and_compaction_validate_on_the_host():
+    lib, cache, params = B.lib(), _cache(), _params()
+    out = C.c_size_t(0)
+    good = dict(block_table=0x6000, table_stride=600, block_size=16, n_blocks=700, stride_block=16 * cache.stride_tok)
+    pg = lambda **kw: B.CPaging(**{**good, **kw})
+    assert lib.skipkv_paged_workspace_bytes(C.byref(cache), C.byref(pg()), C.byref(params), C.byref(out)) == B.OK
+    need = out.value
+    score = lambda p, ws=0x10000, n=need, q=0x6400, lam=0x8000: lib.skipkv_score_paged(
+        C.byref(cache), p, C.byref(params), q, None, 0x7000, lam, None, ws, n, None)
+    assert score(None) == B.EINVAL and score(C.byref(pg()), q=None) == B.EINVAL and score(C.byref(pg()), lam=None) == B.EINVAL
+    assert score(C.byref(pg()), n=need - 1) == B.EWORKSPACE and score(C.byref(pg(block_size=0))) == B.EINVAL
+    size = lambda p, ks=2048: lib.skipkv_compact_paged_workspace_bytes(C.byref(cache), p, ks, C.byref(out))
+    assert size(C.byref(pg())) == B.OK
+    need = out.value
+    assert need >= 4 * cache.total_tokens + 4 * cache.n_layers * cache.n_kv_heads * cache.batch * 2048
+    assert size(None) == B.EINVAL and size(C.byref(pg()), ks=-1) == B.EINVAL
+    assert size(C.byref(pg(n_blocks=1 << 30))) == B.ECAPACITY
+    comp = lambda p, ws=0x10000, n=need, kept=0x9000, nl=0xA000: lib.skipkv_compact_paged(
+        C.byref(cache), p, kept, nl, 2048, None, ws, n, None)
+    assert comp(None) == B.EINVAL and comp(C.byref(pg()), kept=None) == B.EINVAL and comp(C.byref(pg()), nl=None) == B.EINVAL
+    assert comp(C.byref(pg()), n=need - 1) == B.EWORKSPACE and comp(C.byref(pg()), ws=0x10010) == B.EWORKSPACE

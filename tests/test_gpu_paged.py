@@ -187,3 +187,114 @@ def test_paged_degenerate_batch(block_size):
     free = torch.ones(kp.shape[1], kp.shape[2], dtype=torch.bool, device=kp.device)
     free[blk, slot] = False
     assert torch.equal(kp[:, free].view(torch.uint8), kp0[:, free].view(torch.uint8))
+
+
+def _paged_cache(cfg, st, kp, vp, table):
+    so, sp, sf = device_structure(st, kp.device)
+    return B.PagedCache(kp, vp, table, cfg.n_q_heads, so, sp, sf, st.total_tokens, st.total_sentences)
+
+
+@pytest.mark.parametrize("block_size", [16, 24])
+def test_score_select_compact_on_pages_equal_the_paged_step(block_size):
+    cfg = W.CONFIGS[3].scaled(n_layers=2, batch=4)
+    st = W.make_structure(cfg)
+    k0, v0, q = W.fill_cache(cfg, st, device="cuda")
+    kp, vp, table = _to_pages(cfg, st, k0, v0, block_size, seed=21)
+    ka, va = kp.clone(), vp.clone()
+    ref = _run_paged(cfg, st, ka, va, table, q)
+    assert int(ref.dev_status.item()) == 0
+    cache = _paged_cache(cfg, st, kp, vp, table)
+    L, H, Bn, S, T = cfg.n_layers, cfg.n_kv_heads, cfg.batch, st.total_sentences, st.total_tokens
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    params = B.Params(cfg.obs_window, cfg.protect_window, cfg.budget, dev_status=status)
+    ws = torch.empty(B.skipkv_paged_workspace_bytes(cache, params) + 256, dtype=torch.uint8, device="cuda")
+    score = torch.full((L, H, S), float("nan"), dtype=torch.float32, device="cuda")
+    lam, imp = torch.full_like(score, float("nan")), torch.full((L, H, T), float("nan"), dtype=torch.float32, device="cuda")
+    B.skipkv_score_paged(cache, params, q, None, score, lam, imp, ws)
+    torch.cuda.synchronize()  # scoring alone wrote nothing into the pools:
+    assert torch.equal(kp.view(torch.uint8), _to_pages(cfg, st, k0, v0, block_size, seed=21)[0].view(torch.uint8))
+    kept_stride = ref.kept_stride
+    keep = torch.full((L, H, S), 77, dtype=torch.uint8, device="cuda")
+    kept_idx = torch.full((L, H, Bn, kept_stride), -1, dtype=torch.int32, device="cuda")
+    new_len = torch.full((L, H, Bn), -1, dtype=torch.int32, device="cuda")
+    new_off = torch.full((L, H, S + Bn), -1, dtype=torch.int32, device="cuda")
+    new_cnt = torch.full((L, H, Bn), -1, dtype=torch.int32, device="cuda")
+    B.skipkv_select(cache, params, score, keep, kept_idx, new_len, new_off, new_cnt, kept_stride)
+    ws2 = torch.empty(B.skipkv_compact_paged_workspace_bytes(cache, kept_stride) + 256, dtype=torch.uint8, device="cuda")
+    B.skipkv_compact_paged(cache, kept_idx, new_len, kept_stride, status, ws2)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    assert torch.equal(imp.view(torch.int32), ref.tok_imp.view(torch.int32))
+    # blocks of 24 slots take the two-pass scan, whose pooling order varies from run to run
+    if block_size == 16:
+        assert torch.equal(score.view(torch.int32), ref.sent_score.view(torch.int32)) and torch.equal(lam.view(torch.int32), ref.sent_lambda.view(torch.int32))
+    else:
+        torch.testing.assert_close(score, ref.sent_score, rtol=1e-5, atol=1e-6)
+        torch.testing.assert_close(lam, ref.sent_lambda, rtol=1e-5, atol=1e-6)
+    assert torch.equal(keep, ref.sent_keep) and torch.equal(new_len, ref.new_len) and torch.equal(new_cnt, ref.new_sent_cnt)
+    assert torch.equal(kept_idx, ref.kept_idx) and torch.equal(new_off, ref.new_sent_off)
+    # the pools end up the same wherever a kept token lives (rows past the new lengths are unspecified)
+    kg, vg = _from_pages(cfg, st, kp, table, block_size), _from_pages(cfg, st, vp, table, block_size)
+    kr, vr = _from_pages(cfg, st, ka, table, block_size), _from_pages(cfg, st, va, table, block_size)
+    nl = new_len.cpu().numpy()
+    for l in range(L):
+        for h in range(H):
+            for b in range(Bn):
+                t0, n = int(st.seq_off[b]), int(nl[l, h, b])
+                assert torch.equal(kg[l, h, t0:t0 + n].view(torch.uint8), kr[l, h, t0:t0 + n].view(torch.uint8)), (l, h, b)
+                assert torch.equal(vg[l, h, t0:t0 + n].view(torch.uint8), vr[l, h, t0:t0 + n].view(torch.uint8)), (l, h, b)
+
+
+def test_token_level_flow_on_pages_equals_the_contiguous_one():
+    """score -> token-level selection (Eq. 6 as printed) -> compaction, on pages and on the contiguous cache;
+    the token redundancy comes from the contiguous keys in both (it has no paged form)."""
+    from helpers import make_cache
+    cfg = W.CONFIGS[3].scaled(n_layers=1, batch=3)
+    st = W.make_structure(cfg)
+    k0, v0, q = W.fill_cache(cfg, st, device="cuda")
+    L, H, Bn, S, T = cfg.n_layers, cfg.n_kv_heads, cfg.batch, st.total_sentences, st.total_tokens
+    flat = make_cache(cfg, st, k0, v0)
+    red = torch.empty((L, H, T), dtype=torch.float32, device="cuda")
+    B.skipkv_token_redundancy(flat, red, torch.empty(B.skipkv_redundancy_workspace_bytes(flat) + 256, dtype=torch.uint8, device="cuda"))
+    kept_stride = min(cfg.budget, T)
+
+    def flow(cache, paged):
+        status = torch.zeros(1, dtype=torch.int32, device="cuda")
+        params = B.Params(cfg.obs_window, cfg.protect_window, cfg.budget, dev_status=status)
+        score = torch.empty((L, H, S), dtype=torch.float32, device="cuda")
+        lam, imp = torch.empty_like(score), torch.empty((L, H, T), dtype=torch.float32, device="cuda")
+        if paged:
+            ws = torch.empty(B.skipkv_paged_workspace_bytes(cache, params) + 256, dtype=torch.uint8, device="cuda")
+            B.skipkv_score_paged(cache, params, q, red, score, lam, imp, ws)
+        else:
+            ws = torch.empty(B.skipkv_workspace_bytes(cache, params) + 256, dtype=torch.uint8, device="cuda")
+            B.skipkv_score(cache, params, q, red, score, lam, imp, ws)
+        tok_score = torch.empty((L, H, T), dtype=torch.float32, device="cuda")
+        tok_keep = torch.empty((L, H, T), dtype=torch.uint8, device="cuda")
+        kept_idx = torch.full((L, H, Bn, kept_stride), -1, dtype=torch.int32, device="cuda")
+        new_len = torch.empty((L, H, Bn), dtype=torch.int32, device="cuda")
+        new_off = torch.full((L, H, S + Bn), -1, dtype=torch.int32, device="cuda")
+        new_cnt = torch.empty((L, H, Bn), dtype=torch.int32, device="cuda")
+        B.skipkv_select_tokens(cache, params, imp, red, lam, tok_score, tok_keep, kept_idx, new_len, new_off, new_cnt, kept_stride)
+        if paged:
+            ws2 = torch.empty(B.skipkv_compact_paged_workspace_bytes(cache, kept_stride) + 256, dtype=torch.uint8, device="cuda")
+            B.skipkv_compact_paged(cache, kept_idx, new_len, kept_stride, status, ws2)
+        else:
+            B.skipkv_compact(cache, kept_idx, new_len, kept_stride)
+        torch.cuda.synchronize()
+        assert int(status.item()) == 0
+        return tok_score, tok_keep, kept_idx, new_len, new_off, new_cnt
+
+    k, v = k0.clone(), v0.clone()
+    a = flow(make_cache(cfg, st, k, v), False)
+    kp, vp, table = _to_pages(cfg, st, k0, v0, 16, seed=33)
+    b = flow(_paged_cache(cfg, st, kp, vp, table), True)
+    for x, y in zip(a, b):
+        assert torch.equal(x.view(torch.uint8) if x.dtype != torch.uint8 else x, y.view(torch.uint8) if y.dtype != torch.uint8 else y)
+    kg, vg = _from_pages(cfg, st, kp, table, 16), _from_pages(cfg, st, vp, table, 16)
+    nl = a[3].cpu().numpy()
+    assert (nl == np.minimum(cfg.budget, st.seq_len)[None, None, :]).all()
+    for h in range(H):
+        for s in range(Bn):
+            t0, n = int(st.seq_off[s]), int(nl[0, h, s])
+            assert torch.equal(kg[0, h, t0:t0 + n], k[0, h, t0:t0 + n]) and torch.equal(vg[0, h, t0:t0 + n], v[0, h, t0:t0 + n])
