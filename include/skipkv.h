@@ -351,6 +351,17 @@ int skipkv_compact_paged(const skipkv_cache *cache, const skipkv_paging *paging,
                          void *stream);
 
 /*
+ * skipkv_token_redundancy on a paged cache (Eq. 5 with the key rows read through the block
+ * table): same values, same layout of tok_redundancy.  A block id outside [0, n_blocks) raises
+ * SKIPKV_DEV_BAD_BLOCK_TABLE in dev_status (device int32, OR-ed into; may be NULL) and is read as
+ * block 0.  ws: device scratch of at least skipkv_redundancy_paged_workspace_bytes, 256-byte
+ * aligned.
+ */
+int skipkv_redundancy_paged_workspace_bytes(const skipkv_cache *cache, const skipkv_paging *paging, size_t *out_bytes);
+int skipkv_token_redundancy_paged(const skipkv_cache *cache, const skipkv_paging *paging, float *tok_redundancy,
+                                  int32_t *dev_status, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * skipkv_step_ranges on a paged cache: the step of every decode-time compression after the
  * first, when the heads of a sequence have their own lengths and sentence ranges (Sec. 4.1
  * "Multi-step Sentence Range Monitoring", Eq. 9-11) and the cache is paged (Appendix,

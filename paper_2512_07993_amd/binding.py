@@ -86,6 +86,8 @@ def lib() -> C.CDLL:
         L.skipkv_score_paged.argtypes = [cp, gp, pp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.skipkv_compact_paged_workspace_bytes.argtypes = [cp, gp, i32, C.POINTER(sz)]
         L.skipkv_compact_paged.argtypes = [cp, gp, vp, vp, i32, vp, vp, sz, vp]
+        L.skipkv_redundancy_paged_workspace_bytes.argtypes = [cp, gp, C.POINTER(sz)]
+        L.skipkv_token_redundancy_paged.argtypes = [cp, gp, vp, vp, vp, sz, vp]
         L.skipkv_ranges_paged_workspace_bytes.argtypes = [cp, gp, pp, C.POINTER(sz)]
         L.skipkv_step_ranges_paged.argtypes = [cp, rp, gp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
         L.skipkv_profile_create.argtypes = [C.POINTER(vp)]
@@ -327,6 +329,18 @@ def skipkv_compact_paged(cache: PagedCache, kept_idx, new_len, kept_stride: int,
     _check(lib().skipkv_compact_paged(C.byref(cache.c()), C.byref(cache.paging()), _ptr(kept_idx), _ptr(new_len),
                                       kept_stride, _ptr(dev_status), _ptr(ws),
                                       ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
+
+
+def skipkv_redundancy_paged_workspace_bytes(cache: PagedCache) -> int:
+    out = C.c_size_t(0)
+    _check(lib().skipkv_redundancy_paged_workspace_bytes(C.byref(cache.c()), C.byref(cache.paging()), C.byref(out)))
+    return int(out.value)
+
+
+def skipkv_token_redundancy_paged(cache: PagedCache, tok_redundancy, dev_status, ws, stream=None) -> None:
+    _check(lib().skipkv_token_redundancy_paged(C.byref(cache.c()), C.byref(cache.paging()), _ptr(tok_redundancy),
+                                               _ptr(dev_status), _ptr(ws),
+                                               ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
 
 
 def skipkv_ranges_paged_workspace_bytes(cache: PagedCache, params: Params) -> int:

@@ -895,6 +895,58 @@ int skipkv_token_redundancy(const skipkv_cache *cache, float *tok_redundancy, vo
   return launch_token_redundancy(a, static_cast<hipStream_t>(stream)) == hipSuccess ? SKIPKV_OK : SKIPKV_EHIP;
 }
 
+int skipkv_redundancy_paged_workspace_bytes(const skipkv_cache *cache, const skipkv_paging *paging, size_t *out_bytes) {
+  if (!out_bytes) return SKIPKV_EINVAL;
+  int rc = check_cache(cache, false);
+  if (rc) return rc;
+  if (is_empty(cache)) {
+    *out_bytes = 0;
+    return SKIPKV_OK;
+  }
+  CompactPagedView v;
+  rc = check_compact_paging(cache, paging, 0, &v);
+  if (rc) return rc;
+  const size_t per = align_up((size_t)cache->n_layers * cache->n_kv_heads * (size_t)cache->total_tokens * sizeof(float));
+  *out_bytes = 2 * per + v.map_bytes + v.bad_bytes;
+  return SKIPKV_OK;
+}
+
+int skipkv_token_redundancy_paged(const skipkv_cache *cache, const skipkv_paging *paging, float *tok_redundancy,
+                                  int32_t *dev_status, void *ws, size_t ws_bytes, void *stream) {
+  int rc = check_cache(cache, false);
+  if (rc) return rc;
+  if (is_empty(cache) || cache->total_tokens == 0) return SKIPKV_OK;
+  if (!tok_redundancy) return SKIPKV_EINVAL;
+  CompactPagedView v;
+  rc = check_compact_paging(cache, paging, 0, &v);
+  if (rc) return rc;
+  const size_t per = align_up((size_t)cache->n_layers * cache->n_kv_heads * (size_t)cache->total_tokens * sizeof(float));
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < 2 * per + v.map_bytes + v.bad_bytes) return SKIPKV_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int32_t *row_map = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + 2 * per);
+  int32_t *seq_bad = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + 2 * per + v.map_bytes);
+  RowMapArgs ra{cache->seq_off, paging->block_table, cache->batch, paging->table_stride, paging->block_size,
+                paging->n_blocks, 1, 1, cache->total_tokens, 0, 0, v.rows_per_block, 1, row_map, seq_bad, dev_status};
+  if (launch_row_map(ra, st) != hipSuccess) return SKIPKV_EHIP;
+  TokRedArgs a{};
+  a.k = cache->k;
+  a.stride_layer = cache->stride_layer;
+  a.stride_head = cache->stride_head;
+  a.stride_tok = cache->stride_tok;
+  a.dtype = cache->dtype;
+  a.n_layers = cache->n_layers;
+  a.n_kv_heads = cache->n_kv_heads;
+  a.batch = cache->batch;
+  a.total_tokens = cache->total_tokens;
+  a.nrb_max = (cache->total_tokens + 255) / 256 + cache->batch;
+  a.seq_off = cache->seq_off;
+  a.scale = static_cast<float *>(ws);
+  a.neg_log_l = reinterpret_cast<float *>(static_cast<char *>(ws) + per);
+  a.out = tok_redundancy;
+  a.row_map = row_map;
+  return launch_token_redundancy(a, st) == hipSuccess ? SKIPKV_OK : SKIPKV_EHIP;
+}
+
 int skipkv_steer_add(void *hidden, const void *vec, const float *coef, float coef_scalar, const uint8_t *row_mask,
                      int32_t rows, int32_t d_model, int32_t dtype, void *stream) {
   if (rows < 0 || d_model < 0) return SKIPKV_EINVAL;

@@ -256,6 +256,7 @@ struct TokRedArgs {
   float *scale;              // [LH, T] workspace: sqrt(log2 e) / (||k|| + eps)
   float *neg_log_l;          // [LH, T] workspace: -log2 of the row sums
   float *out;                // [LH, T] token redundancy
+  const int32_t *row_map;    // paged cache: logical token -> slot row in units of stride_tok (see ScanArgs); null: contiguous
 };
 hipError_t launch_token_redundancy(const TokRedArgs &a, hipStream_t st);
 

@@ -56,7 +56,8 @@ __global__ void __launch_bounds__(256) k_key_scale(TokRedArgs a) {
   for (int64_t row = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 4; row < n_rows; row += ((int64_t)gridDim.x * 256) >> 4) {
     const int64_t lh = row / a.total_tokens, t = row % a.total_tokens;
     const int l = (int)(lh / a.n_kv_heads), h = (int)(lh % a.n_kv_heads);
-    const char *p = static_cast<const char *>(a.k) + ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head + t * a.stride_tok) * ESZ;
+    const int64_t slot = a.row_map ? (int64_t)a.row_map[t] : t;  // paged cache: the token's slot row
+    const char *p = static_cast<const char *>(a.k) + ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head + slot * a.stride_tok) * ESZ;
     float ss = 0.f;
     if constexpr (DT == SKIPKV_BF16) {
       const uint4 v = *reinterpret_cast<const uint4 *>(p + lane16 * 16);
@@ -105,8 +106,11 @@ __global__ void __launch_bounds__(256) k_tokred_sweep(TokRedArgs a) {
   if (b >= a.batch) return;
   const int r0 = j * kRows;
   const int l = lh / a.n_kv_heads, h = lh % a.n_kv_heads;
-  const char *kbase = static_cast<const char *>(a.k) + ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head + (int64_t)tok0 * a.stride_tok) * ESZ;
+  // paged cache: rows are looked up in the row map (slot rows from the head's base), else they follow tok0
+  const int32_t *rmap = a.row_map ? a.row_map + tok0 : nullptr;
+  const char *kbase = static_cast<const char *>(a.k) + ((int64_t)l * a.stride_layer + (int64_t)h * a.stride_head + (rmap ? 0 : (int64_t)tok0 * a.stride_tok)) * ESZ;
   const int64_t pitch = a.stride_tok * ESZ;
+  auto slot_of = [&](int row) -> int64_t { return rmap ? (int64_t)rmap[row] : (int64_t)row; };
   const int64_t col0 = (int64_t)lh * a.total_tokens + tok0;  // index of the sequence's first token in the per-token arrays
 
   // ---- A operands: this wave's 64 rows (4 tiles), lane (row c16 of a tile, head-dim slice g)
@@ -116,8 +120,9 @@ __global__ void __launch_bounds__(256) k_tokred_sweep(TokRedArgs a) {
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
     const int row = min(rw0 + 16 * t + c16, n_tok - 1);
+    const int64_t srow = slot_of(row);
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) af[t][kk] = __builtin_bit_cast(bf16x8, load_piece_bf16<DT>(kbase + (int64_t)row * pitch, 4 * g + kk));
+    for (int kk = 0; kk < 4; ++kk) af[t][kk] = __builtin_bit_cast(bf16x8, load_piece_bf16<DT>(kbase + srow * pitch, 4 * g + kk));
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) row_c[t][jj] = a.scale[col0 + min(rw0 + 16 * t + 4 * g + jj, n_tok - 1)];
   }
@@ -134,7 +139,7 @@ __global__ void __launch_bounds__(256) k_tokred_sweep(TokRedArgs a) {
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       const int idx = it * 256 + tid, row = min(jb + (idx >> 4), n_tok - 1), piece = idx & 15;
-      pre[it] = load_piece_bf16<DT>(kbase + (int64_t)row * pitch, piece);
+      pre[it] = load_piece_bf16<DT>(kbase + slot_of(row) * pitch, piece);
     }
     if (tid < kCols) {
       const int col = min(jb + tid, n_tok - 1);

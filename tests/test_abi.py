@@ -235,3 +235,20 @@ def test_paged_score_and_compaction_validate_on_the_host():
         C.byref(cache), p, kept, nl, 2048, None, ws, n, None)
     assert comp(None) == B.EINVAL and comp(C.byref(pg()), kept=None) == B.EINVAL and comp(C.byref(pg()), nl=None) == B.EINVAL
     assert comp(C.byref(pg()), n=need - 1) == B.EWORKSPACE and comp(C.byref(pg()), ws=0x10010) == B.EWORKSPACE
+
+
+def test_paged_token_redundancy_validates_on_the_host():
+    lib, cache = B.lib(), _cache()
+    out = C.c_size_t(0)
+    good = dict(block_table=0x6000, table_stride=600, block_size=16, n_blocks=700, stride_block=16 * cache.stride_tok)
+    pg = lambda **kw: B.CPaging(**{**good, **kw})
+    size = lambda p: lib.skipkv_redundancy_paged_workspace_bytes(C.byref(cache), p, C.byref(out))
+    assert size(C.byref(pg())) == B.OK
+    need = out.value
+    flat = C.c_size_t(0)
+    assert lib.skipkv_redundancy_workspace_bytes(C.byref(cache), C.byref(flat)) == B.OK
+    assert need >= flat.value + 4 * cache.total_tokens
+    assert size(None) == B.EINVAL and size(C.byref(pg(block_size=0))) == B.EINVAL
+    run = lambda p, ws=0x10000, n=need, red=0x7000: lib.skipkv_token_redundancy_paged(C.byref(cache), p, red, None, ws, n, None)
+    assert run(None) == B.EINVAL and run(C.byref(pg()), red=None) == B.EINVAL
+    assert run(C.byref(pg()), n=need - 1) == B.EWORKSPACE and run(C.byref(pg()), ws=0x10010) == B.EWORKSPACE

@@ -246,8 +246,8 @@ def test_score_select_compact_on_pages_equal_the_paged_step(block_size):
 
 
 def test_token_level_flow_on_pages_equals_the_contiguous_one():
-    """score -> token-level selection (Eq. 6 as printed) -> compaction, on pages and on the contiguous cache;
-    the token redundancy comes from the contiguous keys in both (it has no paged form)."""
+    """token redundancy -> score -> token-level selection (Eq. 6 as printed) -> compaction, on pages and on the
+    contiguous cache."""
     from helpers import make_cache
     cfg = W.CONFIGS[3].scaled(n_layers=1, batch=3)
     st = W.make_structure(cfg)
@@ -257,6 +257,15 @@ def test_token_level_flow_on_pages_equals_the_contiguous_one():
     red = torch.empty((L, H, T), dtype=torch.float32, device="cuda")
     B.skipkv_token_redundancy(flat, red, torch.empty(B.skipkv_redundancy_workspace_bytes(flat) + 256, dtype=torch.uint8, device="cuda"))
     kept_stride = min(cfg.budget, T)
+    kp, vp, table = _to_pages(cfg, st, k0, v0, 16, seed=33)
+    paged_cache = _paged_cache(cfg, st, kp, vp, table)
+    red_p = torch.full((L, H, T), float("nan"), dtype=torch.float32, device="cuda")
+    st_r = torch.zeros(1, dtype=torch.int32, device="cuda")
+    B.skipkv_token_redundancy_paged(paged_cache, red_p, st_r, torch.empty(
+        B.skipkv_redundancy_paged_workspace_bytes(paged_cache) + 256, dtype=torch.uint8, device="cuda"))
+    torch.cuda.synchronize()
+    assert int(st_r.item()) == 0
+    assert torch.equal(red_p.view(torch.int32), red.view(torch.int32))   # same rows, same order of operations
 
     def flow(cache, paged):
         status = torch.zeros(1, dtype=torch.int32, device="cuda")
@@ -287,8 +296,7 @@ def test_token_level_flow_on_pages_equals_the_contiguous_one():
 
     k, v = k0.clone(), v0.clone()
     a = flow(make_cache(cfg, st, k, v), False)
-    kp, vp, table = _to_pages(cfg, st, k0, v0, 16, seed=33)
-    b = flow(_paged_cache(cfg, st, kp, vp, table), True)
+    b = flow(paged_cache, True)
     for x, y in zip(a, b):
         assert torch.equal(x.view(torch.uint8) if x.dtype != torch.uint8 else x, y.view(torch.uint8) if y.dtype != torch.uint8 else y)
     kg, vg = _from_pages(cfg, st, kp, table, 16), _from_pages(cfg, st, vp, table, 16)
@@ -298,3 +306,29 @@ def test_token_level_flow_on_pages_equals_the_contiguous_one():
         for s in range(Bn):
             t0, n = int(st.seq_off[s]), int(nl[0, h, s])
             assert torch.equal(kg[0, h, t0:t0 + n], k[0, h, t0:t0 + n]) and torch.equal(vg[0, h, t0:t0 + n], v[0, h, t0:t0 + n])
+
+
+@pytest.mark.parametrize("config_id,block_size,heads_before_slots", [(1, 8, False), (3, 24, True)])
+def test_token_redundancy_on_pages_equals_the_contiguous_one(config_id, block_size, heads_before_slots):
+    from helpers import make_cache
+    cfg = W.CONFIGS[config_id] if config_id == 1 else W.CONFIGS[config_id].scaled(n_layers=1, batch=3, len_lo=200, len_hi=1500)
+    st = W.make_structure(cfg)
+    k0, v0, q = W.fill_cache(cfg, st, device="cuda")
+    L, H, T = cfg.n_layers, cfg.n_kv_heads, st.total_tokens
+    flat = make_cache(cfg, st, k0, v0)
+    red = torch.empty((L, H, T), dtype=torch.float32, device="cuda")
+    B.skipkv_token_redundancy(flat, red, torch.empty(B.skipkv_redundancy_workspace_bytes(flat) + 256, dtype=torch.uint8, device="cuda"))
+    kp, vp, table = _to_pages(cfg, st, k0, v0, block_size, seed=5, heads_before_slots=heads_before_slots)
+    cache = _paged_cache(cfg, st, kp, vp, table)
+    red_p = torch.full((L, H, T), float("nan"), dtype=torch.float32, device="cuda")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    B.skipkv_token_redundancy_paged(cache, red_p, status, torch.empty(
+        B.skipkv_redundancy_paged_workspace_bytes(cache) + 256, dtype=torch.uint8, device="cuda"))
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    assert torch.equal(red_p.view(torch.int32), red.view(torch.int32))
+    # R sums to 1 over the tokens of every head and sequence (Eq. 5)
+    for b in range(cfg.batch):
+        t0, t1 = int(st.seq_off[b]), int(st.seq_off[b + 1])
+        if t1 > t0:
+            torch.testing.assert_close(red_p[:, :, t0:t1].double().sum(-1), torch.ones((L, H), dtype=torch.float64, device="cuda"), rtol=1e-4, atol=0)
