@@ -246,6 +246,32 @@ int skipkv_step_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, c
                        void *stream);
 
 /*
+ * The token-level flow on per-head ranges (Sec. 4.1: Eq. 5, Eq. 6 as printed, ranges per Eq. 11,
+ * repeated over the steps of a decode): the counterparts of skipkv_token_redundancy,
+ * skipkv_score and skipkv_select_tokens that take every head's own length and sentence ranges.
+ * Arguments, outputs and layouts are those of the shared-range calls; values at and beyond a
+ * head's length (tokens) or count (sentences) are unspecified.  skipkv_compact serves per-head
+ * ranges as it is (kept_idx and new_len are per head already).
+ * skipkv_token_redundancy_ranges: R over the first ranges->len tokens of every head (only
+ *   ranges->len is read); ws as for skipkv_token_redundancy.
+ * skipkv_score_ranges: needs K contiguous over (layer, head, token) like skipkv_step_ranges; ws of
+ *   at least skipkv_ranges_workspace_bytes, 256-byte aligned.
+ * skipkv_select_tokens_ranges: ws of at least skipkv_ranges_workspace_bytes (only its head is
+ *   used), 256-byte aligned; params->budget, if not NULL, has one entry per (layer, KV head,
+ *   sequence); new_len / new_sent_off / new_sent_cnt must not alias the input ranges.
+ */
+int skipkv_token_redundancy_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, float *tok_redundancy,
+                                   void *ws, size_t ws_bytes, void *stream);
+int skipkv_score_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_params *params,
+                        const void *q_obs, const float *tok_redundancy, float *sent_score, float *sent_lambda,
+                        float *tok_importance, void *ws, size_t ws_bytes, void *stream);
+int skipkv_select_tokens_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_params *params,
+                                const float *tok_importance, const float *tok_redundancy, const float *sent_lambda,
+                                float *tok_score, uint8_t *tok_keep, int32_t *kept_idx, int32_t *new_len,
+                                int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride, void *ws,
+                                size_t ws_bytes, void *stream);
+
+/*
  * Sentence similarity from the last layer's hidden states (Sec. 4.1 "Sentence Similarity Score",
  * Eq. 1-3 as printed): v_s = mean of the hidden states over the tokens of sentence s,
  * shared_lambda[s] = largest cosine between v_s and the embedding of a LATER sentence of the same

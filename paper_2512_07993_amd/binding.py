@@ -79,6 +79,9 @@ def lib() -> C.CDLL:
         rp = C.POINTER(CRanges)
         L.skipkv_ranges_workspace_bytes.argtypes = [cp, pp, C.POINTER(sz)]
         L.skipkv_ranges_append.argtypes = [cp, rp, vp, vp, vp, vp, vp]
+        L.skipkv_token_redundancy_ranges.argtypes = [cp, rp, vp, vp, sz, vp]
+        L.skipkv_score_ranges.argtypes = [cp, rp, pp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.skipkv_select_tokens_ranges.argtypes = [cp, rp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
         L.skipkv_step_ranges.argtypes = [cp, rp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
         gp = C.POINTER(CPaging)
         L.skipkv_paged_workspace_bytes.argtypes = [cp, gp, pp, C.POINTER(sz)]
@@ -267,6 +270,31 @@ def skipkv_step_ranges(cache: Cache, ranges: Ranges, params: Params, q_obs, tok_
                                     _ptr(sent_keep), _ptr(kept_idx), _ptr(new_len), _ptr(new_sent_off),
                                     _ptr(new_sent_cnt), kept_stride, _ptr(ws),
                                     ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
+
+
+def _nbytes(ws) -> int:
+    return ws.numel() * ws.element_size() if ws is not None else 0
+
+
+def skipkv_token_redundancy_ranges(cache: Cache, ranges: Ranges, tok_redundancy, ws, stream=None) -> None:
+    _check(lib().skipkv_token_redundancy_ranges(C.byref(cache.c()), C.byref(ranges.c()), _ptr(tok_redundancy), _ptr(ws),
+                                                _nbytes(ws), _stream(stream)))
+
+
+def skipkv_score_ranges(cache: Cache, ranges: Ranges, params: Params, q_obs, tok_redundancy, sent_score, sent_lambda,
+                        tok_importance, ws, stream=None) -> None:
+    _check(lib().skipkv_score_ranges(C.byref(cache.c()), C.byref(ranges.c()), C.byref(params.c()), _ptr(q_obs),
+                                     _ptr(tok_redundancy), _ptr(sent_score), _ptr(sent_lambda), _ptr(tok_importance),
+                                     _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def skipkv_select_tokens_ranges(cache: Cache, ranges: Ranges, params: Params, tok_importance, tok_redundancy, sent_lambda,
+                                tok_score, tok_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride: int, ws,
+                                stream=None) -> None:
+    _check(lib().skipkv_select_tokens_ranges(C.byref(cache.c()), C.byref(ranges.c()), C.byref(params.c()),
+                                             _ptr(tok_importance), _ptr(tok_redundancy), _ptr(sent_lambda), _ptr(tok_score),
+                                             _ptr(tok_keep), _ptr(kept_idx), _ptr(new_len), _ptr(new_sent_off),
+                                             _ptr(new_sent_cnt), kept_stride, _ptr(ws), _nbytes(ws), _stream(stream)))
 
 
 @dataclass

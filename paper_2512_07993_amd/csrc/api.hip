@@ -381,29 +381,25 @@ int skipkv_select(const skipkv_cache *cache, const skipkv_params *params, const 
                    static_cast<hipStream_t>(stream));
 }
 
-int skipkv_select_tokens(const skipkv_cache *cache, const skipkv_params *params, const float *tok_importance,
-                         const float *tok_redundancy, const float *sent_lambda, float *tok_score,
-                         uint8_t *tok_keep, int32_t *kept_idx, int32_t *new_len, int32_t *new_sent_off,
-                         int32_t *new_sent_cnt, int32_t kept_stride, void *stream) {
-  RowLayout rl;
-  const int rc = check_select_args(cache, params, &rl, sent_lambda, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride);
-  if (rc) return rc;
-  if (is_empty(cache)) return SKIPKV_OK;
-  if (cache->total_tokens > 0 && (!tok_importance || !tok_score)) return SKIPKV_EINVAL;
+namespace {
+int do_select_tokens(const skipkv_cache *c, const skipkv_params *p, const float *tok_importance, const float *tok_redundancy,
+                     const float *sent_lambda, float *tok_score, uint8_t *tok_keep, int32_t *kept_idx, int32_t *new_len,
+                     int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride, hipStream_t st,
+                     const HeadView &hv = HeadView()) {
   TokSelectArgs a{};
-  a.n_lh = cache->n_layers * cache->n_kv_heads;
-  a.batch = cache->batch;
-  a.total_tokens = cache->total_tokens;
-  a.total_sentences = cache->total_sentences;
-  a.protect = params->protect_window;
-  a.budget_scalar = params->budget_scalar;
+  a.n_lh = c->n_layers * c->n_kv_heads;
+  a.batch = c->batch;
+  a.total_tokens = c->total_tokens;
+  a.total_sentences = c->total_sentences;
+  a.protect = p->protect_window;
+  a.budget_scalar = p->budget_scalar;
   a.kept_stride = kept_stride;
-  a.sigma = params->sigma;
-  a.tau = params->tau;
-  a.budget = params->budget;
-  a.seq_off = cache->seq_off;
-  a.sent_ptr = cache->sent_ptr;
-  a.sent_off = cache->sent_off;
+  a.sigma = p->sigma;
+  a.tau = p->tau;
+  a.budget = p->budget;
+  a.seq_off = c->seq_off;
+  a.sent_ptr = c->sent_ptr;
+  a.sent_off = c->sent_off;
   a.tok_imp = tok_importance;
   a.tok_red = tok_redundancy;
   a.sent_lambda = sent_lambda;
@@ -413,8 +409,24 @@ int skipkv_select_tokens(const skipkv_cache *cache, const skipkv_params *params,
   a.new_len = new_len;
   a.new_sent_off = new_sent_off;
   a.new_sent_cnt = new_sent_cnt;
-  a.dev_status = params->dev_status;
-  return launch_select_tokens(a, static_cast<hipStream_t>(stream)) == hipSuccess ? SKIPKV_OK : SKIPKV_EHIP;
+  a.dev_status = p->dev_status;
+  a.len = hv.len;
+  a.cnt = hv.cnt;
+  return launch_select_tokens(a, st) == hipSuccess ? SKIPKV_OK : SKIPKV_EHIP;
+}
+}  // namespace
+
+int skipkv_select_tokens(const skipkv_cache *cache, const skipkv_params *params, const float *tok_importance,
+                         const float *tok_redundancy, const float *sent_lambda, float *tok_score,
+                         uint8_t *tok_keep, int32_t *kept_idx, int32_t *new_len, int32_t *new_sent_off,
+                         int32_t *new_sent_cnt, int32_t kept_stride, void *stream) {
+  RowLayout rl;
+  const int rc = check_select_args(cache, params, &rl, sent_lambda, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride);
+  if (rc) return rc;
+  if (is_empty(cache)) return SKIPKV_OK;
+  if (cache->total_tokens > 0 && (!tok_importance || !tok_score)) return SKIPKV_EINVAL;
+  return do_select_tokens(cache, params, tok_importance, tok_redundancy, sent_lambda, tok_score, tok_keep, kept_idx, new_len,
+                          new_sent_off, new_sent_cnt, kept_stride, static_cast<hipStream_t>(stream));
 }
 
 int skipkv_compact(const skipkv_cache *cache, const int32_t *kept_idx, const int32_t *new_len, int32_t kept_stride,
@@ -680,6 +692,85 @@ int skipkv_step_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, c
   rc = do_select(tm, &v.c, params, sent_score, sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride, st, v.hv);
   if (rc) return rc;
   return do_compact(tm, &v.c, kept_idx, new_len, kept_stride, st);
+}
+
+// The parts of skipkv_step_ranges, for callers that select token by token in between.
+int skipkv_score_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_params *params,
+                        const void *q_obs, const float *tok_redundancy, float *sent_score, float *sent_lambda,
+                        float *tok_importance, void *ws, size_t ws_bytes, void *stream) {
+  RowLayout rl;
+  int rc = check_cache(cache, true);
+  if (rc) return rc;
+  rc = check_params(cache, params, &rl);
+  if (rc) return rc;
+  if (is_empty(cache)) return SKIPKV_OK;
+  if (!q_obs || !aligned16(q_obs)) return SKIPKV_EINVAL;
+  if (cache->total_sentences > 0 && (!sent_score || !sent_lambda)) return SKIPKV_EINVAL;
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SKIPKV_EWORKSPACE;
+  VirtualView v;
+  rc = make_virtual(cache, ranges, ws, &v);
+  if (rc) return rc;
+  const Workspace w = carve(&v.c, rl, nullptr);
+  if (!w.fits) return SKIPKV_ECAPACITY;
+  if (ws_bytes < v.head_bytes + w.bytes) return SKIPKV_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (launch_virtual_layout(cache->seq_off, cache->sent_ptr, cache->batch, cache->n_layers * cache->n_kv_heads,
+                            cache->total_tokens, cache->total_sentences, v.seq_off, v.sent_ptr, st) != hipSuccess)
+    return SKIPKV_EHIP;
+  Timer tm(params->profile, st);
+  return do_score(tm, &v.c, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance,
+                  static_cast<char *>(ws) + v.head_bytes, st, v.hv);
+}
+
+int skipkv_select_tokens_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_params *params,
+                                const float *tok_importance, const float *tok_redundancy, const float *sent_lambda,
+                                float *tok_score, uint8_t *tok_keep, int32_t *kept_idx, int32_t *new_len,
+                                int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride, void *ws,
+                                size_t ws_bytes, void *stream) {
+  RowLayout rl;
+  int rc = check_select_args(cache, params, &rl, sent_lambda, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride);
+  if (rc) return rc;
+  if (is_empty(cache)) return SKIPKV_OK;
+  if (cache->total_tokens > 0 && (!tok_importance || !tok_score)) return SKIPKV_EINVAL;
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SKIPKV_EWORKSPACE;
+  VirtualView v;
+  rc = make_virtual(cache, ranges, ws, &v, true);  // K and V are not read: any strides
+  if (rc) return rc;
+  if (ws_bytes < v.head_bytes) return SKIPKV_EWORKSPACE;
+  if (ranges->sent_off == new_sent_off || ranges->len == new_len || ranges->sent_cnt == new_sent_cnt) return SKIPKV_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (launch_virtual_layout(cache->seq_off, cache->sent_ptr, cache->batch, cache->n_layers * cache->n_kv_heads,
+                            cache->total_tokens, cache->total_sentences, v.seq_off, v.sent_ptr, st) != hipSuccess)
+    return SKIPKV_EHIP;
+  return do_select_tokens(&v.c, params, tok_importance, tok_redundancy, sent_lambda, tok_score, tok_keep, kept_idx, new_len,
+                          new_sent_off, new_sent_cnt, kept_stride, st, v.hv);
+}
+
+int skipkv_token_redundancy_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, float *tok_redundancy, void *ws,
+                                   size_t ws_bytes, void *stream) {
+  const int rc = check_cache(cache, false);
+  if (rc) return rc;
+  if (is_empty(cache) || cache->total_tokens == 0) return SKIPKV_OK;
+  if (!tok_redundancy || !ranges || !ranges->len) return SKIPKV_EINVAL;
+  const size_t per = align_up((size_t)cache->n_layers * cache->n_kv_heads * (size_t)cache->total_tokens * sizeof(float));
+  if (!ws || !aligned16(ws) || ws_bytes < 2 * per) return SKIPKV_EWORKSPACE;
+  TokRedArgs a{};
+  a.k = cache->k;
+  a.stride_layer = cache->stride_layer;
+  a.stride_head = cache->stride_head;
+  a.stride_tok = cache->stride_tok;
+  a.dtype = cache->dtype;
+  a.n_layers = cache->n_layers;
+  a.n_kv_heads = cache->n_kv_heads;
+  a.batch = cache->batch;
+  a.total_tokens = cache->total_tokens;
+  a.nrb_max = (cache->total_tokens + 255) / 256 + cache->batch;
+  a.seq_off = cache->seq_off;
+  a.scale = static_cast<float *>(ws);
+  a.neg_log_l = reinterpret_cast<float *>(static_cast<char *>(ws) + per);
+  a.out = tok_redundancy;
+  a.len = ranges->len;
+  return launch_token_redundancy(a, static_cast<hipStream_t>(stream)) == hipSuccess ? SKIPKV_OK : SKIPKV_EHIP;
 }
 
 namespace {

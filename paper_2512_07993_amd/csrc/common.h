@@ -216,6 +216,7 @@ struct TokSelectArgs {
   uint8_t *tok_keep;
   int32_t *kept_idx, *new_len, *new_sent_off, *new_sent_cnt;
   int32_t *dev_status;
+  const int32_t *len, *cnt;  // per-head ranges (virtual view): tokens and sentences of every sequence; null: from the offsets
 };
 hipError_t launch_select_tokens(const TokSelectArgs &a, hipStream_t st);
 
@@ -257,6 +258,7 @@ struct TokRedArgs {
   float *neg_log_l;          // [LH, T] workspace: -log2 of the row sums
   float *out;                // [LH, T] token redundancy
   const int32_t *row_map;    // paged cache: logical token -> slot row in units of stride_tok (see ScanArgs); null: contiguous
+  const int32_t *len;        // per-head ranges, [LH, batch]: tokens of every head's sequence (within its room); null: from seq_off
 };
 hipError_t launch_token_redundancy(const TokRedArgs &a, hipStream_t st);
 

@@ -318,9 +318,9 @@ __global__ void __launch_bounds__(256) k_select_tokens(TokSelectArgs a) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int lhb = blockIdx.x, lh = lhb / a.batch, b = lhb % a.batch;
   const int tok0 = a.seq_off[b];
-  const int n_tok = a.seq_off[b + 1] - tok0;
+  const int n_tok = min(seq_tokens(a.seq_off, a.len, b), a.seq_off[b + 1] - tok0);  // per-head ranges: the head's own length, within its room
   const int sp = a.sent_ptr[b];
-  const int n_sent = a.sent_ptr[b + 1] - sp - 1;
+  const int n_sent = min(seq_sentences(a.sent_ptr, a.cnt, b), a.sent_ptr[b + 1] - sp - 1);
   const int32_t *off = a.sent_off + sp;
   const int64_t tcol = (int64_t)lh * a.total_tokens + tok0;
   const int64_t scol = (int64_t)lh * a.total_sentences + (sp - b);

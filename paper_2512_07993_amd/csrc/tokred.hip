@@ -105,6 +105,10 @@ __global__ void __launch_bounds__(256) k_tokred_sweep(TokRedArgs a) {
   }
   if (b >= a.batch) return;
   const int r0 = j * kRows;
+  if (a.len) {  // per-head ranges: the head's own length within the sequence's room
+    n_tok = min(n_tok, a.len[lh * a.batch + b]);
+    if (r0 >= n_tok) return;
+  }
   const int l = lh / a.n_kv_heads, h = lh % a.n_kv_heads;
   // paged cache: rows are looked up in the row map (slot rows from the head's base), else they follow tok0
   const int32_t *rmap = a.row_map ? a.row_map + tok0 : nullptr;

@@ -252,3 +252,28 @@ def test_paged_token_redundancy_validates_on_the_host():
     run = lambda p, ws=0x10000, n=need, red=0x7000: lib.skipkv_token_redundancy_paged(C.byref(cache), p, red, None, ws, n, None)
     assert run(None) == B.EINVAL and run(C.byref(pg()), red=None) == B.EINVAL
     assert run(C.byref(pg()), n=need - 1) == B.EWORKSPACE and run(C.byref(pg()), ws=0x10010) == B.EWORKSPACE
+
+
+def test_token_level_range_entry_points_validate_on_the_host():
+    lib, cache, params = B.lib(), _cache(), _params()
+    out = C.c_size_t(0)
+    assert lib.skipkv_ranges_workspace_bytes(C.byref(cache), C.byref(params), C.byref(out)) == B.OK
+    need = out.value
+    rng = B.CRanges(0x6000, 0x6100, 0x6200)
+    score = lambda r, ws=0x10000, n=need, q=0x6400: lib.skipkv_score_ranges(
+        C.byref(cache), r, C.byref(params), q, None, 0x7000, 0x8000, None, ws, n, None)
+    assert score(None) == B.EINVAL and score(C.byref(rng), q=None) == B.EINVAL
+    assert score(C.byref(rng), n=need - 1) == B.EWORKSPACE and score(C.byref(rng), ws=0x10010) == B.EWORKSPACE
+    strided = _cache(stride_head=8192 * 128, stride_layer=8 * 8192 * 128)
+    assert lib.skipkv_score_ranges(C.byref(strided), C.byref(rng), C.byref(params), 0x6400, None, 0x7000, 0x8000, None,
+                                   0x10000, 1 << 40, None) == B.ECAPACITY
+    sel = lambda r, ws=0x10000, n=need, imp=0x7000, noff=0xB000: lib.skipkv_select_tokens_ranges(
+        C.byref(cache), r, C.byref(params), imp, None, 0x8000, 0x8800, None, 0x9000, 0xA000, noff, 0xC000, 2048, ws, n, None)
+    assert sel(None) == B.EINVAL and sel(C.byref(rng), imp=None) == B.EINVAL
+    assert sel(C.byref(rng), n=16) == B.EWORKSPACE and sel(C.byref(rng), ws=0x10010) == B.EWORKSPACE
+    assert sel(C.byref(rng), noff=0x6200) == B.EINVAL      # outputs must not alias the input ranges
+    flat = C.c_size_t(0)
+    assert lib.skipkv_redundancy_workspace_bytes(C.byref(cache), C.byref(flat)) == B.OK
+    red = lambda r, ws=0x10000, n=flat.value, o=0x7000: lib.skipkv_token_redundancy_ranges(C.byref(cache), r, o, ws, n, None)
+    assert red(None) == B.EINVAL and red(C.byref(rng), o=None) == B.EINVAL and red(C.byref(B.CRanges(None, 0x6100, 0x6200))) == B.EINVAL
+    assert red(C.byref(rng), n=flat.value - 1) == B.EWORKSPACE
