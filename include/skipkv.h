@@ -256,6 +256,8 @@ int skipkv_step_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, c
  *   ranges->len is read); ws as for skipkv_token_redundancy.
  * skipkv_score_ranges: needs K contiguous over (layer, head, token) like skipkv_step_ranges; ws of
  *   at least skipkv_ranges_workspace_bytes, 256-byte aligned.
+ * skipkv_select_ranges (the sentence-level selection of skipkv_step_ranges on its own, for scores
+ *   that come from skipkv_score_ranges or skipkv_score_shared_ranges) and
  * skipkv_select_tokens_ranges: ws of at least skipkv_ranges_workspace_bytes (only its head is
  *   used), 256-byte aligned; params->budget, if not NULL, has one entry per (layer, KV head,
  *   sequence); new_len / new_sent_off / new_sent_cnt must not alias the input ranges.
@@ -265,6 +267,10 @@ int skipkv_token_redundancy_ranges(const skipkv_cache *cache, const skipkv_range
 int skipkv_score_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_params *params,
                         const void *q_obs, const float *tok_redundancy, float *sent_score, float *sent_lambda,
                         float *tok_importance, void *ws, size_t ws_bytes, void *stream);
+int skipkv_select_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_params *params,
+                         const float *sent_score, uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len,
+                         int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride, void *ws, size_t ws_bytes,
+                         void *stream);
 int skipkv_select_tokens_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_params *params,
                                 const float *tok_importance, const float *tok_redundancy, const float *sent_lambda,
                                 float *tok_score, uint8_t *tok_keep, int32_t *kept_idx, int32_t *new_len,
@@ -297,6 +303,37 @@ int skipkv_sentence_similarity(const skipkv_cache *cache, const void *hidden, in
 int skipkv_score_shared(const skipkv_cache *cache, const skipkv_params *params, const void *q_obs,
                         const float *tok_redundancy, const float *shared_lambda, float *sent_score,
                         float *sent_lambda, float *tok_importance, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * The shared lambda on per-head ranges, i.e. skipkv_score_shared at every step after the first.
+ * A head's surviving sentences are a subsequence of its sequence's own list of sentences (all
+ * sentences generated so far, which is what the hidden-state similarity is computed over), so
+ * every head carries the numbers its sentences have in that list:
+ *   sent_id  device int32 [n_layers, n_kv_heads, total_sentences], laid out like sent_keep.
+ * skipkv_ranges_ids_select: after a sentence-level selection, sent_id_out = the numbers of the
+ *   sentences that survive it, in order: those with sent_keep != 0 and those that reach into the
+ *   protected window (their tail stays).  ranges = the ranges the selection ran on (NULL: the
+ *   shared ones of cache, the first step), protect_window that of the selection; sent_id_in
+ *   NULL: a sentence's number is its position (the first step).  sent_id_out may be sent_id_in.
+ *   As many numbers are written per head as the selection's new_sent_cnt says.
+ * skipkv_ranges_ids_append: after skipkv_ranges_append, sentences old_cnt .. new_cnt-1 of every
+ *   head continue the numbering after the head's last old sentence (which every selection keeps,
+ *   so it is the sequence's last): old_cnt = a copy of the counts from before the append.
+ * skipkv_score_shared_ranges: skipkv_score_shared with per-head ranges; lambda of a head's
+ *   sentence is shared_lambda[lambda_ptr[b] + its number]; lambda_ptr is a device int32
+ *   [batch + 1] CSR over the sequences' own lists (a number outside a sequence's list raises
+ *   SKIPKV_DEV_BAD_OFFSETS and reads as -inf).  Needs K contiguous over (layer, head, token); ws
+ *   of at least skipkv_ranges_workspace_bytes, 256-byte aligned.  skipkv_select_ranges and
+ *   skipkv_compact complete the step.
+ */
+int skipkv_ranges_ids_select(const skipkv_cache *cache, const skipkv_ranges *ranges, int32_t protect_window,
+                             const uint8_t *sent_keep, const int32_t *sent_id_in, int32_t *sent_id_out, void *stream);
+int skipkv_ranges_ids_append(const skipkv_cache *cache, const int32_t *old_cnt, const int32_t *new_cnt, int32_t *sent_id,
+                             void *stream);
+int skipkv_score_shared_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const int32_t *sent_id,
+                               const int32_t *lambda_ptr, const skipkv_params *params, const void *q_obs,
+                               const float *tok_redundancy, const float *shared_lambda, float *sent_score,
+                               float *sent_lambda, float *tok_importance, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Token redundancy (Sec. 4.1 "Token Redundancy Score", Eq. 5).  Per head, with Kbar the rows of

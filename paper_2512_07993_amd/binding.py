@@ -82,6 +82,10 @@ def lib() -> C.CDLL:
         L.skipkv_token_redundancy_ranges.argtypes = [cp, rp, vp, vp, sz, vp]
         L.skipkv_score_ranges.argtypes = [cp, rp, pp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.skipkv_select_tokens_ranges.argtypes = [cp, rp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+        L.skipkv_select_ranges.argtypes = [cp, rp, pp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+        L.skipkv_ranges_ids_select.argtypes = [cp, rp, i32, vp, vp, vp, vp]
+        L.skipkv_ranges_ids_append.argtypes = [cp, vp, vp, vp, vp]
+        L.skipkv_score_shared_ranges.argtypes = [cp, rp, vp, vp, pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.skipkv_step_ranges.argtypes = [cp, rp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
         gp = C.POINTER(CPaging)
         L.skipkv_paged_workspace_bytes.argtypes = [cp, gp, pp, C.POINTER(sz)]
@@ -295,6 +299,31 @@ def skipkv_select_tokens_ranges(cache: Cache, ranges: Ranges, params: Params, to
                                              _ptr(tok_importance), _ptr(tok_redundancy), _ptr(sent_lambda), _ptr(tok_score),
                                              _ptr(tok_keep), _ptr(kept_idx), _ptr(new_len), _ptr(new_sent_off),
                                              _ptr(new_sent_cnt), kept_stride, _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def skipkv_select_ranges(cache: Cache, ranges: Ranges, params: Params, sent_score, sent_keep, kept_idx, new_len, new_sent_off,
+                         new_sent_cnt, kept_stride: int, ws, stream=None) -> None:
+    _check(lib().skipkv_select_ranges(C.byref(cache.c()), C.byref(ranges.c()), C.byref(params.c()), _ptr(sent_score),
+                                      _ptr(sent_keep), _ptr(kept_idx), _ptr(new_len), _ptr(new_sent_off), _ptr(new_sent_cnt),
+                                      kept_stride, _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def skipkv_ranges_ids_select(cache: Cache, ranges, protect_window: int, sent_keep, sent_id_in, sent_id_out, stream=None) -> None:
+    _check(lib().skipkv_ranges_ids_select(C.byref(cache.c()), C.byref(ranges.c()) if ranges is not None else None,
+                                          protect_window, _ptr(sent_keep), _ptr(sent_id_in), _ptr(sent_id_out),
+                                          _stream(stream)))
+
+
+def skipkv_ranges_ids_append(cache: Cache, old_cnt, new_cnt, sent_id, stream=None) -> None:
+    _check(lib().skipkv_ranges_ids_append(C.byref(cache.c()), _ptr(old_cnt), _ptr(new_cnt), _ptr(sent_id), _stream(stream)))
+
+
+def skipkv_score_shared_ranges(cache: Cache, ranges: Ranges, sent_id, lambda_ptr, params: Params, q_obs, tok_redundancy,
+                               shared_lambda, sent_score, sent_lambda, tok_importance, ws, stream=None) -> None:
+    _check(lib().skipkv_score_shared_ranges(C.byref(cache.c()), C.byref(ranges.c()), _ptr(sent_id), _ptr(lambda_ptr),
+                                            C.byref(params.c()), _ptr(q_obs), _ptr(tok_redundancy), _ptr(shared_lambda),
+                                            _ptr(sent_score), _ptr(sent_lambda), _ptr(tok_importance), _ptr(ws), _nbytes(ws),
+                                            _stream(stream)))
 
 
 @dataclass

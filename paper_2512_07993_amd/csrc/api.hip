@@ -100,6 +100,7 @@ struct HeadView {
   const int32_t *row_map = nullptr;  // paged cache: logical token -> slot row
   int32_t page_size = 0;             // ... and its slots per block
   int64_t map_stride = 0;            // ... and the elements per unit of the map (0: stride_tok)
+  const int32_t *sent_id = nullptr, *lam_ptr = nullptr;  // shared lambda on per-head ranges: sentence numbers, CSR of the lambda array
 };
 
 struct Timer {
@@ -185,6 +186,12 @@ int do_score(Timer &tm, const skipkv_cache *c, const skipkv_params *p, const Row
     fa.shared_lambda = shared_lambda;
     fa.sent_score = sent_score;
     fa.sent_lambda = sent_lambda;
+    fa.len = hv.len;
+    fa.cnt = hv.cnt;
+    fa.sent_id = hv.sent_id;
+    fa.lam_ptr = hv.lam_ptr;
+    fa.virt_b = hv.virt_b;
+    fa.dev_status = p->dev_status;
     if (tm.run("fuse", [&] { return launch_fuse_shared(fa, st); }) != hipSuccess) return SKIPKV_EHIP;
     return SKIPKV_OK;
   }
@@ -694,6 +701,82 @@ int skipkv_step_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, c
   return do_compact(tm, &v.c, kept_idx, new_len, kept_stride, st);
 }
 
+// Shared lambda (hidden-state similarity) on per-head ranges.
+int skipkv_ranges_ids_select(const skipkv_cache *cache, const skipkv_ranges *ranges, int32_t protect_window,
+                             const uint8_t *sent_keep, const int32_t *sent_id_in, int32_t *sent_id_out, void *stream) {
+  const int rc = check_cache(cache, true);
+  if (rc) return rc;
+  if (is_empty(cache) || cache->total_sentences == 0) return SKIPKV_OK;
+  if (!sent_keep || !sent_id_out || protect_window < 0) return SKIPKV_EINVAL;
+  if (ranges && (!ranges->len || !ranges->sent_cnt || !ranges->sent_off)) return SKIPKV_EINVAL;
+  RangesIdsArgs a{};
+  a.n_lh = cache->n_layers * cache->n_kv_heads;
+  a.batch = cache->batch;
+  a.total_sentences = cache->total_sentences;
+  a.protect = protect_window;
+  a.seq_off = cache->seq_off;
+  a.sent_ptr = cache->sent_ptr;
+  a.sent_off = cache->sent_off;
+  if (ranges) {
+    a.len = ranges->len;
+    a.old_cnt = ranges->sent_cnt;
+    a.off = ranges->sent_off;
+  }
+  a.keep = sent_keep;
+  a.id_in = sent_id_in;
+  a.id_out = sent_id_out;
+  return launch_ranges_ids_select(a, static_cast<hipStream_t>(stream)) == hipSuccess ? SKIPKV_OK : SKIPKV_EHIP;
+}
+
+int skipkv_ranges_ids_append(const skipkv_cache *cache, const int32_t *old_cnt, const int32_t *new_cnt, int32_t *sent_id,
+                             void *stream) {
+  const int rc = check_cache(cache, true);
+  if (rc) return rc;
+  if (is_empty(cache) || cache->total_sentences == 0) return SKIPKV_OK;
+  if (!old_cnt || !new_cnt || !sent_id || old_cnt == new_cnt) return SKIPKV_EINVAL;
+  RangesIdsArgs a{};
+  a.n_lh = cache->n_layers * cache->n_kv_heads;
+  a.batch = cache->batch;
+  a.total_sentences = cache->total_sentences;
+  a.seq_off = cache->seq_off;
+  a.sent_ptr = cache->sent_ptr;
+  a.old_cnt = old_cnt;
+  a.new_cnt = new_cnt;
+  a.id_out = sent_id;
+  return launch_ranges_ids_append(a, static_cast<hipStream_t>(stream)) == hipSuccess ? SKIPKV_OK : SKIPKV_EHIP;
+}
+
+int skipkv_score_shared_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const int32_t *sent_id,
+                               const int32_t *lambda_ptr, const skipkv_params *params, const void *q_obs,
+                               const float *tok_redundancy, const float *shared_lambda, float *sent_score,
+                               float *sent_lambda, float *tok_importance, void *ws, size_t ws_bytes, void *stream) {
+  RowLayout rl;
+  int rc = check_cache(cache, true);
+  if (rc) return rc;
+  rc = check_params(cache, params, &rl);
+  if (rc) return rc;
+  if (is_empty(cache)) return SKIPKV_OK;
+  if (!q_obs || !aligned16(q_obs)) return SKIPKV_EINVAL;
+  if (cache->total_sentences > 0 && (!sent_score || !shared_lambda || !sent_id || !lambda_ptr)) return SKIPKV_EINVAL;
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SKIPKV_EWORKSPACE;
+  VirtualView v;
+  rc = make_virtual(cache, ranges, ws, &v);
+  if (rc) return rc;
+  const Workspace w = carve(&v.c, rl, nullptr);
+  if (!w.fits) return SKIPKV_ECAPACITY;
+  if (ws_bytes < v.head_bytes + w.bytes) return SKIPKV_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (launch_virtual_layout(cache->seq_off, cache->sent_ptr, cache->batch, cache->n_layers * cache->n_kv_heads,
+                            cache->total_tokens, cache->total_sentences, v.seq_off, v.sent_ptr, st) != hipSuccess)
+    return SKIPKV_EHIP;
+  HeadView hv = v.hv;
+  hv.sent_id = sent_id;
+  hv.lam_ptr = lambda_ptr;
+  Timer tm(params->profile, st);
+  return do_score(tm, &v.c, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance,
+                  static_cast<char *>(ws) + v.head_bytes, st, hv, shared_lambda);
+}
+
 // The parts of skipkv_step_ranges, for callers that select token by token in between.
 int skipkv_score_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_params *params,
                         const void *q_obs, const float *tok_redundancy, float *sent_score, float *sent_lambda,
@@ -720,6 +803,28 @@ int skipkv_score_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, 
   Timer tm(params->profile, st);
   return do_score(tm, &v.c, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance,
                   static_cast<char *>(ws) + v.head_bytes, st, v.hv);
+}
+
+int skipkv_select_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_params *params,
+                         const float *sent_score, uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len,
+                         int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride, void *ws, size_t ws_bytes,
+                         void *stream) {
+  RowLayout rl;
+  int rc = check_select_args(cache, params, &rl, sent_score, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride);
+  if (rc) return rc;
+  if (is_empty(cache)) return SKIPKV_OK;
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SKIPKV_EWORKSPACE;
+  VirtualView v;
+  rc = make_virtual(cache, ranges, ws, &v, true);  // K and V are not read: any strides
+  if (rc) return rc;
+  if (ws_bytes < v.head_bytes) return SKIPKV_EWORKSPACE;
+  if (ranges->sent_off == new_sent_off || ranges->len == new_len || ranges->sent_cnt == new_sent_cnt) return SKIPKV_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (launch_virtual_layout(cache->seq_off, cache->sent_ptr, cache->batch, cache->n_layers * cache->n_kv_heads,
+                            cache->total_tokens, cache->total_sentences, v.seq_off, v.sent_ptr, st) != hipSuccess)
+    return SKIPKV_EHIP;
+  Timer tm(params->profile, st);
+  return do_select(tm, &v.c, params, sent_score, sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride, st, v.hv);
 }
 
 int skipkv_select_tokens_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_params *params,

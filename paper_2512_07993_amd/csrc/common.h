@@ -130,6 +130,23 @@ struct RangesAppendArgs {
   int32_t *dev_status;
 };
 hipError_t launch_ranges_append(const RangesAppendArgs &a, hipStream_t st);
+// Sentence numbers of per-head ranges (layout [n_lh, total_sentences], sentence s of (lh, b) at column
+// sent_ptr[b] - b + s).  select: numbers of the sentences that survive a sentence-level selection, in
+// order: those with keep != 0 and those that reach into the protected window (their tail stays, so the
+// sentence stays); the ranges are those the selection ran on (len / cnt / off null: the shared ones);
+// id_in null: a sentence's number is its position; may run in place.  append: sentences
+// old_cnt .. new_cnt-1 continue the numbering after the head's last old sentence.
+struct RangesIdsArgs {
+  int32_t n_lh, batch, total_sentences, protect;
+  const int32_t *seq_off, *sent_ptr, *sent_off;  // shared structure (capacities)
+  const int32_t *len, *old_cnt, *off;            // per head: [n_lh, batch], [n_lh, batch], [n_lh, total_sentences + batch]
+  const int32_t *new_cnt;                        // append only
+  const uint8_t *keep;                           // select only
+  const int32_t *id_in;
+  int32_t *id_out;
+};
+hipError_t launch_ranges_ids_select(const RangesIdsArgs &a, hipStream_t st);
+hipError_t launch_ranges_ids_append(const RangesIdsArgs &a, hipStream_t st);
 hipError_t launch_virtual_layout(const int32_t *seq_off, const int32_t *sent_ptr, int32_t batch, int32_t n_lh, int32_t total_tokens,
                                  int32_t total_sentences, int32_t *v_seq_off, int32_t *v_sent_ptr, hipStream_t st);
 
@@ -281,6 +298,12 @@ struct FuseSharedArgs {
   const int32_t *seq_off, *sent_ptr, *sent_off;
   const float *sent_imp, *sent_red, *shared_lambda;
   float *sent_score, *sent_lambda;  // sent_lambda nullable
+  // Per-head ranges (virtual view, sequence v = lh * virt_b + b): tokens and sentences of every head, and
+  // the number each of its sentences has in the sequence's own list: lambda of sentence s of v is
+  // shared_lambda[lam_ptr[b] + sent_id[column of s]].  All null / 0 for shared ranges.
+  const int32_t *len, *cnt, *sent_id, *lam_ptr;
+  int32_t virt_b;
+  int32_t *dev_status;
 };
 hipError_t launch_fuse_shared(const FuseSharedArgs &a, hipStream_t st);
 

@@ -173,9 +173,22 @@ __global__ void __launch_bounds__(256) k_fuse_shared(FuseSharedArgs a) {
   const int b = seq_of_column(a.sent_ptr, a.batch, c);
   const int sp = a.sent_ptr[b];
   const int s = c - (sp - b);
-  const int n_tok = a.seq_off[b + 1] - a.seq_off[b];
+  if (s >= min(seq_sentences(a.sent_ptr, a.cnt, b), a.sent_ptr[b + 1] - sp - 1)) return;  // per-head ranges: beyond the head's sentences
+  const int n_tok = min(seq_tokens(a.seq_off, a.len, b), a.seq_off[b + 1] - a.seq_off[b]);
   const int p_start = n_tok - min(a.protect, n_tok);
-  const float lam = a.shared_lambda[c];
+  float lam;
+  if (a.sent_id) {  // the sentence's number in its sequence's own list
+    const int rb = b % a.virt_b, id = a.sent_id[c];
+    const int lp = a.lam_ptr[rb], ln = a.lam_ptr[rb + 1] - lp;
+    if (id >= 0 && id < ln) {
+      lam = a.shared_lambda[lp + id];
+    } else {
+      lam = -INFINITY;
+      if (a.dev_status) atomicOr(a.dev_status, SKIPKV_DEV_BAD_OFFSETS);
+    }
+  } else {
+    lam = a.shared_lambda[c];
+  }
   float score = INFINITY;
   if (a.sent_off[sp + s] < p_start) {
     score = a.sigma * a.sent_imp[i];

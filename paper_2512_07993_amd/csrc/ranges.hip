@@ -70,7 +70,57 @@ __global__ void __launch_bounds__(256) k_virtual_layout(const int32_t *seq_off, 
   v_sent_ptr[v] = lh * (total_sentences + batch) + sent_ptr[b];
 }
 
+// One wave per (layer, head, sequence): stream compaction of the sentence numbers, 64 at a time.
+// Every chunk is read before anything of it is written and writes never run ahead of the reads,
+// so id_out may be id_in.
+__global__ void __launch_bounds__(256) k_ranges_ids_select(RangesIdsArgs a) {
+  const int v = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (v >= a.n_lh * a.batch) return;
+  const int lh = v / a.batch, b = v % a.batch;
+  const int sp = a.sent_ptr[b];
+  const int room = a.sent_ptr[b + 1] - sp - 1, room_t = a.seq_off[b + 1] - a.seq_off[b];
+  const int n = a.old_cnt ? min(max(a.old_cnt[v], 0), room) : room;
+  const int n_tok = a.len ? min(max(a.len[v], 0), room_t) : room_t;
+  const int p_start = n_tok - min(a.protect, n_tok);  // first protected token
+  const int32_t *off = a.off ? a.off + (int64_t)lh * (a.total_sentences + a.batch) + sp : a.sent_off + sp;
+  const int64_t col = (int64_t)lh * a.total_sentences + (sp - b);
+  int k = 0;
+  for (int s0 = 0; s0 < n; s0 += 64) {
+    const int s = s0 + lane;
+    const bool stays = s < n && (a.keep[col + s] != 0 || off[s + 1] > p_start);
+    const int id = stays ? (a.id_in ? a.id_in[col + s] : s) : 0;
+    const unsigned long long m = __ballot(stays);
+    if (stays) a.id_out[col + k + __popcll(m & ((1ull << lane) - 1ull))] = id;
+    k += __popcll(m);
+  }
+}
+
+__global__ void __launch_bounds__(256) k_ranges_ids_append(RangesIdsArgs a) {
+  const int v = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (v >= a.n_lh * a.batch) return;
+  const int lh = v / a.batch, b = v % a.batch;
+  const int room = a.sent_ptr[b + 1] - a.sent_ptr[b] - 1;
+  const int co = min(max(a.old_cnt[v], 0), room), cn = min(a.new_cnt[v], room);
+  const int64_t col = (int64_t)lh * a.total_sentences + (a.sent_ptr[b] - b);
+  const int next = co > 0 ? a.id_out[col + co - 1] + 1 : 0;
+  for (int s = co + lane; s < cn; s += 64) a.id_out[col + s] = next + (s - co);
+}
+
 }  // namespace
+
+hipError_t launch_ranges_ids_select(const RangesIdsArgs &a, hipStream_t st) {
+  const int n = a.n_lh * a.batch;
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_ranges_ids_select, dim3((n + 3) / 4), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_ranges_ids_append(const RangesIdsArgs &a, hipStream_t st) {
+  const int n = a.n_lh * a.batch;
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_ranges_ids_append, dim3((n + 3) / 4), dim3(256), 0, st, a);
+  return hipGetLastError();
+}
 
 hipError_t launch_ranges_append(const RangesAppendArgs &a, hipStream_t st) {
   const int n = a.n_lh * a.batch;

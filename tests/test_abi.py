@@ -277,3 +277,25 @@ def test_token_level_range_entry_points_validate_on_the_host():
     red = lambda r, ws=0x10000, n=flat.value, o=0x7000: lib.skipkv_token_redundancy_ranges(C.byref(cache), r, o, ws, n, None)
     assert red(None) == B.EINVAL and red(C.byref(rng), o=None) == B.EINVAL and red(C.byref(B.CRanges(None, 0x6100, 0x6200))) == B.EINVAL
     assert red(C.byref(rng), n=flat.value - 1) == B.EWORKSPACE
+
+
+def test_shared_lambda_range_entry_points_validate_on_the_host():
+    lib, cache, params = B.lib(), _cache(), _params()
+    out = C.c_size_t(0)
+    assert lib.skipkv_ranges_workspace_bytes(C.byref(cache), C.byref(params), C.byref(out)) == B.OK
+    need = out.value
+    rng = B.CRanges(0x6000, 0x6100, 0x6200)
+    ids_sel = lambda r=None, w=64, keep=0x7000, out_=0x7800: lib.skipkv_ranges_ids_select(C.byref(cache), r, w, keep, None, out_, None)
+    assert ids_sel(keep=None) == B.EINVAL and ids_sel(out_=None) == B.EINVAL and ids_sel(w=-1) == B.EINVAL
+    assert ids_sel(r=C.byref(B.CRanges(0x6000, None, 0x6200))) == B.EINVAL
+    ids_app = lambda old=0x6100, new=0x6300, ids=0x7800: lib.skipkv_ranges_ids_append(C.byref(cache), old, new, ids, None)
+    assert ids_app(old=None) == B.EINVAL and ids_app(ids=None) == B.EINVAL
+    assert ids_app(new=0x6100) == B.EINVAL                    # the counts from before the append must be a copy
+    score = lambda r, ids=0x7800, lp=0x7900, lam=0x7A00, ws=0x10000, n=need: lib.skipkv_score_shared_ranges(
+        C.byref(cache), r, ids, lp, C.byref(params), 0x6400, None, lam, 0x7000, None, None, ws, n, None)
+    assert score(None) == B.EINVAL and score(C.byref(rng), ids=None) == B.EINVAL and score(C.byref(rng), lp=None) == B.EINVAL
+    assert score(C.byref(rng), lam=None) == B.EINVAL and score(C.byref(rng), n=need - 1) == B.EWORKSPACE
+    sel = lambda r, ws=0x10000, n=need, sc=0x7000, noff=0xB000: lib.skipkv_select_ranges(
+        C.byref(cache), r, C.byref(params), sc, None, 0x9000, 0xA000, noff, 0xC000, 2048, ws, n, None)
+    assert sel(None) == B.EINVAL and sel(C.byref(rng), sc=None) == B.EINVAL
+    assert sel(C.byref(rng), n=16) == B.EWORKSPACE and sel(C.byref(rng), noff=0x6200) == B.EINVAL
