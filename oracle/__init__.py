@@ -15,6 +15,8 @@ from .skipkv_oracle import (  # noqa: F401
     select_sentences,
     remap_ranges,
     append_ranges,
+    surviving_sentence_ids,
+    append_sentence_ids,
     compact,
     compress_head,
     steer_add,

@@ -35,7 +35,11 @@ notes of the repository):
   * across steps (Eq.9-10) ranges are kept in CACHE positions per head: the shift by the number
     of evicted tokens that Eq.10 writes out is contained in the head's cache length; a token
     that follows a delimiter starts a new sentence, any other appended token continues the
-    head's last sentence.
+    head's last sentence;
+  * with the similarity taken from hidden states (one lambda per sentence of the text), a head
+    finds the lambda of a sentence it still holds by the number that sentence has in the
+    sequence's own list: numbers survive an eviction with their sentences (Eq.11) and continue
+    after an append (Eq.10).
 
 Parity pins: every function below is pinned by tests/test_oracle_*.py against library
 routines, closed forms, brute force or invariants.  The whole-step result has no
@@ -297,6 +301,28 @@ def remap_ranges(off, kept_idx):
             continue
         out.append((min(ks_b), max(ks_e)))
     return out
+
+
+def surviving_sentence_ids(off, kept_idx, ids=None):
+    """Numbers of the sentences that still hold a token after an eviction (cf. Eq.11: a range with
+    no surviving token is discarded, every other range stays), in order.  ids : [S] the numbers the
+    sentences had before (default: their positions).  Written from the kept tokens alone: sentence
+    s survives when some kept token lies in [off[s], off[s+1])."""
+    off = np.asarray(off, dtype=np.int64)
+    kept = set(int(t) for t in kept_idx)
+    out = []
+    for s in range(len(off) - 1):
+        if any(t in kept for t in range(int(off[s]), int(off[s + 1]))):
+            out.append(int(ids[s]) if ids is not None else s)
+    return np.asarray(out, dtype=np.int64)
+
+
+def append_sentence_ids(ids, n_added):
+    """Numbers after an append (Eq.10): the new sentences continue after the last old one (which
+    an eviction never removes: the tail of the cache is protected); from 0 for an empty list."""
+    ids = np.asarray(ids, dtype=np.int64)
+    nxt = int(ids[-1]) + 1 if ids.size else 0
+    return np.concatenate([ids, nxt + np.arange(int(n_added), dtype=np.int64)])
 
 
 def append_ranges(off, n_new, starts):

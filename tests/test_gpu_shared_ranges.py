@@ -64,9 +64,8 @@ def test_two_steps_with_shared_lambda_on_per_head_ranges():
                 off = st.offsets(b).astype(np.int64)
                 p = int(off[-1]) - min(cfg.protect_window, int(off[-1]))
                 sb, ns = st.sent_base(b), int(st.n_sent[b])
-                stays = keep1[l, h, sb:sb + ns].astype(bool) | (off[1:] > p)
                 straddlers += int((~keep1[l, h, sb:sb + ns].astype(bool) & (off[1:] > p)).sum())
-                want_ids[(l, h, b)] = np.nonzero(stays)[0]
+                want_ids[(l, h, b)] = oracle.surviving_sentence_ids(off, o1["kept_idx"][l, h, b, :int(len1[l, h, b])].cpu().numpy())
                 assert len(want_ids[(l, h, b)]) == cnt1[l, h, b]
                 np.testing.assert_array_equal(ids[l, h, sb:sb + cnt1[l, h, b]].cpu().numpy(), want_ids[(l, h, b)])
     assert len({tuple(x) for x in want_ids.values()}) > Bn  # heads of a sequence keep different sentences
@@ -99,7 +98,8 @@ def test_two_steps_with_shared_lambda_on_per_head_ranges():
     for key, w in want_ids.items():
         l, h, b = key
         assert cnt2[l, h, b] == len(w) + added[b]
-        want_ids[key] = np.concatenate([w, int(st.n_sent[b]) + np.arange(added[b])])
+        want_ids[key] = oracle.append_sentence_ids(w, added[b])
+        assert want_ids[key][-1] == n_glob[b] - 1   # a head's last sentence is the sequence's last
         np.testing.assert_array_equal(ids[l, h, st.sent_base(b):st.sent_base(b) + cnt2[l, h, b]].cpu().numpy(), want_ids[key])
 
     # ---- step 2: a lambda per sentence of the sequences' own lists (any values serve the lookup: a quarter above tau)
@@ -149,10 +149,9 @@ def test_two_steps_with_shared_lambda_on_per_head_ranges():
                 np.testing.assert_array_equal(o2["new_off"][l, h, p0:p0 + c3 + 1].cpu().numpy(), ora["new_off"], err_msg=tag)
                 kept = torch.from_numpy(ora["kept_idx"]).cuda()
                 assert torch.equal(k[l, h, t0:t0 + nl], k_in[l, h, t0 + kept]) and torch.equal(v[l, h, t0:t0 + nl], v_in[l, h, t0 + kept]), tag
-                p = n2 - min(cfg.protect_window, n2)
-                stays = ora["keep"] | (off[1:] > p)
-                evicted += int((~stays).sum())
-                np.testing.assert_array_equal(ids3[l, h, sb:sb + c3].cpu().numpy(), want_ids[(l, h, b)][stays], err_msg=tag)
+                want3 = oracle.surviving_sentence_ids(off, ora["kept_idx"], ids=want_ids[(l, h, b)])
+                evicted += c2 - len(want3)
+                np.testing.assert_array_equal(ids3[l, h, sb:sb + c3].cpu().numpy(), want3, err_msg=tag)
     assert evicted > 0
     print("straddling sentences after step 1:", straddlers, "sentences evicted in step 2:", evicted, flush=True)
 

@@ -61,3 +61,41 @@ def test_append_after_eviction_keeps_surviving_ranges_and_shifts_new_ones():
     new_off = np.array([b for b, _ in ranges] + [ranges[-1][1] + 1])
     np.testing.assert_array_equal(new_off, [0, 5, 11, 15])
     np.testing.assert_array_equal(oracle.append_ranges(new_off, 7, [2]), [0, 5, 11, 17, 22])
+
+
+def test_sentence_numbers_follow_the_surviving_ranges():
+    # pins: (1) as many numbers as Eq. 11 leaves ranges, for sentence-level and token-level evictions;
+    # (2) a worked case with a sentence that straddles the protected window: its candidate part goes,
+    # its tail stays, so its number stays; (3) composition over two evictions equals one lookup.
+    rng = np.random.default_rng(8)
+    for trial in range(30):
+        n_sent = int(rng.integers(1, 30))
+        off = np.concatenate([[0], np.cumsum(rng.integers(1, 9, size=n_sent))])
+        score = rng.standard_normal(int(off[-1]))
+        budget, protect = int(rng.integers(4, off[-1] + 3)), int(rng.integers(0, 5))
+        if budget < protect:
+            budget = protect
+        tok = oracle.select_tokens(score, off, budget, protect)
+        ids = oracle.surviving_sentence_ids(off, tok["kept_idx"])
+        assert len(ids) == len(tok["new_off"]) - 1 == len(oracle.remap_ranges(off, tok["kept_idx"]))
+        assert list(ids) == sorted(set(ids)) and all(0 <= i < n_sent for i in ids)
+        imp = rng.random(int(off[-1]))
+        lam = rng.uniform(-1, 1, n_sent)
+        sc, candlen = oracle.sentence_scores(imp, lam, off, protect)
+        sel = oracle.select_sentences(sc, candlen, off, budget, protect)
+        ids_s = oracle.surviving_sentence_ids(off, sel["kept_idx"])
+        assert len(ids_s) == len(sel["new_off"]) - 1
+        # the lengths of the surviving sentences are the kept tokens inside each
+        kept = set(int(t) for t in sel["kept_idx"])
+        want_len = [sum(t in kept for t in range(off[s], off[s + 1])) for s in ids_s]
+        np.testing.assert_array_equal(np.diff(sel["new_off"]), want_len)
+    off = np.array([0, 4, 9, 12, 20])           # 20 tokens, window = last 10: sentence 2 = [9, 12) straddles position 10
+    kept = np.concatenate([np.arange(0, 4), np.arange(10, 20)])   # sentence 1 evicted, candidate part of sentence 2 evicted
+    np.testing.assert_array_equal(oracle.surviving_sentence_ids(off, kept), [0, 2, 3])
+    np.testing.assert_array_equal(oracle.surviving_sentence_ids(off, kept, ids=[5, 7, 8, 11]), [5, 8, 11])
+    np.testing.assert_array_equal(oracle.append_sentence_ids([5, 8, 11], 2), [5, 8, 11, 12, 13])
+    np.testing.assert_array_equal(oracle.append_sentence_ids([], 3), [0, 1, 2])
+    first = oracle.surviving_sentence_ids(off, kept)
+    off2 = np.array([0, 4, 6, 14])               # the compacted ranges of the three survivors
+    second = oracle.surviving_sentence_ids(off2, np.arange(4, 14), ids=first)
+    np.testing.assert_array_equal(second, [2, 3])
