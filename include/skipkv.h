@@ -398,6 +398,8 @@ int skipkv_step_paged(const skipkv_cache *cache, const skipkv_paging *paging, co
  * they serve a paged cache as they are).
  * skipkv_score_paged: skipkv_score on a paged cache; ws as for skipkv_step_paged
  * (skipkv_paged_workspace_bytes).
+ * skipkv_score_shared_paged: skipkv_score_shared on a paged cache (lambda from the hidden-state
+ * similarity, which does not read K or V and so needs no paged form); same ws.
  * skipkv_compact_paged: skipkv_compact on a paged cache, K[slot of k] <- K[slot of kept_idx[k]]
  * for k < new_len <= kept_stride, bit for bit; a sequence with an invalid block id is left alone
  * and SKIPKV_DEV_BAD_BLOCK_TABLE is raised in dev_status (device int32, OR-ed into; may be NULL).
@@ -407,6 +409,9 @@ int skipkv_step_paged(const skipkv_cache *cache, const skipkv_paging *paging, co
 int skipkv_score_paged(const skipkv_cache *cache, const skipkv_paging *paging, const skipkv_params *params,
                        const void *q_obs, const float *tok_redundancy, float *sent_score, float *sent_lambda,
                        float *tok_importance, void *ws, size_t ws_bytes, void *stream);
+int skipkv_score_shared_paged(const skipkv_cache *cache, const skipkv_paging *paging, const skipkv_params *params,
+                              const void *q_obs, const float *tok_redundancy, const float *shared_lambda, float *sent_score,
+                              float *sent_lambda, float *tok_importance, void *ws, size_t ws_bytes, void *stream);
 int skipkv_compact_paged_workspace_bytes(const skipkv_cache *cache, const skipkv_paging *paging, int32_t kept_stride,
                                          size_t *out_bytes);
 int skipkv_compact_paged(const skipkv_cache *cache, const skipkv_paging *paging, const int32_t *kept_idx,

@@ -91,6 +91,7 @@ def lib() -> C.CDLL:
         L.skipkv_paged_workspace_bytes.argtypes = [cp, gp, pp, C.POINTER(sz)]
         L.skipkv_step_paged.argtypes = [cp, gp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
         L.skipkv_score_paged.argtypes = [cp, gp, pp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.skipkv_score_shared_paged.argtypes = [cp, gp, pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.skipkv_compact_paged_workspace_bytes.argtypes = [cp, gp, i32, C.POINTER(sz)]
         L.skipkv_compact_paged.argtypes = [cp, gp, vp, vp, i32, vp, vp, sz, vp]
         L.skipkv_redundancy_paged_workspace_bytes.argtypes = [cp, gp, C.POINTER(sz)]
@@ -374,6 +375,13 @@ def skipkv_score_paged(cache: PagedCache, params: Params, q_obs, tok_redundancy,
     _check(lib().skipkv_score_paged(C.byref(cache.c()), C.byref(cache.paging()), C.byref(params.c()), _ptr(q_obs),
                                     _ptr(tok_redundancy), _ptr(sent_score), _ptr(sent_lambda), _ptr(tok_importance),
                                     _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
+
+
+def skipkv_score_shared_paged(cache: PagedCache, params: Params, q_obs, tok_redundancy, shared_lambda, sent_score, sent_lambda,
+                              tok_importance, ws, stream=None) -> None:
+    _check(lib().skipkv_score_shared_paged(C.byref(cache.c()), C.byref(cache.paging()), C.byref(params.c()), _ptr(q_obs),
+                                           _ptr(tok_redundancy), _ptr(shared_lambda), _ptr(sent_score), _ptr(sent_lambda),
+                                           _ptr(tok_importance), _ptr(ws), _nbytes(ws), _stream(stream)))
 
 
 def skipkv_compact_paged_workspace_bytes(cache: PagedCache, kept_stride: int) -> int:

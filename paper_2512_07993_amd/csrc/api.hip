@@ -520,9 +520,10 @@ int skipkv_paged_workspace_bytes(const skipkv_cache *cache, const skipkv_paging 
   return SKIPKV_OK;
 }
 
-int skipkv_score_paged(const skipkv_cache *cache, const skipkv_paging *paging, const skipkv_params *params,
-                       const void *q_obs, const float *tok_redundancy, float *sent_score, float *sent_lambda,
-                       float *tok_importance, void *ws, size_t ws_bytes, void *stream) {
+namespace {
+int score_paged(const skipkv_cache *cache, const skipkv_paging *paging, const skipkv_params *params, const void *q_obs,
+                const float *tok_redundancy, const float *shared_lambda, bool need_lambda_out, float *sent_score,
+                float *sent_lambda, float *tok_importance, void *ws, size_t ws_bytes, void *stream) {
   RowLayout rl;
   int rc = check_cache(cache, true);
   if (rc) return rc;
@@ -530,7 +531,7 @@ int skipkv_score_paged(const skipkv_cache *cache, const skipkv_paging *paging, c
   if (rc) return rc;
   if (is_empty(cache)) return SKIPKV_OK;
   if (!q_obs || !aligned16(q_obs)) return SKIPKV_EINVAL;
-  if (cache->total_sentences > 0 && (!sent_score || !sent_lambda)) return SKIPKV_EINVAL;
+  if (cache->total_sentences > 0 && (!sent_score || (need_lambda_out && !sent_lambda))) return SKIPKV_EINVAL;
   PagedView pv;
   rc = check_paging(cache, paging, params, rl, &pv);
   if (rc) return rc;
@@ -545,7 +546,23 @@ int skipkv_score_paged(const skipkv_cache *cache, const skipkv_paging *paging, c
   HeadView hv;
   hv.row_map = row_map;
   hv.page_size = paging->block_size;
-  return do_score(tm, cache, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, ws, st, hv);
+  return do_score(tm, cache, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, ws, st, hv, shared_lambda);
+}
+}  // namespace
+
+int skipkv_score_paged(const skipkv_cache *cache, const skipkv_paging *paging, const skipkv_params *params,
+                       const void *q_obs, const float *tok_redundancy, float *sent_score, float *sent_lambda,
+                       float *tok_importance, void *ws, size_t ws_bytes, void *stream) {
+  return score_paged(cache, paging, params, q_obs, tok_redundancy, nullptr, true, sent_score, sent_lambda, tok_importance, ws,
+                     ws_bytes, stream);
+}
+
+int skipkv_score_shared_paged(const skipkv_cache *cache, const skipkv_paging *paging, const skipkv_params *params,
+                              const void *q_obs, const float *tok_redundancy, const float *shared_lambda, float *sent_score,
+                              float *sent_lambda, float *tok_importance, void *ws, size_t ws_bytes, void *stream) {
+  if (cache && cache->total_sentences > 0 && !shared_lambda) return SKIPKV_EINVAL;
+  return score_paged(cache, paging, params, q_obs, tok_redundancy, shared_lambda, false, sent_score, sent_lambda, tok_importance,
+                     ws, ws_bytes, stream);
 }
 
 namespace {

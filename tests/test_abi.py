@@ -299,3 +299,15 @@ def test_shared_lambda_range_entry_points_validate_on_the_host():
         C.byref(cache), r, C.byref(params), sc, None, 0x9000, 0xA000, noff, 0xC000, 2048, ws, n, None)
     assert sel(None) == B.EINVAL and sel(C.byref(rng), sc=None) == B.EINVAL
     assert sel(C.byref(rng), n=16) == B.EWORKSPACE and sel(C.byref(rng), noff=0x6200) == B.EINVAL
+
+
+def test_paged_shared_lambda_score_validates_on_the_host():
+    lib, cache, params = B.lib(), _cache(), _params()
+    out = C.c_size_t(0)
+    pg = B.CPaging(block_table=0x6000, table_stride=600, block_size=16, n_blocks=700, stride_block=16 * cache.stride_tok)
+    assert lib.skipkv_paged_workspace_bytes(C.byref(cache), C.byref(pg), C.byref(params), C.byref(out)) == B.OK
+    need = out.value
+    score = lambda p=C.byref(pg), lam=0x7A00, sc=0x7000, n=need: lib.skipkv_score_shared_paged(
+        C.byref(cache), p, C.byref(params), 0x6400, None, lam, sc, None, None, 0x10000, n, None)
+    assert score(p=None) == B.EINVAL and score(lam=None) == B.EINVAL and score(sc=None) == B.EINVAL
+    assert score(n=need - 1) == B.EWORKSPACE

@@ -332,3 +332,26 @@ def test_token_redundancy_on_pages_equals_the_contiguous_one(config_id, block_si
         t0, t1 = int(st.seq_off[b]), int(st.seq_off[b + 1])
         if t1 > t0:
             torch.testing.assert_close(red_p[:, :, t0:t1].double().sum(-1), torch.ones((L, H), dtype=torch.float64, device="cuda"), rtol=1e-4, atol=0)
+
+
+def test_scores_with_shared_lambda_on_pages_equal_the_contiguous_ones():
+    from helpers import make_cache
+    cfg = W.CONFIGS[3].scaled(n_layers=2, batch=3, len_lo=500, len_hi=2500, budget=512)
+    st = W.make_structure(cfg)
+    k0, v0, q = W.fill_cache(cfg, st, device="cuda")
+    L, H, S, T = cfg.n_layers, cfg.n_kv_heads, st.total_sentences, st.total_tokens
+    lam = torch.from_numpy(np.random.default_rng(2).uniform(0.5, 1.0, S).astype(np.float32)).cuda()
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    params = B.Params(cfg.obs_window, cfg.protect_window, cfg.budget, dev_status=status)
+    flat = make_cache(cfg, st, k0, v0)
+    sa, la, ia = (torch.full(s, float("nan"), dtype=torch.float32, device="cuda") for s in ((L, H, S), (L, H, S), (L, H, T)))
+    B.skipkv_score_shared(flat, params, q, None, lam, sa, la, ia, torch.empty(B.skipkv_workspace_bytes(flat, params) + 256, dtype=torch.uint8, device="cuda"))
+    kp, vp, table = _to_pages(cfg, st, k0, v0, 16, seed=12)
+    cache = _paged_cache(cfg, st, kp, vp, table)
+    sb, lb, ib = (torch.full(s, float("nan"), dtype=torch.float32, device="cuda") for s in ((L, H, S), (L, H, S), (L, H, T)))
+    B.skipkv_score_shared_paged(cache, params, q, None, lam, sb, lb, ib, torch.empty(B.skipkv_paged_workspace_bytes(cache, params) + 256, dtype=torch.uint8, device="cuda"))
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    for x, y in ((sa, sb), (la, lb), (ia, ib)):
+        assert torch.equal(x.view(torch.int32), y.view(torch.int32))
+    assert torch.equal(la, lam.expand(L, H, S))
