@@ -230,7 +230,9 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     } else {
       // Paged cache, blocks of a power of two >= 16 slots: the stage's 16 tokens lie in at most two
       // blocks, in consecutive slots within each.  Two scalar reads of the row map give the slot
-      // row of the stage's first token and of the first token of the next block.
+      // row of the stage's first token and of the first token of the next block.  Map entries count
+      // units of map_stride elements (the token pitch, or one head row when every (layer, head) has a
+      // map of its own); consecutive slots of a block are one token pitch apart either way.
       const int jb = a.page_size - (ts & (a.page_size - 1));  // rows of the stage before the next block begins (may be >= 16)
       const int r0 = row_map_c[iss.tok0 + ts];
       const int r1 = row_map_c[iss.tok0 + min(ts + jb, iss.n_tok - 1)];
