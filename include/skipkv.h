@@ -453,6 +453,27 @@ int skipkv_step_ranges_paged(const skipkv_cache *cache, const skipkv_ranges *ran
                              int32_t kept_stride, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * The parts of skipkv_step_ranges_paged, for the token-level flow and for the shared lambda on
+ * per-head ranges and pages.  The selections (skipkv_select_ranges, skipkv_select_tokens_ranges)
+ * read neither K nor V and serve pages as they are; skipkv_compact_paged takes per-head kept_idx
+ * and new_len as it is.
+ * skipkv_score_ranges_paged: skipkv_score_ranges on pages; with shared_lambda != NULL it is
+ *   skipkv_score_shared_ranges on pages (then sent_id and lambda_ptr are required and
+ *   sent_lambda may be NULL), else sent_id / lambda_ptr are ignored.  ws as for
+ *   skipkv_step_ranges_paged.
+ * skipkv_token_redundancy_ranges_paged: skipkv_token_redundancy_ranges on pages; ws as for
+ *   skipkv_token_redundancy_paged.
+ */
+int skipkv_score_ranges_paged(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_paging *paging,
+                              const int32_t *sent_id, const int32_t *lambda_ptr, const float *shared_lambda,
+                              const skipkv_params *params, const void *q_obs, const float *tok_redundancy,
+                              float *sent_score, float *sent_lambda, float *tok_importance, void *ws, size_t ws_bytes,
+                              void *stream);
+int skipkv_token_redundancy_ranges_paged(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_paging *paging,
+                                         float *tok_redundancy, int32_t *dev_status, void *ws, size_t ws_bytes,
+                                         void *stream);
+
+/*
  * Steering injection (Sec. 4.2): hidden[b, :] <- hidden[b, :] + coef_b * vec for every row b
  * with row_mask[b] != 0 (all rows when row_mask is NULL).  coef_b = coef[b] when coef is
  * non-NULL, else coef_scalar.  The sum is formed in fp64 and rounded once (nearest even)

@@ -96,6 +96,8 @@ def lib() -> C.CDLL:
         L.skipkv_compact_paged.argtypes = [cp, gp, vp, vp, i32, vp, vp, sz, vp]
         L.skipkv_redundancy_paged_workspace_bytes.argtypes = [cp, gp, C.POINTER(sz)]
         L.skipkv_token_redundancy_paged.argtypes = [cp, gp, vp, vp, vp, sz, vp]
+        L.skipkv_score_ranges_paged.argtypes = [cp, rp, gp, vp, vp, vp, pp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.skipkv_token_redundancy_ranges_paged.argtypes = [cp, rp, gp, vp, vp, vp, sz, vp]
         L.skipkv_ranges_paged_workspace_bytes.argtypes = [cp, gp, pp, C.POINTER(sz)]
         L.skipkv_step_ranges_paged.argtypes = [cp, rp, gp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
         L.skipkv_profile_create.argtypes = [C.POINTER(vp)]
@@ -406,6 +408,20 @@ def skipkv_token_redundancy_paged(cache: PagedCache, tok_redundancy, dev_status,
     _check(lib().skipkv_token_redundancy_paged(C.byref(cache.c()), C.byref(cache.paging()), _ptr(tok_redundancy),
                                                _ptr(dev_status), _ptr(ws),
                                                ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
+
+
+def skipkv_score_ranges_paged(cache: PagedCache, ranges: Ranges, sent_id, lambda_ptr, shared_lambda, params: Params, q_obs,
+                              tok_redundancy, sent_score, sent_lambda, tok_importance, ws, stream=None) -> None:
+    _check(lib().skipkv_score_ranges_paged(C.byref(cache.c()), C.byref(ranges.c()), C.byref(cache.paging()), _ptr(sent_id),
+                                           _ptr(lambda_ptr), _ptr(shared_lambda), C.byref(params.c()), _ptr(q_obs),
+                                           _ptr(tok_redundancy), _ptr(sent_score), _ptr(sent_lambda), _ptr(tok_importance),
+                                           _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def skipkv_token_redundancy_ranges_paged(cache: PagedCache, ranges: Ranges, tok_redundancy, dev_status, ws, stream=None) -> None:
+    _check(lib().skipkv_token_redundancy_ranges_paged(C.byref(cache.c()), C.byref(ranges.c()), C.byref(cache.paging()),
+                                                      _ptr(tok_redundancy), _ptr(dev_status), _ptr(ws), _nbytes(ws),
+                                                      _stream(stream)))
 
 
 def skipkv_ranges_paged_workspace_bytes(cache: PagedCache, params: Params) -> int:

@@ -955,6 +955,62 @@ int skipkv_ranges_paged_workspace_bytes(const skipkv_cache *cache, const skipkv_
   return SKIPKV_OK;
 }
 
+namespace {
+// Scoring half of the per-head step on pages; leaves the row maps, flags and the view behind for the caller.
+int score_ranges_paged(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_paging *paging,
+                       const skipkv_params *params, const RowLayout &rl, const void *q_obs, const float *tok_redundancy,
+                       const float *shared_lambda, const int32_t *sent_id, const int32_t *lambda_ptr, float *sent_score,
+                       float *sent_lambda, float *tok_importance, void *ws, size_t ws_bytes, hipStream_t st, Timer &tm,
+                       RangesPagedView *pv, HeadView *hv_out) {
+  if (!q_obs || !aligned16(q_obs)) return SKIPKV_EINVAL;
+  if (cache->total_sentences > 0 && (!sent_score || (!shared_lambda && !sent_lambda))) return SKIPKV_EINVAL;
+  if (shared_lambda && cache->total_sentences > 0 && (!sent_id || !lambda_ptr)) return SKIPKV_EINVAL;
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SKIPKV_EWORKSPACE;
+  int rc = check_ranges_paging(cache, ranges, paging, params, rl, ws, pv);
+  if (rc) return rc;
+  if (ws_bytes < pv->total) return SKIPKV_EWORKSPACE;
+  const VirtualView &v = pv->v;
+  const int32_t n_lh = cache->n_layers * cache->n_kv_heads;
+  if (launch_virtual_layout(cache->seq_off, cache->sent_ptr, cache->batch, n_lh, cache->total_tokens,
+                            cache->total_sentences, v.seq_off, v.sent_ptr, st) != hipSuccess)
+    return SKIPKV_EHIP;
+  char *ws2 = static_cast<char *>(ws) + v.head_bytes;
+  int32_t *row_map = reinterpret_cast<int32_t *>(ws2 + pv->step_bytes);
+  int32_t *seq_bad = reinterpret_cast<int32_t *>(ws2 + pv->step_bytes + pv->map_bytes);
+  RowMapArgs ra{cache->seq_off, paging->block_table, cache->batch, paging->table_stride, paging->block_size,
+                paging->n_blocks, n_lh, cache->n_kv_heads, cache->total_tokens, pv->unit_layer, pv->unit_head,
+                pv->unit_block, pv->unit_tok, row_map, seq_bad, params->dev_status};
+  if (tm.run("row_map", [&] { return launch_row_map(ra, st); }) != hipSuccess) return SKIPKV_EHIP;
+  HeadView hv = v.hv;
+  hv.row_map = row_map;
+  hv.page_size = paging->block_size;
+  hv.map_stride = cache->head_dim;
+  hv.sent_id = shared_lambda ? sent_id : nullptr;
+  hv.lam_ptr = shared_lambda ? lambda_ptr : nullptr;
+  *hv_out = hv;
+  return do_score(tm, &v.c, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, ws2, st, hv, shared_lambda);
+}
+}  // namespace
+
+int skipkv_score_ranges_paged(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_paging *paging,
+                              const int32_t *sent_id, const int32_t *lambda_ptr, const float *shared_lambda,
+                              const skipkv_params *params, const void *q_obs, const float *tok_redundancy,
+                              float *sent_score, float *sent_lambda, float *tok_importance, void *ws, size_t ws_bytes,
+                              void *stream) {
+  RowLayout rl;
+  int rc = check_cache(cache, true);
+  if (rc) return rc;
+  rc = check_params(cache, params, &rl);
+  if (rc) return rc;
+  if (is_empty(cache)) return SKIPKV_OK;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Timer tm(params->profile, st);
+  RangesPagedView pv;
+  HeadView hv;
+  return score_ranges_paged(cache, ranges, paging, params, rl, q_obs, tok_redundancy, shared_lambda, sent_id, lambda_ptr,
+                            sent_score, sent_lambda, tok_importance, ws, ws_bytes, st, tm, &pv, &hv);
+}
+
 int skipkv_step_ranges_paged(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_paging *paging,
                              const skipkv_params *params, const void *q_obs, const float *tok_redundancy,
                              float *sent_score, float *sent_lambda, float *tok_importance, uint8_t *sent_keep,
@@ -968,38 +1024,21 @@ int skipkv_step_ranges_paged(const skipkv_cache *cache, const skipkv_ranges *ran
   rc = check_select_args(cache, params, &rl, sent_score, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride);
   if (rc) return rc;
   if (is_empty(cache)) return SKIPKV_OK;
-  if (!q_obs || !aligned16(q_obs)) return SKIPKV_EINVAL;
-  if (cache->total_sentences > 0 && (!sent_score || !sent_lambda)) return SKIPKV_EINVAL;
-  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SKIPKV_EWORKSPACE;
-  RangesPagedView pv;
-  rc = check_ranges_paging(cache, ranges, paging, params, rl, ws, &pv);
-  if (rc) return rc;
-  if (ws_bytes < pv.total) return SKIPKV_EWORKSPACE;
-  if (ranges->sent_off == new_sent_off || ranges->len == new_len || ranges->sent_cnt == new_sent_cnt) return SKIPKV_EINVAL;
+  if (ranges && (ranges->sent_off == new_sent_off || ranges->len == new_len || ranges->sent_cnt == new_sent_cnt)) return SKIPKV_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const VirtualView &v = pv.v;
-  const int32_t n_lh = cache->n_layers * cache->n_kv_heads;
-  if (launch_virtual_layout(cache->seq_off, cache->sent_ptr, cache->batch, n_lh, cache->total_tokens,
-                            cache->total_sentences, v.seq_off, v.sent_ptr, st) != hipSuccess)
-    return SKIPKV_EHIP;
-  char *ws2 = static_cast<char *>(ws) + v.head_bytes;
-  int32_t *row_map = reinterpret_cast<int32_t *>(ws2 + pv.step_bytes);
-  int32_t *seq_bad = reinterpret_cast<int32_t *>(ws2 + pv.step_bytes + pv.map_bytes);
-  int32_t *src_rows = reinterpret_cast<int32_t *>(ws2 + pv.step_bytes + pv.map_bytes + pv.bad_bytes);
   Timer tm(params->profile, st);
-  RowMapArgs ra{cache->seq_off, paging->block_table, cache->batch, paging->table_stride, paging->block_size,
-                paging->n_blocks, n_lh, cache->n_kv_heads, cache->total_tokens, pv.unit_layer, pv.unit_head,
-                pv.unit_block, pv.unit_tok, row_map, seq_bad, params->dev_status};
-  if (tm.run("row_map", [&] { return launch_row_map(ra, st); }) != hipSuccess) return SKIPKV_EHIP;
-  HeadView hv = v.hv;
-  hv.row_map = row_map;
-  hv.page_size = paging->block_size;
-  hv.map_stride = cache->head_dim;
-  rc = do_score(tm, &v.c, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, ws2, st, hv);
+  RangesPagedView pv;
+  HeadView hv;
+  rc = score_ranges_paged(cache, ranges, paging, params, rl, q_obs, tok_redundancy, nullptr, nullptr, nullptr, sent_score,
+                          sent_lambda, tok_importance, ws, ws_bytes, st, tm, &pv, &hv);
   if (rc) return rc;
+  const VirtualView &v = pv.v;
   rc = do_select(tm, &v.c, params, sent_score, sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride, st, hv);
   if (rc) return rc;
-  return do_compact(tm, &v.c, kept_idx, new_len, kept_stride, st, row_map, seq_bad, src_rows, pv.src_stride, cache->head_dim);
+  char *ws2 = static_cast<char *>(ws) + v.head_bytes;
+  int32_t *seq_bad = reinterpret_cast<int32_t *>(ws2 + pv.step_bytes + pv.map_bytes);
+  int32_t *src_rows = reinterpret_cast<int32_t *>(ws2 + pv.step_bytes + pv.map_bytes + pv.bad_bytes);
+  return do_compact(tm, &v.c, kept_idx, new_len, kept_stride, st, hv.row_map, seq_bad, src_rows, pv.src_stride, cache->head_dim);
 }
 
 int skipkv_ranges_append(const skipkv_cache *cache, const skipkv_ranges *ranges, const int32_t *n_new,
@@ -1124,8 +1163,26 @@ int skipkv_redundancy_paged_workspace_bytes(const skipkv_cache *cache, const ski
   return SKIPKV_OK;
 }
 
+namespace {
+int token_redundancy_paged(const skipkv_cache *cache, const int32_t *len, const skipkv_paging *paging, float *tok_redundancy,
+                           int32_t *dev_status, void *ws, size_t ws_bytes, void *stream);
+}
+
 int skipkv_token_redundancy_paged(const skipkv_cache *cache, const skipkv_paging *paging, float *tok_redundancy,
                                   int32_t *dev_status, void *ws, size_t ws_bytes, void *stream) {
+  return token_redundancy_paged(cache, nullptr, paging, tok_redundancy, dev_status, ws, ws_bytes, stream);
+}
+
+int skipkv_token_redundancy_ranges_paged(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_paging *paging,
+                                         float *tok_redundancy, int32_t *dev_status, void *ws, size_t ws_bytes,
+                                         void *stream) {
+  if (!ranges || !ranges->len) return SKIPKV_EINVAL;
+  return token_redundancy_paged(cache, ranges->len, paging, tok_redundancy, dev_status, ws, ws_bytes, stream);
+}
+
+namespace {
+int token_redundancy_paged(const skipkv_cache *cache, const int32_t *len, const skipkv_paging *paging, float *tok_redundancy,
+                           int32_t *dev_status, void *ws, size_t ws_bytes, void *stream) {
   int rc = check_cache(cache, false);
   if (rc) return rc;
   if (is_empty(cache) || cache->total_tokens == 0) return SKIPKV_OK;
@@ -1157,8 +1214,10 @@ int skipkv_token_redundancy_paged(const skipkv_cache *cache, const skipkv_paging
   a.neg_log_l = reinterpret_cast<float *>(static_cast<char *>(ws) + per);
   a.out = tok_redundancy;
   a.row_map = row_map;
+  a.len = len;
   return launch_token_redundancy(a, st) == hipSuccess ? SKIPKV_OK : SKIPKV_EHIP;
 }
+}  // namespace
 
 int skipkv_steer_add(void *hidden, const void *vec, const float *coef, float coef_scalar, const uint8_t *row_mask,
                      int32_t rows, int32_t d_model, int32_t dtype, void *stream) {

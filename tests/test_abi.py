@@ -311,3 +311,22 @@ def test_paged_shared_lambda_score_validates_on_the_host():
         C.byref(cache), p, C.byref(params), 0x6400, None, lam, sc, None, None, 0x10000, n, None)
     assert score(p=None) == B.EINVAL and score(lam=None) == B.EINVAL and score(sc=None) == B.EINVAL
     assert score(n=need - 1) == B.EWORKSPACE
+
+
+def test_paged_per_head_parts_validate_on_the_host():
+    lib, params = B.lib(), _params()
+    cache = _cache(stride_tok=8 * 128, stride_head=128, stride_layer=700 * 16 * 8 * 128)
+    out = C.c_size_t(0)
+    pg = B.CPaging(block_table=0x6000, table_stride=600, block_size=16, n_blocks=700, stride_block=16 * cache.stride_tok)
+    assert lib.skipkv_ranges_paged_workspace_bytes(C.byref(cache), C.byref(pg), C.byref(params), C.byref(out)) == B.OK
+    need = out.value
+    rng = B.CRanges(0x6000, 0x6100, 0x6200)
+    score = lambda r=C.byref(rng), p=C.byref(pg), ids=None, lp=None, lam=None, sl=0x8000, n=need: lib.skipkv_score_ranges_paged(
+        C.byref(cache), r, p, ids, lp, lam, C.byref(params), 0x6400, None, 0x7000, sl, None, 0x10000, n, None)
+    assert score(r=None) == B.EINVAL and score(p=None) == B.EINVAL and score(sl=None) == B.EINVAL
+    assert score(lam=0x7A00) == B.EINVAL                       # a shared lambda needs the sentence numbers and its CSR
+    assert score(n=need - 1) == B.EWORKSPACE
+    assert lib.skipkv_redundancy_paged_workspace_bytes(C.byref(cache), C.byref(pg), C.byref(out)) == B.OK
+    red = lambda r=C.byref(rng), o=0x7000, n=out.value: lib.skipkv_token_redundancy_ranges_paged(
+        C.byref(cache), r, C.byref(pg), o, None, 0x10000, n, None)
+    assert red(r=None) == B.EINVAL and red(o=None) == B.EINVAL and red(n=out.value - 1) == B.EWORKSPACE

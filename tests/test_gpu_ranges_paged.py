@@ -127,3 +127,82 @@ def test_paged_per_head_step_reports_a_bad_block_id_and_leaves_the_sequence_alon
     new_len = out.new_len.cpu().numpy()
     assert (new_len >= 0).all() and (new_len <= cfg.budget // 2).all()
     assert not torch.equal(kp.view(torch.uint8), kp0.view(torch.uint8))
+
+
+def test_token_level_flow_and_shared_lambda_on_per_head_ranges_and_pages():
+    """After a first step on the contiguous cache: the token-level flow (R, scores, token selection,
+    compaction) and the scores with a shared lambda, on pages and on the contiguous cache."""
+    from test_gpu_ranges_tokens import _bytes
+    cfg = W.CONFIGS[3].scaled(n_layers=2, batch=3, len_lo=900, len_hi=2400, budget=768)
+    st, k1, v1, q2, s1 = _first_step(cfg)
+    L, H, Bn, S, T = cfg.n_layers, cfg.n_kv_heads, cfg.batch, st.total_sentences, st.total_tokens
+    budget2 = cfg.budget // 2
+    kept_stride = budget2
+    kp, vp, table = _to_pages(cfg, st, k1, v1, 16, seed=41)
+    so, sp, sf = device_structure(st, kp.device)
+    paged = B.PagedCache(kp, vp, table, cfg.n_q_heads, so, sp, sf, T, S)
+    k, v = k1.clone(), v1.clone()
+    from helpers import make_cache
+    flat = make_cache(cfg, st, k, v)
+    f32 = lambda *shape: torch.full(shape, float("nan"), dtype=torch.float32, device="cuda")
+    ids = torch.arange(S, dtype=torch.int32, device="cuda").expand(L, H, S).contiguous() % 7   # any numbers inside the lists
+    lam_ptr = torch.from_numpy(np.concatenate([[0], np.cumsum(st.n_sent)]).astype(np.int32)).cuda()
+    shared = torch.from_numpy(np.random.default_rng(6).uniform(0.6, 1.0, S).astype(np.float32)).cuda()
+    res = {}
+    for name, cache in (("flat", flat), ("paged", paged)):
+        status = torch.zeros(1, dtype=torch.int32, device="cuda")
+        params = B.Params(cfg.obs_window, cfg.protect_window, budget2, dev_status=status)
+        ranges = _ranges_of(s1)
+        red, imp, score, lam, tok_score, score_sh, lam_sh = f32(L, H, T), f32(L, H, T), f32(L, H, S), f32(L, H, S), f32(L, H, T), f32(L, H, S), f32(L, H, S)
+        tok_keep = torch.full((L, H, T), 77, dtype=torch.uint8, device="cuda")
+        kept_idx = torch.full((L, H, Bn, kept_stride), -1, dtype=torch.int32, device="cuda")
+        new_len = torch.full((L, H, Bn), -1, dtype=torch.int32, device="cuda")
+        new_off = torch.full((L, H, S + Bn), -1, dtype=torch.int32, device="cuda")
+        new_cnt = torch.full((L, H, Bn), -1, dtype=torch.int32, device="cuda")
+        if name == "flat":
+            ws = _bytes(B.skipkv_ranges_workspace_bytes(cache, params))
+            B.skipkv_token_redundancy_ranges(cache, ranges, red, _bytes(B.skipkv_redundancy_workspace_bytes(cache)))
+            B.skipkv_score_shared_ranges(cache, ranges, ids, lam_ptr, params, q2, red, shared, score_sh, lam_sh, None, ws)
+            B.skipkv_score_ranges(cache, ranges, params, q2, red, score, lam, imp, ws)
+        else:
+            ws = _bytes(B.skipkv_ranges_paged_workspace_bytes(cache, params))
+            B.skipkv_token_redundancy_ranges_paged(cache, ranges, red, status, _bytes(B.skipkv_redundancy_paged_workspace_bytes(cache)))
+            B.skipkv_score_ranges_paged(cache, ranges, ids, lam_ptr, shared, params, q2, red, score_sh, lam_sh, None, ws)
+            B.skipkv_score_ranges_paged(cache, ranges, None, None, None, params, q2, red, score, lam, imp, ws)
+        B.skipkv_select_tokens_ranges(cache, ranges, params, imp, red, lam, tok_score, tok_keep, kept_idx, new_len, new_off, new_cnt,
+                                      kept_stride, ws)
+        if name == "flat":
+            B.skipkv_compact(cache, kept_idx, new_len, kept_stride)
+        else:
+            B.skipkv_compact_paged(cache, kept_idx, new_len, kept_stride, status, _bytes(B.skipkv_compact_paged_workspace_bytes(cache, kept_stride)))
+        torch.cuda.synchronize()
+        assert int(status.item()) == 0
+        res[name] = dict(red=red, imp=imp, score=score, lam=lam, tok_score=tok_score, score_sh=score_sh, lam_sh=lam_sh,
+                         tok_keep=tok_keep, kept_idx=kept_idx, new_len=new_len, new_off=new_off, new_cnt=new_cnt)
+    len1, cnt1 = s1.new_len.cpu().numpy(), s1.new_sent_cnt.cpu().numpy()
+    nl = res["flat"]["new_len"].cpu().numpy()
+    assert np.array_equal(nl, res["paged"]["new_len"].cpu().numpy()) and np.array_equal(res["flat"]["new_cnt"].cpu().numpy(), res["paged"]["new_cnt"].cpu().numpy())
+    assert (nl == np.minimum(budget2, len1)).all()
+    kg, vg = _from_pages(cfg, st, kp, table, 16), _from_pages(cfg, st, vp, table, 16)
+    a, b_ = res["flat"], res["paged"]
+    for l in range(L):
+        for h in range(H):
+            for b in range(Bn):
+                t0, p0, n1, c1, n2 = int(st.seq_off[b]), int(st.sent_ptr[b]), int(len1[l, h, b]), int(cnt1[l, h, b]), int(nl[l, h, b])
+                s0 = p0 - b
+                for name in ("red", "imp", "tok_score"):
+                    assert torch.equal(a[name][l, h, t0:t0 + n1].view(torch.int32), b_[name][l, h, t0:t0 + n1].view(torch.int32)), (name, l, h, b)
+                for name in ("score", "lam", "score_sh", "lam_sh"):
+                    assert torch.equal(a[name][l, h, s0:s0 + c1].view(torch.int32), b_[name][l, h, s0:s0 + c1].view(torch.int32)), (name, l, h, b)
+                assert torch.equal(a["tok_keep"][l, h, t0:t0 + n1], b_["tok_keep"][l, h, t0:t0 + n1])
+                assert torch.equal(a["kept_idx"][l, h, b, :n2], b_["kept_idx"][l, h, b, :n2])
+                c2 = int(a["new_cnt"][l, h, b])
+                assert torch.equal(a["new_off"][l, h, p0:p0 + c2 + 1], b_["new_off"][l, h, p0:p0 + c2 + 1])
+                assert torch.equal(kg[l, h, t0:t0 + n2].view(torch.uint8), k[l, h, t0:t0 + n2].view(torch.uint8)), (l, h, b)
+                assert torch.equal(vg[l, h, t0:t0 + n2].view(torch.uint8), v[l, h, t0:t0 + n2].view(torch.uint8)), (l, h, b)
+    # the looked-up lambda is the one of the sentence's number
+    sh = shared.cpu().numpy()
+    for (l, h, b) in [(0, 0, 0), (1, 3, 2)]:
+        s0, c1 = int(st.sent_ptr[b]) - b, int(cnt1[l, h, b])
+        want = sh[int(lam_ptr[b]) + ids[l, h, s0:s0 + c1].cpu().numpy()]
+        np.testing.assert_array_equal(b_["lam_sh"][l, h, s0:s0 + c1].cpu().numpy(), want)
