@@ -104,3 +104,16 @@ def test_long_sequences_counter_protocol_next_to_short_ones():
                               sent_mean=40.0)
     stats = _run_and_compare(cfg, 6, seed=7)
     assert stats["heads"] == 6
+
+
+@pytest.mark.parametrize("group,alpha,dtype", [
+    (1, 1, "bf16"), (1, 32, "bf16"), (2, 16, "bf16"), (3, 8, "bf16"), (4, 4, "f32"), (5, 8, "bf16"), (6, 10, "bf16"),
+    (7, 8, "bf16"), (8, 8, "bf16"), (8, 4, "f32"), (4, 32, "bf16"), (8, 32, "bf16"), (5, 32, "f32"),
+])
+def test_group_sizes_and_observation_windows(group, alpha, dtype):
+    """Every shape of the query block: group sizes 1-8, windows 1-32; up to 64 query rows the
+    single-pass scan runs, beyond that the two-pass one.  All heads against the oracle."""
+    cfg = W.Config("rows-%dx%d" % (group, alpha), 40 + group * 33 + alpha, 3, 1, 2, 2 * group, dtype, 150, 900, 256,
+                   alpha, max(alpha, 40), 12.0, 0.2)
+    stats = _run_and_compare(cfg, 6)
+    assert stats["heads"] == 6
