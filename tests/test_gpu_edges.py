@@ -334,10 +334,7 @@ def test_step_replays_from_a_hip_graph():
                                    w_.view(torch.uint8) if w_.dtype != torch.uint8 else w_), (rep, name)
 
 
-@pytest.mark.parametrize("dtype,sent_hi", [("bf16", 9), ("bf16", 2), ("f32", 40)])
-def test_lengths_around_chunk_and_stage_edges(dtype, sent_hi):
-    """Sequence lengths one below, at and one above the multiples of the scan's chunk (256 tokens) and
-    stage (16 tokens) sizes, with short, one-token and long sentences: every head against the oracle."""
+def _boundary_structure(sent_hi):
     rng = np.random.default_rng(sent_hi)
     lens = [15, 16, 17, 65, 255, 256, 257, 511, 512, 513, 1023, 1024, 1025, 1280]
     offsets = []
@@ -346,7 +343,14 @@ def test_lengths_around_chunk_and_stage_edges(dtype, sent_hi):
         while off[-1] < n:
             off.append(min(n, off[-1] + int(rng.integers(1, sent_hi))))
         offsets.append(off)
-    st = _structure(offsets)
+    return _structure(offsets), lens
+
+
+@pytest.mark.parametrize("dtype,sent_hi", [("bf16", 9), ("bf16", 2), ("f32", 40)])
+def test_lengths_around_chunk_and_stage_edges(dtype, sent_hi):
+    """Sequence lengths one below, at and one above the multiples of the scan's chunk (256 tokens) and
+    stage (16 tokens) sizes, with short, one-token and long sentences: every head against the oracle."""
+    st, lens = _boundary_structure(sent_hi)
     cfg = W.Config("edges", 9, len(lens), 1, 2, 8, dtype, 0, 0, 96, 8, 16, 16.0, 0.0)
     k0, v0, q = _random_kvq(cfg, st, 23 + sent_hi)
     k, v = k0.clone(), v0.clone()

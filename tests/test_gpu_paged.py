@@ -355,3 +355,19 @@ def test_scores_with_shared_lambda_on_pages_equal_the_contiguous_ones():
     for x, y in ((sa, sb), (la, lb), (ia, ib)):
         assert torch.equal(x.view(torch.int32), y.view(torch.int32))
     assert torch.equal(la, lam.expand(L, H, S))
+
+
+@pytest.mark.parametrize("block_size,sent_hi", [(16, 9), (64, 2), (32, 40)])
+def test_paged_lengths_around_chunk_stage_and_block_edges(block_size, sent_hi):
+    """Sequence lengths one below, at and one above the multiples of the scan's chunk and stage sizes
+    (and so of the blocks) on a paged cache, every head against the oracle."""
+    from test_gpu_edges import _boundary_structure, _compare_all, _random_kvq
+    st, lens = _boundary_structure(sent_hi)
+    cfg = W.Config("edges", 9, len(lens), 1, 2, 8, "bf16", 0, 0, 96, 8, 16, 16.0, 0.0)
+    k0, v0, q = _random_kvq(cfg, st, 50 + block_size)
+    kp, vp, table = _to_pages(cfg, st, k0, v0, block_size, seed=block_size + 7)
+    out = _run_paged(cfg, st, kp, vp, table, q)
+    assert int(out.dev_status.item()) == 0
+    kg, vg = _from_pages(cfg, st, kp, table, block_size), _from_pages(cfg, st, vp, table, block_size)
+    stats = _compare_all(cfg, st, out, kg, vg, k0, v0, q)
+    assert stats["heads"] == 2 * len(lens)
