@@ -206,3 +206,60 @@ def test_token_level_flow_and_shared_lambda_on_per_head_ranges_and_pages():
         s0, c1 = int(st.sent_ptr[b]) - b, int(cnt1[l, h, b])
         want = sh[int(lam_ptr[b]) + ids[l, h, s0:s0 + c1].cpu().numpy()]
         np.testing.assert_array_equal(b_["lam_sh"][l, h, s0:s0 + c1].cpu().numpy(), want)
+
+
+def test_paged_per_head_step_replays_from_a_hip_graph():
+    """Like the contiguous step, the per-head step on pages allocates nothing, never synchronises and
+    clears its flags with fill kernels: captured into a HIP graph, every replay (with eager work and
+    synchronisations in between) reproduces the eager result bit for bit."""
+    cfg = W.CONFIGS[3].scaled(n_layers=1, batch=3, len_lo=900, len_hi=2000, budget=512)
+    st, k1, v1, q2, s1 = _first_step(cfg)
+    budget2 = cfg.budget // 2
+    kp0, vp0, table = _to_pages(cfg, st, k1, v1, 16, seed=77)
+    ka, va = kp0.clone(), vp0.clone()
+    eager = _run_ranges_paged(cfg, st, ka, va, table, q2, _ranges_of(s1), budget2)
+    assert int(eager.dev_status.item()) == 0
+    kp, vp = kp0.clone(), vp0.clone()
+    so, sp, sf = device_structure(st, kp.device)
+    cache = B.PagedCache(kp, vp, table, cfg.n_q_heads, so, sp, sf, st.total_tokens, st.total_sentences)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    params = B.Params(cfg.obs_window, cfg.protect_window, budget2, dev_status=status)
+    ws = torch.empty(B.skipkv_ranges_paged_workspace_bytes(cache, params) + 256, dtype=torch.uint8, device="cuda")
+    ranges = _ranges_of(s1)
+    o = _outputs(cfg, st, eager.kept_stride)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            B.skipkv_step_ranges_paged(cache, ranges, params, q2, None, o["sent_score"], o["sent_lambda"], o["tok_imp"],
+                                       o["sent_keep"], o["kept_idx"], o["new_len"], o["new_sent_off"], o["new_sent_cnt"],
+                                       eager.kept_stride, ws)
+    torch.cuda.synchronize()
+    len1, cnt1 = s1.new_len.cpu().numpy(), s1.new_sent_cnt.cpu().numpy()
+    for rep in range(3):
+        kp.copy_(kp0)
+        vp.copy_(vp0)
+        for t in (o["sent_score"], o["kept_idx"], o["new_len"]):
+            t.fill_(-7)                       # eager work between the replays
+        ws.fill_(0xAB)                        # nothing in the workspace is carried from call to call
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert int(status.item()) == 0
+        assert torch.equal(o["new_len"], eager.new_len) and torch.equal(o["new_sent_cnt"], eager.new_sent_cnt), rep
+        nl = o["new_len"].cpu().numpy()
+        for l in range(cfg.n_layers):
+            for h in range(cfg.n_kv_heads):
+                for b in range(cfg.batch):
+                    s0, c1, n2 = int(st.sent_ptr[b]) - b, int(cnt1[l, h, b]), int(nl[l, h, b])
+                    assert torch.equal(o["sent_score"][l, h, s0:s0 + c1].view(torch.int32), eager.sent_score[l, h, s0:s0 + c1].view(torch.int32)), (rep, l, h, b)
+                    assert torch.equal(o["kept_idx"][l, h, b, :n2], eager.kept_idx[l, h, b, :n2]), (rep, l, h, b)
+        # the pools: wherever a kept token lives the replay wrote what the eager call wrote
+        kg, kr = _from_pages(cfg, st, kp, table, 16), _from_pages(cfg, st, ka, table, 16)
+        vg, vr = _from_pages(cfg, st, vp, table, 16), _from_pages(cfg, st, va, table, 16)
+        for l in range(cfg.n_layers):
+            for h in range(cfg.n_kv_heads):
+                for b in range(cfg.batch):
+                    t0, n2 = int(st.seq_off[b]), int(nl[l, h, b])
+                    assert torch.equal(kg[l, h, t0:t0 + n2], kr[l, h, t0:t0 + n2]) and torch.equal(vg[l, h, t0:t0 + n2], vr[l, h, t0:t0 + n2]), (rep, l, h, b)
