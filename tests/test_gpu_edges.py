@@ -313,6 +313,7 @@ def test_step_replays_from_a_hip_graph():
         vg.copy_(v0)
         for t in (sent_score, kept_idx, new_len):
             t.fill_(-7)                       # eager work between the replays
+        ws.fill_(0xAB if rep % 2 else 0)      # nothing in the workspace is carried from call to call
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
