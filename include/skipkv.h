@@ -177,6 +177,25 @@ int skipkv_step(const skipkv_cache *cache, const skipkv_params *params, const vo
                 size_t ws_bytes, void *stream);
 
 /*
+ * skipkv_step for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation,
+ * arguments and outputs as skipkv_step, but the scratch space is an array of
+ * SKIPKV_STATIC_WS_BYTES that the library's code object holds on every GPU it is loaded on until the
+ * process ends.  Nothing is allocated or freed, by this library or through it.  A problem whose
+ * skipkv_workspace_bytes() exceeds SKIPKV_STATIC_WS_BYTES is refused with SKIPKV_EWORKSPACE and
+ * nothing is enqueued.  The first call on a device looks the array's address up (not while a
+ * stream is capturing: make one call before capture starts).  All calls on one GPU share the
+ * array: calls whose enqueued work may overlap on that GPU race (serialise them on one stream,
+ * or order the streams with events); the contents the previous call left are reset by the
+ * step's own kernels where they matter.
+ */
+#define SKIPKV_STATIC_WS_BYTES (64u << 20)
+int skipkv_step_static(const skipkv_cache *cache, const skipkv_params *params, const void *q_obs,
+                       const float *tok_redundancy, float *sent_score, float *sent_lambda,
+                       float *tok_importance, uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len,
+                       int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride, void *stream);
+
+/*
  * Token-level selection: Eq. 6 as printed and the rule after it ("evict tokens in increasing
  * order of the final score").  Per head and token t of sentence s:
  *   tok_score[t] = sigma * I[t] - (1 - sigma) * R[t] - (lambda_s if lambda_s > tau)

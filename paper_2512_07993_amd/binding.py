@@ -68,6 +68,7 @@ def lib() -> C.CDLL:
         L.skipkv_select.argtypes = [cp, pp, vp, vp, vp, vp, vp, vp, i32, vp]
         L.skipkv_compact.argtypes = [cp, vp, vp, i32, vp]
         L.skipkv_step.argtypes = [cp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+        L.skipkv_step_static.argtypes = [cp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
         L.skipkv_select_tokens.argtypes = [cp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp]
         L.skipkv_redundancy_workspace_bytes.argtypes = [cp, C.POINTER(sz)]
         L.skipkv_token_redundancy.argtypes = [cp, vp, vp, sz, vp]
@@ -244,6 +245,17 @@ def skipkv_step(cache: Cache, params: Params, q_obs, tok_redundancy, sent_score,
                              _ptr(sent_score), _ptr(sent_lambda), _ptr(tok_importance), _ptr(sent_keep),
                              _ptr(kept_idx), _ptr(new_len), _ptr(new_sent_off), _ptr(new_sent_cnt), kept_stride,
                              _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream(stream)))
+
+
+STATIC_WS_BYTES = 64 << 20  # SKIPKV_STATIC_WS_BYTES
+
+
+def skipkv_step_static(cache: Cache, params: Params, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance,
+                       sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride: int, stream=None) -> None:
+    _check(lib().skipkv_step_static(C.byref(cache.c()), C.byref(params.c()), _ptr(q_obs), _ptr(tok_redundancy),
+                                    _ptr(sent_score), _ptr(sent_lambda), _ptr(tok_importance), _ptr(sent_keep),
+                                    _ptr(kept_idx), _ptr(new_len), _ptr(new_sent_off), _ptr(new_sent_cnt), kept_stride,
+                                    _stream(stream)))
 
 
 @dataclass

@@ -1,6 +1,7 @@
 // Host side of libskipkv: argument validation, workspace carving, kernel sequencing, timing.
 // No device work happens here and nothing is allocated on the device.
 #include <algorithm>
+#include <atomic>
 #include <cstdlib>
 #include <new>
 
@@ -463,6 +464,51 @@ int skipkv_step(const skipkv_cache *cache, const skipkv_params *params, const vo
   rc = do_select(tm, cache, params, sent_score, sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride, st);
   if (rc) return rc;
   return do_compact(tm, cache, kept_idx, new_len, kept_stride, st);
+}
+
+// Scratch of skipkv_step_static: one array per GPU, held by the code object from the moment it is
+// loaded until the process ends.  In host code this name only stands for the symbol; the
+// array's address on a device comes from hipGetSymbolAddress (static_scratch below).
+static __device__ __align__(256) unsigned char scratch[SKIPKV_STATIC_WS_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+// Address of `scratch` on the current device, looked up once per device.
+int static_scratch(void **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return SKIPKV_EHIP;
+  if (dev < 0 || dev >= kMaxDevices) return SKIPKV_ECAPACITY;
+  void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SKIPKV_EHIP;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);  // every thread finds the same address
+  }
+  *out = p;
+  return SKIPKV_OK;
+}
+}  // namespace
+
+int skipkv_step_static(const skipkv_cache *cache, const skipkv_params *params, const void *q_obs,
+                       const float *tok_redundancy, float *sent_score, float *sent_lambda, float *tok_importance,
+                       uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len, int32_t *new_sent_off,
+                       int32_t *new_sent_cnt, int32_t kept_stride, void *stream) {
+  int rc = check_cache(cache, true);
+  if (rc) return rc;
+  RowLayout rl;
+  rc = check_params(cache, params, &rl);
+  if (rc) return rc;
+  const Workspace w = carve(cache, rl, nullptr);
+  if (!w.fits) return SKIPKV_ECAPACITY;
+  if (w.bytes > (size_t)SKIPKV_STATIC_WS_BYTES) return SKIPKV_EWORKSPACE;  // the problem needs more scratch than the array holds
+  void *ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc) return rc;
+  // From here on this is skipkv_step on the array: the plan's fill kernels reset every counter
+  // and marker that must start from a known value, so what the previous call left is harmless.
+  return skipkv_step(cache, params, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, sent_keep, kept_idx,
+                     new_len, new_sent_off, new_sent_cnt, kept_stride, ws, (size_t)SKIPKV_STATIC_WS_BYTES, stream);
 }
 
 namespace {
@@ -1281,7 +1327,7 @@ const char *skipkv_strerror(int status) {
     case SKIPKV_EINVAL: return "invalid argument (null pointer, shape, stride, alignment or dtype)";
     case SKIPKV_EBUDGET: return "budget smaller than the protected window, or observation window larger than the protected window";
     case SKIPKV_ECAPACITY: return "shape outside the limits this build supports";
-    case SKIPKV_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case SKIPKV_EWORKSPACE: return "workspace missing, misaligned or too small (skipkv_step_static: the problem needs more than SKIPKV_STATIC_WS_BYTES)";
     case SKIPKV_EHIP: return "HIP runtime error";
     default: return "unknown status";
   }
