@@ -6,7 +6,7 @@
  * Conventions shared by every entry point
  * ---------------------------------------
  *  - Plain C ABI.  Every call returns an int status: SKIPKV_OK (0) or a negative code;
- *    skipkv_strerror() names it.  No exceptions, no global state.
+ *    skipkv_strerror() names it.  No exceptions, no global state, no environment variables.
  *  - Pointers marked "device" must be GPU-accessible memory owned by the caller and must
  *    stay valid until the work enqueued by the call has finished.  The library never
  *    allocates or frees device memory; scratch space comes from the caller's workspace
@@ -46,7 +46,7 @@
 extern "C" {
 #endif
 
-#define SKIPKV_VERSION 100 /* major*10000 + minor*100 + patch */
+#define SKIPKV_VERSION 101 /* major*10000 + minor*100 + patch */
 
 enum {
   SKIPKV_OK = 0,
@@ -61,10 +61,19 @@ enum {
 enum {
   SKIPKV_DEV_BAD_OFFSETS = 1,  /* sentence offsets not strictly ascending from 0 to N_b   */
   SKIPKV_DEV_TOO_MANY_SENT = 2, /* a sequence has more than SKIPKV_MAX_SENTENCES sentences */
-  SKIPKV_DEV_TIMEOUT = 4,       /* a bounded cross-workgroup wait ran out: scores are invalid  */
+  SKIPKV_DEV_TIMEOUT = 4,       /* a bounded cross-workgroup wait ran out: the scores concerned are NaN */
   SKIPKV_DEV_TOO_MANY_TOK = 8,  /* skipkv_select_tokens: a sequence is longer than SKIPKV_MAX_TOKENS_TOKEN_SELECT */
-  SKIPKV_DEV_BAD_BLOCK_TABLE = 16 /* paged cache: a block id outside [0, n_blocks); that sequence's K/V are left untouched */
+  SKIPKV_DEV_BAD_BLOCK_TABLE = 16, /* paged cache: a block id outside [0, n_blocks); that sequence's K/V are left untouched */
+  SKIPKV_DEV_BAD_BUDGET = 32,   /* a device budget below the protected window, negative, or too large for kept_stride */
+  SKIPKV_DEV_BAD_SCORES = 64    /* selection: a candidate sentence's score is NaN                 */
 };
+/*
+ * A head (layer, KV head, sequence) that one of these bits concerns is never compacted from
+ * inputs the library could not trust: the selections give it new_len = N_b (everything kept),
+ * kept_idx = the identity as far as the row reaches, sent_keep = 1 and unchanged ranges, and the
+ * compaction leaves its K and V rows alone (it also skips any head whose new_len exceeds
+ * kept_stride).  The other heads of the call are processed normally.
+ */
 
 typedef enum { SKIPKV_F32 = 0, SKIPKV_BF16 = 1 } skipkv_dtype;
 
@@ -106,7 +115,12 @@ typedef struct skipkv_params {
   int32_t max_budget;     /* host upper bound on any budget (sizes kept_idx rows)          */
   int32_t *dev_status;    /* device, nullable: SKIPKV_DEV_* bits are OR-ed into it         */
   void *profile;          /* nullable: handle from skipkv_profile_create                   */
+  uint32_t flags;         /* SKIPKV_FLAG_* bits, 0 for the defaults                        */
+  int32_t spin_limit;     /* polls that a cross-workgroup wait of the single-pass key scan may
+                             take before it gives up: 0 = default (4000000), negative = give
+                             up at the first poll (for tests of the time-out path)          */
 } skipkv_params;
+#define SKIPKV_FLAG_FORCE_TWO_PASS 1u /* read K twice: statistics pass + score pass, no waits across workgroups */
 
 /* Bytes of device scratch that skipkv_score / skipkv_step need for this problem.         */
 int skipkv_workspace_bytes(const skipkv_cache *cache, const skipkv_params *params, size_t *out_bytes);
@@ -128,10 +142,11 @@ int skipkv_workspace_bytes(const skipkv_cache *cache, const skipkv_params *param
  * tok_importance  device out [n_layers, n_kv_heads, total_tokens] fp32, or NULL.
  * The key scan reads K once where it can (query rows n * obs_window <= 64 after padding, no
  * sentence longer than 256 tokens, at most 131072 tokens per sequence) and twice otherwise.
- * Its single-pass form waits across workgroups; the wait is bounded (environment variable
- * SKIPKV_SPIN_LIMIT, polls, default 4000000): on expiry SKIPKV_DEV_TIMEOUT is OR-ed into
- * dev_status, scores are invalid and the call still completes.  SKIPKV_FORCE_TWO_PASS=1
- * selects the two-pass form for every sequence.
+ * Its single-pass form waits across workgroups; the wait is bounded (params->spin_limit): on
+ * expiry SKIPKV_DEV_TIMEOUT is OR-ed into dev_status, every later wait of the call gives up at
+ * once, the scores of the sentences concerned are NaN (which makes the selection keep those
+ * heads whole) and the call still completes.  SKIPKV_FLAG_FORCE_TWO_PASS selects the two-pass
+ * form for every sequence.
  * ws              device workspace, 256-byte aligned, >= skipkv_workspace_bytes().
  */
 int skipkv_score(const skipkv_cache *cache, const skipkv_params *params, const void *q_obs,
@@ -207,8 +222,8 @@ int skipkv_step_static(const skipkv_cache *cache, const skipkv_params *params, c
  * tok_redundancy  device, same shape, or NULL (R = 0).   sent_lambda  device (from skipkv_score).
  * tok_score       device out, same shape, required (also the kernel's working copy).
  * tok_keep        device out [n_layers, n_kv_heads, total_tokens] u8, or NULL.
- * A sequence longer than SKIPKV_MAX_TOKENS_TOKEN_SELECT gets new_len 0 and
- * SKIPKV_DEV_TOO_MANY_TOK in dev_status.
+ * A sequence longer than SKIPKV_MAX_TOKENS_TOKEN_SELECT is reported (SKIPKV_DEV_TOO_MANY_TOK in
+ * dev_status) and keeps everything, like any head whose inputs cannot be used (see SKIPKV_DEV_*).
  */
 int skipkv_select_tokens(const skipkv_cache *cache, const skipkv_params *params, const float *tok_importance,
                          const float *tok_redundancy, const float *sent_lambda, float *tok_score,

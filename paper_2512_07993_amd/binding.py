@@ -16,7 +16,8 @@ import torch
 
 F32, BF16 = 0, 1
 OK, EINVAL, EBUDGET, ECAPACITY, EWORKSPACE, EHIP = 0, -1, -2, -3, -4, -5
-DEV_BAD_OFFSETS, DEV_TOO_MANY_SENT, DEV_TIMEOUT, DEV_TOO_MANY_TOK, DEV_BAD_BLOCK_TABLE = 1, 2, 4, 8, 16
+DEV_BAD_OFFSETS, DEV_TOO_MANY_SENT, DEV_TIMEOUT, DEV_TOO_MANY_TOK, DEV_BAD_BLOCK_TABLE, DEV_BAD_BUDGET, DEV_BAD_SCORES = 1, 2, 4, 8, 16, 32, 64
+FLAG_FORCE_TWO_PASS = 1
 PROFILE_SLOTS = 16
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libskipkv.so")
@@ -49,6 +50,7 @@ class CParams(C.Structure):
         ("sigma", C.c_float), ("tau", C.c_float),
         ("budget", C.c_void_p), ("budget_scalar", C.c_int32), ("max_budget", C.c_int32),
         ("dev_status", C.c_void_p), ("profile", C.c_void_p),
+        ("flags", C.c_uint32), ("spin_limit", C.c_int32),
     ]
 
 
@@ -188,6 +190,8 @@ class Params:
     tau: float = 0.95
     dev_status: Optional[torch.Tensor] = None
     profile: Optional[int] = None
+    flags: int = 0
+    spin_limit: int = 0
 
     def c(self) -> CParams:
         if isinstance(self.budget, int):
@@ -196,7 +200,7 @@ class Params:
         else:
             bptr, bs, mb = self.budget.data_ptr(), 0, self.max_budget
         return CParams(self.obs_window, self.protect_window, self.sigma, self.tau, bptr, bs, mb,
-                       _ptr(self.dev_status), self.profile)
+                       _ptr(self.dev_status), self.profile, self.flags, self.spin_limit)
 
 
 def skipkv_version() -> int:

@@ -152,16 +152,12 @@ int do_score(Timer &tm, const skipkv_cache *c, const skipkv_params *p, const Row
   sa.tok_imp = tok_imp;
   sa.ws = w;
   sa.rl = rl;
-  // Debugging aids (environment): SKIPKV_FORCE_TWO_PASS=1 sends every sequence through the
-  // two-pass scan; SKIPKV_SPIN_LIMIT bounds the polls of the single-pass scan's wait.
-  const char *env_two = std::getenv("SKIPKV_FORCE_TWO_PASS");
-  const char *env_spin = std::getenv("SKIPKV_SPIN_LIMIT");
   sa.row_map = hv.row_map;
   sa.page_size = hv.page_size;
   sa.map_stride = hv.map_stride ? hv.map_stride : c->stride_tok;
   const bool pages_fit_stages = hv.page_size >= 16 && (hv.page_size & (hv.page_size - 1)) == 0;
-  sa.force_two_pass = (hv.row_map != nullptr && !pages_fit_stages) || (env_two && env_two[0] == '1') || !scan_fused_supported(rl, c->stride_tok * (c->dtype == SKIPKV_BF16 ? 2 : 4));
-  sa.spin_limit = env_spin ? std::atoi(env_spin) : 4000000;
+  sa.force_two_pass = (hv.row_map != nullptr && !pages_fit_stages) || (p->flags & SKIPKV_FLAG_FORCE_TWO_PASS) || !scan_fused_supported(rl, c->stride_tok * (c->dtype == SKIPKV_BF16 ? 2 : 4));
+  sa.spin_limit = p->spin_limit == 0 ? 4000000 : std::max(p->spin_limit, 0);
   sa.dev_status = p->dev_status;
   sa.virt_hk = hv.virt_hk;
   sa.virt_b = hv.virt_b;

@@ -60,7 +60,8 @@ struct PlanHeader {
   // row blocks in bits 43..63.
   unsigned long long ranges;
   int32_t n_unfused;  // number of sequences that take the two-pass scan
-  int32_t pad[61];
+  int32_t abort;      // set by the first cross-workgroup wait of the single-pass scan that runs out: every later wait gives up at once
+  int32_t pad[60];
 };
 constexpr int kHdrPairShift = 22, kHdrRbShift = 43;
 constexpr int64_t kHdrMaxChunks = (1ll << 22) - 1, kHdrMaxPairs = (1ll << 21) - 1, kHdrMaxRowBlocks = (1ll << 21) - 1;

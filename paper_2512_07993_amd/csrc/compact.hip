@@ -37,6 +37,10 @@ __global__ void __launch_bounds__(256) k_compact(CompactArgs a) {
   const int32_t *srcs = PAGED ? a.src_rows + lhb * a.src_stride : kept;  // what the row loads are addressed with
   const int32_t *rmap = PAGED ? a.row_map + a.seq_off[b] : nullptr;
   const int nl = a.new_len[lhb];
+  // A head that kept everything because its inputs could not be trusted reports its full length,
+  // which its row of indices may not even hold: nothing to move, and nothing to read past the row.
+  if (nl > a.kept_stride || (PAGED && nl > a.src_stride)) return;
+  const int room = a.seq_off[b + 1] - a.seq_off[b];  // contiguous cache: a source index is a row of the sequence
 
   // first row that actually moves
   int first = nl;
@@ -59,7 +63,8 @@ __global__ void __launch_bounds__(256) k_compact(CompactArgs a) {
   constexpr int TR = U * RPI;  // rows per tile
   static_assert(TR <= 64, "one lane per row index of a tile");
   auto load_idx = [&](int k0) -> int {  // unconditional (clamped), so that it always counts as one outstanding load
-    return srcs[min(k0 + lane, nl - 1)];
+    const int i = srcs[min(k0 + lane, nl - 1)];
+    return PAGED ? i : max(0, min(i, room - 1));  // never address a row outside the sequence, whatever the indices say
   };
   auto load_dst = [&](int k0) -> int {  // paged: slot rows of the tile's destinations (same rule)
     return PAGED ? rmap[min(k0 + lane, nl - 1)] : 0;
@@ -136,8 +141,9 @@ __global__ void __launch_bounds__(256) k_kept_rows(CompactArgs a) {
   const int32_t *kept = a.kept_idx + lhb * a.kept_stride;
   const int32_t *rmap = a.row_map + a.seq_off[b];
   int32_t *out = a.src_rows + lhb * a.src_stride;
-  const int nl = min(a.new_len[lhb], a.src_stride);
-  for (int k = lane; k < nl; k += 64) out[k] = rmap[kept[k]];
+  const int nl = min(min(a.new_len[lhb], a.src_stride), a.kept_stride);
+  const int room = a.seq_off[b + 1] - a.seq_off[b];
+  for (int k = lane; k < nl; k += 64) out[k] = rmap[max(0, min(kept[k], room - 1))];
 }
 
 }  // namespace

@@ -13,6 +13,7 @@ __global__ void k_plan_reset(PlanHeader *hdr, int32_t *flags, int n_flags, uint3
   if (i == 0) {
     hdr->ranges = 0;
     hdr->n_unfused = 0;
+    hdr->abort = 0;
   }
   for (int j = i; j < n_flags; j += gridDim.x * blockDim.x) flags[j] = 0;
   for (int j = i; j < n_norm; j += gridDim.x * blockDim.x) row_norm_bits[j] = kRowNormUnset;

@@ -89,6 +89,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
   __shared__ float wstat[4][R][2];
   __shared__ float imp[2][kChunkCap];
   __shared__ int s_flag;
+  __shared__ int s_timeout;  // a wait of the current item ran out: its sentences get NaN means, so that the selection keeps the head whole
   __shared__ float row_norm_l[R];
 
   const int tid = threadIdx.x, lane = tid & 63, c16 = lane & 15, g = lane >> 4;
@@ -253,6 +254,16 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     return true;
   };
 
+  // A wait has run out when it has used up its polls, or when any wait of this launch did before
+  // (looked up every 256 polls): the first time-out is reported and raises the launch's abort word.
+  auto wait_expired = [](const ScanArgs &a, int polls) -> bool {
+    if (polls < a.spin_limit && ((polls & 255) != 255 || __hip_atomic_load(&a.ws.hdr->abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0)) return false;
+    if ((threadIdx.x & 63) == 0) {
+      if (a.dev_status) atomicOr(a.dev_status, SKIPKV_DEV_TIMEOUT);
+      __hip_atomic_store(&a.ws.hdr->abort, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    return true;
+  };
   Pair cur = load_pair(blockIdx.x);
   if (cur.item >= n_items) return;
 #pragma unroll
@@ -561,7 +572,10 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
       }
     }
     q_commit(nxt, nq, par ^ 1);
-    if (tid == 192) s_flag = all_merge || (arrived == cur.np - 1);
+    if (tid == 192) {
+      s_flag = all_merge || (arrived == cur.np - 1);
+      s_timeout = 0;
+    }
     lds_barrier();
     float *rn = a.ws.row_norm + (int64_t)lhb * R;
     if (s_flag) {  // merge the head's partials into the normalisers (every share, or the last one to arrive)
@@ -582,8 +596,8 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
               ok = ok && __float_as_uint(pv[u].x) != kRowNormUnset;
             }
             if (__all(ok)) break;
-            if (polls >= a.spin_limit) {
-              if (lane == 0 && a.dev_status) atomicOr(a.dev_status, SKIPKV_DEV_TIMEOUT);
+            if (wait_expired(a, polls)) {
+              if (lane == 0) s_timeout = 1;
               break;
             }
             __builtin_amdgcn_s_sleep(1);
@@ -618,8 +632,8 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
       for (int polls = 0;; ++polls) {
         const uint32_t u = lane < R ? __hip_atomic_load(&rn_bits[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
         const bool done = __all(u != kRowNormUnset);
-        if (done || polls >= a.spin_limit) {
-          if (!done && lane == 0 && a.dev_status) atomicOr(a.dev_status, SKIPKV_DEV_TIMEOUT);
+        if (done || wait_expired(a, polls)) {
+          if (!done && lane == 0) s_timeout = 1;
           if (lane < R) row_norm_l[opaque(lane)] = __uint_as_float(u);
           break;
         }
@@ -687,6 +701,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
         const int sent_col0 = (k ? cur.ch[1].soff_idx : cur.ch[0].soff_idx) - b;
         const int64_t o = (int64_t)lh * a.total_sentences + sent_col0 + s_idx;
         const float inv = hi > lo ? 1.f / (float)(hi - lo) : 0.f;
+        if (s_timeout) sum_i = __builtin_nanf("");
         a.ws.sent_imp[o] = sum_i * inv;
         a.ws.sent_red[o] = sum_r * inv;
       }

@@ -92,33 +92,71 @@ __device__ __forceinline__ int group_scan_excl(int v, int gw, int lane, Exchange
   }
 }
 
+// What a head's inputs say about its size, clamped to the room that the CSR arrays describe, and
+// whether they can be trusted.  A head with a problem keeps its whole cache (keep_everything).
+struct HeadShape {
+  int n_tok, n_sent, sp, budget;
+  int problem;  // SKIPKV_DEV_* bits, 0: fine so far
+};
+__device__ __forceinline__ HeadShape head_shape(const SelectArgs &a, int lhb) {
+  const int b = lhb % a.batch;
+  HeadShape h;
+  const int room_tok = a.seq_off[b + 1] - a.seq_off[b];
+  const int n_tok_raw = seq_tokens(a.seq_off, a.len, b);
+  h.sp = a.sent_ptr[b];
+  const int room_sent = a.sent_ptr[b + 1] - h.sp - 1;
+  const int n_sent_raw = seq_sentences(a.sent_ptr, a.cnt, b);
+  h.n_tok = max(0, min(n_tok_raw, room_tok));
+  h.n_sent = max(0, min(n_sent_raw, room_sent));
+  h.budget = a.budget ? a.budget[b] : a.budget_scalar;
+  h.problem = 0;
+  if (h.n_tok != n_tok_raw || h.n_sent != n_sent_raw || (h.n_sent == 0 && h.n_tok != 0)) h.problem |= SKIPKV_DEV_BAD_OFFSETS;
+  if (h.n_sent > SKIPKV_MAX_SENTENCES) h.problem |= SKIPKV_DEV_TOO_MANY_SENT;
+  // the kept indices must fit their row, and the protected window must fit the budget
+  const int protect = min(a.protect, h.n_tok);
+  if (h.budget < 0 || min(h.budget, h.n_tok) > a.kept_stride || (h.n_tok > h.budget && h.budget < protect)) h.problem |= SKIPKV_DEV_BAD_BUDGET;
+  return h;
+}
+
+// A head whose inputs cannot be trusted (offsets, counts, budget, a NaN score) keeps everything:
+// new_len = N, the identity as far as the row of kept indices reaches, every sentence flagged
+// kept, ranges copied.  The compaction leaves a head with new_len > kept_stride alone and moves
+// nothing where the indices are the identity, so the cache of such a head is not touched.
+__device__ __forceinline__ void keep_everything(const SelectArgs &a, int lhb, const HeadShape &h, int gt, int G, int problem) {
+  const int lh = lhb / a.batch, b = lhb % a.batch;
+  int32_t *kept = a.kept_idx + (int64_t)lhb * a.kept_stride;
+  const int64_t col0 = (int64_t)lh * a.total_sentences + (h.sp - b);
+  const int n_sent = min(h.n_sent, SKIPKV_MAX_SENTENCES);
+  for (int t = gt; t < min(h.n_tok, a.kept_stride); t += G) kept[t] = t;
+  if (a.sent_keep)
+    for (int s = gt; s < n_sent; s += G) a.sent_keep[col0 + s] = 1;
+  if (a.new_sent_off) {
+    int32_t *noff = a.new_sent_off + (int64_t)lh * (a.total_sentences + a.batch) + h.sp;
+    const int32_t *off = a.sent_off + h.sp;
+    for (int s = gt; s <= n_sent; s += G) noff[s] = off[s];
+  }
+  if (gt == 0) {
+    a.new_len[lhb] = h.n_tok;
+    if (a.new_sent_cnt) a.new_sent_cnt[lhb] = n_sent;
+    if (problem && a.dev_status) atomicOr(a.dev_status, problem);
+  }
+}
+
 // One head, handled by NW waves; gt = thread index inside the group, gw = wave inside the group.
 // keep_l: 1024 * NW bytes of LDS, 16-byte aligned.
 template <int NW>
-__device__ __forceinline__ void select_head(const SelectArgs &a, int lhb, int gt, int gw, uint8_t *keep_l, Exchange &x) {
+__device__ __forceinline__ void select_head(const SelectArgs &a, int lhb, const HeadShape &hs, int gt, int gw, uint8_t *keep_l, Exchange &x) {
   constexpr int G = 64 * NW;
   const int lane = gt & 63;
   const int lh = lhb / a.batch, b = lhb % a.batch;
-  // explicit lengths and counts are clamped to the room the CSR arrays describe (the plan reports them)
-  const int n_tok = min(seq_tokens(a.seq_off, a.len, b), a.seq_off[b + 1] - a.seq_off[b]);
-  const int sp = a.sent_ptr[b];
-  const int n_sent = min(seq_sentences(a.sent_ptr, a.cnt, b), a.sent_ptr[b + 1] - sp - 1);
+  const int n_tok = hs.n_tok, sp = hs.sp, n_sent = hs.n_sent, budget = hs.budget;
   const int32_t *off = a.sent_off + sp;
   const int64_t col0 = (int64_t)lh * a.total_sentences + (sp - b);
   int32_t *kept = a.kept_idx + (int64_t)lhb * a.kept_stride;
   int32_t *noff = a.new_sent_off ? a.new_sent_off + (int64_t)lh * (a.total_sentences + a.batch) + sp : nullptr;
-  const int budget = a.budget ? a.budget[b] : a.budget_scalar;
 
-  if (n_tok <= budget) {  // the cache already fits: nothing is evicted
-    for (int t = gt; t < n_tok; t += G) kept[t] = t;
-    if (a.sent_keep)
-      for (int s = gt; s < n_sent; s += G) a.sent_keep[col0 + s] = 1;
-    if (noff)
-      for (int s = gt; s <= n_sent; s += G) noff[s] = off[s];
-    if (gt == 0) {
-      a.new_len[lhb] = n_tok;
-      if (a.new_sent_cnt) a.new_sent_cnt[lhb] = n_sent;
-    }
+  if (hs.problem || n_tok <= budget) {  // nothing can be evicted, or the cache already fits
+    keep_everything(a, lhb, hs, gt, G, hs.problem);
     return;
   }
 
@@ -128,20 +166,31 @@ __device__ __forceinline__ void select_head(const SelectArgs &a, int lhb, int gt
   // ---- candidates, sentence s = r * G + gt: order-preserving image of the score, unprotected length
   uint32_t hi[kEPL];
   int len[kEPL];
+  int bad = 0;  // low half: offsets out of order, high half: NaN scores
 #pragma unroll
   for (int r = 0; r < kEPL; ++r) {
     const int s = r * G + gt;
     hi[r] = 0;
     len[r] = 0;  // not a candidate: protected, or past the end
     if (s < n_sent) {
-      const int o0 = off[s];
+      const int o0 = off[s], o1 = off[s + 1];
+      // the ranges must run from 0 to N, strictly ascending (the scores of a head whose ranges the
+      // plan rejected were never written)
+      if (o1 <= o0 || (s == 0 && o0 != 0) || (s == n_sent - 1 && o1 != n_tok)) bad += 1;
       if (o0 < p_start) {
-        uint32_t u = __float_as_uint(a.sent_score[col0 + s]);
+        const float sc = a.sent_score[col0 + s];
+        if (sc != sc) bad += 1 << 16;  // a NaN cannot be ranked (the scan marks scores it could not finish this way)
+        uint32_t u = __float_as_uint(sc);
         if (u == 0x80000000u) u = 0;  // -0.0 ties with 0.0
         hi[r] = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-        len[r] = min(off[s + 1], p_start) - o0;
+        len[r] = max(0, min(o1, p_start) - o0);
       }
     }
+  }
+  bad = group_sum<NW>(bad, gw, x);
+  if (bad) {
+    keep_everything(a, lhb, hs, gt, G, (bad & 0xFFFF) ? SKIPKV_DEV_BAD_OFFSETS : SKIPKV_DEV_BAD_SCORES);  // scores under bad ranges were never written
+    return;
   }
 
   // ---- score part of K0: the largest H such that the candidates with hi >= H do not fit.
@@ -237,11 +286,6 @@ __device__ __forceinline__ void select_head(const SelectArgs &a, int lhb, int gt
   }
 }
 
-__device__ __forceinline__ int head_sentences(const SelectArgs &a, int lhb) {
-  const int b = lhb % a.batch;
-  return min(seq_sentences(a.sent_ptr, a.cnt, b), a.sent_ptr[b + 1] - a.sent_ptr[b] - 1);
-}
-
 __global__ void __launch_bounds__(256, 4) k_select(SelectArgs a) {
   __shared__ __align__(16) uint8_t keep_l[4 * kWaveSent];
   __shared__ int slots[8];
@@ -253,25 +297,17 @@ __global__ void __launch_bounds__(256, 4) k_select(SelectArgs a) {
   {  // every wave takes one head of its own if the head is small enough
     const int lhb = blockIdx.x * 4 + wave;
     if (lhb < n_heads) {
-      const int n_sent = head_sentences(a, lhb);
-      if (n_sent >= 0 && n_sent <= kWaveSent) select_head<1>(a, lhb, lane, 0, keep_l + wave * kWaveSent, x);
+      const HeadShape hs = head_shape(a, lhb);
+      if (hs.n_sent <= kWaveSent) select_head<1>(a, lhb, hs, lane, 0, keep_l + wave * kWaveSent, x);
     }
   }
   for (int w = 0; w < 4; ++w) {  // the larger heads, one after the other, by the whole workgroup
     const int lhb = blockIdx.x * 4 + w;
     if (lhb >= n_heads) break;
-    const int n_sent = head_sentences(a, lhb);
-    if (n_sent >= 0 && n_sent <= kWaveSent) continue;
-    if (n_sent < 0 || n_sent > SKIPKV_MAX_SENTENCES) {
-      if (tid == 0) {
-        if (a.dev_status) atomicOr(a.dev_status, SKIPKV_DEV_TOO_MANY_SENT);
-        a.new_len[lhb] = 0;
-        if (a.new_sent_cnt) a.new_sent_cnt[lhb] = 0;
-      }
-      continue;
-    }
+    const HeadShape hs = head_shape(a, lhb);
+    if (hs.n_sent <= kWaveSent) continue;
     __syncthreads();  // the flag buffer is free: every wave is done with its own head (or the previous large one)
-    select_head<4>(a, lhb, tid, wave, keep_l, x);
+    select_head<4>(a, lhb, hs, tid, wave, keep_l, x);  // more than SKIPKV_MAX_SENTENCES: flagged by head_shape, keeps everything
   }
 }
 
@@ -318,9 +354,11 @@ __global__ void __launch_bounds__(256) k_select_tokens(TokSelectArgs a) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int lhb = blockIdx.x, lh = lhb / a.batch, b = lhb % a.batch;
   const int tok0 = a.seq_off[b];
-  const int n_tok = min(seq_tokens(a.seq_off, a.len, b), a.seq_off[b + 1] - tok0);  // per-head ranges: the head's own length, within its room
+  const int n_tok_raw = seq_tokens(a.seq_off, a.len, b);
+  const int n_tok = max(0, min(n_tok_raw, a.seq_off[b + 1] - tok0));  // per-head ranges: the head's own length, within its room
   const int sp = a.sent_ptr[b];
-  const int n_sent = min(seq_sentences(a.sent_ptr, a.cnt, b), a.sent_ptr[b + 1] - sp - 1);
+  const int n_sent_raw = seq_sentences(a.sent_ptr, a.cnt, b);
+  const int n_sent = max(0, min(n_sent_raw, a.sent_ptr[b + 1] - sp - 1));
   const int32_t *off = a.sent_off + sp;
   const int64_t tcol = (int64_t)lh * a.total_tokens + tok0;
   const int64_t scol = (int64_t)lh * a.total_sentences + (sp - b);
@@ -329,11 +367,33 @@ __global__ void __launch_bounds__(256) k_select_tokens(TokSelectArgs a) {
   const int budget = a.budget ? a.budget[b] : a.budget_scalar;
   int call = 0;
 
-  if (n_tok > kMaxTokens || n_sent < 0 || n_sent > SKIPKV_MAX_SENTENCES) {
+  // A head whose inputs cannot be trusted keeps everything (see keep_everything above): sizes outside
+  // the room or the kernel's limits, a budget that the row of kept indices or the protected window
+  // does not fit, ranges that do not run strictly ascending from 0 to N.
+  int problem = 0;
+  if (n_tok > kMaxTokens) problem |= SKIPKV_DEV_TOO_MANY_TOK;
+  if (n_sent > SKIPKV_MAX_SENTENCES) problem |= SKIPKV_DEV_TOO_MANY_SENT;
+  if (n_tok != n_tok_raw || n_sent != n_sent_raw || (n_sent == 0 && n_tok != 0)) problem |= SKIPKV_DEV_BAD_OFFSETS;
+  if (budget < 0 || min(budget, n_tok) > a.kept_stride || (n_tok > budget && budget < min(a.protect, n_tok))) problem |= SKIPKV_DEV_BAD_BUDGET;
+  if (!problem) {
+    int bad = 0;
+    for (int s = tid; s < n_sent; s += 256) {
+      const int o0 = off[s], o1 = off[s + 1];
+      bad |= o1 <= o0 || (s == 0 && o0 != 0) || (s == n_sent - 1 && o1 != n_tok);
+    }
+    if (block_sum(bad, slots, call, wave, lane)) problem |= SKIPKV_DEV_BAD_OFFSETS;
+  }
+  if (problem) {
+    const int ns = min(n_sent, SKIPKV_MAX_SENTENCES);
+    for (int t = tid; t < min(n_tok, a.kept_stride); t += 256) kept[t] = t;
+    if (a.tok_keep)
+      for (int t = tid; t < n_tok; t += 256) a.tok_keep[tcol + t] = 1;
+    if (noff)
+      for (int s = tid; s <= ns; s += 256) noff[s] = off[s];
     if (tid == 0) {
-      if (a.dev_status) atomicOr(a.dev_status, n_sent > SKIPKV_MAX_SENTENCES ? SKIPKV_DEV_TOO_MANY_SENT : SKIPKV_DEV_TOO_MANY_TOK);
-      a.new_len[lhb] = 0;
-      if (a.new_sent_cnt) a.new_sent_cnt[lhb] = 0;
+      if (a.dev_status) atomicOr(a.dev_status, problem);
+      a.new_len[lhb] = n_tok;
+      if (a.new_sent_cnt) a.new_sent_cnt[lhb] = ns;
     }
     return;
   }

@@ -47,7 +47,7 @@ def make_cache(cfg: W.Config, st: W.Structure, k, v) -> B.Cache:
 
 
 def run_step(cfg: W.Config, st: W.Structure, k, v, q, *, budget=None, red=None, want_tok_imp=True,
-             fused=True, profile=None) -> GpuStep:
+             fused=True, profile=None, flags=0, spin_limit=0) -> GpuStep:
     """Runs score -> select -> compact on (k, v) IN PLACE through the C ABI."""
     dev = k.device
     cache = make_cache(cfg, st, k, v)
@@ -56,12 +56,13 @@ def run_step(cfg: W.Config, st: W.Structure, k, v, q, *, budget=None, red=None, 
     if budget is None:
         budget = cfg.budget
     if isinstance(budget, int):
-        params = B.Params(cfg.obs_window, cfg.protect_window, budget, dev_status=status, profile=profile)
+        params = B.Params(cfg.obs_window, cfg.protect_window, budget, dev_status=status, profile=profile, flags=flags,
+                          spin_limit=spin_limit)
         max_budget = budget
     else:
         max_budget = int(budget.max().item())
         params = B.Params(cfg.obs_window, cfg.protect_window, budget, max_budget=max_budget, dev_status=status,
-                          profile=profile)
+                          profile=profile, flags=flags, spin_limit=spin_limit)
     ws = torch.empty(B.skipkv_workspace_bytes(cache, params) + 256, dtype=torch.uint8, device=dev)
     assert ws.data_ptr() % 256 == 0
     S, T = st.total_sentences, st.total_tokens

@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported():
     lib = B.lib()
     for n in names:
         assert hasattr(lib, n), n
-    assert B.skipkv_version() == 100
+    assert B.skipkv_version() == 101
     for code in (0, -1, -2, -3, -4, -5, -99):
         assert len(B.skipkv_strerror(code)) > 0
 
@@ -46,7 +46,7 @@ def _cache(**kw):
 
 def _params(**kw):
     d = dict(obs_window=16, protect_window=64, sigma=0.1, tau=0.95, budget=None, budget_scalar=2048, max_budget=2048,
-             dev_status=None, profile=None)
+             dev_status=None, profile=None, flags=0, spin_limit=0)
     d.update(kw)
     return B.CParams(*[d[f[0]] for f in B.CParams._fields_])
 

@@ -130,12 +130,25 @@ def test_exact_duplicates_score_maximal_redundancy():
 
 
 def test_bad_offsets_are_reported_not_executed():
+    """A sequence whose ranges are not strictly ascending (all offsets still inside the sequence) is
+    reported and left whole: new_len = N, identity indices, K and V bit-identical to the input;
+    the other sequence of the batch is processed as usual."""
     cfg = _edge_cfg(batch=2)
     st = _structure([[0, 10, 10, 30], [0, 5, 40]])         # first sequence: an empty sentence
     k0, v0, q = _random_kvq(cfg, st, 31)
     k, v = k0.clone(), v0.clone()
-    out = run_step(cfg, st, k, v, q)
+    out = run_step(cfg, st, k, v, q, budget=24)
     assert int(out.dev_status.item()) & B.DEV_BAD_OFFSETS
+    assert not int(out.dev_status.item()) & ~B.DEV_BAD_OFFSETS
+    n0 = 30
+    assert (out.new_len[:, :, 0] == n0).all()
+    assert torch.equal(k[:, :, :n0], k0[:, :, :n0]) and torch.equal(v[:, :, :n0], v0[:, :, :n0])
+    kept = out.kept_idx[:, :, 0, :24].cpu().numpy()
+    assert (kept == np.arange(24)[None, None, :]).all()
+    stats = {}
+    for l, h in ((0, 0), (cfg.n_layers - 1, cfg.n_kv_heads - 1)):
+        ora = oracle_head(cfg, st, k0, v0, q, l, h, 1, budget=24)
+        compare_head(cfg, st, out, k, v, k0, v0, ora, l, h, 1, stats, budget=24)
 
 
 def test_many_tiny_sequences_more_items_than_workgroups():
@@ -222,6 +235,54 @@ def test_select_ties_signs_and_all_group_sizes():
                 assert cnt == len(ora["new_off"]) - 1, tag
                 np.testing.assert_array_equal(new_off[0, h, st.sent_ptr[b]:st.sent_ptr[b] + cnt + 1].cpu().numpy(),
                                               ora["new_off"], err_msg=tag)
+
+
+def test_untrusted_heads_keep_everything_and_are_not_compacted():
+    """skipkv_select + skipkv_compact on inputs the library must refuse per head: a device budget
+    larger than the row of kept indices can hold, one below the protected window, a negative one, and a
+    NaN score.  Those heads report their full length, identity indices and the matching status bit,
+    and their K/V stay bit-identical; the healthy heads of the batch, whose rows of kept indices lie between
+    those of the refused ones, are selected and compacted as usual."""
+    rng = np.random.default_rng(3)
+    offsets = []
+    for _ in range(5):
+        lens = rng.integers(2, 9, size=40)
+        offsets.append(np.concatenate([[0], np.cumsum(lens)]).tolist())
+    st = _structure(offsets)
+    cfg = W.Config("untrusted", 9, 5, 1, 2, 8, "bf16", 0, 0, 0, 8, 16, 4.0, 0.0)
+    T, S, Bn, L, H = st.total_tokens, st.total_sentences, 5, 1, 2
+    g = torch.Generator(device="cuda").manual_seed(5)
+    k0 = torch.randn((L, H, T, 128), device="cuda", generator=g).to(torch.bfloat16)
+    v0 = torch.randn((L, H, T, 128), device="cuda", generator=g).to(torch.bfloat16)
+    k, v = k0.clone(), v0.clone()
+    cache = make_cache(cfg, st, k, v)
+    score = rng.standard_normal((L, H, S)).astype(np.float32)
+    score[0, :, st.sent_base(4) + 7] = np.nan                      # sequence 4: a score that cannot be ranked
+    max_budget = 64
+    budgets = np.array([64, 100000, 8, -5, 64], dtype=np.int32)   # 1: beyond max_budget, 2: below the window, 3: negative
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    params = B.Params(cfg.obs_window, cfg.protect_window, torch.from_numpy(budgets).cuda(), max_budget=max_budget,
+                      dev_status=status)
+    kept_stride = max_budget
+    kept_idx = torch.full((L, H, Bn, kept_stride), -99, dtype=torch.int32, device="cuda")
+    new_len = torch.full((L, H, Bn), -1, dtype=torch.int32, device="cuda")
+    sent_keep = torch.full((L, H, S), 77, dtype=torch.uint8, device="cuda")
+    B.skipkv_select(cache, params, torch.from_numpy(score).cuda(), sent_keep, kept_idx, new_len, None, None, kept_stride)
+    B.skipkv_compact(cache, kept_idx, new_len, kept_stride)
+    torch.cuda.synchronize()
+    assert int(status.item()) == (B.DEV_BAD_BUDGET | B.DEV_BAD_SCORES)
+    for h in range(H):
+        for b in (1, 2, 3, 4):
+            t0, t1 = int(st.seq_off[b]), int(st.seq_off[b + 1])
+            assert int(new_len[0, h, b]) == t1 - t0 > kept_stride
+            assert torch.equal(kept_idx[0, h, b], torch.arange(kept_stride, dtype=torch.int32, device="cuda"))
+            assert torch.equal(k[0, h, t0:t1], k0[0, h, t0:t1]) and torch.equal(v[0, h, t0:t1], v0[0, h, t0:t1])
+        for b in (0,):
+            t0, t1 = int(st.seq_off[b]), int(st.seq_off[b + 1])
+            n = int(new_len[0, h, b])
+            assert 16 <= n <= 64
+            idx = kept_idx[0, h, b, :n].long()
+            assert torch.equal(k[0, h, t0:t0 + n], k0[0, h, t0:t1][idx]) and torch.equal(v[0, h, t0:t0 + n], v0[0, h, t0:t1][idx])
 
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])

@@ -96,12 +96,8 @@ def _check_against_contiguous(cfg, block_size, heads_before_slots, monkeypatch, 
     # the same step on the contiguous cache, through the same form of the key scan: blocks of a power
     # of two >= 16 slots take the single-pass scan, other sizes the two-pass one
     two_pass = block_size < 16 or (block_size & (block_size - 1)) != 0
-    if two_pass:
-        monkeypatch.setenv("SKIPKV_FORCE_TWO_PASS", "1")
     k, v = k0.clone(), v0.clone()
-    ref = run_step(cfg, st, k, v, q)
-    if two_pass:
-        monkeypatch.delenv("SKIPKV_FORCE_TWO_PASS")
+    ref = run_step(cfg, st, k, v, q, flags=B.FLAG_FORCE_TWO_PASS if two_pass else 0)
     for name in ("tok_imp", "sent_keep", "kept_idx", "new_len", "new_sent_off", "new_sent_cnt"):
         a, b = getattr(out, name), getattr(ref, name)
         assert torch.equal(a.view(torch.uint8) if a.dtype != torch.uint8 else a, b.view(torch.uint8) if b.dtype != torch.uint8 else b), name

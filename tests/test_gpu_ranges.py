@@ -27,10 +27,10 @@ def _outputs(cfg, st, kept_stride, want_tok_imp=True):
         new_sent_cnt=torch.full((L, H, Bn), -1, dtype=torch.int32, device=dev))
 
 
-def run_step_ranges(cfg, st, k, v, q, ranges, budget):
+def run_step_ranges(cfg, st, k, v, q, ranges, budget, flags=0):
     cache = make_cache(cfg, st, k, v)
     status = torch.zeros(1, dtype=torch.int32, device="cuda")
-    params = B.Params(cfg.obs_window, cfg.protect_window, budget, dev_status=status)
+    params = B.Params(cfg.obs_window, cfg.protect_window, budget, dev_status=status, flags=flags)
     ws = torch.empty(B.skipkv_ranges_workspace_bytes(cache, params) + 256, dtype=torch.uint8, device="cuda")
     kept_stride = max(1, min(budget, st.total_tokens))
     o = _outputs(cfg, st, kept_stride)
@@ -94,15 +94,15 @@ def _assert_same_step(cfg, st, a, ka, va, b, kb, vb):
                 assert torch.equal(ka[l, h, t0:t0 + n], kb[l, h, t0:t0 + n]) and torch.equal(va[l, h, t0:t0 + n], vb[l, h, t0:t0 + n])
 
 
-def test_per_head_step_through_the_two_pass_scan(monkeypatch):
-    monkeypatch.setenv("SKIPKV_FORCE_TWO_PASS", "1")
+def test_per_head_step_through_the_two_pass_scan():
+    two = B.FLAG_FORCE_TWO_PASS
     cfg = W.CONFIGS[4].scaled(n_layers=1, batch=3, len_lo=500, len_hi=1300, budget=384)
     st = W.make_structure(cfg)
     k0, v0, q = W.fill_cache(cfg, st, device="cuda")
     ka, va = k0.clone(), v0.clone()
-    a = run_step(cfg, st, ka, va, q)
+    a = run_step(cfg, st, ka, va, q, flags=two)
     kb, vb = k0.clone(), v0.clone()
-    b = run_step_ranges(cfg, st, kb, vb, q, shared_as_ranges(cfg, st), cfg.budget)
+    b = run_step_ranges(cfg, st, kb, vb, q, shared_as_ranges(cfg, st), cfg.budget, flags=two)
     assert int(a.dev_status.item()) == 0 and int(b.dev_status.item()) == 0
     _assert_same_step(cfg, st, a, ka, va, b, kb, vb)
 

@@ -69,12 +69,8 @@ def test_paged_per_head_step_equals_the_contiguous_one(config_id, kw, block_size
     out = _run_ranges_paged(cfg, st, kp, vp, table, q2, _ranges_of(s1), budget2)
     assert int(out.dev_status.item()) == 0
     two_pass = block_size < 16 or (block_size & (block_size - 1)) != 0
-    if two_pass:
-        monkeypatch.setenv("SKIPKV_FORCE_TWO_PASS", "1")
     k, v = k1.clone(), v1.clone()
-    ref = run_step_ranges(cfg, st, k, v, q2, _ranges_of(s1), budget2)
-    if two_pass:
-        monkeypatch.delenv("SKIPKV_FORCE_TWO_PASS")
+    ref = run_step_ranges(cfg, st, k, v, q2, _ranges_of(s1), budget2, flags=B.FLAG_FORCE_TWO_PASS if two_pass else 0)
     assert int(ref.dev_status.item()) == 0
     # per-token and per-sentence arrays are defined inside every head's own ranges only
     len1, cnt1 = s1.new_len.cpu().numpy(), s1.new_sent_cnt.cpu().numpy()

@@ -122,4 +122,7 @@ def test_too_long_sequence_is_reported():
     imp = torch.zeros((1, 1, n), dtype=torch.float32, device="cuda")
     lam = torch.zeros((1, 1, 1), dtype=torch.float32, device="cuda")
     out = _select_tokens(cfg, st, cache, imp, None, lam, [64])
-    assert int(out["status"].item()) & B.DEV_TOO_MANY_TOK and int(out["new_len"][0, 0, 0]) == 0
+    # reported, and the head keeps everything: its full length, the identity as far as the row reaches
+    assert int(out["status"].item()) & B.DEV_TOO_MANY_TOK and int(out["new_len"][0, 0, 0]) == n
+    ks = out["kept_stride"]
+    assert torch.equal(out["kept_idx"][0, 0, 0, :ks].cpu(), torch.arange(ks, dtype=torch.int32))
