@@ -61,9 +61,13 @@ Workspace carve(const skipkv_cache *c, const RowLayout &rl, void *base) {
   Workspace w{};
   const size_t B = (size_t)c->batch, LH = (size_t)c->n_layers * c->n_kv_heads;
   const size_t T = (size_t)c->total_tokens, S = (size_t)c->total_sentences;
-  w.nc_max = (int32_t)(2 * ((T + kChunkCap - 1) / kChunkCap) + B + (S + kChunkMaxSent - 1) / kChunkMaxSent);
+  // two consecutive chunks of a sequence together exceed kChunkCap tokens or kChunkMaxSent sentences
+  w.nc_max = (int32_t)(2 * ((T + kChunkCap - 1) / kChunkCap + (S + kChunkMaxSent - 1) / kChunkMaxSent) + B);
   w.nrb_max = (int32_t)((S + kRowBlock - 1) / kRowBlock + B);
-  w.fits = w.nc_max <= kHdrMaxChunks && w.nc_max / 2 + (int64_t)B <= kHdrMaxPairs && w.nrb_max <= kHdrMaxRowBlocks;
+  // two consecutive spans of a sequence together exceed kSpanCap tokens or kSpanMaxSent sentences
+  const size_t spans_max = 2 * ((T + kSpanCap - 1) / kSpanCap + (S + kSpanMaxSent - 1) / kSpanMaxSent) + B;
+  w.ni_max = (int32_t)std::min<size_t>(spans_max / kItemSpans + B + 1, (size_t)0x7FFFFFFF);
+  w.fits = w.nc_max <= kHdrMaxChunks && spans_max / kItemSpans + B + 1 <= (size_t)kHdrMaxItems && w.nrb_max <= kHdrMaxRowBlocks;
   w.rows = rl.rows;
   size_t off = 0;
   char *p = static_cast<char *>(base);
@@ -78,12 +82,11 @@ Workspace carve(const skipkv_cache *c, const RowLayout &rl, void *base) {
   w.rb_base = static_cast<int32_t *>(take(B * 4));
   w.rb_cnt = static_cast<int32_t *>(take(B * 4));
   w.seq_fused = static_cast<int32_t *>(take(B * 4));
-  w.pair_cnt = static_cast<int32_t *>(take(B * 4));
-  w.pair_rec = static_cast<int32_t *>(take((size_t)w.nc_max * kPairRecInts * 4));
-  w.arrive = static_cast<int32_t *>(take(LH * B * 4));
+  w.item_rec = static_cast<int32_t *>(take((size_t)w.ni_max * kItemRecInts * 4));
   w.chunks = static_cast<Chunk *>(take((size_t)w.nc_max * sizeof(Chunk)));
   w.rowblocks = static_cast<RowBlock *>(take((size_t)w.nrb_max * sizeof(RowBlock)));
   w.stat_part = static_cast<float2 *>(take(LH * w.nc_max * rl.rows * sizeof(float2)));
+  w.item_stat = static_cast<float2 *>(take(LH * w.ni_max * rl.rows * sizeof(float2)));
   w.row_norm = static_cast<float *>(take(LH * B * rl.rows * sizeof(float)));
   w.vhat_hi = static_cast<uint16_t *>(take(LH * S * kD * 2));
   w.vhat_lo = static_cast<uint16_t *>(take(LH * S * kD * 2));

@@ -11,8 +11,15 @@ namespace skipkv {
 constexpr int kD = SKIPKV_HEAD_DIM;  // head dimension
 constexpr int kChunkCap = 256;       // a chunk of scan work = a maximal run of whole sentences of at most this many tokens
 constexpr int kChunkMaxSent = 32;    // ... and at most this many sentences (a single longer sentence is a chunk of its own)
-constexpr int kFuseMaxChunks = 512;  // sequences with more chunks than this take the two-pass scan (see scan_fused.hip)
-constexpr int kAllMergeMax = 128;    // heads with at most this many scan items: every workgroup merges the head's records itself (see scan_fused.hip)
+// Units of the single-pass scan (scan_fused.hip): a span is a maximal run of whole sentences of at most
+// kSpanCap tokens and kSpanMaxSent sentences, the share of ONE wave; an item is up to kItemSpans
+// consecutive spans of one sequence, the share of one workgroup.  A sequence with a sentence longer than
+// kSpanCap tokens, or with more than kFuseMaxItems items, takes the two-pass scan.
+constexpr int kSpanCap = 128;
+constexpr int kSpanMaxSent = 16;
+constexpr int kItemSpans = 4;
+constexpr int kItemMaxSent = kItemSpans * kSpanMaxSent;
+constexpr int kFuseMaxItems = 256;
 constexpr uint32_t kRowNormUnset = 0xFFFFFFFFu;  // bit pattern no computed normaliser has (a NaN with full payload)
 constexpr float kRefInit = -3.0e38f;  // "no key seen yet" softmax reference, finite so that -inf - ref stays -inf
 constexpr int kRowBlock = 128;       // sentences per row block of the redundancy kernel
@@ -33,40 +40,39 @@ struct RowBlock {
   int32_t b, r0;
 };
 
-// Device scalars at the head of the workspace.
-// Record of one work item of the single-pass scan (a pair of consecutive chunks of one sequence),
-// written by the plan so that a workgroup learns everything about an item from one 64-byte read.
-constexpr int kPairRecInts = 16;
-enum PairRec : int {
-  kPrB = 0,        // sequence
-  kPrNch,          // chunks in the pair: 1 or 2; 0 = the sequence takes the two-pass scan
-  kPrC0,           // index of the first chunk (its statistics record is filed there)
-  kPrTok0,         // first token of the sequence in the packed cache
-  kPrNTok,         // tokens of the sequence
-  kPrTBegin,       // first token of the pair, relative to the sequence
-  kPrLen0,         // tokens of the first chunk (the second one follows it directly)
-  kPrNs0,          // sentences of the first chunk
-  kPrSoffIdx,      // index of the first chunk's first sentence offset in sent_off
-  kPrLen1,
-  kPrNs1,
-  kPrNPairs,       // pairs of the sequence
-  kPrCFirst,       // first chunk of the sequence
+// Record of one work item of the single-pass scan, written by the plan so that a workgroup learns
+// everything about an item from one 64-byte read.
+constexpr int kItemRecInts = 16;
+enum ItemRec : int {
+  kIrB = 0,        // sequence
+  kIrNsp,          // spans in the item: 1..kItemSpans; 0 = the sequence takes the two-pass scan
+  kIrRec,          // index of the item (its statistics record is filed there)
+  kIrTok0,         // first token of the sequence in the packed cache
+  kIrNTok,         // tokens of the sequence
+  kIrNItems,       // items of the sequence
+  kIrFirst,        // index of the sequence's first item
+  kIrSoffIdx,      // index of the item's first sentence offset in sent_off
+  kIrT0,           // kIrT0 + w: first token of span w, relative to the sequence; kIrT0 + nsp: end of the item
+  kIrNs = kIrT0 + kItemSpans + 1,  // sentences of the four spans, one byte each
 };
+static_assert(kIrNs < kItemRecInts && kSpanMaxSent < 256, "the record holds the spans' bounds and sentence counts");
+
+// Device scalars at the head of the workspace.
 
 struct PlanHeader {
   // The three range counters that every plan block draws from, packed into one word so that a
   // block needs ONE atomic (with thousands of blocks the same-address atomics are what the plan
-  // costs): chunks in bits 0..21, chunk pairs (units of the single-pass scan) in bits 22..42,
-  // row blocks in bits 43..63.
+  // costs): chunks (units of the two-pass scan) in bits 0..21, items (units of the single-pass scan)
+  // in bits 22..42, row blocks in bits 43..63.
   unsigned long long ranges;
   int32_t n_unfused;  // number of sequences that take the two-pass scan
   int32_t abort;      // set by the first cross-workgroup wait of the single-pass scan that runs out: every later wait gives up at once
   int32_t pad[60];
 };
-constexpr int kHdrPairShift = 22, kHdrRbShift = 43;
-constexpr int64_t kHdrMaxChunks = (1ll << 22) - 1, kHdrMaxPairs = (1ll << 21) - 1, kHdrMaxRowBlocks = (1ll << 21) - 1;
-__host__ __device__ inline int32_t hdr_chunks(unsigned long long r) { return (int32_t)(r & ((1ull << kHdrPairShift) - 1)); }
-__host__ __device__ inline int32_t hdr_pairs(unsigned long long r) { return (int32_t)((r >> kHdrPairShift) & ((1ull << (kHdrRbShift - kHdrPairShift)) - 1)); }
+constexpr int kHdrItemShift = 22, kHdrRbShift = 43;
+constexpr int64_t kHdrMaxChunks = (1ll << 22) - 1, kHdrMaxItems = (1ll << 21) - 1, kHdrMaxRowBlocks = (1ll << 21) - 1;
+__host__ __device__ inline int32_t hdr_chunks(unsigned long long r) { return (int32_t)(r & ((1ull << kHdrItemShift) - 1)); }
+__host__ __device__ inline int32_t hdr_items(unsigned long long r) { return (int32_t)((r >> kHdrItemShift) & ((1ull << (kHdrRbShift - kHdrItemShift)) - 1)); }
 __host__ __device__ inline int32_t hdr_rowblocks(unsigned long long r) { return (int32_t)(r >> kHdrRbShift); }
 
 // Carved-up view of the caller's workspace.  All sections 256-byte aligned.
@@ -77,18 +83,17 @@ struct Workspace {
   int32_t *rb_base;      // [B] first row block of each sequence
   int32_t *rb_cnt;       // [B]
   int32_t *seq_fused;    // [B] 1: the sequence goes through the single-pass scan
-  int32_t *pair_rec;     // [nc_max][kPairRecInts] one record per pair of consecutive chunks of one sequence (PairRec)
-  int32_t *pair_cnt;     // [B] number of pairs of each sequence
-  int32_t *arrive;       // [LH, B] chunks of the head that have published their row statistics
+  int32_t *item_rec;     // [ni_max][kItemRecInts] one record per item of the single-pass scan (ItemRec)
   Chunk *chunks;         // [nc_max]
   RowBlock *rowblocks;   // [nrb_max]
-  float2 *stat_part;     // [LH, nc_max, R]  per-chunk (max, sum) of every query row, log2 domain; the plan presets .x of the used records to kRowNormUnset
-  float *row_norm;       // [LH, B, R]       log2 of the softmax normaliser of every query row; preset to kRowNormUnset by the plan
+  float2 *stat_part;     // [LH, nc_max, R]  two-pass scan: per-chunk (max, sum) of every query row, log2 domain
+  float2 *item_stat;     // [LH, ni_max, R]  single-pass scan: per-item (reference, sum) of every query row; the plan presets .x of the used records to kRowNormUnset
+  float *row_norm;       // [LH, B, R]       two-pass scan: log2 of the softmax normaliser of every query row
   uint16_t *vhat_hi;     // [LH, S_total, 128] bf16 high part of the unit sentence embedding
   uint16_t *vhat_lo;     // [LH, S_total, 128] bf16 low part (residual)
   float *sent_imp;       // [LH, S_total]    mean token importance over the candidate span
   float *sent_red;       // [LH, S_total]    mean token redundancy over the candidate span
-  int32_t nc_max, nrb_max, rows;  // rows = R, padded query rows per head
+  int32_t nc_max, ni_max, nrb_max, rows;  // rows = R, padded query rows per head
   bool fits;                      // the counts fit the packed range counters of the plan header
   size_t bytes;
 };
