@@ -462,8 +462,11 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
       float tot[SLP];
       bool doubt = false;
 #pragma unroll
+      for (int q = 0; q < SLP; ++q) tot[q] = lsum[q];
+#pragma unroll
+      for (int q = 0; q < SLP; ++q) tot[q] = row16_sum_fast(tot[q]);
+#pragma unroll
       for (int q = 0; q < SLP; ++q) {
-        tot[q] = row16_sum_fast(lsum[q]);
         const bool used = q < SL && (q % NP) < n && (g + 4 * (q / NP)) < a.alpha;  // padding rows hold zero queries: whatever they sum to is never used
         doubt = doubt || (used && !(tot[q] > 1e-30f && tot[q] < 3e38f));  // also catches NaN and infinity
       }
@@ -517,29 +520,36 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     // ---- the head's normalisers, first half: every wave loads a quarter of the records of the head's items
     // (wave w: items w, w + 4, ...; lane = query row), kMergeDepth coherent loads in flight per lane, and
     // lets them travel while it commits the next item's queries and writes its embeddings.
+    // (The queries are committed first: they arrived long ago, and a wait for them placed behind the
+    // record loads would wait for those as well.  Always kMergeDepth loads, surplus ones on the head's last
+    // record, so that the number of loads in flight is known where later code waits for older ones.)
+    q_commit(nxt, nq, par ^ 1);
     const int np = cur.np;
-    const float2 *recs = a.ws.item_stat + ((int64_t)lh * a.ws.ni_max + cur.first) * R + opaque(lane);
+    const float2 *recs = a.ws.item_stat + ((int64_t)lh * a.ws.ni_max + cur.first) * R + min(opaque(lane), R - 1);
     float2 pv[kMergeDepth];
     auto load_records = [&](int pp) {
 #pragma unroll
-      for (int u = 0; u < kMergeDepth; ++u) {
-        pv[u] = make_float2(kRefInit, 0.f);
-        if (lane < R && pp + 4 * u < np) pv[u] = coherent_load2(recs + (int64_t)(pp + 4 * u) * R);
-      }
+      for (int u = 0; u < kMergeDepth; ++u) pv[u] = coherent_load2(recs + (int64_t)min(pp + 4 * u, np - 1) * R);
     };
     load_records(wave);
-    q_commit(nxt, nq, par ^ 1);
 
     // ---- sentence embeddings of the span: unit vectors as bf16 hi + lo, four sentences at a time
     if (!a.no_pool && ns > 0) {
-      const int64_t col0 = (int64_t)lh * a.total_sentences + (cur.soff_idx - b) + cur.sb;
+      // (addresses are formed here, from an opaque copy: formed early they are spilled, and a reload from
+      // scratch waits for every load in flight, the record loads above included)
+      const int64_t col0 = (int64_t)lh * a.total_sentences + opaque(cur.soff_idx - b + cur.sb);
+      const int g4 = 4 * opaque(g);
+      float ssq[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) ssq[r] = fmaf(pool[j][r], pool[j][r], ssq[r]);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) ssq[r] = row16_sum_fast(ssq[r]);  // the 16 lanes of the group hold a sentence's 128 dimensions
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        float ss = 0.f;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) ss = fmaf(pool[j][r], pool[j][r], ss);
-        ss = row16_sum_fast(ss);  // the 16 lanes of the group hold the sentence's 128 dimensions
-        const int slot = 4 * g + r, sl = cur.sb + min(slot, ns - 1);
+        const float ss = ssq[r];
+        const int slot = g4 + r, sl = cur.sb + min(slot, ns - 1);
         const int len = soff[sl + 1] - soff[sl];
         // mean / (|mean| + eps) = sum / (|sum| + eps * len): no division by the length.  1-ulp
         // reciprocal and square root: a common scale error of ~1e-7 on the unit vector
@@ -569,7 +579,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
         for (int polls = 0;; ++polls) {
           bool ok = true;
 #pragma unroll
-          for (int u = 0; u < kMergeDepth; ++u) ok = ok && __float_as_uint(pv[u].x) != kRowNormUnset;
+          for (int u = 0; u < kMergeDepth; ++u) ok = ok && __float_as_uint(pv[u].x) != kRowNormUnset;  // surplus loads hold a real record too
           if (__all(ok)) break;
           if (wait_expired(polls)) {
             if (lane == 0) s_timeout[par] = 1;
@@ -580,9 +590,11 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
         }
 #pragma unroll
         for (int u = 0; u < kMergeDepth; ++u) {
-          const float nm = fmaxf(m, pv[u].x);
-          s = s * __builtin_amdgcn_exp2f(m - nm) + pv[u].y * __builtin_amdgcn_exp2f(pv[u].x - nm);
-          m = nm;
+          if (pp + 4 * u < np) {  // uniform
+            const float nm = fmaxf(m, pv[u].x);
+            s = s * __builtin_amdgcn_exp2f(m - nm) + pv[u].y * __builtin_amdgcn_exp2f(pv[u].x - nm);
+            m = nm;
+          }
         }
       }
       if (lane < R) {
