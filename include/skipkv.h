@@ -141,8 +141,10 @@ int skipkv_workspace_bytes(const skipkv_cache *cache, const skipkv_params *param
  * sent_score, sent_lambda   device out [n_layers, n_kv_heads, total_sentences] fp32.
  * tok_importance  device out [n_layers, n_kv_heads, total_tokens] fp32, or NULL.
  * The key scan reads K once where it can (query rows n * obs_window <= 64 after padding, no
- * sentence longer than 256 tokens, at most 131072 tokens per sequence) and twice otherwise.
- * Its single-pass form waits across workgroups; the wait is bounded (params->spin_limit): on
+ * sentence longer than 128 tokens, at most 256 work items of up to 512 tokens per sequence, i.e.
+ * about 120000 tokens) and twice otherwise.  Its single-pass form is a persistent grid that must
+ * have the GPU's compute units to itself (work of other streams running at the same time can
+ * only be waited out).  It waits across workgroups; the wait is bounded (params->spin_limit): on
  * expiry SKIPKV_DEV_TIMEOUT is OR-ed into dev_status, every later wait of the call gives up at
  * once, the scores of the sentences concerned are NaN (which makes the selection keep those
  * heads whole) and the call still completes.  SKIPKV_FLAG_FORCE_TWO_PASS selects the two-pass
@@ -231,7 +233,7 @@ int skipkv_select_tokens(const skipkv_cache *cache, const skipkv_params *params,
                          int32_t *new_sent_cnt, int32_t kept_stride, void *stream);
 
 /*
- * Per-head sentence ranges across steps (Sec. 4.1 "Sentence-level eviction": the ranges M^(cs) and
+ * Per-head sentence ranges across steps (Sec. 4.1 "KV Cache Sentence Range Monitoring Logic": the ranges M^(cs) and
  * cache lengths l_t^(cs) of Eq. 9-11 and Alg. 1).  After a step every (layer, KV head, sequence)
  * has evicted sentences of its own, so lengths and ranges are per head from then on:
  *   len       device [n_layers, n_kv_heads, batch]   cache length N of every head's sequence
@@ -466,7 +468,7 @@ int skipkv_token_redundancy_paged(const skipkv_cache *cache, const skipkv_paging
 /*
  * skipkv_step_ranges on a paged cache: the step of every decode-time compression after the
  * first, when the heads of a sequence have their own lengths and sentence ranges (Sec. 4.1
- * "Multi-step Sentence Range Monitoring", Eq. 9-11) and the cache is paged (Appendix,
+ * "KV Cache Sentence Range Monitoring Logic", Eq. 9-11) and the cache is paged (Appendix,
  * "System-Level Evaluation on vLLM").  ranges, the outputs and their layouts are those of
  * skipkv_step_ranges; paging is that of skipkv_step_paged, with the block table shared by the
  * layers and heads of a sequence and sized for the sequence's extent in cache->seq_off (a head

@@ -1,4 +1,4 @@
-// Per-head sentence ranges across compression steps (Sec. 4.1 "Sentence-level eviction", Eq. 9-11).
+// Per-head sentence ranges across compression steps (Sec. 4.1 "KV Cache Sentence Range Monitoring Logic", Eq. 9-11).
 // After the first step every (layer, KV head, sequence) has evicted its own sentences, so cache
 // lengths and sentence ranges are per head.  Eq. 11 (remapping the surviving ranges onto the
 // compacted cache) is part of the selection kernel; here are the append rule of Eq. 10 and the

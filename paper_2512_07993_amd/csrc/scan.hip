@@ -192,32 +192,29 @@ __global__ void __launch_bounds__(256, ((DT == SKIPKV_BF16 && NP * AL <= 40) ? 2
 #pragma unroll
         for (int q = 0; q < SLP; ++q) lsum[q] += __builtin_amdgcn_exp2f(acc[s][q >> 2][q & 3] - ref[q]);
 
-      // ---- sentence key sums: the wave walks its tokens in order, lane = 2 head-dim columns
+      // ---- sentence key sums: wave w takes sentences w, w + 4, ... of the chunk, lane = 2 head-dim
+      // columns.  A sentence's rows are added in token order by one wave only (also across the tiles
+      // of the chunk), so the sums are the same bits on every run.
       {
-        int t = wt0;
-        const int t_hi = min(wt0 + WT, t_end);
-        if (t < t_hi) {
-          const bool before = lane < ns && soff[lane + 1] <= t;
-          int si = __popcll(__ballot(before));
-          while (t < t_hi) {
-            const int run_end = min(soff[si + 1], t_hi);
-            float s0 = 0.f, s1 = 0.f;
-            for (; t < run_end; ++t) {
-              const char *rowp = kt + (t - tile_t) * LSTR;
-              if constexpr (DT == SKIPKV_BF16) {
-                const uint32_t w = *reinterpret_cast<const uint32_t *>(rowp + lane * 4);
-                s0 += __uint_as_float(w << 16);
-                s1 += __uint_as_float(w & 0xFFFF0000u);
-              } else {
-                const float2 w = *reinterpret_cast<const float2 *>(rowp + lane * 8);
-                s0 += w.x;
-                s1 += w.y;
-              }
+        const int t_hi = min(tile_t + TT, t_end);
+        for (int si = __popcll(__ballot(lane < ns && soff[lane + 1] <= tile_t)); si < ns && soff[si] < t_hi; ++si) {
+          if ((si & 3) != wave) continue;
+          const int lo = max(soff[si], tile_t), hi = min(soff[si + 1], t_hi);
+          float s0 = 0.f, s1 = 0.f;
+          for (int t = lo; t < hi; ++t) {
+            const char *rowp = kt + (t - tile_t) * LSTR;
+            if constexpr (DT == SKIPKV_BF16) {
+              const uint32_t w = *reinterpret_cast<const uint32_t *>(rowp + lane * 4);
+              s0 += __uint_as_float(w << 16);
+              s1 += __uint_as_float(w & 0xFFFF0000u);
+            } else {
+              const float2 w = *reinterpret_cast<const float2 *>(rowp + lane * 8);
+              s0 += w.x;
+              s1 += w.y;
             }
-            atomicAdd(&sbuf[si * kD + 2 * lane], s0);
-            atomicAdd(&sbuf[si * kD + 2 * lane + 1], s1);
-            ++si;
           }
+          sbuf[si * kD + 2 * lane] += s0;
+          sbuf[si * kD + 2 * lane + 1] += s1;
         }
       }
     } else {
@@ -516,33 +513,22 @@ __global__ void __launch_bounds__(256, 2) k_scan_wide(ScanArgs a) {
     }
 
     if constexpr (!PASSB) {
-      // ---- sentence key sums: wave w takes tokens 16w .. 16w+15 of the tile, lane = 2 head-dim columns.
-      // The 16 rows come into registers with one LDS round trip (rows past the end of the chunk hold
-      // zeros); every run of rows that belongs to one sentence is added with a 0/1 weight per row.
+      // ---- sentence key sums: wave w takes sentences w, w + 4, ... of the chunk, lane = 2 head-dim
+      // columns.  A sentence's rows are added in token order by one wave only (also across the tiles
+      // of the chunk), so the sums are the same bits on every run.
       {
-        const int t_lo = tile_t + 16 * wave, t_hi = min(t_lo + 16, t_end);
-        if (t_lo < t_hi) {
-          uint32_t xw[16];
-#pragma unroll
-          for (int i = 0; i < 16; ++i) xw[i] = *reinterpret_cast<const uint32_t *>(kt + (16 * wave + i) * LSTR + lane * 4);
-          int t = t_lo;
-          int si = __popcll(__ballot(lane < ns && soff[lane + 1] <= t));
-          while (t < t_hi) {
-            const int run_end = min(soff[si + 1], t_hi);
-            if (run_end <= t) break;  // cannot happen with validated offsets; never spin on bad ones
-            const uint32_t rows = ((1u << (run_end - t_lo)) - 1u) & ~((1u << (t - t_lo)) - 1u);  // run_end - t_lo <= 16
-            float s0 = 0.f, s1 = 0.f;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const float m = ((rows >> i) & 1u) ? 1.f : 0.f;
-              s0 = fmaf(__uint_as_float(xw[i] << 16), m, s0);
-              s1 = fmaf(__uint_as_float(xw[i] & 0xFFFF0000u), m, s1);
-            }
-            atomicAdd(&sbuf[si * kD + 2 * lane], s0);
-            atomicAdd(&sbuf[si * kD + 2 * lane + 1], s1);
-            ++si;
-            t = run_end;
+        const int t_hi = min(tile_t + TT, t_end);
+        for (int si = __popcll(__ballot(lane < ns && soff[lane + 1] <= tile_t)); si < ns && soff[si] < t_hi; ++si) {
+          if ((si & 3) != wave) continue;
+          const int lo = max(soff[si], tile_t), hi = min(soff[si + 1], t_hi);
+          float s0 = 0.f, s1 = 0.f;
+          for (int t = lo; t < hi; ++t) {
+            const uint32_t w = *reinterpret_cast<const uint32_t *>(kt + (t - tile_t) * LSTR + lane * 4);
+            s0 += __uint_as_float(w << 16);
+            s1 += __uint_as_float(w & 0xFFFF0000u);
           }
+          sbuf[si * kD + 2 * lane] += s0;
+          sbuf[si * kD + 2 * lane + 1] += s1;
         }
       }
     } else {

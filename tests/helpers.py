@@ -18,6 +18,7 @@ from paper_2512_07993_amd import workloads as W
 
 SCORE_RTOL = 1e-3
 TIE_RTOL = 1e-4
+LAMBDA_TAU_ATOL = 1e-5   # |lambda - tau| below the absolute lambda tolerance: the threshold test may go either way
 
 
 @dataclass
@@ -118,9 +119,18 @@ def compare_head(cfg, st, out: GpuStep, k_after, v_after, k0, v0, ora, l, h, b, 
     score = out.sent_score[l, h, sb:sb + S].cpu().numpy().astype(np.float64)
     cand = ora["candlen"] > 0
     np.testing.assert_array_equal(np.isinf(score) & (score > 0), ~cand, err_msg="candidates " + tag)
-    np.testing.assert_allclose(score[cand], ora["score"][cand], rtol=SCORE_RTOL, atol=1e-12, err_msg="score " + tag)
+    # A lambda within the library's own lambda error of tau may fall on the other side of the threshold
+    # (strict >) than the oracle's: that sentence's score then differs by lambda itself.  Such sentences
+    # are counted, their scores are excused, and a kept-set difference made of them alone is admissible.
+    tau = out.params.tau
+    near_tau = np.zeros(S, dtype=bool)
+    if S:
+        near_tau[:-1] = np.abs(ora["lam"][:-1] - tau) <= LAMBDA_TAU_ATOL
+    chk = cand & ~near_tau
+    stats["near_tau_sentences"] = stats.get("near_tau_sentences", 0) + int((cand & near_tau).sum())
+    np.testing.assert_allclose(score[chk], ora["score"][chk], rtol=SCORE_RTOL, atol=1e-12, err_msg="score " + tag)
     stats["score_rel_err"] = max(stats.get("score_rel_err", 0.0), float(
-        np.max(np.abs(score[cand] - ora["score"][cand]) / np.maximum(np.abs(ora["score"][cand]), 1e-300), initial=0.0)))
+        np.max(np.abs(score[chk] - ora["score"][chk]) / np.maximum(np.abs(ora["score"][chk]), 1e-300), initial=0.0)))
 
     keep = out.sent_keep[l, h, sb:sb + S].cpu().numpy().astype(bool)
     new_len = int(out.new_len[l, h, b].item())
@@ -132,7 +142,13 @@ def compare_head(cfg, st, out: GpuStep, k_after, v_after, k0, v0, ora, l, h, b, 
         kept_c = np.nonzero(cand & ora["keep"])[0]
         cut = ora["score"][kept_c].min() if kept_c.size else ora["score"][cand].max()
         gap = np.abs(ora["score"][diff] - cut) / np.maximum(np.abs(cut), np.abs(ora["score"][diff]))
-        assert np.all(gap <= TIE_RTOL), "kept set differs away from a tie: %s sentences %s gaps %s" % (tag, diff, gap)
+        # a sentence whose penalty flipped at the threshold (see above) changes which sentences fit: then the
+        # GPU's selection is only required to be the valid selection of its own scores (checked below)
+        with np.errstate(invalid="ignore"):  # non-candidates carry +inf on both sides
+            flipped = bool((cand & near_tau & (np.abs(score - ora["score"]) > SCORE_RTOL * np.abs(ora["score"]))).any())
+        assert flipped or np.all(gap <= TIE_RTOL), "kept set differs away from a tie: %s sentences %s gaps %s" % (tag, diff, gap)
+        if flipped:
+            stats["near_tau_heads"] = stats.get("near_tau_heads", 0) + 1
         stats["near_tie_heads"] = stats.get("near_tie_heads", 0) + 1
         # the GPU's own selection must still be a valid one
         sel = oracle.select_sentences(score, ora["candlen"], off, cfg.budget if budget is None else budget,
@@ -159,3 +175,62 @@ def sample_heads(cfg, st, n, seed=0):
         return all_heads
     idx = rng.choice(len(all_heads), size=n, replace=False)
     return [all_heads[i] for i in sorted(idx)]
+
+
+def check_all_heads_on_gpu(cfg, st, out: GpuStep, k_after, v_after, k0, v0, budget=None):
+    """Checks that need no oracle, for EVERY head of the step, with torch on the GPU: lengths within the
+    budget, kept indices strictly ascending and inside the sequence, the protected window kept, whole
+    sentences only (a candidate's unprotected tokens are all kept or all dropped, as sent_keep says), and
+    the compacted K and V equal to a gather of the pristine cache by the library's own kept indices, bit
+    for bit (the definition of the compaction, Alg. 1 eviction line).  Returns the number of heads."""
+    dev = k_after.device
+    bud = cfg.budget if budget is None else budget
+    L, H, Bn = cfg.n_layers, cfg.n_kv_heads, cfg.batch
+    w = cfg.protect_window
+    new_len = out.new_len.to(torch.int64)
+    for b in range(Bn):
+        t0, t1 = int(st.seq_off[b]), int(st.seq_off[b + 1])
+        n_tok = t1 - t0
+        nl = new_len[:, :, b]                                         # [L, H]
+        if n_tok <= bud:
+            assert bool((nl == n_tok).all()), ("fits the budget: everything kept", b)
+        else:
+            assert bool(((nl <= bud) & (nl >= min(w, n_tok))).all()), ("length within the budget", b)
+        n_max = int(nl.max().item())
+        if n_max == 0:
+            continue
+        idx = out.kept_idx[:, :, b, :n_max].to(torch.int64)           # [L, H, n_max]
+        pos = torch.arange(n_max, device=dev)[None, None, :]
+        valid = pos < nl[:, :, None]
+        assert bool(((idx >= 0) & (idx < n_tok))[valid].all()), ("indices inside the sequence", b)
+        asc = (idx[:, :, 1:] > idx[:, :, :-1]) | ~valid[:, :, 1:]
+        assert bool(asc.all()), ("indices strictly ascending", b)
+        # the protected window: the last min(w, N) kept indices are the last min(w, N) tokens
+        pw = min(w, n_tok)
+        tail_pos = nl[:, :, None] - pw + torch.arange(pw, device=dev)[None, None, :]
+        tail = torch.gather(idx, 2, tail_pos.clamp(min=0))
+        assert bool((tail == (n_tok - pw + torch.arange(pw, device=dev))[None, None, :]).all()), ("protected window kept", b)
+        # whole sentences: kept-token mask, then kept count per candidate span against sent_keep
+        mask = torch.zeros((L, H, n_tok + 1), dtype=torch.int32, device=dev)
+        mask.scatter_(2, torch.where(valid, idx, torch.full_like(idx, n_tok)), 1)
+        csum = torch.cat([torch.zeros((L, H, 1), dtype=torch.int32, device=dev), mask[:, :, :n_tok].cumsum(2, dtype=torch.int32)], 2)
+        off = torch.from_numpy(st.offsets(b).astype(np.int64)).to(dev)
+        p = n_tok - pw
+        lo, hi = off[:-1], torch.minimum(off[1:], torch.tensor(p, device=dev))
+        cand = lo < p
+        cnt = csum[:, :, hi.clamp(min=0)] - csum[:, :, lo]            # [L, H, S]
+        span = (hi - lo)[None, None, :]
+        sb, S = st.sent_base(b), int(st.n_sent[b])
+        keep = out.sent_keep[:, :, sb:sb + S].to(torch.int64)
+        ok = torch.where(cand[None, None, :], (cnt == span * keep), keep == 1)
+        assert bool(ok.all()), ("whole sentences, as flagged", b)
+        # the compaction: a gather of the pristine rows by the kept indices
+        gidx = torch.where(valid, idx, torch.zeros_like(idx))[:, :, :, None].expand(L, H, n_max, cfg.head_dim)
+        for name, after, before in (("K", k_after, k0), ("V", v_after, v0)):
+            ref = torch.gather(before[:, :, t0:t1], 2, gidx)
+            got = after[:, :, t0:t0 + n_max]
+            same = (ref.view(torch.int16 if ref.dtype == torch.bfloat16 else torch.int32) ==
+                    got.view(torch.int16 if got.dtype == torch.bfloat16 else torch.int32)).all(dim=3)
+            assert bool((same | ~valid).all()), (name + " rows are the pristine rows at the kept indices", b)
+            del ref, same
+    return L * H * Bn

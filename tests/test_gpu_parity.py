@@ -7,12 +7,12 @@ import torch
 
 from paper_2512_07993_amd import workloads as W
 
-from helpers import compare_head, oracle_head, run_step, sample_heads
+from helpers import check_all_heads_on_gpu, compare_head, oracle_head, run_step, sample_heads
 
 pytestmark = pytest.mark.gpu
 
 
-def _run_and_compare(cfg, n_heads, fused=True, seed=0, flags=0):
+def _run_and_compare(cfg, n_heads, fused=True, seed=0, flags=0, all_heads=False):
     st = W.make_structure(cfg)
     k0, v0, q = W.fill_cache(cfg, st, device="cuda")
     k, v = k0.clone(), v0.clone()
@@ -23,6 +23,8 @@ def _run_and_compare(cfg, n_heads, fused=True, seed=0, flags=0):
     for (l, h, b) in sample_heads(cfg, st, n_heads, seed):
         ora = oracle_head(cfg, st, k0, v0, q, l, h, b)
         compare_head(cfg, st, out, k, v, k0, v0, ora, l, h, b, stats)
+    if all_heads:  # definition-level checks of every head of the step, on the GPU
+        stats["all_heads_checked"] = check_all_heads_on_gpu(cfg, st, out, k, v, k0, v0)
     print(cfg.name, stats, flush=True)
     assert stats.get("near_tie_heads", 0) <= max(1, stats["heads"] // 20)
     return stats
@@ -36,8 +38,11 @@ def test_config1_separate_calls_match_fused():
     _run_and_compare(W.CONFIGS[1], 8, fused=False)
 
 
-def test_config2_llama8b_single_two_layers():
-    _run_and_compare(W.CONFIGS[2].scaled(n_layers=2), 16)
+def test_config2_llama8b_single_full_size():
+    """Config 2 as the benchmark spec gives it (all 32 layers): 16 heads against the oracle, all 256 heads against
+    the definition-level checks."""
+    stats = _run_and_compare(W.CONFIGS[2], 16, seed=2, all_heads=True)
+    assert stats["all_heads_checked"] == 256
 
 
 def test_config3_ragged_batch_one_layer():
@@ -57,6 +62,48 @@ def test_two_pass_scan_matches_oracle():
     from paper_2512_07993_amd import binding as B
     _run_and_compare(W.CONFIGS[3].scaled(n_layers=1, batch=4), 8, flags=B.FLAG_FORCE_TWO_PASS)
     _run_and_compare(W.CONFIGS[1], 4, flags=B.FLAG_FORCE_TWO_PASS)
+
+
+def test_two_pass_scan_is_reproducible_bit_for_bit():
+    """The forced two-pass step run twice on the same bits: sentence key sums are accumulated in a fixed
+    order (one wave per sentence, tokens in order), so lambda, scores and kept indices repeat exactly."""
+    import torch
+    from paper_2512_07993_amd import binding as B
+    cfg = W.CONFIGS[3].scaled(n_layers=2, batch=4)
+    st = W.make_structure(cfg)
+    k0, v0, q = W.fill_cache(cfg, st, device="cuda")
+    runs = []
+    for _ in range(2):
+        k, v = k0.clone(), v0.clone()
+        out = run_step(cfg, st, k, v, q, flags=B.FLAG_FORCE_TWO_PASS)
+        assert int(out.dev_status.item()) == 0
+        runs.append((out, k, v))
+    (a, ka, va), (b, kb, vb) = runs
+    for name in ("sent_lambda", "sent_score", "tok_imp"):
+        assert torch.equal(getattr(a, name).view(torch.int32), getattr(b, name).view(torch.int32)), name
+    for name in ("sent_keep", "kept_idx", "new_len", "new_sent_off", "new_sent_cnt"):
+        assert torch.equal(getattr(a, name), getattr(b, name)), name
+    assert torch.equal(ka.view(torch.int16), kb.view(torch.int16)) and torch.equal(va.view(torch.int16), vb.view(torch.int16))
+
+
+def test_single_pass_scan_is_reproducible_bit_for_bit():
+    """The same for the single-pass scan: records are merged in item order whatever the order of arrival."""
+    import torch
+    cfg = W.CONFIGS[3].scaled(n_layers=2, batch=4)
+    st = W.make_structure(cfg)
+    k0, v0, q = W.fill_cache(cfg, st, device="cuda")
+    runs = []
+    for _ in range(2):
+        k, v = k0.clone(), v0.clone()
+        out = run_step(cfg, st, k, v, q)
+        assert int(out.dev_status.item()) == 0
+        runs.append((out, k, v))
+    (a, ka, va), (b, kb, vb) = runs
+    for name in ("sent_lambda", "sent_score", "tok_imp"):
+        assert torch.equal(getattr(a, name).view(torch.int32), getattr(b, name).view(torch.int32)), name
+    for name in ("sent_keep", "kept_idx", "new_len", "new_sent_off", "new_sent_cnt"):
+        assert torch.equal(getattr(a, name), getattr(b, name)), name
+    assert torch.equal(ka.view(torch.int16), kb.view(torch.int16)) and torch.equal(va.view(torch.int16), vb.view(torch.int16))
 
 
 def test_bounded_wait_reports_timeout_and_leaves_those_heads_whole():
@@ -98,21 +145,21 @@ def test_bounded_wait_reports_timeout_and_leaves_those_heads_whole():
 def test_config3_full_size_sampled_heads():
     """The benchmark workload itself (all 32 layers, batch 16: the grid, plan and workspace sizes
     that bench.py times), checked on heads sampled across layers, heads and sequences."""
-    stats = _run_and_compare(W.CONFIGS[3], 16, seed=3)
-    assert stats["heads"] == 16
+    stats = _run_and_compare(W.CONFIGS[3], 16, seed=3, all_heads=True)
+    assert stats["heads"] == 16 and stats["all_heads_checked"] == 4096
 
 
 def test_config4_full_size_sampled_heads():
     """Qwen-7B shape at full size (64 sequences, 28 layers, GQA 7, alpha 8) on sampled heads."""
-    stats = _run_and_compare(W.CONFIGS[4], 12, seed=4)
-    assert stats["heads"] == 12
+    stats = _run_and_compare(W.CONFIGS[4], 12, seed=4, all_heads=True)
+    assert stats["heads"] == 12 and stats["all_heads_checked"] == 7168
 
 
 def test_config5_full_size_sampled_heads():
     """Long-CoT shape at full size (8 sequences of 32896 tokens, 48 layers, 160 query rows per head:
     the two-pass scan) on sampled heads."""
-    stats = _run_and_compare(W.CONFIGS[5], 6, seed=5)
-    assert stats["heads"] == 6
+    stats = _run_and_compare(W.CONFIGS[5], 6, seed=5, all_heads=True)
+    assert stats["heads"] == 6 and stats["all_heads_checked"] == 3072
 
 
 def test_long_sequences_counter_protocol_next_to_short_ones():
