@@ -24,10 +24,24 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch measured with rocprofv3 counters (FETCH_SIZE and WRITE_SIZE, each scaled by what
-# the same counter reads for a copy of known size; profiles/scan_fused_config3_hbm_traffic.txt).
-# Only for the workload they were measured on.
-MEASURED_TRAFFIC = {(3, "scan_fused"): 12.18e9, (3, "compact"): 8.40e9}
+# HBM bytes per launch from rocprofv3 counters (FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter
+# reads for a copy of known size).  They are NOT measured by this run: they are the stored result of the
+# profiler runs written up in the file below, valid only for the workload they were taken on, and the JSON
+# line names that file as their source.
+TRAFFIC_PROFILE = os.path.join("profiles", "scan_fused_config3_hbm_traffic.txt")
+
+
+def stored_traffic(config: int, kernel: str):
+    """Bytes per launch from the profile's `traffic config=C kernel=K bytes=B` lines, None if there is none."""
+    try:
+        with open(os.path.join(ROOT, TRAFFIC_PROFILE)) as f:
+            for line in f:
+                w = line.split()
+                if len(w) == 4 and w[0] == "traffic" and w[1] == "config=%d" % config and w[2] == "kernel=" + kernel:
+                    return float(w[3].split("=", 1)[1])
+    except OSError:
+        pass
+    return None
 
 
 def _oracle_worker(args):
@@ -492,6 +506,7 @@ def main() -> int:
     avg = {name: sum(v) / len(v) for name, v in kernels.items()}
     dominant = max((n for n in avg if n in kernel_bytes), key=lambda n: avg[n])
     achieved = kernel_bytes[dominant] / (avg[dominant] * 1e-3) / 1e9
+    traffic = stored_traffic(args.config, dominant)
     result = {
         "metric": "compressed KV tokens/sec per compression step; achieved HBM GB/s vs peak",
         "value": T / (ms_per_step * 1e-3),
@@ -520,7 +535,8 @@ def main() -> int:
         "kernel_ms": {n: round(t, 4) for n, t in avg.items()},
         "roofline": {
             "kernel": dominant, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC.get((args.config, dominant)),
+            "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+            "traffic_source": ("stored rocprofv3 FETCH_SIZE + WRITE_SIZE counters, " + TRAFFIC_PROFILE) if traffic else None,
             "algorithmic_bytes_per_launch": kernel_bytes[dominant],
         },
     }
