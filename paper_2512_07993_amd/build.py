@@ -59,6 +59,29 @@ def build_library(verbose: bool = False, jobs: int = 8) -> str:
     return LIB
 
 
+HOSTSAN_LIB = os.path.join(PKG, "_build", "libskipkv_hostsan.so")
+# host side only (-Xarch_host): the device code is compiled as always.  Trap mode needs no sanitizer
+# runtime, so the library loads into an ordinary Python process; undefined behaviour ends in SIGILL.
+HOSTSAN_FLAGS = ["-Xarch_host", "-fsanitize=undefined,float-divide-by-zero,implicit-integer-truncation",
+                 "-Xarch_host", "-fsanitize-trap=all"]
+
+
+def build_host_sanitized() -> str:
+    """A second library whose host side of the ABI (argument validation, workspace carving: api.hip) is
+    compiled at -O1 with the undefined-behaviour sanitizer; the other objects are those of the normal
+    build.  Used by tests/test_abi_sanitized.py on the CPU; never shipped, never loaded by the binding."""
+    hipcc = _hipcc()
+    bdir = os.path.join(PKG, "_build")
+    objs = [os.path.join(bdir, s.replace(".hip", ".o")) for s in SOURCES]
+    if not all(os.path.exists(o) for o in objs):
+        build_library()
+    san = os.path.join(bdir, "api_hostsan.o")
+    flags = [f for f in FLAGS if f != "-O3"]
+    _run([hipcc, *flags, "-O1", "-g", *HOSTSAN_FLAGS, "-c", os.path.join(CSRC, "api.hip"), "-o", san])
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", HOSTSAN_LIB, san, *objs[1:]])
+    return HOSTSAN_LIB
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
     sys.exit(0)

@@ -13,9 +13,19 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 @pytest.fixture(scope="module", autouse=True)
 def _built():
+    """The library under test: the product library, or (tests/test_abi_sanitized.py runs this file again
+    in a child process with SKIPKV_ABI_TEST_LIB set) a build whose host side is sanitizer-instrumented."""
+    other = os.environ.get("SKIPKV_ABI_TEST_LIB")
+    if other:
+        saved = (B._LIB_PATH, B._lib)
+        B._LIB_PATH, B._lib = other, None
+        yield
+        B._LIB_PATH, B._lib = saved
+        return
     if not os.path.exists(B._LIB_PATH):
         from paper_2512_07993_amd.build import build_library
         build_library()
+    yield
 
 
 def _declared():
@@ -330,3 +340,34 @@ def test_paged_per_head_parts_validate_on_the_host():
     red = lambda r=C.byref(rng), o=0x7000, n=out.value: lib.skipkv_token_redundancy_ranges_paged(
         C.byref(cache), r, C.byref(pg), o, None, 0x10000, n, None)
     assert red(r=None) == B.EINVAL and red(o=None) == B.EINVAL and red(n=out.value - 1) == B.EWORKSPACE
+
+
+_I = 2 ** 31 - 1
+
+
+@pytest.mark.parametrize("ckw", [
+    dict(total_tokens=_I, total_sentences=_I), dict(n_layers=_I), dict(n_layers=1 << 20, n_kv_heads=1 << 10, n_q_heads=1 << 10),
+    dict(batch=_I), dict(total_tokens=_I, total_sentences=_I, n_layers=4096, batch=1 << 20),
+    dict(stride_tok=_I // 128 * 128, stride_head=1 << 62, stride_layer=1 << 62),
+    dict(total_tokens=-5), dict(total_sentences=-1), dict(batch=-1), dict(n_layers=-3),
+])
+@pytest.mark.parametrize("pkw", [{}, dict(max_budget=_I, budget_scalar=_I),
+                                 dict(obs_window=32, protect_window=_I, budget_scalar=_I, max_budget=_I)])
+def test_extreme_sizes_give_an_error_or_a_sane_size(ckw, pkw):
+    """Sizes at the edge of the 32-bit fields: every size query either refuses (negative counts: EINVAL;
+    more than the 32-bit indices of the kernels can address: ECAPACITY) or returns a 256-byte multiple that
+    did not wrap.  Run again under the sanitizer by tests/test_abi_sanitized.py."""
+    lib, cache, params = B.lib(), _cache(**ckw), _params(**pkw)
+    negative = any(v < 0 for v in ckw.values())
+    out = C.c_size_t(0)
+    for fn, extra in ((lib.skipkv_workspace_bytes, (C.byref(params),)), (lib.skipkv_ranges_workspace_bytes, (C.byref(params),)),
+                      (lib.skipkv_similarity_workspace_bytes, (4096,))):
+        out.value = 0
+        rc = fn(C.byref(cache), *extra, C.byref(out))
+        if negative:
+            assert rc == B.EINVAL
+        else:
+            assert rc in (B.OK, B.ECAPACITY)
+        if rc == B.OK:
+            lower = 2 * cache.total_sentences * 128 * 2 if fn is not lib.skipkv_similarity_workspace_bytes else cache.total_sentences * 4096 * 4
+            assert out.value % 256 == 0 and out.value >= lower
