@@ -133,6 +133,12 @@ def test_paged_step_matches_contiguous_and_oracle(block_size, heads_before_slots
     _check_against_contiguous(W.CONFIGS[3].scaled(n_layers=2, batch=4), block_size, heads_before_slots, monkeypatch)
 
 
+def test_paged_step_config3_full_size(monkeypatch):
+    """The workload that bench.py --paged 16 times (all 32 layers, 16 sequences, 9678 blocks of 16 slots): every
+    head bit for bit against the contiguous step, sampled heads against the oracle."""
+    _check_against_contiguous(W.CONFIGS[3], 16, False, monkeypatch, n_oracle_heads=6)
+
+
 def test_paged_step_fp32(monkeypatch):
     _check_against_contiguous(W.CONFIGS[1], 16, False, monkeypatch, n_oracle_heads=3)
 

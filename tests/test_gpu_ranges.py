@@ -54,6 +54,7 @@ def shared_as_ranges(cfg, st):
     (2, dict(n_layers=2, len_lo=1500, len_hi=1500, budget=640)),
     (3, dict(n_layers=1, batch=5, len_lo=300, len_hi=2600, budget=512)),
     (4, dict(n_layers=2, batch=3, len_lo=700, len_hi=1800, budget=512)),
+    (3, dict()),  # the workload that bench.py --ranges times, at full size
 ])
 def test_per_head_step_equals_shared_step_on_the_same_cache(config_id, kw):
     cfg = W.CONFIGS[config_id].scaled(**kw)
@@ -69,12 +70,13 @@ def test_per_head_step_equals_shared_step_on_the_same_cache(config_id, kw):
         x, y = getattr(a, name), getattr(b, name)
         assert torch.equal(x.view(torch.uint8), y.view(torch.uint8)), name
     L, H, Bn = cfg.n_layers, cfg.n_kv_heads, cfg.batch
+    new_len, new_cnt = a.new_len.cpu().numpy(), a.new_sent_cnt.cpu().numpy()
     for l in range(L):
         for h in range(H):
             for s in range(Bn):
-                n = int(a.new_len[l, h, s])
+                n = int(new_len[l, h, s])
                 assert torch.equal(a.kept_idx[l, h, s, :n], b.kept_idx[l, h, s, :n])
-                c = int(a.new_sent_cnt[l, h, s])
+                c = int(new_cnt[l, h, s])
                 p = int(st.sent_ptr[s])
                 assert torch.equal(a.new_sent_off[l, h, p:p + c + 1], b.new_sent_off[l, h, p:p + c + 1])
                 t0 = int(st.seq_off[s])
