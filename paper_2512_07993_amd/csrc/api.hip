@@ -270,6 +270,33 @@ int do_compact(Timer &tm, const skipkv_cache *c, const int32_t *kept_idx, const 
 
 bool is_empty(const skipkv_cache *c) { return c->n_layers == 0 || c->n_kv_heads == 0 || c->batch == 0; }
 
+// Workspace of the token redundancy: per key row a scale factor and a reciprocal row sum (fp32 each) and a
+// 64-bit fixed-point accumulator.
+size_t tokred_per(const skipkv_cache *c) {
+  return align_up((size_t)c->n_layers * c->n_kv_heads * (size_t)c->total_tokens * sizeof(float));
+}
+size_t tokred_bytes(const skipkv_cache *c) { return 4 * tokred_per(c); }
+TokRedArgs tokred_args(const skipkv_cache *c, void *ws, float *out) {
+  const size_t per = tokred_per(c);
+  TokRedArgs a{};
+  a.k = c->k;
+  a.stride_layer = c->stride_layer;
+  a.stride_head = c->stride_head;
+  a.stride_tok = c->stride_tok;
+  a.dtype = c->dtype;
+  a.n_layers = c->n_layers;
+  a.n_kv_heads = c->n_kv_heads;
+  a.batch = c->batch;
+  a.total_tokens = c->total_tokens;
+  a.nrb_max = (c->total_tokens + 255) / 256 + c->batch;
+  a.seq_off = c->seq_off;
+  a.scale = static_cast<float *>(ws);
+  a.inv_l = reinterpret_cast<float *>(static_cast<char *>(ws) + per);
+  a.acc = reinterpret_cast<unsigned long long *>(static_cast<char *>(ws) + 2 * per);
+  a.out = out;
+  return a;
+}
+
 // Per-head ranges.  Every (layer, KV head, sequence) triple becomes a sequence of its own of a
 // cache with ONE layer and ONE KV head: v = (l * H_k + h) * B + b, whose tokens start at packed
 // row (l * H_k + h) * T + seq_off[b] of the (contiguous) K and V and whose offsets start at
@@ -919,23 +946,8 @@ int skipkv_token_redundancy_ranges(const skipkv_cache *cache, const skipkv_range
   if (rc) return rc;
   if (is_empty(cache) || cache->total_tokens == 0) return SKIPKV_OK;
   if (!tok_redundancy || !ranges || !ranges->len) return SKIPKV_EINVAL;
-  const size_t per = align_up((size_t)cache->n_layers * cache->n_kv_heads * (size_t)cache->total_tokens * sizeof(float));
-  if (!ws || !aligned16(ws) || ws_bytes < 2 * per) return SKIPKV_EWORKSPACE;
-  TokRedArgs a{};
-  a.k = cache->k;
-  a.stride_layer = cache->stride_layer;
-  a.stride_head = cache->stride_head;
-  a.stride_tok = cache->stride_tok;
-  a.dtype = cache->dtype;
-  a.n_layers = cache->n_layers;
-  a.n_kv_heads = cache->n_kv_heads;
-  a.batch = cache->batch;
-  a.total_tokens = cache->total_tokens;
-  a.nrb_max = (cache->total_tokens + 255) / 256 + cache->batch;
-  a.seq_off = cache->seq_off;
-  a.scale = static_cast<float *>(ws);
-  a.neg_log_l = reinterpret_cast<float *>(static_cast<char *>(ws) + per);
-  a.out = tok_redundancy;
+  if (!ws || !aligned16(ws) || ws_bytes < tokred_bytes(cache)) return SKIPKV_EWORKSPACE;
+  TokRedArgs a = tokred_args(cache, ws, tok_redundancy);
   a.len = ranges->len;
   return launch_token_redundancy(a, static_cast<hipStream_t>(stream)) == hipSuccess ? SKIPKV_OK : SKIPKV_EHIP;
 }
@@ -1162,8 +1174,7 @@ int skipkv_redundancy_workspace_bytes(const skipkv_cache *cache, size_t *out_byt
   if (!out_bytes) return SKIPKV_EINVAL;
   const int rc = check_cache(cache, false);
   if (rc) return rc;
-  const size_t per = align_up((size_t)cache->n_layers * cache->n_kv_heads * (size_t)cache->total_tokens * sizeof(float));
-  *out_bytes = 2 * per;
+  *out_bytes = tokred_bytes(cache);
   return SKIPKV_OK;
 }
 
@@ -1172,23 +1183,8 @@ int skipkv_token_redundancy(const skipkv_cache *cache, float *tok_redundancy, vo
   if (rc) return rc;
   if (is_empty(cache) || cache->total_tokens == 0) return SKIPKV_OK;
   if (!tok_redundancy) return SKIPKV_EINVAL;
-  const size_t per = align_up((size_t)cache->n_layers * cache->n_kv_heads * (size_t)cache->total_tokens * sizeof(float));
-  if (!ws || !aligned16(ws) || ws_bytes < 2 * per) return SKIPKV_EWORKSPACE;
-  TokRedArgs a{};
-  a.k = cache->k;
-  a.stride_layer = cache->stride_layer;
-  a.stride_head = cache->stride_head;
-  a.stride_tok = cache->stride_tok;
-  a.dtype = cache->dtype;
-  a.n_layers = cache->n_layers;
-  a.n_kv_heads = cache->n_kv_heads;
-  a.batch = cache->batch;
-  a.total_tokens = cache->total_tokens;
-  a.nrb_max = (cache->total_tokens + 255) / 256 + cache->batch;
-  a.seq_off = cache->seq_off;
-  a.scale = static_cast<float *>(ws);
-  a.neg_log_l = reinterpret_cast<float *>(static_cast<char *>(ws) + per);
-  a.out = tok_redundancy;
+  if (!ws || !aligned16(ws) || ws_bytes < tokred_bytes(cache)) return SKIPKV_EWORKSPACE;
+  TokRedArgs a = tokred_args(cache, ws, tok_redundancy);
   return launch_token_redundancy(a, static_cast<hipStream_t>(stream)) == hipSuccess ? SKIPKV_OK : SKIPKV_EHIP;
 }
 
@@ -1203,8 +1199,7 @@ int skipkv_redundancy_paged_workspace_bytes(const skipkv_cache *cache, const ski
   CompactPagedView v;
   rc = check_compact_paging(cache, paging, 0, &v);
   if (rc) return rc;
-  const size_t per = align_up((size_t)cache->n_layers * cache->n_kv_heads * (size_t)cache->total_tokens * sizeof(float));
-  *out_bytes = 2 * per + v.map_bytes + v.bad_bytes;
+  *out_bytes = tokred_bytes(cache) + v.map_bytes + v.bad_bytes;
   return SKIPKV_OK;
 }
 
@@ -1235,29 +1230,15 @@ int token_redundancy_paged(const skipkv_cache *cache, const int32_t *len, const 
   CompactPagedView v;
   rc = check_compact_paging(cache, paging, 0, &v);
   if (rc) return rc;
-  const size_t per = align_up((size_t)cache->n_layers * cache->n_kv_heads * (size_t)cache->total_tokens * sizeof(float));
-  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < 2 * per + v.map_bytes + v.bad_bytes) return SKIPKV_EWORKSPACE;
+  const size_t red_bytes = tokred_bytes(cache);
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < red_bytes + v.map_bytes + v.bad_bytes) return SKIPKV_EWORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  int32_t *row_map = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + 2 * per);
-  int32_t *seq_bad = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + 2 * per + v.map_bytes);
+  int32_t *row_map = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + red_bytes);
+  int32_t *seq_bad = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + red_bytes + v.map_bytes);
   RowMapArgs ra{cache->seq_off, paging->block_table, cache->batch, paging->table_stride, paging->block_size,
                 paging->n_blocks, 1, 1, cache->total_tokens, 0, 0, v.rows_per_block, 1, row_map, seq_bad, dev_status};
   if (launch_row_map(ra, st) != hipSuccess) return SKIPKV_EHIP;
-  TokRedArgs a{};
-  a.k = cache->k;
-  a.stride_layer = cache->stride_layer;
-  a.stride_head = cache->stride_head;
-  a.stride_tok = cache->stride_tok;
-  a.dtype = cache->dtype;
-  a.n_layers = cache->n_layers;
-  a.n_kv_heads = cache->n_kv_heads;
-  a.batch = cache->batch;
-  a.total_tokens = cache->total_tokens;
-  a.nrb_max = (cache->total_tokens + 255) / 256 + cache->batch;
-  a.seq_off = cache->seq_off;
-  a.scale = static_cast<float *>(ws);
-  a.neg_log_l = reinterpret_cast<float *>(static_cast<char *>(ws) + per);
-  a.out = tok_redundancy;
+  TokRedArgs a = tokred_args(cache, ws, tok_redundancy);
   a.row_map = row_map;
   a.len = len;
   return launch_token_redundancy(a, st) == hipSuccess ? SKIPKV_OK : SKIPKV_EHIP;

@@ -278,7 +278,8 @@ struct TokRedArgs {
   int32_t nrb_max;           // upper bound on the 256-row blocks of all sequences
   const int32_t *seq_off;
   float *scale;              // [LH, T] workspace: sqrt(log2 e) / (||k|| + eps)
-  float *neg_log_l;          // [LH, T] workspace: -log2 of the row sums
+  float *inv_l;              // [LH, T] workspace: 1 / row sums
+  unsigned long long *acc;   // [LH, T] workspace: fixed-point totals of the sweep that is running
   float *out;                // [LH, T] token redundancy
   const int32_t *row_map;    // paged cache: logical token -> slot row in units of stride_tok (see ScanArgs); null: contiguous
   const int32_t *len;        // per-head ranges, [LH, batch]: tokens of every head's sequence (within its room); null: from seq_off

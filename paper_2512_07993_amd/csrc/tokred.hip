@@ -2,19 +2,28 @@
 // scaled to unit length, R[t] = mean over rows i of softmax_j(Kbar Kbar^T)[i, t].
 //
 // The cosine matrix is symmetric and its entries lie in [-1, 1], so no running maximum is
-// needed: with E = exp(Kbar Kbar^T), l = E 1 (row sums) and R = (1/N) E (1 / l).  Both are
-// "row block times all columns" sweeps over the same N x N matrix, which is never stored:
-//   sweep 1:  l_i = sum_j exp2(s_ij)                      -> kept as  -log2(l_i)
-//   sweep 2:  R_i = (1/N) sum_j exp2(s_ij - log2 l_j)
-// where s_ij = <k_i, k_j> * c_i * c_j and c = sqrt(log2 e) / (||k|| + eps) carries both the
+// needed: with E = exp(Kbar Kbar^T), l = E 1 (row sums) and R = (1/N) E (1 / l).  Both are sums
+// over the same symmetric N x N matrix, which is never stored:
+//   sweep 1:  l_i = sum_j e_ij
+//   sweep 2:  R_i = (1/N) sum_j e_ij / l_j
+// with e_ij = exp2(<k_i, k_j> * c_i * c_j), where c = sqrt(log2 e) / (||k|| + eps) carries both the
 // normalisation and the change of base.  The dot products run on the bf16 matrix cores with the
 // RAW keys (exact products, fp32 accumulation; fp32 caches are rounded to bf16 first) and the
 // scale factors are applied to the accumulators.
 //
-// One workgroup owns 256 rows (64 per wave: the A operands stay in registers) and walks the
-// 64-column blocks of its sequence, staged through LDS and shared by the 4 waves; the next block
-// is fetched into registers while the current one is multiplied.
+// Only the blocks at and right of the diagonal are computed.  One workgroup owns 256 rows (64 per
+// wave: the A operands stay in registers) and walks the 64-column blocks from its own rows to the
+// end of the sequence, staged through LDS and shared by the 4 waves; the next block is fetched
+// into registers while the current one is multiplied.  The 256 x 256 square on the diagonal is
+// computed in full and gives row sums only; every block right of it gives e_ij both to row i
+// (weighted with column j's factor) and, by symmetry, to row j (weighted with row i's factor):
+// the column sums of a block are reduced over the workgroup's rows and added to the row's total.
+// Totals are accumulated across workgroups as 64-bit FIXED-POINT integers (integer addition is
+// associative: the result does not depend on the order in which workgroups arrive, and the
+// conversion of an fp32 partial sum is exact at the chosen scale for all but negligible terms),
+// then turned back into fp32 by a small kernel after each sweep.
 #include <algorithm>
+#include <type_traits>
 
 #include "common.h"
 
@@ -26,6 +35,13 @@ constexpr int kRows = 256;     // rows per workgroup
 constexpr int kCols = 64;      // columns per staged block
 constexpr int LSTR = 272;      // bytes per staged key row (256 + 16: 16-byte reads of 8 rows hit distinct banks)
 constexpr float kSqrtLog2e = 1.2011224087864498f;
+// fixed-point scales of the two accumulations: row sums l <= e * N (2^40: room for N up to 2^21 tokens,
+// resolution 1e-12 against terms >= 0.37), and R <= e^2 / N... <= 8 (2^50: resolution 1e-15 against R ~ 1/N)
+constexpr float kFix1 = 1099511627776.f, kFix2 = 1125899906842624.f;
+
+__device__ __forceinline__ void add_fixed(unsigned long long *dst, float x, float scale) {
+  atomicAdd(dst, (unsigned long long)__float2ll_rn(x * scale));  // x >= 0
+}
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {  // two fp32 -> packed bf16, nearest even
   typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
@@ -78,17 +94,22 @@ __global__ void __launch_bounds__(256) k_key_scale(TokRedArgs a) {
       }
     }
     ss = row16_sum(ss);
-    if (lane16 == 0) a.scale[row] = kSqrtLog2e / (sqrtf(ss) + 1e-12f);
+    if (lane16 == 0) {
+      a.scale[row] = kSqrtLog2e / (sqrtf(ss) + 1e-12f);
+      a.acc[row] = 0ull;  // the first sweep's accumulator
+    }
   }
 }
 
-// SWEEP 1: writes neg_log_l[row] = -log2(sum_j exp2(s_ij)).  SWEEP 2: writes R[row].
+// SWEEP 1: adds every row's sum of e_ij into acc (scale kFix1).  SWEEP 2: adds R (scale kFix2).
 template <int DT, int SWEEP>
-__global__ void __launch_bounds__(256) k_tokred_sweep(TokRedArgs a) {
+__global__ void __launch_bounds__(256, 2) k_tokred_sweep(TokRedArgs a) {
   constexpr int ESZ = DT == SKIPKV_BF16 ? 2 : 4;
+  constexpr float kFix = SWEEP == 1 ? kFix1 : kFix2;
   __shared__ __align__(16) char cols[kCols * LSTR];
-  __shared__ float col_c[kCols];   // scale factor of each staged column
-  __shared__ float col_w[kCols];   // sweep 2: -log2 l of each staged column
+  __shared__ float col_c[kCols];     // scale factor of each staged column
+  __shared__ float col_w[kCols];     // weight of each staged column in a row's sum: 1 (sweep 1), 1 / l (sweep 2)
+  __shared__ float cpart[2][4][kCols];  // [block parity]: column sums of a block over each wave's rows
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, c16 = lane & 15, g = lane >> 4;
   // ---- which (head, sequence, row block) is this?
@@ -105,10 +126,8 @@ __global__ void __launch_bounds__(256) k_tokred_sweep(TokRedArgs a) {
   }
   if (b >= a.batch) return;
   const int r0 = j * kRows;
-  if (a.len) {  // per-head ranges: the head's own length within the sequence's room
-    n_tok = min(n_tok, a.len[lh * a.batch + b]);
-    if (r0 >= n_tok) return;
-  }
+  if (a.len) n_tok = min(n_tok, a.len[lh * a.batch + b]);  // per-head ranges: the head's own length within the sequence's room
+  if (r0 >= n_tok) return;
   const int l = lh / a.n_kv_heads, h = lh % a.n_kv_heads;
   // paged cache: rows are looked up in the row map (slot rows from the head's base), else they follow tok0
   const int32_t *rmap = a.row_map ? a.row_map + tok0 : nullptr;
@@ -121,6 +140,7 @@ __global__ void __launch_bounds__(256) k_tokred_sweep(TokRedArgs a) {
   const int rw0 = r0 + 64 * wave;
   bf16x8 af[4][4];
   float row_c[4][4];  // scale factors of the lane's output rows (rows 4g+j of every tile)
+  float row_w[4][4];  // their weights in a column's sum (0 for rows past the end)
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
     const int row = min(rw0 + 16 * t + c16, n_tok - 1);
@@ -128,13 +148,18 @@ __global__ void __launch_bounds__(256) k_tokred_sweep(TokRedArgs a) {
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) af[t][kk] = __builtin_bit_cast(bf16x8, load_piece_bf16<DT>(kbase + srow * pitch, 4 * g + kk));
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) row_c[t][jj] = a.scale[col0 + min(rw0 + 16 * t + 4 * g + jj, n_tok - 1)];
+    for (int jj = 0; jj < 4; ++jj) {
+      const int r = rw0 + 16 * t + 4 * g + jj;
+      row_c[t][jj] = a.scale[col0 + min(r, n_tok - 1)];
+      row_w[t][jj] = r < n_tok ? (SWEEP == 1 ? 1.f : a.inv_l[col0 + r]) : 0.f;
+    }
   }
   float rsum[4][4];
 #pragma unroll
   for (int t = 0; t < 4; ++t)
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) rsum[t][jj] = 0.f;
+  const float inv_n = SWEEP == 1 ? 1.f : 1.f / (float)n_tok;
 
   // a column block is 64 rows x 16 pieces of 16 bytes: 4 pieces per thread
   uint4 pre[4];
@@ -146,9 +171,9 @@ __global__ void __launch_bounds__(256) k_tokred_sweep(TokRedArgs a) {
       pre[it] = load_piece_bf16<DT>(kbase + slot_of(row) * pitch, piece);
     }
     if (tid < kCols) {
-      const int col = min(jb + tid, n_tok - 1);
-      pre_c = a.scale[col0 + col];
-      if (SWEEP == 2) pre_w = a.neg_log_l[col0 + col];
+      const int col = jb + tid;
+      pre_c = a.scale[col0 + min(col, n_tok - 1)];
+      pre_w = col < n_tok ? (SWEEP == 1 ? 1.f : a.inv_l[col0 + col]) : 0.f;  // weight 0 drops columns past the end
     }
   };
   auto commit = [&]() {
@@ -163,12 +188,30 @@ __global__ void __launch_bounds__(256) k_tokred_sweep(TokRedArgs a) {
     }
   };
 
-  fetch(0);
-  for (int jb = 0; jb < n_tok; jb += kCols) {
+  // The column sums of block jb are added to the totals one block later, right after the next fetch has
+  // been issued: the atomics then travel during that block's products, and the wait for the fetched
+  // columns (which waits for everything this thread has in flight) finds them done.
+  auto emit = [&](int jb, int buf) {
+    if (jb >= r0 + kRows && tid < kCols && jb + tid < n_tok) {
+      const float tot = ((cpart[buf][0][tid] + cpart[buf][1][tid]) + cpart[buf][2][tid]) + cpart[buf][3][tid];
+      add_fixed(a.acc + col0 + jb + tid, tot * inv_n, kFix);
+    }
+  };
+  fetch(r0);
+  int buf = 0;
+  for (int jb = r0; jb < n_tok; jb += kCols, buf ^= 1) {
     commit();
     __syncthreads();
     if (jb + kCols < n_tok) fetch(jb + kCols);  // lands while this block is multiplied
-    if (rw0 < n_tok) {
+    if (jb > r0) emit(jb - kCols, buf ^ 1);
+    const bool mirror = jb >= r0 + kRows;       // right of the diagonal square: the block also stands for its transpose
+    float csum[kCols / 16][4];  // four independent chains per column tile (one per register of the output tile)
+#pragma unroll
+    for (int ct = 0; ct < kCols / 16; ++ct)
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) csum[ct][jj] = 0.f;
+    auto products = [&](auto mirror_c) {
+      constexpr bool MIRROR = decltype(mirror_c)::value;
 #pragma unroll
       for (int ct = 0; ct < kCols / 16; ++ct) {
         const int cbase = jb + 16 * ct;
@@ -176,36 +219,68 @@ __global__ void __launch_bounds__(256) k_tokred_sweep(TokRedArgs a) {
         bf16x8 bfr[4];
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) bfr[kk] = *reinterpret_cast<const bf16x8 *>(cols + (16 * ct + c16) * LSTR + (4 * g + kk) * 16);
-        const bool live = cbase + c16 < n_tok;                  // this lane's column exists
         const float cc = col_c[16 * ct + c16];
-        const float cw = live ? col_w[16 * ct + c16] : -INFINITY;  // exp2(-inf) = 0 drops columns past the end
+        const float cw = col_w[16 * ct + c16];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int kk = 0; kk < 4; ++kk) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[t][kk], bfr[kk], acc, 0, 0, 0);
 #pragma unroll
-          for (int jj = 0; jj < 4; ++jj) rsum[t][jj] += __builtin_amdgcn_exp2f(fmaf(acc[jj], row_c[t][jj] * cc, cw));
+          for (int jj = 0; jj < 4; ++jj) {
+            const float e = __builtin_amdgcn_exp2f(acc[jj] * (row_c[t][jj] * cc));
+            rsum[t][jj] = fmaf(e, cw, rsum[t][jj]);
+            if constexpr (MIRROR) csum[ct][jj] = fmaf(e, row_w[t][jj], csum[ct][jj]);
+          }
         }
       }
+    };
+    if (rw0 < n_tok) {
+      if (mirror) products(std::true_type{});
+      else products(std::false_type{});
     }
-    __syncthreads();
+    if (mirror) {
+      // the four lane groups hold different rows of the same columns
+#pragma unroll
+      for (int ct = 0; ct < kCols / 16; ++ct) {
+        float v = (csum[ct][0] + csum[ct][1]) + (csum[ct][2] + csum[ct][3]);
+        v += __shfl_xor(v, 16);
+        v += __shfl_xor(v, 32);
+        if (g == 0) cpart[buf][wave][16 * ct + c16] = v;
+      }
+    }
+    __syncthreads();  // (a cpart buffer is written again two blocks later, behind two more barriers)
+  }
+  {
+    const int last = r0 + (n_tok - 1 - r0) / kCols * kCols;
+    emit(last, ((last - r0) / kCols) & 1);
   }
 
-  // ---- sums across the 16 column lanes, then the sweep's output
-  const float inv_n = 1.f / (float)n_tok;
+  // ---- sums across the 16 column lanes, then the rows' share of their totals
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) {
       const float s = row16_sum(rsum[t][jj]);
       const int row = rw0 + 16 * t + 4 * g + jj;
-      if (c16 == 0 && row < n_tok) {
-        if (SWEEP == 1)
-          a.neg_log_l[col0 + row] = -__builtin_amdgcn_logf(s);  // log2
-        else
-          a.out[col0 + row] = s * inv_n;
-      }
+      if (c16 == 0 && row < n_tok) add_fixed(a.acc + col0 + row, s * inv_n, kFix);
+    }
+  }
+}
+
+// After sweep 1: inv_l = 1 / l, accumulator cleared for sweep 2.  After sweep 2: R.  Entries that no row
+// contributed to (beyond a head's own length) stay as they are.
+template <int SWEEP>
+__global__ void __launch_bounds__(256) k_tokred_finish(TokRedArgs a) {
+  const int64_t n = (int64_t)a.n_layers * a.n_kv_heads * a.total_tokens;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const unsigned long long v = a.acc[i];
+    if (v == 0ull) continue;
+    if (SWEEP == 1) {
+      a.inv_l[i] = 1.f / ((float)v * (1.f / kFix1));
+      a.acc[i] = 0ull;
+    } else {
+      a.out[i] = (float)v * (1.f / kFix2);
     }
   }
 }
@@ -219,14 +294,19 @@ hipError_t launch_token_redundancy(const TokRedArgs &a, hipStream_t st) {
   const unsigned g0 = (unsigned)std::min<int64_t>((rows + 15) / 16, 1 << 16);
   const int64_t items = n_lh * a.nrb_max;
   const unsigned g1 = (unsigned)((items + 7) / 8 * 8);
+  const unsigned g2 = (unsigned)std::min<int64_t>((rows + 255) / 256, 1 << 16);
   if (a.dtype == SKIPKV_BF16) {
     hipLaunchKernelGGL(k_key_scale<SKIPKV_BF16>, dim3(g0), dim3(256), 0, st, a);
     hipLaunchKernelGGL((k_tokred_sweep<SKIPKV_BF16, 1>), dim3(g1), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(k_tokred_finish<1>, dim3(g2), dim3(256), 0, st, a);
     hipLaunchKernelGGL((k_tokred_sweep<SKIPKV_BF16, 2>), dim3(g1), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(k_tokred_finish<2>, dim3(g2), dim3(256), 0, st, a);
   } else {
     hipLaunchKernelGGL(k_key_scale<SKIPKV_F32>, dim3(g0), dim3(256), 0, st, a);
     hipLaunchKernelGGL((k_tokred_sweep<SKIPKV_F32, 1>), dim3(g1), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(k_tokred_finish<1>, dim3(g2), dim3(256), 0, st, a);
     hipLaunchKernelGGL((k_tokred_sweep<SKIPKV_F32, 2>), dim3(g1), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(k_tokred_finish<2>, dim3(g2), dim3(256), 0, st, a);
   }
   return hipGetLastError();
 }

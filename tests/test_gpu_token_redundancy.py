@@ -76,6 +76,29 @@ def test_config3_shape_sampled_heads():
     _check(cfg, st, k0, out, [(0, 0, 0), (0, 3, 1), (0, 5, 2), (0, 7, 3)], 1e-4)
 
 
+def test_repeats_bit_for_bit_and_clears_its_own_workspace():
+    """Only the blocks at and right of the diagonal are computed and every block adds to the totals of
+    its rows AND of its columns, from many workgroups at once: the totals are 64-bit fixed-point integers,
+    so the result must not depend on the order of arrival.  Two calls on the same workspace (the second
+    one finds the first one's totals and factors in it), and one on a fresh, garbage-filled workspace."""
+    cfg = W.CONFIGS[3].scaled(n_layers=2, batch=4)
+    st = W.make_structure(cfg)
+    k0, v0, q = W.fill_cache(cfg, st, device="cuda")
+    cache = make_cache(cfg, st, k0, k0)
+    n = B.skipkv_redundancy_workspace_bytes(cache) + 256
+    ws = torch.empty(n, dtype=torch.uint8, device="cuda")
+    outs = []
+    for w in (ws, ws, torch.full((n,), 0xA5, dtype=torch.uint8, device="cuda")):
+        out = torch.full((cfg.n_layers, cfg.n_kv_heads, st.total_tokens), float("nan"), dtype=torch.float32, device="cuda")
+        B.skipkv_token_redundancy(cache, out, w)
+        torch.cuda.synchronize()
+        outs.append(out)
+    assert not bool(torch.isnan(outs[0]).any())
+    assert torch.equal(outs[0].view(torch.int32), outs[1].view(torch.int32))
+    assert torch.equal(outs[0].view(torch.int32), outs[2].view(torch.int32))
+    _check(cfg, st, k0, outs[2], [(1, 2, 0), (0, 6, 3)], 1e-4)
+
+
 def test_feeds_the_sentence_scores():
     """The output is accepted as the tok_redundancy input of the step and matches the oracle's
     step run with the oracle's R."""
