@@ -288,7 +288,7 @@ TokRedArgs tokred_args(const skipkv_cache *c, void *ws, float *out) {
   a.n_kv_heads = c->n_kv_heads;
   a.batch = c->batch;
   a.total_tokens = c->total_tokens;
-  a.nrb_max = (c->total_tokens + 255) / 256 + c->batch;
+  a.nrb_max = (c->total_tokens + kTokredRows - 1) / kTokredRows + c->batch;
   a.seq_off = c->seq_off;
   a.scale = static_cast<float *>(ws);
   a.inv_l = reinterpret_cast<float *>(static_cast<char *>(ws) + per);

@@ -271,11 +271,13 @@ struct RowMapArgs {
 };
 hipError_t launch_row_map(const RowMapArgs &a, hipStream_t st);
 
+constexpr int kTokredRows = 256;  // key rows per workgroup of the token-redundancy sweeps
+
 struct TokRedArgs {
   const void *k;
   int64_t stride_layer, stride_head, stride_tok;
   int32_t dtype, n_layers, n_kv_heads, batch, total_tokens;
-  int32_t nrb_max;           // upper bound on the 256-row blocks of all sequences
+  int32_t nrb_max;           // upper bound on the kTokredRows-row blocks of all sequences
   const int32_t *seq_off;
   float *scale;              // [LH, T] workspace: sqrt(log2 e) / (||k|| + eps)
   float *inv_l;              // [LH, T] workspace: 1 / row sums

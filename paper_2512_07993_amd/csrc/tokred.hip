@@ -31,7 +31,8 @@ namespace skipkv {
 
 namespace {
 
-constexpr int kRows = 256;     // rows per workgroup
+constexpr int kRows = kTokredRows;  // rows per workgroup
+constexpr int kTW = kRows / 64;      // 16-row tiles per wave
 constexpr int kCols = 64;      // columns per staged block
 constexpr int LSTR = 272;      // bytes per staged key row (256 + 16: 16-byte reads of 8 rows hit distinct banks)
 constexpr float kSqrtLog2e = 1.2011224087864498f;
@@ -103,7 +104,7 @@ __global__ void __launch_bounds__(256) k_key_scale(TokRedArgs a) {
 
 // SWEEP 1: adds every row's sum of e_ij into acc (scale kFix1).  SWEEP 2: adds R (scale kFix2).
 template <int DT, int SWEEP>
-__global__ void __launch_bounds__(256, 2) k_tokred_sweep(TokRedArgs a) {
+__global__ void __launch_bounds__(256, kTW == 4 ? 2 : 3) k_tokred_sweep(TokRedArgs a) {
   constexpr int ESZ = DT == SKIPKV_BF16 ? 2 : 4;
   constexpr float kFix = SWEEP == 1 ? kFix1 : kFix2;
   __shared__ __align__(16) char cols[kCols * LSTR];
@@ -137,12 +138,12 @@ __global__ void __launch_bounds__(256, 2) k_tokred_sweep(TokRedArgs a) {
   const int64_t col0 = (int64_t)lh * a.total_tokens + tok0;  // index of the sequence's first token in the per-token arrays
 
   // ---- A operands: this wave's 64 rows (4 tiles), lane (row c16 of a tile, head-dim slice g)
-  const int rw0 = r0 + 64 * wave;
-  bf16x8 af[4][4];
-  float row_c[4][4];  // scale factors of the lane's output rows (rows 4g+j of every tile)
-  float row_w[4][4];  // their weights in a column's sum (0 for rows past the end)
+  const int rw0 = r0 + 16 * kTW * wave;
+  bf16x8 af[kTW][4];
+  float row_c[kTW][4];  // scale factors of the lane's output rows (rows 4g+j of every tile)
+  float row_w[kTW][4];  // their weights in a column's sum (0 for rows past the end)
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
+  for (int t = 0; t < kTW; ++t) {
     const int row = min(rw0 + 16 * t + c16, n_tok - 1);
     const int64_t srow = slot_of(row);
 #pragma unroll
@@ -154,9 +155,9 @@ __global__ void __launch_bounds__(256, 2) k_tokred_sweep(TokRedArgs a) {
       row_w[t][jj] = r < n_tok ? (SWEEP == 1 ? 1.f : a.inv_l[col0 + r]) : 0.f;
     }
   }
-  float rsum[4][4];
+  float rsum[kTW][4];
 #pragma unroll
-  for (int t = 0; t < 4; ++t)
+  for (int t = 0; t < kTW; ++t)
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) rsum[t][jj] = 0.f;
   const float inv_n = SWEEP == 1 ? 1.f : 1.f / (float)n_tok;
@@ -222,7 +223,7 @@ __global__ void __launch_bounds__(256, 2) k_tokred_sweep(TokRedArgs a) {
         const float cc = col_c[16 * ct + c16];
         const float cw = col_w[16 * ct + c16];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
+        for (int t = 0; t < kTW; ++t) {
           f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int kk = 0; kk < 4; ++kk) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[t][kk], bfr[kk], acc, 0, 0, 0);
@@ -258,7 +259,7 @@ __global__ void __launch_bounds__(256, 2) k_tokred_sweep(TokRedArgs a) {
 
   // ---- sums across the 16 column lanes, then the rows' share of their totals
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
+  for (int t = 0; t < kTW; ++t) {
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) {
       const float s = row16_sum(rsum[t][jj]);
