@@ -341,81 +341,6 @@ int make_virtual(const skipkv_cache *c, const skipkv_ranges *r, void *ws, Virtua
   return SKIPKV_OK;
 }
 
-int check_score_args(const skipkv_cache *c, const skipkv_params *p, RowLayout *rl, const void *q_obs, float *sent_score,
-                     float *sent_lambda, void *ws, size_t ws_bytes) {
-  int rc = check_cache(c, true);
-  if (rc) return rc;
-  rc = check_params(c, p, rl);
-  if (rc) return rc;
-  if (is_empty(c)) return SKIPKV_OK;
-  if (!q_obs || !aligned16(q_obs)) return SKIPKV_EINVAL;
-  if (c->total_sentences > 0 && (!sent_score || !sent_lambda)) return SKIPKV_EINVAL;
-  const Workspace w = carve(c, *rl, nullptr);
-  if (!w.fits) return SKIPKV_ECAPACITY;
-  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < w.bytes) return SKIPKV_EWORKSPACE;
-  return SKIPKV_OK;
-}
-
-int check_select_args(const skipkv_cache *c, const skipkv_params *p, RowLayout *rl, const float *sent_score,
-                      int32_t *kept_idx, int32_t *new_len, int32_t *new_sent_off, int32_t *new_sent_cnt,
-                      int32_t kept_stride) {
-  int rc = check_cache(c, true);
-  if (rc) return rc;
-  rc = check_params(c, p, rl);
-  if (rc) return rc;
-  if (is_empty(c)) return SKIPKV_OK;
-  if (!new_len || (c->total_sentences > 0 && !sent_score)) return SKIPKV_EINVAL;
-  if ((new_sent_off == nullptr) != (new_sent_cnt == nullptr)) return SKIPKV_EINVAL;
-  const int32_t need = p->max_budget < c->total_tokens ? p->max_budget : c->total_tokens;
-  if (kept_stride < need || (need > 0 && !kept_idx)) return SKIPKV_EINVAL;
-  return SKIPKV_OK;
-}
-
-}  // namespace
-}  // namespace skipkv
-
-using namespace skipkv;
-
-extern "C" {
-
-int skipkv_workspace_bytes(const skipkv_cache *cache, const skipkv_params *params, size_t *out_bytes) {
-  if (!out_bytes) return SKIPKV_EINVAL;
-  int rc = check_cache(cache, true);
-  if (rc) return rc;
-  RowLayout rl;
-  rc = check_params(cache, params, &rl);
-  if (rc) return rc;
-  const Workspace w = carve(cache, rl, nullptr);
-  if (!w.fits) return SKIPKV_ECAPACITY;
-  *out_bytes = w.bytes;
-  return SKIPKV_OK;
-}
-
-int skipkv_score(const skipkv_cache *cache, const skipkv_params *params, const void *q_obs,
-                 const float *tok_redundancy, float *sent_score, float *sent_lambda, float *tok_importance,
-                 void *ws, size_t ws_bytes, void *stream) {
-  RowLayout rl;
-  const int rc = check_score_args(cache, params, &rl, q_obs, sent_score, sent_lambda, ws, ws_bytes);
-  if (rc) return rc;
-  if (is_empty(cache)) return SKIPKV_OK;
-  Timer tm(params->profile, static_cast<hipStream_t>(stream));
-  return do_score(tm, cache, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, ws,
-                  static_cast<hipStream_t>(stream));
-}
-
-int skipkv_select(const skipkv_cache *cache, const skipkv_params *params, const float *sent_score,
-                  uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len, int32_t *new_sent_off,
-                  int32_t *new_sent_cnt, int32_t kept_stride, void *stream) {
-  RowLayout rl;
-  const int rc = check_select_args(cache, params, &rl, sent_score, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride);
-  if (rc) return rc;
-  if (is_empty(cache)) return SKIPKV_OK;
-  Timer tm(params->profile, static_cast<hipStream_t>(stream));
-  return do_select(tm, cache, params, sent_score, sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride,
-                   static_cast<hipStream_t>(stream));
-}
-
-namespace {
 int do_select_tokens(const skipkv_cache *c, const skipkv_params *p, const float *tok_importance, const float *tok_redundancy,
                      const float *sent_lambda, float *tok_score, uint8_t *tok_keep, int32_t *kept_idx, int32_t *new_len,
                      int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride, hipStream_t st,
@@ -448,19 +373,312 @@ int do_select_tokens(const skipkv_cache *c, const skipkv_params *p, const float 
   a.cnt = hv.cnt;
   return launch_select_tokens(a, st) == hipSuccess ? SKIPKV_OK : SKIPKV_EHIP;
 }
+
+// ---------------------------------------------------------------------------------------------------
+// One call through the scoring / selection / compaction path, as the caller described it.  Every exported
+// score, select and step entry point (shared or per-head ranges, contiguous or paged cache, per-head or
+// shared lambda, sentence- or token-level selection) fills one of these and hands it to run_call, and every
+// size query goes through resolve: nothing else validates these arguments, lays out this workspace or
+// sequences these kernels.
+enum : unsigned { kScore = 1u, kSelect = 2u, kSelectTokens = 4u, kCompact = 8u };
+
+struct Call {
+  unsigned stages = 0;
+  const skipkv_cache *cache = nullptr;
+  const skipkv_params *params = nullptr;
+  bool per_head = false;                    // the entry point works on per-head ranges (`ranges` is then required)
+  const skipkv_ranges *ranges = nullptr;
+  bool paged = false;                       // ... on a paged cache (`paging` is then required)
+  const skipkv_paging *paging = nullptr;
+  // scoring
+  const void *q_obs = nullptr;
+  const float *tok_red = nullptr;
+  bool shared = false;                      // lambda is the caller's (hidden-state similarity), not computed per head
+  const float *shared_lambda = nullptr;
+  const int32_t *sent_id = nullptr, *lam_ptr = nullptr;  // ... looked up by sentence number under per-head ranges
+  float *sent_score = nullptr, *sent_lambda = nullptr, *tok_imp = nullptr;
+  // selection (sentence level: by sent_score; token level: from tok_imp_in, tok_red and lambda_in)
+  const float *tok_imp_in = nullptr, *lambda_in = nullptr;
+  float *tok_score = nullptr;
+  uint8_t *keep = nullptr;                  // sent_keep, or tok_keep at token level
+  int32_t *kept_idx = nullptr, *new_len = nullptr, *new_sent_off = nullptr, *new_sent_cnt = nullptr;
+  int32_t kept_stride = 0;
+  void *ws = nullptr;
+  size_t ws_bytes = 0;
+  void *stream = nullptr;
+};
+
+// What resolve makes of a call: the cache as the kernels see it (the virtual one under per-head ranges) and
+// where the pieces of the workspace are: [virtual layout | step | row maps | per-sequence flags | slot rows].
+struct Layout {
+  bool empty = false;
+  RowLayout rl;
+  skipkv_cache c;
+  HeadView hv;
+  int32_t *v_seq_off = nullptr, *v_sent_ptr = nullptr;
+  size_t head_bytes = 0, step_bytes = 0, map_bytes = 0, bad_bytes = 0, src_bytes = 0, total = 0;
+  int32_t src_stride = 0;
+  int64_t unit_layer = 0, unit_head = 0, unit_block = 0, unit_tok = 1;  // row-map units (per-head ranges: head rows)
+};
+
+// Validation of a paged cache's description.
+int check_paging_desc(const skipkv_cache *c, const skipkv_paging *pg, int64_t *rows_per_block) {
+  if (!pg) return SKIPKV_EINVAL;
+  if (pg->block_size < 1 || pg->n_blocks < 1 || pg->table_stride < 0 || pg->stride_block < 0) return SKIPKV_EINVAL;
+  if (!pg->block_table && c->total_tokens > 0) return SKIPKV_EINVAL;
+  if (c->stride_tok <= 0 || pg->stride_block % c->stride_tok) return SKIPKV_EINVAL;
+  const int64_t rpb = pg->stride_block / c->stride_tok;
+  if (rpb < pg->block_size) return SKIPKV_EINVAL;  // the slots of a block must not reach into the next one
+  *rows_per_block = rpb;
+  return SKIPKV_OK;
+}
+
+// Checks every argument of the call on the host and computes the layout.  With `sizing` only the sizes are
+// wanted (no workspace, no per-call pointers are looked at).
+int resolve(const Call &k, bool sizing, Layout *o) {
+  const skipkv_cache *c = k.cache;
+  const skipkv_params *p = k.params;
+  Layout L;
+  int rc = check_cache(c, true);
+  if (rc) return rc;
+  rc = check_params(c, p, &L.rl);
+  if (rc) return rc;
+  const bool selects = (k.stages & (kSelect | kSelectTokens)) != 0;
+  if (selects && !sizing && !is_empty(c)) {
+    const float *ranked = (k.stages & kSelect) ? k.sent_score : k.lambda_in;
+    if (!k.new_len || (c->total_sentences > 0 && !ranked)) return SKIPKV_EINVAL;
+    if ((k.new_sent_off == nullptr) != (k.new_sent_cnt == nullptr)) return SKIPKV_EINVAL;
+    const int32_t need = p->max_budget < c->total_tokens ? p->max_budget : c->total_tokens;
+    if (k.kept_stride < need || (need > 0 && !k.kept_idx)) return SKIPKV_EINVAL;
+  }
+  L.c = *c;
+  if (is_empty(c)) {
+    L.empty = true;
+    if (!k.per_head && !k.paged && (k.stages & kScore)) L.total = carve(c, L.rl, nullptr).bytes;
+    *o = L;
+    return SKIPKV_OK;
+  }
+  if ((k.stages & kScore) && !sizing) {
+    if (!k.q_obs || !aligned16(k.q_obs)) return SKIPKV_EINVAL;
+    if (c->total_sentences > 0 && (!k.sent_score || (!k.shared && !k.sent_lambda))) return SKIPKV_EINVAL;
+    if (k.shared && c->total_sentences > 0 && (!k.shared_lambda || (k.per_head && (!k.sent_id || !k.lam_ptr)))) return SKIPKV_EINVAL;
+  }
+  if ((k.stages & kSelectTokens) && !sizing && c->total_tokens > 0 && (!k.tok_imp_in || !k.tok_score)) return SKIPKV_EINVAL;
+  if (!sizing && (k.per_head || k.paged || (k.stages & kScore)) && (!k.ws || (reinterpret_cast<uintptr_t>(k.ws) & 255u)))
+    return SKIPKV_EWORKSPACE;
+
+  int64_t rpb = 0;
+  if (k.paged) {
+    rc = check_paging_desc(c, k.paging, &rpb);
+    if (rc) return rc;
+  }
+  if (k.per_head) {
+    // K and V are addressed by the kernels as one flat array of rows unless they are not read at all
+    // (selection only) or a row map says where the rows are
+    const bool any_strides = k.paged || !(k.stages & (kScore | kCompact));
+    const skipkv_ranges sizing_ranges{reinterpret_cast<int32_t *>(16), reinterpret_cast<int32_t *>(16), reinterpret_cast<int32_t *>(16)};
+    VirtualView v;
+    if (k.paged) {  // the (layer, head) part of an address moves into the row maps, whose unit is one head row
+      const int64_t D = c->head_dim;
+      if ((c->stride_tok % D) || (c->stride_head % D) || (c->stride_layer % D) || (k.paging->stride_block % D)) return SKIPKV_EINVAL;
+      L.unit_layer = c->stride_layer / D;
+      L.unit_head = c->stride_head / D;
+      L.unit_block = k.paging->stride_block / D;
+      L.unit_tok = c->stride_tok / D;
+      const int64_t last_row = (int64_t)(c->n_layers - 1) * L.unit_layer + (int64_t)(c->n_kv_heads - 1) * L.unit_head +
+                               (int64_t)(k.paging->n_blocks - 1) * L.unit_block + (int64_t)(k.paging->block_size - 1) * L.unit_tok;
+      if (last_row > 0x7FFFFFFFll) return SKIPKV_ECAPACITY;  // slot rows are 32-bit
+    }
+    rc = make_virtual(c, sizing ? &sizing_ranges : k.ranges, sizing ? nullptr : k.ws, &v, any_strides);
+    if (rc) return rc;
+    if (selects && !sizing &&
+        (k.ranges->sent_off == k.new_sent_off || k.ranges->len == k.new_len || k.ranges->sent_cnt == k.new_sent_cnt))
+      return SKIPKV_EINVAL;  // outputs must not alias the input ranges
+    L.c = v.c;
+    L.hv = v.hv;
+    L.v_seq_off = v.seq_off;
+    L.v_sent_ptr = v.sent_ptr;
+    L.head_bytes = v.head_bytes;
+    if (k.shared) {
+      L.hv.sent_id = k.sent_id;
+      L.hv.lam_ptr = k.lam_ptr;
+    }
+  } else if (k.paged) {
+    if ((int64_t)k.paging->n_blocks * rpb > 0x7FFFFFFFll) return SKIPKV_ECAPACITY;  // slot rows are 32-bit
+    L.unit_block = rpb;  // the shared map counts in token rows
+  }
+  if (k.stages & kScore) {
+    const Workspace w = carve(&L.c, L.rl, nullptr);
+    if (!w.fits) return SKIPKV_ECAPACITY;
+    L.step_bytes = align_up(w.bytes);
+  }
+  if (k.paged) {
+    const size_t LH = (size_t)c->n_layers * c->n_kv_heads;
+    L.map_bytes = align_up((k.per_head ? LH : 1) * (size_t)c->total_tokens * 4);
+    L.bad_bytes = align_up((k.per_head ? LH : 1) * (size_t)c->batch * 4);
+    // slot rows of the kept tokens of every head: no head keeps more than its budget, nor more than there is
+    L.src_stride = std::max(1, std::min(p->max_budget, c->total_tokens));
+    L.src_bytes = align_up(LH * c->batch * L.src_stride * 4);
+    L.hv.page_size = k.paging->block_size;
+    L.hv.map_stride = k.per_head ? c->head_dim : 0;
+  }
+  L.total = L.head_bytes + L.step_bytes + L.map_bytes + L.bad_bytes + L.src_bytes;
+  if (!sizing && L.total > 0 && k.ws_bytes < L.total) return SKIPKV_EWORKSPACE;
+  *o = L;
+  return SKIPKV_OK;
+}
+
+int size_call(const Call &k, size_t *out_bytes) {
+  if (!out_bytes) return SKIPKV_EINVAL;
+  Layout L;
+  const int rc = resolve(k, true, &L);
+  if (rc) return rc;
+  *out_bytes = L.total;
+  return SKIPKV_OK;
+}
+
+int run_call(const Call &k) {
+  Layout L;
+  int rc = resolve(k, false, &L);
+  if (rc || L.empty) return rc;
+  const skipkv_cache *c = k.cache;
+  const skipkv_params *p = k.params;
+  hipStream_t st = static_cast<hipStream_t>(k.stream);
+  Timer tm(p->profile, st);
+  char *ws = static_cast<char *>(k.ws);
+  const int32_t n_lh = c->n_layers * c->n_kv_heads;
+  if (k.per_head &&
+      launch_virtual_layout(c->seq_off, c->sent_ptr, c->batch, n_lh, c->total_tokens, c->total_sentences, L.v_seq_off,
+                            L.v_sent_ptr, st) != hipSuccess)
+    return SKIPKV_EHIP;
+  char *step_ws = ws + L.head_bytes;
+  int32_t *row_map = nullptr, *seq_bad = nullptr, *src_rows = nullptr;
+  if (k.paged) {
+    row_map = reinterpret_cast<int32_t *>(step_ws + L.step_bytes);
+    seq_bad = reinterpret_cast<int32_t *>(step_ws + L.step_bytes + L.map_bytes);
+    src_rows = reinterpret_cast<int32_t *>(step_ws + L.step_bytes + L.map_bytes + L.bad_bytes);
+    const skipkv_paging *pg = k.paging;
+    RowMapArgs ra{c->seq_off, pg->block_table, c->batch, pg->table_stride, pg->block_size, pg->n_blocks,
+                  k.per_head ? n_lh : 1, k.per_head ? c->n_kv_heads : 1, c->total_tokens, L.unit_layer, L.unit_head,
+                  L.unit_block, L.unit_tok, row_map, seq_bad, p->dev_status};
+    if (tm.run("row_map", [&] { return launch_row_map(ra, st); }) != hipSuccess) return SKIPKV_EHIP;
+    L.hv.row_map = row_map;
+  }
+  if (k.stages & kScore) {
+    rc = do_score(tm, &L.c, p, L.rl, k.q_obs, k.tok_red, k.sent_score, k.sent_lambda, k.tok_imp, step_ws, st, L.hv,
+                  k.shared ? k.shared_lambda : nullptr);
+    if (rc) return rc;
+  }
+  if (k.stages & kSelect) {
+    rc = do_select(tm, &L.c, p, k.sent_score, k.keep, k.kept_idx, k.new_len, k.new_sent_off, k.new_sent_cnt, k.kept_stride, st, L.hv);
+    if (rc) return rc;
+  }
+  if (k.stages & kSelectTokens) {
+    rc = do_select_tokens(&L.c, p, k.tok_imp_in, k.tok_red, k.lambda_in, k.tok_score, k.keep, k.kept_idx, k.new_len,
+                          k.new_sent_off, k.new_sent_cnt, k.kept_stride, st, L.hv);
+    if (rc) return rc;
+  }
+  if (k.stages & kCompact) {
+    rc = do_compact(tm, &L.c, k.kept_idx, k.new_len, k.kept_stride, st, row_map, seq_bad, src_rows, L.src_stride,
+                    k.paged && k.per_head ? c->head_dim : 0);
+    if (rc) return rc;
+  }
+  return SKIPKV_OK;
+}
+
 }  // namespace
+}  // namespace skipkv
+
+using namespace skipkv;
+
+extern "C" {
+
+// ---- the path on the cache's shared ranges, contiguous cache ------------------------------------------
+
+int skipkv_workspace_bytes(const skipkv_cache *cache, const skipkv_params *params, size_t *out_bytes) {
+  Call k;
+  k.stages = kScore | kSelect | kCompact;
+  k.cache = cache;
+  k.params = params;
+  return size_call(k, out_bytes);
+}
+
+int skipkv_score(const skipkv_cache *cache, const skipkv_params *params, const void *q_obs,
+                 const float *tok_redundancy, float *sent_score, float *sent_lambda, float *tok_importance,
+                 void *ws, size_t ws_bytes, void *stream) {
+  Call k;
+  k.stages = kScore;
+  k.cache = cache;
+  k.params = params;
+  k.q_obs = q_obs;
+  k.tok_red = tok_redundancy;
+  k.sent_score = sent_score;
+  k.sent_lambda = sent_lambda;
+  k.tok_imp = tok_importance;
+  k.ws = ws;
+  k.ws_bytes = ws_bytes;
+  k.stream = stream;
+  return run_call(k);
+}
+
+int skipkv_score_shared(const skipkv_cache *cache, const skipkv_params *params, const void *q_obs,
+                        const float *tok_redundancy, const float *shared_lambda, float *sent_score, float *sent_lambda,
+                        float *tok_importance, void *ws, size_t ws_bytes, void *stream) {
+  Call k;
+  k.stages = kScore;
+  k.cache = cache;
+  k.params = params;
+  k.q_obs = q_obs;
+  k.tok_red = tok_redundancy;
+  k.shared = true;
+  k.shared_lambda = shared_lambda;
+  k.sent_score = sent_score;
+  k.sent_lambda = sent_lambda;
+  k.tok_imp = tok_importance;
+  k.ws = ws;
+  k.ws_bytes = ws_bytes;
+  k.stream = stream;
+  return run_call(k);
+}
+
+int skipkv_select(const skipkv_cache *cache, const skipkv_params *params, const float *sent_score,
+                  uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len, int32_t *new_sent_off,
+                  int32_t *new_sent_cnt, int32_t kept_stride, void *stream) {
+  Call k;
+  k.stages = kSelect;
+  k.cache = cache;
+  k.params = params;
+  k.sent_score = const_cast<float *>(sent_score);
+  k.keep = sent_keep;
+  k.kept_idx = kept_idx;
+  k.new_len = new_len;
+  k.new_sent_off = new_sent_off;
+  k.new_sent_cnt = new_sent_cnt;
+  k.kept_stride = kept_stride;
+  k.stream = stream;
+  return run_call(k);
+}
 
 int skipkv_select_tokens(const skipkv_cache *cache, const skipkv_params *params, const float *tok_importance,
                          const float *tok_redundancy, const float *sent_lambda, float *tok_score,
                          uint8_t *tok_keep, int32_t *kept_idx, int32_t *new_len, int32_t *new_sent_off,
                          int32_t *new_sent_cnt, int32_t kept_stride, void *stream) {
-  RowLayout rl;
-  const int rc = check_select_args(cache, params, &rl, sent_lambda, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride);
-  if (rc) return rc;
-  if (is_empty(cache)) return SKIPKV_OK;
-  if (cache->total_tokens > 0 && (!tok_importance || !tok_score)) return SKIPKV_EINVAL;
-  return do_select_tokens(cache, params, tok_importance, tok_redundancy, sent_lambda, tok_score, tok_keep, kept_idx, new_len,
-                          new_sent_off, new_sent_cnt, kept_stride, static_cast<hipStream_t>(stream));
+  Call k;
+  k.stages = kSelectTokens;
+  k.cache = cache;
+  k.params = params;
+  k.tok_imp_in = tok_importance;
+  k.tok_red = tok_redundancy;
+  k.lambda_in = sent_lambda;
+  k.tok_score = tok_score;
+  k.keep = tok_keep;
+  k.kept_idx = kept_idx;
+  k.new_len = new_len;
+  k.new_sent_off = new_sent_off;
+  k.new_sent_cnt = new_sent_cnt;
+  k.kept_stride = kept_stride;
+  k.stream = stream;
+  return run_call(k);
 }
 
 int skipkv_compact(const skipkv_cache *cache, const int32_t *kept_idx, const int32_t *new_len, int32_t kept_stride,
@@ -473,23 +691,40 @@ int skipkv_compact(const skipkv_cache *cache, const int32_t *kept_idx, const int
   return do_compact(tm, cache, kept_idx, new_len, kept_stride, static_cast<hipStream_t>(stream));
 }
 
+namespace {
+// The arguments that every whole-step entry point has in common.
+Call step_call(const skipkv_cache *cache, const skipkv_params *params, const void *q_obs, const float *tok_redundancy,
+               float *sent_score, float *sent_lambda, float *tok_importance, uint8_t *sent_keep, int32_t *kept_idx,
+               int32_t *new_len, int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride, void *ws,
+               size_t ws_bytes, void *stream) {
+  Call k;
+  k.stages = kScore | kSelect | kCompact;
+  k.cache = cache;
+  k.params = params;
+  k.q_obs = q_obs;
+  k.tok_red = tok_redundancy;
+  k.sent_score = sent_score;
+  k.sent_lambda = sent_lambda;
+  k.tok_imp = tok_importance;
+  k.keep = sent_keep;
+  k.kept_idx = kept_idx;
+  k.new_len = new_len;
+  k.new_sent_off = new_sent_off;
+  k.new_sent_cnt = new_sent_cnt;
+  k.kept_stride = kept_stride;
+  k.ws = ws;
+  k.ws_bytes = ws_bytes;
+  k.stream = stream;
+  return k;
+}
+}  // namespace
+
 int skipkv_step(const skipkv_cache *cache, const skipkv_params *params, const void *q_obs,
                 const float *tok_redundancy, float *sent_score, float *sent_lambda, float *tok_importance,
                 uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len, int32_t *new_sent_off,
                 int32_t *new_sent_cnt, int32_t kept_stride, void *ws, size_t ws_bytes, void *stream) {
-  RowLayout rl;
-  int rc = check_score_args(cache, params, &rl, q_obs, sent_score, sent_lambda, ws, ws_bytes);
-  if (rc) return rc;
-  rc = check_select_args(cache, params, &rl, sent_score, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride);
-  if (rc) return rc;
-  if (is_empty(cache)) return SKIPKV_OK;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  Timer tm(params->profile, st);
-  rc = do_score(tm, cache, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, ws, st);
-  if (rc) return rc;
-  rc = do_select(tm, cache, params, sent_score, sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride, st);
-  if (rc) return rc;
-  return do_compact(tm, cache, kept_idx, new_len, kept_stride, st);
+  return run_call(step_call(cache, params, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, sent_keep,
+                            kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride, ws, ws_bytes, stream));
 }
 
 // Scratch of skipkv_step_static: one array per GPU, held by the code object from the moment it is
@@ -520,14 +755,10 @@ int skipkv_step_static(const skipkv_cache *cache, const skipkv_params *params, c
                        const float *tok_redundancy, float *sent_score, float *sent_lambda, float *tok_importance,
                        uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len, int32_t *new_sent_off,
                        int32_t *new_sent_cnt, int32_t kept_stride, void *stream) {
-  int rc = check_cache(cache, true);
+  size_t need = 0;
+  int rc = skipkv_workspace_bytes(cache, params, &need);
   if (rc) return rc;
-  RowLayout rl;
-  rc = check_params(cache, params, &rl);
-  if (rc) return rc;
-  const Workspace w = carve(cache, rl, nullptr);
-  if (!w.fits) return SKIPKV_ECAPACITY;
-  if (w.bytes > (size_t)SKIPKV_STATIC_WS_BYTES) return SKIPKV_EWORKSPACE;  // the problem needs more scratch than the array holds
+  if (need > (size_t)SKIPKV_STATIC_WS_BYTES) return SKIPKV_EWORKSPACE;  // the problem needs more scratch than the array holds
   void *ws = nullptr;
   rc = static_scratch(&ws);
   if (rc) return rc;
@@ -537,104 +768,180 @@ int skipkv_step_static(const skipkv_cache *cache, const skipkv_params *params, c
                      new_len, new_sent_off, new_sent_cnt, kept_stride, ws, (size_t)SKIPKV_STATIC_WS_BYTES, stream);
 }
 
-namespace {
-// Validation of a paged cache's description, and where the row map and the per-sequence flags sit
-// behind the step's workspace.
-struct PagedView {
-  size_t step_bytes, map_bytes, bad_bytes, total;
-  int32_t rows_per_block, src_stride;
-};
-int check_paging_desc(const skipkv_cache *c, const skipkv_paging *pg, int64_t *rows_per_block) {
-  if (!pg) return SKIPKV_EINVAL;
-  if (pg->block_size < 1 || pg->n_blocks < 1 || pg->table_stride < 0 || pg->stride_block < 0) return SKIPKV_EINVAL;
-  if (!pg->block_table && c->total_tokens > 0) return SKIPKV_EINVAL;
-  if (c->stride_tok <= 0 || pg->stride_block % c->stride_tok) return SKIPKV_EINVAL;
-  const int64_t rpb = pg->stride_block / c->stride_tok;
-  if (rpb < pg->block_size) return SKIPKV_EINVAL;  // the slots of a block must not reach into the next one
-  *rows_per_block = rpb;
-  return SKIPKV_OK;
-}
-int check_paging(const skipkv_cache *c, const skipkv_paging *pg, const skipkv_params *p, const RowLayout &rl, PagedView *v) {
-  int64_t rpb = 0;
-  const int rc = check_paging_desc(c, pg, &rpb);
-  if (rc) return rc;
-  if ((int64_t)pg->n_blocks * rpb > 0x7FFFFFFFll) return SKIPKV_ECAPACITY;  // slot rows are 32-bit
-  v->rows_per_block = (int32_t)rpb;
-  const Workspace w = carve(c, rl, nullptr);
-  if (!w.fits) return SKIPKV_ECAPACITY;
-  v->step_bytes = align_up(w.bytes);
-  v->map_bytes = align_up((size_t)c->total_tokens * 4);
-  v->bad_bytes = align_up((size_t)c->batch * 4);
-  // slot rows of the kept tokens of every head: no head keeps more than its budget, nor more than there is
-  v->src_stride = std::max(1, std::min(p->max_budget, c->total_tokens));
-  v->total = v->step_bytes + v->map_bytes + v->bad_bytes +
-             align_up((size_t)c->n_layers * c->n_kv_heads * c->batch * v->src_stride * 4);
-  return SKIPKV_OK;
-}
-}  // namespace
+// ---- paged cache ------------------------------------------------------------------------------------------
 
 int skipkv_paged_workspace_bytes(const skipkv_cache *cache, const skipkv_paging *paging, const skipkv_params *params,
                                  size_t *out_bytes) {
-  if (!out_bytes) return SKIPKV_EINVAL;
-  int rc = check_cache(cache, true);
-  if (rc) return rc;
-  RowLayout rl;
-  rc = check_params(cache, params, &rl);
-  if (rc) return rc;
-  if (is_empty(cache)) {
-    *out_bytes = 0;
-    return SKIPKV_OK;
-  }
-  PagedView pv;
-  rc = check_paging(cache, paging, params, rl, &pv);
-  if (rc) return rc;
-  *out_bytes = pv.total;
-  return SKIPKV_OK;
+  Call k;
+  k.stages = kScore | kSelect | kCompact;
+  k.cache = cache;
+  k.params = params;
+  k.paged = true;
+  k.paging = paging;
+  return size_call(k, out_bytes);
 }
-
-namespace {
-int score_paged(const skipkv_cache *cache, const skipkv_paging *paging, const skipkv_params *params, const void *q_obs,
-                const float *tok_redundancy, const float *shared_lambda, bool need_lambda_out, float *sent_score,
-                float *sent_lambda, float *tok_importance, void *ws, size_t ws_bytes, void *stream) {
-  RowLayout rl;
-  int rc = check_cache(cache, true);
-  if (rc) return rc;
-  rc = check_params(cache, params, &rl);
-  if (rc) return rc;
-  if (is_empty(cache)) return SKIPKV_OK;
-  if (!q_obs || !aligned16(q_obs)) return SKIPKV_EINVAL;
-  if (cache->total_sentences > 0 && (!sent_score || (need_lambda_out && !sent_lambda))) return SKIPKV_EINVAL;
-  PagedView pv;
-  rc = check_paging(cache, paging, params, rl, &pv);
-  if (rc) return rc;
-  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < pv.total) return SKIPKV_EWORKSPACE;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  Timer tm(params->profile, st);
-  int32_t *row_map = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + pv.step_bytes);
-  int32_t *seq_bad = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + pv.step_bytes + pv.map_bytes);
-  RowMapArgs ra{cache->seq_off, paging->block_table, cache->batch, paging->table_stride, paging->block_size,
-                paging->n_blocks, 1, 1, cache->total_tokens, 0, 0, pv.rows_per_block, 1, row_map, seq_bad, params->dev_status};
-  if (tm.run("row_map", [&] { return launch_row_map(ra, st); }) != hipSuccess) return SKIPKV_EHIP;
-  HeadView hv;
-  hv.row_map = row_map;
-  hv.page_size = paging->block_size;
-  return do_score(tm, cache, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, ws, st, hv, shared_lambda);
-}
-}  // namespace
 
 int skipkv_score_paged(const skipkv_cache *cache, const skipkv_paging *paging, const skipkv_params *params,
                        const void *q_obs, const float *tok_redundancy, float *sent_score, float *sent_lambda,
                        float *tok_importance, void *ws, size_t ws_bytes, void *stream) {
-  return score_paged(cache, paging, params, q_obs, tok_redundancy, nullptr, true, sent_score, sent_lambda, tok_importance, ws,
-                     ws_bytes, stream);
+  Call k = step_call(cache, params, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, nullptr, nullptr, nullptr,
+                     nullptr, nullptr, 0, ws, ws_bytes, stream);
+  k.stages = kScore;
+  k.paged = true;
+  k.paging = paging;
+  return run_call(k);
 }
 
 int skipkv_score_shared_paged(const skipkv_cache *cache, const skipkv_paging *paging, const skipkv_params *params,
                               const void *q_obs, const float *tok_redundancy, const float *shared_lambda, float *sent_score,
                               float *sent_lambda, float *tok_importance, void *ws, size_t ws_bytes, void *stream) {
-  if (cache && cache->total_sentences > 0 && !shared_lambda) return SKIPKV_EINVAL;
-  return score_paged(cache, paging, params, q_obs, tok_redundancy, shared_lambda, false, sent_score, sent_lambda, tok_importance,
-                     ws, ws_bytes, stream);
+  Call k = step_call(cache, params, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, nullptr, nullptr, nullptr,
+                     nullptr, nullptr, 0, ws, ws_bytes, stream);
+  k.stages = kScore;
+  k.paged = true;
+  k.paging = paging;
+  k.shared = true;
+  k.shared_lambda = shared_lambda;
+  return run_call(k);
+}
+
+int skipkv_step_paged(const skipkv_cache *cache, const skipkv_paging *paging, const skipkv_params *params,
+                      const void *q_obs, const float *tok_redundancy, float *sent_score, float *sent_lambda,
+                      float *tok_importance, uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len,
+                      int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride, void *ws, size_t ws_bytes,
+                      void *stream) {
+  Call k = step_call(cache, params, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, sent_keep, kept_idx,
+                     new_len, new_sent_off, new_sent_cnt, kept_stride, ws, ws_bytes, stream);
+  k.paged = true;
+  k.paging = paging;
+  return run_call(k);
+}
+
+// ---- per-head ranges --------------------------------------------------------------------------------------
+
+int skipkv_ranges_workspace_bytes(const skipkv_cache *cache, const skipkv_params *params, size_t *out_bytes) {
+  Call k;
+  k.stages = kScore | kSelect | kCompact;
+  k.cache = cache;
+  k.params = params;
+  k.per_head = true;
+  return size_call(k, out_bytes);
+}
+
+int skipkv_step_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_params *params,
+                       const void *q_obs, const float *tok_redundancy, float *sent_score, float *sent_lambda,
+                       float *tok_importance, uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len,
+                       int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride, void *ws, size_t ws_bytes,
+                       void *stream) {
+  Call k = step_call(cache, params, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, sent_keep, kept_idx,
+                     new_len, new_sent_off, new_sent_cnt, kept_stride, ws, ws_bytes, stream);
+  k.per_head = true;
+  k.ranges = ranges;
+  return run_call(k);
+}
+
+// The parts of skipkv_step_ranges, for callers that select token by token in between.
+int skipkv_score_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_params *params,
+                        const void *q_obs, const float *tok_redundancy, float *sent_score, float *sent_lambda,
+                        float *tok_importance, void *ws, size_t ws_bytes, void *stream) {
+  Call k = step_call(cache, params, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, nullptr, nullptr, nullptr,
+                     nullptr, nullptr, 0, ws, ws_bytes, stream);
+  k.stages = kScore;
+  k.per_head = true;
+  k.ranges = ranges;
+  return run_call(k);
+}
+
+// Shared lambda (hidden-state similarity) on per-head ranges.
+int skipkv_score_shared_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const int32_t *sent_id,
+                               const int32_t *lambda_ptr, const skipkv_params *params, const void *q_obs,
+                               const float *tok_redundancy, const float *shared_lambda, float *sent_score,
+                               float *sent_lambda, float *tok_importance, void *ws, size_t ws_bytes, void *stream) {
+  Call k = step_call(cache, params, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, nullptr, nullptr, nullptr,
+                     nullptr, nullptr, 0, ws, ws_bytes, stream);
+  k.stages = kScore;
+  k.per_head = true;
+  k.ranges = ranges;
+  k.shared = true;
+  k.shared_lambda = shared_lambda;
+  k.sent_id = sent_id;
+  k.lam_ptr = lambda_ptr;
+  return run_call(k);
+}
+
+int skipkv_select_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_params *params,
+                         const float *sent_score, uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len,
+                         int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride, void *ws, size_t ws_bytes,
+                         void *stream) {
+  Call k = step_call(cache, params, nullptr, nullptr, const_cast<float *>(sent_score), nullptr, nullptr, sent_keep, kept_idx,
+                     new_len, new_sent_off, new_sent_cnt, kept_stride, ws, ws_bytes, stream);
+  k.stages = kSelect;
+  k.per_head = true;
+  k.ranges = ranges;
+  return run_call(k);
+}
+
+int skipkv_select_tokens_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_params *params,
+                                const float *tok_importance, const float *tok_redundancy, const float *sent_lambda,
+                                float *tok_score, uint8_t *tok_keep, int32_t *kept_idx, int32_t *new_len,
+                                int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride, void *ws,
+                                size_t ws_bytes, void *stream) {
+  Call k = step_call(cache, params, nullptr, tok_redundancy, nullptr, nullptr, nullptr, tok_keep, kept_idx, new_len,
+                     new_sent_off, new_sent_cnt, kept_stride, ws, ws_bytes, stream);
+  k.stages = kSelectTokens;
+  k.per_head = true;
+  k.ranges = ranges;
+  k.tok_imp_in = tok_importance;
+  k.lambda_in = sent_lambda;
+  k.tok_score = tok_score;
+  return run_call(k);
+}
+
+// ---- per-head ranges on a paged cache --------------------------------------------------------------------
+
+int skipkv_ranges_paged_workspace_bytes(const skipkv_cache *cache, const skipkv_paging *paging,
+                                        const skipkv_params *params, size_t *out_bytes) {
+  Call k;
+  k.stages = kScore | kSelect | kCompact;
+  k.cache = cache;
+  k.params = params;
+  k.per_head = true;
+  k.paged = true;
+  k.paging = paging;
+  return size_call(k, out_bytes);
+}
+
+int skipkv_score_ranges_paged(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_paging *paging,
+                              const int32_t *sent_id, const int32_t *lambda_ptr, const float *shared_lambda,
+                              const skipkv_params *params, const void *q_obs, const float *tok_redundancy,
+                              float *sent_score, float *sent_lambda, float *tok_importance, void *ws, size_t ws_bytes,
+                              void *stream) {
+  Call k = step_call(cache, params, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, nullptr, nullptr, nullptr,
+                     nullptr, nullptr, 0, ws, ws_bytes, stream);
+  k.stages = kScore;
+  k.per_head = true;
+  k.ranges = ranges;
+  k.paged = true;
+  k.paging = paging;
+  k.shared = shared_lambda != nullptr;
+  k.shared_lambda = shared_lambda;
+  k.sent_id = sent_id;
+  k.lam_ptr = lambda_ptr;
+  return run_call(k);
+}
+
+int skipkv_step_ranges_paged(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_paging *paging,
+                             const skipkv_params *params, const void *q_obs, const float *tok_redundancy,
+                             float *sent_score, float *sent_lambda, float *tok_importance, uint8_t *sent_keep,
+                             int32_t *kept_idx, int32_t *new_len, int32_t *new_sent_off, int32_t *new_sent_cnt,
+                             int32_t kept_stride, void *ws, size_t ws_bytes, void *stream) {
+  Call k = step_call(cache, params, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, sent_keep, kept_idx,
+                     new_len, new_sent_off, new_sent_cnt, kept_stride, ws, ws_bytes, stream);
+  k.per_head = true;
+  k.ranges = ranges;
+  k.paged = true;
+  k.paging = paging;
+  return run_call(k);
 }
 
 namespace {
@@ -696,101 +1003,7 @@ int skipkv_compact_paged(const skipkv_cache *cache, const skipkv_paging *paging,
   return do_compact(tm, cache, kept_idx, new_len, kept_stride, st, row_map, seq_bad, src_rows, v.src_stride);
 }
 
-int skipkv_step_paged(const skipkv_cache *cache, const skipkv_paging *paging, const skipkv_params *params,
-                      const void *q_obs, const float *tok_redundancy, float *sent_score, float *sent_lambda,
-                      float *tok_importance, uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len,
-                      int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride, void *ws, size_t ws_bytes,
-                      void *stream) {
-  RowLayout rl;
-  int rc = check_cache(cache, true);
-  if (rc) return rc;
-  rc = check_params(cache, params, &rl);
-  if (rc) return rc;
-  rc = check_select_args(cache, params, &rl, sent_score, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride);
-  if (rc) return rc;
-  if (is_empty(cache)) return SKIPKV_OK;
-  if (!q_obs || !aligned16(q_obs)) return SKIPKV_EINVAL;
-  if (cache->total_sentences > 0 && (!sent_score || !sent_lambda)) return SKIPKV_EINVAL;
-  PagedView pv;
-  rc = check_paging(cache, paging, params, rl, &pv);
-  if (rc) return rc;
-  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < pv.total) return SKIPKV_EWORKSPACE;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  Timer tm(params->profile, st);
-  int32_t *row_map = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + pv.step_bytes);
-  int32_t *seq_bad = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + pv.step_bytes + pv.map_bytes);
-  RowMapArgs ra{cache->seq_off, paging->block_table, cache->batch, paging->table_stride, paging->block_size,
-                paging->n_blocks, 1, 1, cache->total_tokens, 0, 0, pv.rows_per_block, 1, row_map, seq_bad, params->dev_status};
-  if (tm.run("row_map", [&] { return launch_row_map(ra, st); }) != hipSuccess) return SKIPKV_EHIP;
-  HeadView hv;
-  hv.row_map = row_map;
-  hv.page_size = paging->block_size;
-  rc = do_score(tm, cache, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, ws, st, hv);
-  if (rc) return rc;
-  rc = do_select(tm, cache, params, sent_score, sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride, st);
-  if (rc) return rc;
-  int32_t *src_rows = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + pv.step_bytes + pv.map_bytes + pv.bad_bytes);
-  return do_compact(tm, cache, kept_idx, new_len, kept_stride, st, row_map, seq_bad, src_rows, pv.src_stride);
-}
-
-int skipkv_ranges_workspace_bytes(const skipkv_cache *cache, const skipkv_params *params, size_t *out_bytes) {
-  if (!out_bytes) return SKIPKV_EINVAL;
-  int rc = check_cache(cache, true);
-  if (rc) return rc;
-  RowLayout rl;
-  rc = check_params(cache, params, &rl);
-  if (rc) return rc;
-  if (is_empty(cache)) {
-    *out_bytes = 0;
-    return SKIPKV_OK;
-  }
-  skipkv_ranges dummy{reinterpret_cast<int32_t *>(16), reinterpret_cast<int32_t *>(16), reinterpret_cast<int32_t *>(16)};
-  VirtualView v;
-  rc = make_virtual(cache, &dummy, nullptr, &v);
-  if (rc) return rc;
-  const Workspace w = carve(&v.c, rl, nullptr);
-  if (!w.fits) return SKIPKV_ECAPACITY;
-  *out_bytes = v.head_bytes + w.bytes;
-  return SKIPKV_OK;
-}
-
-int skipkv_step_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_params *params,
-                       const void *q_obs, const float *tok_redundancy, float *sent_score, float *sent_lambda,
-                       float *tok_importance, uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len,
-                       int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride, void *ws, size_t ws_bytes,
-                       void *stream) {
-  RowLayout rl;
-  int rc = check_cache(cache, true);
-  if (rc) return rc;
-  rc = check_params(cache, params, &rl);
-  if (rc) return rc;
-  rc = check_select_args(cache, params, &rl, sent_score, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride);
-  if (rc) return rc;
-  if (is_empty(cache)) return SKIPKV_OK;
-  if (!q_obs || !aligned16(q_obs)) return SKIPKV_EINVAL;
-  if (cache->total_sentences > 0 && (!sent_score || !sent_lambda)) return SKIPKV_EINVAL;
-  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SKIPKV_EWORKSPACE;
-  VirtualView v;
-  rc = make_virtual(cache, ranges, ws, &v);
-  if (rc) return rc;
-  const Workspace w = carve(&v.c, rl, nullptr);
-  if (!w.fits) return SKIPKV_ECAPACITY;
-  if (ws_bytes < v.head_bytes + w.bytes) return SKIPKV_EWORKSPACE;
-  if (ranges->sent_off == new_sent_off || ranges->len == new_len || ranges->sent_cnt == new_sent_cnt) return SKIPKV_EINVAL;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  if (launch_virtual_layout(cache->seq_off, cache->sent_ptr, cache->batch, cache->n_layers * cache->n_kv_heads,
-                            cache->total_tokens, cache->total_sentences, v.seq_off, v.sent_ptr, st) != hipSuccess)
-    return SKIPKV_EHIP;
-  void *ws2 = static_cast<char *>(ws) + v.head_bytes;
-  Timer tm(params->profile, st);
-  rc = do_score(tm, &v.c, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, ws2, st, v.hv);
-  if (rc) return rc;
-  rc = do_select(tm, &v.c, params, sent_score, sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride, st, v.hv);
-  if (rc) return rc;
-  return do_compact(tm, &v.c, kept_idx, new_len, kept_stride, st);
-}
-
-// Shared lambda (hidden-state similarity) on per-head ranges.
+// Sentence numbers of a head's surviving sentences (shared lambda on per-head ranges).
 int skipkv_ranges_ids_select(const skipkv_cache *cache, const skipkv_ranges *ranges, int32_t protect_window,
                              const uint8_t *sent_keep, const int32_t *sent_id_in, int32_t *sent_id_out, void *stream) {
   const int rc = check_cache(cache, true);
@@ -835,111 +1048,6 @@ int skipkv_ranges_ids_append(const skipkv_cache *cache, const int32_t *old_cnt, 
   return launch_ranges_ids_append(a, static_cast<hipStream_t>(stream)) == hipSuccess ? SKIPKV_OK : SKIPKV_EHIP;
 }
 
-int skipkv_score_shared_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const int32_t *sent_id,
-                               const int32_t *lambda_ptr, const skipkv_params *params, const void *q_obs,
-                               const float *tok_redundancy, const float *shared_lambda, float *sent_score,
-                               float *sent_lambda, float *tok_importance, void *ws, size_t ws_bytes, void *stream) {
-  RowLayout rl;
-  int rc = check_cache(cache, true);
-  if (rc) return rc;
-  rc = check_params(cache, params, &rl);
-  if (rc) return rc;
-  if (is_empty(cache)) return SKIPKV_OK;
-  if (!q_obs || !aligned16(q_obs)) return SKIPKV_EINVAL;
-  if (cache->total_sentences > 0 && (!sent_score || !shared_lambda || !sent_id || !lambda_ptr)) return SKIPKV_EINVAL;
-  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SKIPKV_EWORKSPACE;
-  VirtualView v;
-  rc = make_virtual(cache, ranges, ws, &v);
-  if (rc) return rc;
-  const Workspace w = carve(&v.c, rl, nullptr);
-  if (!w.fits) return SKIPKV_ECAPACITY;
-  if (ws_bytes < v.head_bytes + w.bytes) return SKIPKV_EWORKSPACE;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  if (launch_virtual_layout(cache->seq_off, cache->sent_ptr, cache->batch, cache->n_layers * cache->n_kv_heads,
-                            cache->total_tokens, cache->total_sentences, v.seq_off, v.sent_ptr, st) != hipSuccess)
-    return SKIPKV_EHIP;
-  HeadView hv = v.hv;
-  hv.sent_id = sent_id;
-  hv.lam_ptr = lambda_ptr;
-  Timer tm(params->profile, st);
-  return do_score(tm, &v.c, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance,
-                  static_cast<char *>(ws) + v.head_bytes, st, hv, shared_lambda);
-}
-
-// The parts of skipkv_step_ranges, for callers that select token by token in between.
-int skipkv_score_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_params *params,
-                        const void *q_obs, const float *tok_redundancy, float *sent_score, float *sent_lambda,
-                        float *tok_importance, void *ws, size_t ws_bytes, void *stream) {
-  RowLayout rl;
-  int rc = check_cache(cache, true);
-  if (rc) return rc;
-  rc = check_params(cache, params, &rl);
-  if (rc) return rc;
-  if (is_empty(cache)) return SKIPKV_OK;
-  if (!q_obs || !aligned16(q_obs)) return SKIPKV_EINVAL;
-  if (cache->total_sentences > 0 && (!sent_score || !sent_lambda)) return SKIPKV_EINVAL;
-  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SKIPKV_EWORKSPACE;
-  VirtualView v;
-  rc = make_virtual(cache, ranges, ws, &v);
-  if (rc) return rc;
-  const Workspace w = carve(&v.c, rl, nullptr);
-  if (!w.fits) return SKIPKV_ECAPACITY;
-  if (ws_bytes < v.head_bytes + w.bytes) return SKIPKV_EWORKSPACE;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  if (launch_virtual_layout(cache->seq_off, cache->sent_ptr, cache->batch, cache->n_layers * cache->n_kv_heads,
-                            cache->total_tokens, cache->total_sentences, v.seq_off, v.sent_ptr, st) != hipSuccess)
-    return SKIPKV_EHIP;
-  Timer tm(params->profile, st);
-  return do_score(tm, &v.c, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance,
-                  static_cast<char *>(ws) + v.head_bytes, st, v.hv);
-}
-
-int skipkv_select_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_params *params,
-                         const float *sent_score, uint8_t *sent_keep, int32_t *kept_idx, int32_t *new_len,
-                         int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride, void *ws, size_t ws_bytes,
-                         void *stream) {
-  RowLayout rl;
-  int rc = check_select_args(cache, params, &rl, sent_score, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride);
-  if (rc) return rc;
-  if (is_empty(cache)) return SKIPKV_OK;
-  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SKIPKV_EWORKSPACE;
-  VirtualView v;
-  rc = make_virtual(cache, ranges, ws, &v, true);  // K and V are not read: any strides
-  if (rc) return rc;
-  if (ws_bytes < v.head_bytes) return SKIPKV_EWORKSPACE;
-  if (ranges->sent_off == new_sent_off || ranges->len == new_len || ranges->sent_cnt == new_sent_cnt) return SKIPKV_EINVAL;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  if (launch_virtual_layout(cache->seq_off, cache->sent_ptr, cache->batch, cache->n_layers * cache->n_kv_heads,
-                            cache->total_tokens, cache->total_sentences, v.seq_off, v.sent_ptr, st) != hipSuccess)
-    return SKIPKV_EHIP;
-  Timer tm(params->profile, st);
-  return do_select(tm, &v.c, params, sent_score, sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride, st, v.hv);
-}
-
-int skipkv_select_tokens_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_params *params,
-                                const float *tok_importance, const float *tok_redundancy, const float *sent_lambda,
-                                float *tok_score, uint8_t *tok_keep, int32_t *kept_idx, int32_t *new_len,
-                                int32_t *new_sent_off, int32_t *new_sent_cnt, int32_t kept_stride, void *ws,
-                                size_t ws_bytes, void *stream) {
-  RowLayout rl;
-  int rc = check_select_args(cache, params, &rl, sent_lambda, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride);
-  if (rc) return rc;
-  if (is_empty(cache)) return SKIPKV_OK;
-  if (cache->total_tokens > 0 && (!tok_importance || !tok_score)) return SKIPKV_EINVAL;
-  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SKIPKV_EWORKSPACE;
-  VirtualView v;
-  rc = make_virtual(cache, ranges, ws, &v, true);  // K and V are not read: any strides
-  if (rc) return rc;
-  if (ws_bytes < v.head_bytes) return SKIPKV_EWORKSPACE;
-  if (ranges->sent_off == new_sent_off || ranges->len == new_len || ranges->sent_cnt == new_sent_cnt) return SKIPKV_EINVAL;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  if (launch_virtual_layout(cache->seq_off, cache->sent_ptr, cache->batch, cache->n_layers * cache->n_kv_heads,
-                            cache->total_tokens, cache->total_sentences, v.seq_off, v.sent_ptr, st) != hipSuccess)
-    return SKIPKV_EHIP;
-  return do_select_tokens(&v.c, params, tok_importance, tok_redundancy, sent_lambda, tok_score, tok_keep, kept_idx, new_len,
-                          new_sent_off, new_sent_cnt, kept_stride, st, v.hv);
-}
-
 int skipkv_token_redundancy_ranges(const skipkv_cache *cache, const skipkv_ranges *ranges, float *tok_redundancy, void *ws,
                                    size_t ws_bytes, void *stream) {
   const int rc = check_cache(cache, false);
@@ -950,152 +1058,6 @@ int skipkv_token_redundancy_ranges(const skipkv_cache *cache, const skipkv_range
   TokRedArgs a = tokred_args(cache, ws, tok_redundancy);
   a.len = ranges->len;
   return launch_token_redundancy(a, static_cast<hipStream_t>(stream)) == hipSuccess ? SKIPKV_OK : SKIPKV_EHIP;
-}
-
-namespace {
-// Per-head ranges on a paged cache.  The virtual cache of make_virtual has one layer and one head,
-// so the (layer, head) part of an address moves into the row map: every (layer, head) gets a map
-// of its own whose unit is one head row (head_dim elements), which every stride must be a
-// multiple of.  Behind the virtual layout and the step's workspace sit these maps, the
-// per-(head, sequence) flags and the slot rows of the kept tokens.
-struct RangesPagedView {
-  VirtualView v;
-  size_t step_bytes, map_bytes, bad_bytes, total;
-  int32_t src_stride;
-  int64_t unit_layer, unit_head, unit_block, unit_tok;
-};
-int check_ranges_paging(const skipkv_cache *c, const skipkv_ranges *r, const skipkv_paging *pg, const skipkv_params *p,
-                        const RowLayout &rl, void *ws, RangesPagedView *o) {
-  int64_t rpb = 0;
-  int rc = check_paging_desc(c, pg, &rpb);
-  if (rc) return rc;
-  const int64_t D = c->head_dim;
-  if ((c->stride_tok % D) || (c->stride_head % D) || (c->stride_layer % D) || (pg->stride_block % D)) return SKIPKV_EINVAL;
-  o->unit_layer = c->stride_layer / D;
-  o->unit_head = c->stride_head / D;
-  o->unit_block = pg->stride_block / D;
-  o->unit_tok = c->stride_tok / D;
-  const int64_t last_row = (int64_t)(c->n_layers - 1) * o->unit_layer + (int64_t)(c->n_kv_heads - 1) * o->unit_head +
-                           (int64_t)(pg->n_blocks - 1) * o->unit_block + (int64_t)(pg->block_size - 1) * o->unit_tok;
-  if (last_row > 0x7FFFFFFFll) return SKIPKV_ECAPACITY;  // slot rows are 32-bit
-  rc = make_virtual(c, r, ws, &o->v, true);
-  if (rc) return rc;
-  const Workspace w = carve(&o->v.c, rl, nullptr);
-  if (!w.fits) return SKIPKV_ECAPACITY;
-  const size_t LH = (size_t)c->n_layers * c->n_kv_heads;
-  o->step_bytes = align_up(w.bytes);
-  o->map_bytes = align_up(LH * c->total_tokens * 4);
-  o->bad_bytes = align_up(LH * c->batch * 4);
-  o->src_stride = std::max(1, std::min(p->max_budget, c->total_tokens));
-  o->total = o->v.head_bytes + o->step_bytes + o->map_bytes + o->bad_bytes + align_up(LH * c->batch * o->src_stride * 4);
-  return SKIPKV_OK;
-}
-}  // namespace
-
-int skipkv_ranges_paged_workspace_bytes(const skipkv_cache *cache, const skipkv_paging *paging,
-                                        const skipkv_params *params, size_t *out_bytes) {
-  if (!out_bytes) return SKIPKV_EINVAL;
-  int rc = check_cache(cache, true);
-  if (rc) return rc;
-  RowLayout rl;
-  rc = check_params(cache, params, &rl);
-  if (rc) return rc;
-  if (is_empty(cache)) {
-    *out_bytes = 0;
-    return SKIPKV_OK;
-  }
-  skipkv_ranges dummy{reinterpret_cast<int32_t *>(16), reinterpret_cast<int32_t *>(16), reinterpret_cast<int32_t *>(16)};
-  RangesPagedView pv;
-  rc = check_ranges_paging(cache, &dummy, paging, params, rl, nullptr, &pv);
-  if (rc) return rc;
-  *out_bytes = pv.total;
-  return SKIPKV_OK;
-}
-
-namespace {
-// Scoring half of the per-head step on pages; leaves the row maps, flags and the view behind for the caller.
-int score_ranges_paged(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_paging *paging,
-                       const skipkv_params *params, const RowLayout &rl, const void *q_obs, const float *tok_redundancy,
-                       const float *shared_lambda, const int32_t *sent_id, const int32_t *lambda_ptr, float *sent_score,
-                       float *sent_lambda, float *tok_importance, void *ws, size_t ws_bytes, hipStream_t st, Timer &tm,
-                       RangesPagedView *pv, HeadView *hv_out) {
-  if (!q_obs || !aligned16(q_obs)) return SKIPKV_EINVAL;
-  if (cache->total_sentences > 0 && (!sent_score || (!shared_lambda && !sent_lambda))) return SKIPKV_EINVAL;
-  if (shared_lambda && cache->total_sentences > 0 && (!sent_id || !lambda_ptr)) return SKIPKV_EINVAL;
-  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SKIPKV_EWORKSPACE;
-  int rc = check_ranges_paging(cache, ranges, paging, params, rl, ws, pv);
-  if (rc) return rc;
-  if (ws_bytes < pv->total) return SKIPKV_EWORKSPACE;
-  const VirtualView &v = pv->v;
-  const int32_t n_lh = cache->n_layers * cache->n_kv_heads;
-  if (launch_virtual_layout(cache->seq_off, cache->sent_ptr, cache->batch, n_lh, cache->total_tokens,
-                            cache->total_sentences, v.seq_off, v.sent_ptr, st) != hipSuccess)
-    return SKIPKV_EHIP;
-  char *ws2 = static_cast<char *>(ws) + v.head_bytes;
-  int32_t *row_map = reinterpret_cast<int32_t *>(ws2 + pv->step_bytes);
-  int32_t *seq_bad = reinterpret_cast<int32_t *>(ws2 + pv->step_bytes + pv->map_bytes);
-  RowMapArgs ra{cache->seq_off, paging->block_table, cache->batch, paging->table_stride, paging->block_size,
-                paging->n_blocks, n_lh, cache->n_kv_heads, cache->total_tokens, pv->unit_layer, pv->unit_head,
-                pv->unit_block, pv->unit_tok, row_map, seq_bad, params->dev_status};
-  if (tm.run("row_map", [&] { return launch_row_map(ra, st); }) != hipSuccess) return SKIPKV_EHIP;
-  HeadView hv = v.hv;
-  hv.row_map = row_map;
-  hv.page_size = paging->block_size;
-  hv.map_stride = cache->head_dim;
-  hv.sent_id = shared_lambda ? sent_id : nullptr;
-  hv.lam_ptr = shared_lambda ? lambda_ptr : nullptr;
-  *hv_out = hv;
-  return do_score(tm, &v.c, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, ws2, st, hv, shared_lambda);
-}
-}  // namespace
-
-int skipkv_score_ranges_paged(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_paging *paging,
-                              const int32_t *sent_id, const int32_t *lambda_ptr, const float *shared_lambda,
-                              const skipkv_params *params, const void *q_obs, const float *tok_redundancy,
-                              float *sent_score, float *sent_lambda, float *tok_importance, void *ws, size_t ws_bytes,
-                              void *stream) {
-  RowLayout rl;
-  int rc = check_cache(cache, true);
-  if (rc) return rc;
-  rc = check_params(cache, params, &rl);
-  if (rc) return rc;
-  if (is_empty(cache)) return SKIPKV_OK;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  Timer tm(params->profile, st);
-  RangesPagedView pv;
-  HeadView hv;
-  return score_ranges_paged(cache, ranges, paging, params, rl, q_obs, tok_redundancy, shared_lambda, sent_id, lambda_ptr,
-                            sent_score, sent_lambda, tok_importance, ws, ws_bytes, st, tm, &pv, &hv);
-}
-
-int skipkv_step_ranges_paged(const skipkv_cache *cache, const skipkv_ranges *ranges, const skipkv_paging *paging,
-                             const skipkv_params *params, const void *q_obs, const float *tok_redundancy,
-                             float *sent_score, float *sent_lambda, float *tok_importance, uint8_t *sent_keep,
-                             int32_t *kept_idx, int32_t *new_len, int32_t *new_sent_off, int32_t *new_sent_cnt,
-                             int32_t kept_stride, void *ws, size_t ws_bytes, void *stream) {
-  RowLayout rl;
-  int rc = check_cache(cache, true);
-  if (rc) return rc;
-  rc = check_params(cache, params, &rl);
-  if (rc) return rc;
-  rc = check_select_args(cache, params, &rl, sent_score, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride);
-  if (rc) return rc;
-  if (is_empty(cache)) return SKIPKV_OK;
-  if (ranges && (ranges->sent_off == new_sent_off || ranges->len == new_len || ranges->sent_cnt == new_sent_cnt)) return SKIPKV_EINVAL;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  Timer tm(params->profile, st);
-  RangesPagedView pv;
-  HeadView hv;
-  rc = score_ranges_paged(cache, ranges, paging, params, rl, q_obs, tok_redundancy, nullptr, nullptr, nullptr, sent_score,
-                          sent_lambda, tok_importance, ws, ws_bytes, st, tm, &pv, &hv);
-  if (rc) return rc;
-  const VirtualView &v = pv.v;
-  rc = do_select(tm, &v.c, params, sent_score, sent_keep, kept_idx, new_len, new_sent_off, new_sent_cnt, kept_stride, st, hv);
-  if (rc) return rc;
-  char *ws2 = static_cast<char *>(ws) + v.head_bytes;
-  int32_t *seq_bad = reinterpret_cast<int32_t *>(ws2 + pv.step_bytes + pv.map_bytes);
-  int32_t *src_rows = reinterpret_cast<int32_t *>(ws2 + pv.step_bytes + pv.map_bytes + pv.bad_bytes);
-  return do_compact(tm, &v.c, kept_idx, new_len, kept_stride, st, hv.row_map, seq_bad, src_rows, pv.src_stride, cache->head_dim);
 }
 
 int skipkv_ranges_append(const skipkv_cache *cache, const skipkv_ranges *ranges, const int32_t *n_new,
@@ -1154,20 +1116,6 @@ int skipkv_sentence_similarity(const skipkv_cache *cache, const void *hidden, in
   a.vhat_lo = reinterpret_cast<uint16_t *>(p + align_up(n * 4) + align_up(n * 2));
   a.sent_lambda = shared_lambda;
   return launch_hidden_similarity(a, static_cast<hipStream_t>(stream)) == hipSuccess ? SKIPKV_OK : SKIPKV_EHIP;
-}
-
-int skipkv_score_shared(const skipkv_cache *cache, const skipkv_params *params, const void *q_obs,
-                        const float *tok_redundancy, const float *shared_lambda, float *sent_score, float *sent_lambda,
-                        float *tok_importance, void *ws, size_t ws_bytes, void *stream) {
-  RowLayout rl;
-  float dummy = 0.f;
-  const int rc = check_score_args(cache, params, &rl, q_obs, sent_score, sent_lambda ? sent_lambda : &dummy, ws, ws_bytes);
-  if (rc) return rc;
-  if (is_empty(cache)) return SKIPKV_OK;
-  if (cache->total_sentences > 0 && !shared_lambda) return SKIPKV_EINVAL;
-  Timer tm(params->profile, static_cast<hipStream_t>(stream));
-  return do_score(tm, cache, params, rl, q_obs, tok_redundancy, sent_score, sent_lambda, tok_importance, ws,
-                  static_cast<hipStream_t>(stream), HeadView(), shared_lambda);
 }
 
 int skipkv_redundancy_workspace_bytes(const skipkv_cache *cache, size_t *out_bytes) {
