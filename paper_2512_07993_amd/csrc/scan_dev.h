@@ -7,21 +7,14 @@
 namespace skipkv {
 
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
-typedef __attribute__((__vector_size__(4 * sizeof(short)))) short bf16x4_t;  // operand type of the 4x4x4 bf16 matrix instruction
 
 // Cross-workgroup communication (the workgroups may sit on different XCDs, whose L2 caches are not
-// coherent with each other).  Everything that is communicated - share statistics, row normalisers,
-// the arrive counter - is accessed ONLY with device-scope relaxed atomics, which
-// are coherent by themselves; ordering comes from waiting until the data stores have been
-// acknowledged before the counter or flag is touched, and from program order plus a workgroup
-// barrier on the reading side.  No device-scope fence is used: on this chip such a fence writes
-// back and invalidates a whole L2, which is ruinous when thousands of workgroups do it.
-__device__ __forceinline__ void coherent_store(float *p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float coherent_load(const float *p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
+// coherent with each other).  Everything that is communicated - the statistics records of the items, the
+// abort word - is accessed ONLY with device-scope relaxed atomics, which are coherent by themselves.
+// A record is ONE 8-byte store and carries its own validity (its first word holds a marker until it is
+// written), so readers need no ordering between words and writers need no fence or flag.  No device-scope
+// fence is used: on this chip such a fence writes back and invalidates a whole L2, which is ruinous when
+// thousands of workgroups do it.
 __device__ __forceinline__ void coherent_store2(float2 *p, float2 v) {
   unsigned long long u = (unsigned long long)__float_as_uint(v.x) | ((unsigned long long)__float_as_uint(v.y) << 32);
   __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -75,9 +68,6 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 __device__ __forceinline__ uint32_t lds_addr(const void *p) {
   return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char *)p;
 }
-__device__ __forceinline__ uint32_t lds_read_u32(uint32_t addr) {
-  return *(const __attribute__((address_space(3))) uint32_t *)(uintptr_t)addr;
-}
 __device__ __forceinline__ float lds_read_f32(uint32_t addr) {
   return *(const __attribute__((address_space(3))) float *)(uintptr_t)addr;
 }
@@ -99,16 +89,6 @@ __device__ __forceinline__ float row16_sum_fast(float v) {
   SKIPKV_DPP_STEP("v_add_f32_dpp", 2);
   SKIPKV_DPP_STEP("v_add_f32_dpp", 1);
   return v;
-}
-// Sum over the whole wave, returned in a scalar register: rows first, then row 0 -> 1 and
-// 2 -> 3 (row_bcast:15), then the lower half -> the upper half (row_bcast:31); lane 63 ends up
-// with the total.
-__device__ __forceinline__ float wave_sum_fast(float v) {
-  v = row16_sum_fast(v);
-  // rows that are masked off keep their value, so the operand must be read-write (same register)
-  asm volatile("s_nop 1\n\tv_add_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf" : "+v"(v));
-  asm volatile("s_nop 1\n\tv_add_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf" : "+v"(v));
-  return __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v), 63));  // the builtin moves 32-bit integers
 }
 #undef SKIPKV_DPP_STEP
 

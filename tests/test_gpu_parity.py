@@ -162,10 +162,10 @@ def test_config5_full_size_sampled_heads():
     assert stats["heads"] == 6 and stats["all_heads_checked"] == 3072
 
 
-def test_long_sequences_counter_protocol_next_to_short_ones():
-    """Sequences of more than 128 scan items (here 75 K and 99 K tokens: 160 and 211 items) exchange
-    their row statistics through the arrive counter and one merging workgroup, shorter ones (55 K
-    tokens: 118 items) have every workgroup merge the records itself; one launch holds both."""
+def test_long_sequences_next_to_short_ones():
+    """Sequences of up to 99 K tokens (about 210 scan items of four spans each, near the 256 that one head may
+    have in the single-pass scan: every workgroup of such a head merges all of its records) in one launch
+    with sequences a third as long."""
     cfg = W.CONFIGS[3].scaled(n_layers=1, batch=3, n_kv_heads=2, n_q_heads=8, len_lo=30000, len_hi=100000,
                               sent_mean=40.0)
     stats = _run_and_compare(cfg, 6, seed=7)
