@@ -91,12 +91,15 @@ __device__ __forceinline__ i16x4 lds_read_tr16(uint32_t addr) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)(uintptr_t)addr);
 }
 
+// A uniform 64-bit address as a scalar register pair (the compiler may hold it in vector registers).
+__device__ __forceinline__ uint64_t scalar64(const void *p_) {
+  const uint64_t p = (uint64_t)(uintptr_t)p_;
+  return ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(p >> 32)) << 32) | (uint32_t)__builtin_amdgcn_readfirstlane((int)p);
+}
 // Direct HBM -> LDS load with a scalar base and a 32-bit offset per lane.
-__device__ __forceinline__ void load_to_lds_16_sbase(const void *sbase, uint32_t voff, void *wave_lds_base) {
+__device__ __forceinline__ void load_to_lds_16_sbase(uint64_t sbase, uint32_t voff, void *wave_lds_base) {
   const uint32_t l = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)wave_lds_base;
-  const uint64_t p = (uint64_t)(uintptr_t)sbase;  // uniform by construction; the intrinsic makes it a scalar register pair
-  const uint64_t sp = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(p >> 32)) << 32) | (uint32_t)__builtin_amdgcn_readfirstlane((int)p);
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(l), "v"(voff), "s"(sp) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(l), "v"(voff), "s"(sbase) : "memory");
 }
 
 template <int DT, int NP, int AL>
@@ -239,20 +242,13 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     if (a.row_map == nullptr) {
       // scalar 64-bit base of the stage + a 32-bit offset per lane (the launcher only takes this
       // kernel for row pitches below 2^24 bytes)
-      const char *sbase = kbase + (int64_t)ts * tok_pitch;
+      const uint64_t sbase = scalar64(kbase + (int64_t)ts * tok_pitch);
       const uint32_t ln = (uint32_t)opaque(lane);
       const uint32_t vp0 = ((ln % PPR) ^ (uint32_t)swz((int)(ln / PPR))) << 4;
-      if (last >= kStageRows - 1) {
-        const uint32_t vrow = __umul24(ln / PPR, pitch32);
 #pragma unroll
-        for (int j = 0; j < GL; ++j)
-          load_to_lds_16_sbase(sbase + (int64_t)(j * RPL) * tok_pitch, (vp0 ^ (uint32_t)(swz(j * RPL) << 4)) + vrow, dst + j * 1024);
-      } else {
-#pragma unroll
-        for (int j = 0; j < GL; ++j) {
-          const int row = j * RPL + (int)(ln / PPR);
-          load_to_lds_16_sbase(sbase, __umul24((uint32_t)min(row, last), pitch32) + (vp0 ^ (uint32_t)(swz(j * RPL) << 4)), dst + j * 1024);
-        }
+      for (int j = 0; j < GL; ++j) {
+        const int row = j * RPL + (int)(ln / PPR);
+        load_to_lds_16_sbase(sbase, __umul24((uint32_t)min(row, last), pitch32) + (vp0 ^ (uint32_t)(swz(j * RPL) << 4)), dst + j * 1024);
       }
     } else {
       // Paged cache, blocks of a power of two >= 16 slots: the stage's 16 tokens lie in at most two
