@@ -470,6 +470,9 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
     {
       float tot[SLP];
       bool doubt = false;
+      // From here until the head's records are folded the wave runs at raised priority: what it does now is
+      // what the other workgroups of its head wait for, while the other wave of the SIMD is mostly in its first phase.
+      __builtin_amdgcn_s_setprio(3);
 #pragma unroll
       for (int q = 0; q < SLP; ++q) tot[q] = lsum[q];
 #pragma unroll
@@ -611,6 +614,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
         mstat[wave][lane][1] = s;
       }
     }
+    __builtin_amdgcn_s_setprio(0);
     lds_barrier();  // B2: the quarters are there; the next item's queries and offsets are committed
     if (lane < R) {  // every wave folds the four quarters into its own copy of the normalisers
       float m = kRefInit;
