@@ -330,7 +330,7 @@ struct WideShape {
 };
 
 template <int NP, int AL, bool PASSB>
-__global__ void __launch_bounds__(256, 2) k_scan_wide(ScanArgs a) {
+__global__ void __launch_bounds__(256, PASSB ? 4 : 3) k_scan_wide(ScanArgs a) {
   using WS = WideShape<NP, AL>;
   constexpr int APW = WS::APW, SPW = WS::SPW, TPW = WS::TPW, SLW = WS::SLW, RW = WS::RW;
   constexpr int TT = 64;             // tokens per key tile: four sub-tiles of 16
@@ -341,8 +341,10 @@ __global__ void __launch_bounds__(256, 2) k_scan_wide(ScanArgs a) {
   __shared__ __align__(16) char kt[TT * LSTR];
   __shared__ int soff[kChunkMaxSent + 1];
   // pass A: sentence key sums [kChunkMaxSent][128]
-  // pass B: token importance of the tile [TT], sentence sums of I and of R [2][kChunkMaxSent], per-wave parts [4][TT]
-  constexpr int SBUF = PASSB ? (TT + 2 * kChunkMaxSent + 4 * TT) : (kChunkMaxSent * kD);
+  // pass B, per group of GT tokens (four tiles): token importance [GT], sentence sums of I and of R
+  // [2][kChunkMaxSent], per-wave parts [4][GT]
+  constexpr int GT = 4 * TT;
+  constexpr int SBUF = PASSB ? (GT + 2 * kChunkMaxSent + 4 * GT) : (kChunkMaxSent * kD);
   __shared__ float sbuf[SBUF];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, c16 = lane & 15, g = lane >> 4;
@@ -421,6 +423,23 @@ __global__ void __launch_bounds__(256, 2) k_scan_wide(ScanArgs a) {
   }
   const int p_start = n_tok - min(a.protect, n_tok);  // first protected token
 
+  // Pass A keeps the softmax statistics of a row relative to a reference that is fixed by the chunk's first
+  // 16 tokens (one fma, one exponential, one add per logit).  Should a row's sum then lie outside what fp32
+  // holds comfortably (a later logit far above the first ones, or all of them far below), the whole chunk is
+  // done again with a running reference per row, as exactly as before; results agree up to rounding.
+  [[maybe_unused]] bool exact = false;
+  for (int attempt = 0; attempt < (PASSB ? 1 : 2); ++attempt) {
+  if (attempt == 1) {
+    exact = true;
+#pragma unroll
+    for (int q = 0; q < SLW; ++q) {
+      ref[q] = kRefInit;
+      lsum[q] = 0.f;
+    }
+    __syncthreads();
+    for (int i = tid; i < SBUF; i += 256) sbuf[i] = 0.f;
+    __syncthreads();
+  }
   for (int tile_t = t_begin; tile_t < t_end; tile_t += TT) {
     // ---- stream the tile into LDS
     {
@@ -448,12 +467,12 @@ __global__ void __launch_bounds__(256, 2) k_scan_wide(ScanArgs a) {
 
     // ---- per sub-tile of 16 tokens: logits of the wave's rows (acc[T][j] = row 4g+j of tile T, token 16s + c16),
     // then straight away what the pass needs from them, so that only one sub-tile's logits are live
-    [[maybe_unused]] float *part = sbuf + TT + 2 * kChunkMaxSent;
+    [[maybe_unused]] float *part = sbuf + GT + 2 * kChunkMaxSent + ((tile_t - t_begin) % GT);  // this tile's slice of the group
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       if (tile_t + 16 * s >= t_end) {
         if constexpr (PASSB)
-          if (g == 0) part[wave * TT + 16 * s + c16] = 0.f;
+          if (g == 0) part[wave * GT + 16 * s + c16] = 0.f;
         continue;
       }
       f32x4 acc[TPW];
@@ -468,8 +487,31 @@ __global__ void __launch_bounds__(256, 2) k_scan_wide(ScanArgs a) {
       }
       const int t = tile_t + 16 * s + c16;
       if constexpr (!PASSB) {
-        // running softmax statistics of the wave's query rows
         const bool edge = (tile_t + 16 * s + 15 >= t_end) || (tile_t + 16 * s + 15 > last_free);
+        if (!exact) {
+          if (s == 0 && tile_t == t_begin) {  // the chunk's first 16 tokens fix the references
+#pragma unroll
+            for (int q = 0; q < SLW; ++q) {
+              float x = acc[q >> 2][q & 3] * kScale2;
+              if (edge) {
+                const int aq = g + 4 * (wave * APW + q / NP);
+                if (!(t < t_end && t <= last_free + aq)) x = -INFINITY;
+              }
+              ref[q] = fmaxf(row16_max(x), kRefInit);
+            }
+          }
+#pragma unroll
+          for (int q = 0; q < SLW; ++q) {
+            float x = fmaf(acc[q >> 2][q & 3], kScale2, -ref[q]);
+            if (edge) {
+              const int aq = g + 4 * (wave * APW + q / NP);
+              if (!(t < t_end && t <= last_free + aq)) x = -INFINITY;
+            }
+            lsum[q] += __builtin_amdgcn_exp2f(x);
+          }
+          continue;
+        }
+        // running softmax statistics of the wave's query rows
         bool need = false;
 #pragma unroll
         for (int q = 0; q < SLW; ++q) {
@@ -508,7 +550,7 @@ __global__ void __launch_bounds__(256, 2) k_scan_wide(ScanArgs a) {
         }
         sum += __shfl_xor(sum, 16);
         sum += __shfl_xor(sum, 32);
-        if (g == 0) part[wave * TT + 16 * s + c16] = sum;
+        if (g == 0) part[wave * GT + 16 * s + c16] = sum;
       }
     }
 
@@ -532,33 +574,62 @@ __global__ void __launch_bounds__(256, 2) k_scan_wide(ScanArgs a) {
         }
       }
     } else {
-      // ---- the four waves' parts of the token importance are added in a fixed order through LDS
-      float *imp = sbuf;
-      __syncthreads();
-      if (tid < TT) {
-        const float tot = ((part[tid] + part[TT + tid]) + part[2 * TT + tid]) + part[3 * TT + tid];
-        imp[tid] = (tile_t + tid < t_end) ? tot / (float)a.alpha : 0.f;
-      }
-      __syncthreads();
-      // sentence sums over the unprotected part, and the optional per-token outputs / inputs
-      const int64_t tok_col = (int64_t)lh * a.total_tokens + tok0;
-      if (tid < ns) {
-        const int lo = max(soff[tid], tile_t), hi = min(min(soff[tid + 1], p_start), tile_t + TT);
-        float si = 0.f, sr = 0.f;
-        for (int t = lo; t < hi; ++t) {
-          si += imp[t - tile_t];
-          if (a.tok_red) sr += a.tok_red[tok_col + t];
+      // ---- at the end of a group of four tiles (or of the chunk): the four waves' parts of the token
+      // importance are added in a fixed order, then the sentences' sums over their unprotected part
+      const int g0 = t_begin + (tile_t - t_begin) / GT * GT;  // first token of the group
+      if (tile_t + TT >= t_end || tile_t + TT >= g0 + GT) {
+        float *imp = sbuf;
+        const float *parts = sbuf + GT + 2 * kChunkMaxSent;
+        const int g1 = min(min(t_end, tile_t + TT), g0 + GT);
+        __syncthreads();
+        {
+          const float tot = ((parts[tid] + parts[GT + tid]) + parts[2 * GT + tid]) + parts[3 * GT + tid];
+          imp[tid] = (g0 + tid < g1) ? tot / (float)a.alpha : 0.f;
         }
-        sbuf[TT + tid] += si;
-        sbuf[TT + kChunkMaxSent + tid] += sr;
-      }
-      if (a.tok_imp) {
-        for (int i = tid; i < TT && tile_t + i < t_end; i += 256) a.tok_imp[tok_col + tile_t + i] = imp[i];
+        __syncthreads();
+        const int64_t tok_col = (int64_t)lh * a.total_tokens + tok0;
+        {  // eight lanes per sentence
+          static_assert(kChunkMaxSent * 8 <= 256, "eight lanes per sentence of a chunk");
+          const int si = tid >> 3, sub = tid & 7;
+          float sum_i = 0.f, sum_r = 0.f;
+          if (si < ns) {
+            const int lo = max(soff[si], g0), hi = min(min(soff[si + 1], p_start), g1);
+            for (int t = lo + sub; t < hi; t += 8) {
+              sum_i += imp[t - g0];
+              if (a.tok_red) sum_r += a.tok_red[tok_col + t];
+            }
+          }
+#pragma unroll
+          for (int m = 1; m < 8; m <<= 1) {
+            sum_i += __shfl_xor(sum_i, m);
+            sum_r += __shfl_xor(sum_r, m);
+          }
+          if (si < ns && sub == 0) {
+            sbuf[GT + si] += sum_i;
+            sbuf[GT + kChunkMaxSent + si] += sum_r;
+          }
+        }
+        if (a.tok_imp && g0 + tid < g1) a.tok_imp[tok_col + g0 + tid] = imp[tid];
       }
     }
-    __syncthreads();  // the next tile overwrites kt / imp / part
+    __syncthreads();  // the next tile overwrites kt; the next group imp and the parts
   }
 
+  if constexpr (!PASSB) {
+    if (attempt == 0) {
+      bool doubt = false;
+#pragma unroll
+      for (int q = 0; q < SLW; ++q) {
+        const int i = q % NP, aq = g + 4 * (wave * APW + q / NP);
+        // rows of padding hold zero queries, and a window query that does not even see the chunk's first token sees none of it
+        const bool used = q < SPW && i < n && aq < a.alpha && t_begin <= last_free + aq && t_begin < t_end;
+        const float tot = row16_sum(lsum[q]);
+        doubt = doubt || (used && !(tot > 1e-30f && tot < 3e38f));  // also catches NaN and infinity
+      }
+      if (!__syncthreads_or(doubt)) break;
+    }
+  }
+  }  // attempts
   if constexpr (!PASSB) {
     // ---- unit sentence embeddings, split into bf16 hi + lo, one wave per sentence
     for (int si = wave; si < ns && !a.no_pool; si += 4) {
@@ -584,8 +655,8 @@ __global__ void __launch_bounds__(256, 2) k_scan_wide(ScanArgs a) {
     if (tid < ns) {
       const int len = min(soff[tid + 1], p_start) - soff[tid];
       const int64_t o = (int64_t)lh * a.total_sentences + sent_col0 + tid;
-      a.ws.sent_imp[o] = len > 0 ? sbuf[TT + tid] / (float)len : 0.f;
-      a.ws.sent_red[o] = len > 0 ? sbuf[TT + kChunkMaxSent + tid] / (float)len : 0.f;
+      a.ws.sent_imp[o] = len > 0 ? sbuf[GT + tid] / (float)len : 0.f;
+      a.ws.sent_red[o] = len > 0 ? sbuf[GT + kChunkMaxSent + tid] / (float)len : 0.f;
     }
   }
   }  // item loop

@@ -183,3 +183,40 @@ def test_group_sizes_and_observation_windows(group, alpha, dtype):
                    alpha, max(alpha, 40), 12.0, 0.2)
     stats = _run_and_compare(cfg, 6)
     assert stats["heads"] == 6
+
+
+@pytest.mark.parametrize("group,alpha,flags_name", [(4, 16, ""), (7, 8, ""), (5, 32, ""), (4, 16, "two_pass")])
+def test_logits_far_from_the_first_ones_take_the_exact_statistics(group, alpha, flags_name):
+    """Keys that carry a large component along a fixed direction during every other stretch of 50 tokens, queries
+    that point along it or against it: the logits of half the rows jump up by about 200 log2 units where such a
+    stretch begins, those of the other half drop by as much.  The fixed reference that the scans take from a
+    span's (or chunk's) first 16 tokens is then off by more than the exponent range of fp32 wherever a stretch
+    begins later in the span (sums overflow; sums of the dropping rows vanish next to a jumping row of the
+    same lane group), and those spans and chunks must be redone with exact references.  Everything is
+    compared with the oracle as usual."""
+    import torch
+    from paper_2512_07993_amd import binding as B
+    cfg = W.Config("jumps-%dx%d" % (group, alpha), 900 + group * 33 + alpha, 3, 1, 2, 2 * group, "bf16", 700, 2600, 384,
+                   alpha, max(alpha, 40), 14.0, 0.2)
+    st = W.make_structure(cfg)
+    k0, v0, q = W.fill_cache(cfg, st, device="cuda")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    u = torch.randn(128, generator=gen, device="cuda")
+    u = u / u.norm()
+    for b in range(cfg.batch):
+        t0, t1 = int(st.seq_off[b]), int(st.seq_off[b + 1])
+        ramp = 40.0 * ((torch.arange(t1 - t0, device="cuda") // 50) % 2).float()
+        k0[:, :, t0:t1] = (k0[:, :, t0:t1].float() + ramp[None, None, :, None] * u).to(k0.dtype)
+    sign = torch.ones(q.shape[2], q.shape[3], device="cuda")
+    sign[(torch.arange(q.shape[2], device="cuda")[:, None] + torch.arange(q.shape[3], device="cuda")[None, :]) % 2 == 1] = -1.0
+    q = (q.float() + 40.0 * sign[None, None, :, :, None] * u).to(q.dtype)
+    k, v = k0.clone(), v0.clone()
+    out = run_step(cfg, st, k, v, q, flags=B.FLAG_FORCE_TWO_PASS if flags_name else 0)
+    assert int(out.dev_status.item()) == 0
+    stats = {}
+    for (l, h, b) in sample_heads(cfg, st, 6, 11):
+        ora = oracle_head(cfg, st, k0, v0, q, l, h, b)
+        compare_head(cfg, st, out, k, v, k0, v0, ora, l, h, b, stats)
+    print(cfg.name, stats, flush=True)
+    assert stats["heads"] == 6
