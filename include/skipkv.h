@@ -61,7 +61,7 @@ enum {
 enum {
   SKIPKV_DEV_BAD_OFFSETS = 1,  /* sentence offsets not strictly ascending from 0 to N_b   */
   SKIPKV_DEV_TOO_MANY_SENT = 2, /* a sequence has more than SKIPKV_MAX_SENTENCES sentences */
-  SKIPKV_DEV_TIMEOUT = 4,       /* a bounded cross-workgroup wait ran out: the scores concerned are NaN */
+  SKIPKV_DEV_TIMEOUT = 4,       /* a bounded cross-workgroup wait ran out: the heads concerned were done by the two-pass scan (results valid, the call slower) */
   SKIPKV_DEV_TOO_MANY_TOK = 8,  /* skipkv_select_tokens: a sequence is longer than SKIPKV_MAX_TOKENS_TOKEN_SELECT */
   SKIPKV_DEV_BAD_BLOCK_TABLE = 16, /* paged cache: a block id outside [0, n_blocks); that sequence's K/V are left untouched */
   SKIPKV_DEV_BAD_BUDGET = 32,   /* a device budget below the protected window, negative, or too large for kept_stride */
@@ -146,9 +146,10 @@ int skipkv_workspace_bytes(const skipkv_cache *cache, const skipkv_params *param
  * have the GPU's compute units to itself (work of other streams running at the same time can
  * only be waited out).  It waits across workgroups; the wait is bounded (params->spin_limit): on
  * expiry SKIPKV_DEV_TIMEOUT is OR-ed into dev_status, every later wait of the call gives up at
- * once, the scores of the sentences concerned are NaN (which makes the selection keep those
- * heads whole) and the call still completes.  SKIPKV_FLAG_FORCE_TWO_PASS selects the two-pass
- * form for every sequence.
+ * once, and the heads concerned are flagged and done again by the two-pass kernels that follow in
+ * the stream: the call completes with valid results, only slower (the bit tells the caller that the
+ * GPU was not the call's alone).  SKIPKV_FLAG_FORCE_TWO_PASS selects the two-pass form for every
+ * sequence.
  * ws              device workspace, 256-byte aligned, >= skipkv_workspace_bytes().
  */
 int skipkv_score(const skipkv_cache *cache, const skipkv_params *params, const void *q_obs,

@@ -82,6 +82,7 @@ Workspace carve(const skipkv_cache *c, const RowLayout &rl, void *base) {
   w.rb_base = static_cast<int32_t *>(take(B * 4));
   w.rb_cnt = static_cast<int32_t *>(take(B * 4));
   w.seq_fused = static_cast<int32_t *>(take(B * 4));
+  w.head_redo = static_cast<int32_t *>(take(LH * B * 4));
   w.item_rec = static_cast<int32_t *>(take((size_t)w.ni_max * kItemRecInts * 4));
   w.chunks = static_cast<Chunk *>(take((size_t)w.nc_max * sizeof(Chunk)));
   w.rowblocks = static_cast<RowBlock *>(take((size_t)w.nrb_max * sizeof(RowBlock)));

@@ -83,6 +83,7 @@ struct Workspace {
   int32_t *rb_base;      // [B] first row block of each sequence
   int32_t *rb_cnt;       // [B]
   int32_t *seq_fused;    // [B] 1: the sequence goes through the single-pass scan
+  int32_t *head_redo;    // [LH, B] 1: a wait of the single-pass scan ran out for this head: the two-pass scan does it again
   int32_t *item_rec;     // [ni_max][kItemRecInts] one record per item of the single-pass scan (ItemRec)
   Chunk *chunks;         // [nc_max]
   RowBlock *rowblocks;   // [nrb_max]

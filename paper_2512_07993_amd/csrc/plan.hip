@@ -70,6 +70,7 @@ __global__ void __launch_bounds__(256) k_plan(PlanArgs a) {
   __shared__ uint16_t s_snext[SKIPKV_MAX_SENTENCES];   // the same for spans
   __shared__ uint16_t s_sfirst[SKIPKV_MAX_SENTENCES + 1];
   const bool ok = !reject && !s_bad;
+  for (int lh = tid; lh < a.n_lh; lh += 256) a.ws.head_redo[(int64_t)lh * a.batch + b] = 0;
   // the greedy packing is a walk along s -> chunk_end(s); the ends are found for all sentences at
   // once, so that the (serial) walk is one LDS read per chunk
   if (ok)

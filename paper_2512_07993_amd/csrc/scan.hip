@@ -56,7 +56,7 @@ __global__ void __launch_bounds__(256, ((DT == SKIPKV_BF16 && NP * AL <= 40) ? 2
   const int lh = item / n_chunks, c = item % n_chunks;
   const Chunk ch = a.ws.chunks[c];
   const int b = ch.b, ns = ch.ns;
-  if (!a.force_two_pass && a.ws.seq_fused[b]) continue;
+  if (!a.force_two_pass && a.ws.seq_fused[b] && !a.ws.head_redo[(int64_t)lh * a.batch + b]) continue;  // done by the single-pass scan
   const int l = lh / a.n_kv_heads, h = lh % a.n_kv_heads;
   const int tok0 = ch.tok0;
   const int n_tok = ch.n_tok;
@@ -358,7 +358,7 @@ __global__ void __launch_bounds__(256, PASSB ? 4 : 3) k_scan_wide(ScanArgs a) {
   const int lh = item / n_chunks, c = item % n_chunks;
   const Chunk ch = a.ws.chunks[c];
   const int b = ch.b, ns = ch.ns;
-  if (!a.force_two_pass && a.ws.seq_fused[b]) continue;
+  if (!a.force_two_pass && a.ws.seq_fused[b] && !a.ws.head_redo[(int64_t)lh * a.batch + b]) continue;  // done by the single-pass scan
   const int l = lh / a.n_kv_heads, h = lh % a.n_kv_heads;
   const int tok0 = ch.tok0;
   const int n_tok = ch.n_tok;
@@ -665,7 +665,7 @@ __global__ void __launch_bounds__(256, PASSB ? 4 : 3) k_scan_wide(ScanArgs a) {
 // log2 of the softmax normaliser of every query row: merge the chunk partials of a head.
 __global__ void k_row_norm(ScanArgs a, int R) {
   const int lhb = blockIdx.x, lh = lhb / a.batch, b = lhb % a.batch;
-  if (!a.force_two_pass && a.ws.seq_fused[b]) return;  // the single-pass scan computed these itself
+  if (!a.force_two_pass && a.ws.seq_fused[b] && !a.ws.head_redo[lhb]) return;  // the single-pass scan computed these itself
   const int c0 = a.ws.chunk_base[b], nc = a.ws.chunk_cnt[b];
   for (int r = threadIdx.x; r < R; r += blockDim.x) {
     float m = kRefInit, s = 0.f;

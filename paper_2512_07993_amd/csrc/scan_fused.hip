@@ -594,7 +594,12 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
           for (int u = 0; u < kMergeDepth; ++u) ok = ok && __float_as_uint(pv[u].x) != kRowNormUnset;  // surplus loads hold a real record too
           if (__all(ok)) break;
           if (wait_expired(polls)) {
-            if (lane == 0) s_timeout[par] = 1;
+            if (lane == 0) {
+              s_timeout[par] = 1;
+              // the head is done again by the two-pass kernels that follow this one in the stream
+              a.ws.head_redo[(int64_t)lh * a.batch + b] = 1;
+              atomicAdd(&a.ws.hdr->n_unfused, 1);
+            }
             break;
           }
           __builtin_amdgcn_s_sleep(1);
