@@ -61,11 +61,9 @@ def test_hidden_state_similarity_matches_oracle(dtype, d_model):
     assert n_dup > 0  # the planted copies are found
 
 
-def test_scores_with_shared_lambda_match_oracle():
-    cfg = W.CONFIGS[3].scaled(n_layers=2, batch=3, len_lo=500, len_hi=2500, budget=512)
+def _check_scores_with_shared_lambda(cfg, d_model, heads):
     st = W.make_structure(cfg)
     k0, v0, q = W.fill_cache(cfg, st, device="cuda")
-    d_model = 1024
     h = _hidden_with_copies(st, d_model, torch.bfloat16, 5)
     cache = make_cache(cfg, st, k0, v0)
     L, H, S, T = cfg.n_layers, cfg.n_kv_heads, st.total_sentences, st.total_tokens
@@ -81,19 +79,32 @@ def test_scores_with_shared_lambda_match_oracle():
     B.skipkv_score_shared(cache, params, q, None, shared, score, lam_out, imp, ws)
     torch.cuda.synchronize()
     assert int(status.item()) == 0
+    # every head carries the sequence's lambda unchanged, and nothing is left unwritten
+    assert torch.equal(lam_out.view(torch.int32), shared.view(torch.int32).expand(L, H, S))
+    assert not bool(torch.isnan(score).any()) and not bool(torch.isnan(imp).any())
     shared_np = shared.cpu().numpy().astype(np.float64)
-    for l in range(L):
-        for hh in range(H):
-            for b in range(cfg.batch):
-                qq, kk, vv, off = W.head_arrays(cfg, st, k0, v0, q, l, hh, b)
-                t0, t1 = int(st.seq_off[b]), int(st.seq_off[b + 1])
-                sb, Sb = st.sent_base(b), int(st.n_sent[b])
-                want_imp = oracle.token_importance(qq, kk)
-                np.testing.assert_allclose(imp[l, hh, t0:t1].cpu().numpy(), want_imp, rtol=SCORE_RTOL, atol=1e-12)
-                lam_b = shared_np[sb:sb + Sb]
-                want, candlen = oracle.sentence_scores(want_imp, lam_b, off, cfg.protect_window)
-                got = score[l, hh, sb:sb + Sb].cpu().numpy().astype(np.float64)
-                cand = candlen > 0
-                np.testing.assert_array_equal(np.isinf(got) & (got > 0), ~cand)
-                np.testing.assert_allclose(got[cand], want[cand], rtol=SCORE_RTOL, atol=1e-12)
-                np.testing.assert_array_equal(lam_out[l, hh, sb:sb + Sb].cpu().numpy(), shared[sb:sb + Sb].cpu().numpy())
+    for (l, hh, b) in heads(cfg, st):
+        qq, kk, vv, off = W.head_arrays(cfg, st, k0, v0, q, l, hh, b)
+        t0, t1 = int(st.seq_off[b]), int(st.seq_off[b + 1])
+        sb, Sb = st.sent_base(b), int(st.n_sent[b])
+        want_imp = oracle.token_importance(qq, kk)
+        np.testing.assert_allclose(imp[l, hh, t0:t1].cpu().numpy(), want_imp, rtol=SCORE_RTOL, atol=1e-12)
+        lam_b = shared_np[sb:sb + Sb]
+        want, candlen = oracle.sentence_scores(want_imp, lam_b, off, cfg.protect_window)
+        got = score[l, hh, sb:sb + Sb].cpu().numpy().astype(np.float64)
+        cand = candlen > 0
+        np.testing.assert_array_equal(np.isinf(got) & (got > 0), ~cand)
+        np.testing.assert_allclose(got[cand], want[cand], rtol=SCORE_RTOL, atol=1e-12)
+
+
+def test_scores_with_shared_lambda_match_oracle():
+    cfg = W.CONFIGS[3].scaled(n_layers=2, batch=3, len_lo=500, len_hi=2500, budget=512)
+    _check_scores_with_shared_lambda(cfg, 1024, lambda cfg, st: [(l, h, b) for l in range(cfg.n_layers) for h in range(cfg.n_kv_heads)
+                                                                  for b in range(cfg.batch)])
+
+
+def test_scores_with_shared_lambda_config3_full_size():
+    """The workload that bench.py --shared-lambda times (all 32 layers, 16 sequences, d_model 4096), on heads
+    sampled across layers, heads and sequences."""
+    from helpers import sample_heads
+    _check_scores_with_shared_lambda(W.CONFIGS[3], 4096, lambda cfg, st: sample_heads(cfg, st, 8, 9))
