@@ -206,11 +206,6 @@ __global__ void __launch_bounds__(256, kTW == 4 ? 2 : 3) k_tokred_sweep(TokRedAr
     if (jb + kCols < n_tok) fetch(jb + kCols);  // lands while this block is multiplied
     if (jb > r0) emit(jb - kCols, buf ^ 1);
     const bool mirror = jb >= r0 + kRows;       // right of the diagonal square: the block also stands for its transpose
-    float csum[kCols / 16][4];  // four independent chains per column tile (one per register of the output tile)
-#pragma unroll
-    for (int ct = 0; ct < kCols / 16; ++ct)
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) csum[ct][jj] = 0.f;
     auto products = [&](auto mirror_c) {
       constexpr bool MIRROR = decltype(mirror_c)::value;
 #pragma unroll
@@ -222,6 +217,7 @@ __global__ void __launch_bounds__(256, kTW == 4 ? 2 : 3) k_tokred_sweep(TokRedAr
         for (int kk = 0; kk < 4; ++kk) bfr[kk] = *reinterpret_cast<const bf16x8 *>(cols + (16 * ct + c16) * LSTR + (4 * g + kk) * 16);
         const float cc = col_c[16 * ct + c16];
         const float cw = col_w[16 * ct + c16];
+        float csum[4] = {0.f, 0.f, 0.f, 0.f};  // the lane's column over the wave's rows: four independent chains
 #pragma unroll
         for (int t = 0; t < kTW; ++t) {
           f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -231,24 +227,24 @@ __global__ void __launch_bounds__(256, kTW == 4 ? 2 : 3) k_tokred_sweep(TokRedAr
           for (int jj = 0; jj < 4; ++jj) {
             const float e = __builtin_amdgcn_exp2f(acc[jj] * (row_c[t][jj] * cc));
             rsum[t][jj] = fmaf(e, cw, rsum[t][jj]);
-            if constexpr (MIRROR) csum[ct][jj] = fmaf(e, row_w[t][jj], csum[ct][jj]);
+            if constexpr (MIRROR) csum[jj] = fmaf(e, row_w[t][jj], csum[jj]);
           }
+        }
+        if constexpr (MIRROR) {
+          // the four lane groups hold different rows of the same column
+          float v = (csum[0] + csum[1]) + (csum[2] + csum[3]);
+          v += __shfl_xor(v, 16);
+          v += __shfl_xor(v, 32);
+          if (g == 0) cpart[buf][wave][16 * ct + c16] = v;
         }
       }
     };
     if (rw0 < n_tok) {
       if (mirror) products(std::true_type{});
       else products(std::false_type{});
-    }
-    if (mirror) {
-      // the four lane groups hold different rows of the same columns
+    } else if (mirror && g == 0) {  // a wave without rows adds nothing to the columns
 #pragma unroll
-      for (int ct = 0; ct < kCols / 16; ++ct) {
-        float v = (csum[ct][0] + csum[ct][1]) + (csum[ct][2] + csum[ct][3]);
-        v += __shfl_xor(v, 16);
-        v += __shfl_xor(v, 32);
-        if (g == 0) cpart[buf][wave][16 * ct + c16] = v;
-      }
+      for (int ct = 0; ct < kCols / 16; ++ct) cpart[buf][wave][16 * ct + c16] = 0.f;
     }
     __syncthreads();  // (a cpart buffer is written again two blocks later, behind two more barriers)
   }
