@@ -560,6 +560,7 @@ __global__ void __launch_bounds__(256, (DT == SKIPKV_BF16 ? 2 : 1)) k_scan_fused
       for (int r = 0; r < 4; ++r) ssq[r] = row16_sum_fast(ssq[r]);  // the 16 lanes of the group hold a sentence's 128 dimensions
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
+        if (r == 2) load_records(wave);  // a second look, timed to land when the embeddings are out
         const float ss = ssq[r];
         const int slot = g4 + r, sl = cur.sb + min(slot, ns - 1);
         const int len = soff[sl + 1] - soff[sl];
